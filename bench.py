@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the broadcast hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+                    [--algo chain|direct|binomial|fanout|auto] [--chunk BYTES] [--lanes N]
+
+A "step" is one whole broadcast (every chunk over every hop) of the workload's
+message to all P virtual ranks, with all buffers already resident in HBM.
+The default workload is the top of the message-size sweep: 64 MiB to P=8.
+Prints ONE JSON line.  `value` is the effective bandwidth 2(P-1)M / t of the
+pipelined chain in GB/s (algorithmic bytes: each delivered byte is read once
+from the left neighbour and written once); `ms_per_step` is the latency.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+KiB, MiB, GiB = 1 << 10, 1 << 20, 1 << 30
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+# name -> (P, root, message bytes, seed, what it stands for)
+WORKLOADS = {
+    "cfg1": (4, 0, 1 * MiB, 0, "1 MiB fp32 uniform[-1,1), P=4"),
+    "cfg2": (8, 0, 64 * MiB, 1, "64 MiB random bytes, P=8 (top of the message-size sweep)"),
+    "cfg3": (16, 0, 553430176, 2, "VGG-16 parameters packed (138M fp32, N(0,0.01)), P=16"),
+    "cfg4": (32, 0, 512 * MiB, 3, "512 MiB random bytes, P=32"),
+    "cfg5": (64, 17, 1 * GiB, 4, "1 GiB random bytes, P=64, root 17"),
+}
+
+# HBM traffic per launch of the chain kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def make_message(name, seed, nbytes):
+    from paper_1707_09414_amd import inputs
+
+    if name == "cfg1":
+        return inputs.uniform_fp32_message(seed, nbytes // 4)
+    if name == "cfg3":
+        return inputs.vgg16_packed_message(seed)[0]
+    return inputs.random_bytes(seed, nbytes)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOADS))
+    ap.add_argument("--algo", default="chain", choices=["chain", "direct", "binomial", "fanout", "auto"])
+    ap.add_argument("--chunk", type=int, default=0, help="chain chunk bytes (0 = tuned table / built-in rule)")
+    ap.add_argument("--lanes", type=int, default=0, help="wavefronts per chain hop (0 = automatic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-verify", action="store_true")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (P virtual ranks are buffers in one GPU's HBM); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_1707_09414_amd import binding as B
+    from paper_1707_09414_amd import inputs
+    from paper_1707_09414_amd import tuned
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    P, root, M, seed, what = WORKLOADS[args.workload]
+    algo = {"chain": B.BCAST_ALGO_CHAIN, "direct": B.BCAST_ALGO_DIRECT, "binomial": B.BCAST_ALGO_BINOMIAL,
+            "fanout": B.BCAST_ALGO_FANOUT, "auto": B.BCAST_ALGO_AUTO}[args.algo]
+
+    table = tuned.load_default_table()  # installs the shipped MI355X table if present
+
+    msg = make_message(args.workload, seed, M)
+    assert msg.nbytes == M
+    d_msg = torch.from_numpy(msg).cuda()
+    bufs = []
+    for r in range(P):
+        t = torch.empty(M, dtype=torch.uint8, device="cuda")
+        if r == root:
+            t.copy_(d_msg)
+        else:
+            t.fill_(inputs.FILL_BYTE)
+        bufs.append(t)
+    del d_msg
+
+    plan = B.bcast_plan_create(P, M, args.chunk, algo)
+    if args.lanes:
+        B.bcast_plan_set_lanes(plan, args.lanes)
+    info = B.bcast_plan_info(plan, M, bufs)
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        B.bcast_run(plan, bufs, root, M, stream)
+    torch.cuda.synchronize()
+
+    # timed region: exactly --steps broadcasts, each bracketed by HIP events on
+    # the launch stream (torch's current stream is the stream we launch on)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for e0, e1 in ev:
+        e0.record(stream)
+        B.bcast_run(plan, bufs, root, M, stream)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    status, detail = B.bcast_plan_status(plan)
+    if status != B.BCAST_OK:
+        print("bench.py: plan status %d detail %x" % (status, detail), file=sys.stderr)
+        return 1
+    wall_ms = (t1 - t0) * 1e3 / args.steps
+    launch_ms = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    avg_launch_ms = sum(launch_ms) / len(launch_ms)
+    med_launch_ms = launch_ms[len(launch_ms) // 2]
+
+    # every rank must now hold the root's message: one rank at a time over PCIe
+    verified = None
+    if not args.no_verify:
+        verified = True
+        for r in range(P):
+            if not np.array_equal(bufs[r].cpu().numpy(), msg):
+                verified = False
+                print("bench.py: rank %d does not hold the root's message" % r, file=sys.stderr)
+        if not verified:
+            return 1
+
+    algorithmic = int(info["algorithmic_bytes"])
+    value = algorithmic / (wall_ms * 1e-3) / 1e9
+    achieved = algorithmic / (avg_launch_ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(P, root, M, int(info["chunk_bytes"]) or M, msg)
+
+    out = {
+        "metric": "broadcast effective HBM bandwidth 2(P-1)M/t (GB/s) at the stated message size and P; latency in ms_per_step",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5),
+        "latency_us": round(wall_ms * 1e3, 2),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: %s, root %d" % (args.workload, what, root),
+            "P": P, "message_bytes": M, "algo": B.ALGO_NAMES[info["algo"]],
+            "chunk_bytes": int(info["chunk_bytes"]), "nchunks": int(info["nchunks"]), "lanes": info["lanes"],
+            "grid_blocks": info["grid_blocks"], "vec_bytes": info["vec_bytes"], "launches_per_step": info["launches"],
+            "tuning_table": table,
+        },
+        "delivered_GBps": round((P - 1) * M / (wall_ms * 1e-3) / 1e9, 2),
+        "verified_bit_exact": verified,
+        "roofline": {
+            "bound": "hbm",
+            "achieved": round(achieved, 2),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": traffic,
+            "kernel": "chain_kernel<16>" if info["algo"] == B.BCAST_ALGO_CHAIN else B.ALGO_NAMES[info["algo"]],
+            "algorithmic_bytes_per_launch": algorithmic,
+            "avg_launch_ms": round(avg_launch_ms, 5),
+            "median_launch_ms": round(med_launch_ms, 5),
+        },
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    plan.destroy()
+    return 0
+
+
+def cpu_baseline(P, root, M, C, msg):
+    """The CPU oracle's chain simulation, as it stands, timed on this host on a
+    bounded sample: the same P and chunk size, the message cut to at most 64 MiB."""
+    import numpy as np
+
+    import oracle
+
+    sample = min(M, 64 * MiB)
+    host = np.full((P, sample), 0xFF, dtype=np.uint8)
+    host[root] = msg[:sample]
+    oracle.chain_bcast(host, P, root, sample, C)  # touch pages once
+    reps = 0
+    t0 = time.perf_counter()
+    while True:
+        oracle.chain_bcast(host, P, root, sample, C)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt > 5.0 or reps >= 20:
+            break
+    sec = dt / reps
+    return {
+        "value": round(2 * (P - 1) * sample / sec / 1e9, 3),
+        "unit": "GB/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": "oracle.chain_bcast, P=%d, first %d bytes of the message, C=%d, %d reps, %.1f ms each"
+                  % (P, sample, C, reps, sec * 1e3),
+    }
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,179 @@
+/*
+ * bcast.h -- C ABI of the single-GPU broadcast library for MI355X (gfx950).
+ *
+ * The library implements the rooted broadcast of the paper's Sec. I / III-A
+ * (MPI_Bcast: every rank owns one buffer, the root's is the input, afterwards
+ * every buffer holds the root's bytes) for P "virtual ranks" that are P
+ * distinct device buffers in one GPU's HBM.  The flagship algorithm is the
+ * pipelined chain of Sec. IV-B (Eq. 5); the direct algorithm (Eq. 1), the
+ * binomial tree (Eq. 3, k = 2), a one-die fan-out and a tuning table that picks
+ * algorithm and chunk size per (message bytes, ranks) (Sec. III-B, IV-B) sit
+ * beside it.
+ *
+ * Conventions for every call
+ *   - Plain C linkage, no C++ or torch types.  Every pointer argument says
+ *     whether it is a HOST or a DEVICE pointer.
+ *   - Return value: BCAST_OK (0) or a negative bcast_status_t.  Nothing
+ *     aborts or throws.  After BCAST_ERR_HIP, bcast_last_hip_error() gives the
+ *     hipError_t value of the failing runtime call on this thread.
+ *   - The caller owns all rank buffers and the rank_bufs array; the library
+ *     owns what a plan allocates (ready flags, status word) until
+ *     bcast_plan_destroy.
+ *   - Streams are passed as HIP's own handle type.  To keep this header free
+ *     of HIP includes it is spelled bcast_stream_t, which is the same type as
+ *     hipStream_t (struct ihipStream_t *); NULL is the default stream.
+ */
+#ifndef BCAST_H
+#define BCAST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BCAST_MAX_RANKS 64
+
+typedef struct ihipStream_t *bcast_stream_t; /* == hipStream_t */
+typedef struct bcast_plan bcast_plan_t;      /* opaque, library-owned */
+
+typedef enum {
+    BCAST_ALGO_AUTO = 0,     /* look (bytes, nranks) up in the tuning table (Sec. IV-B, last paragraph) */
+    BCAST_ALGO_CHAIN = 1,    /* pipelined chain, Sec. IV-B Eq. 5; one chunk = plain chain, Eq. 2 */
+    BCAST_ALGO_DIRECT = 2,   /* root copies to each other rank in turn, Sec. III-A Eq. 1 */
+    BCAST_ALGO_BINOMIAL = 3, /* binomial tree, Sec. III-A Eq. 3 with k = 2 */
+    BCAST_ALGO_FANOUT = 4,   /* one-die shortcut: read root once, store to all ranks (no paper equivalent) */
+    BCAST_ALGO_SCATTER_ALLGATHER = 5 /* binomial scatter + ring allgather, Sec. III-A Eq. 4 */
+} bcast_algo_t;
+
+typedef enum {
+    BCAST_OK = 0,
+    BCAST_ERR_ARG = -1,     /* invalid argument; nothing was enqueued */
+    BCAST_ERR_NOMEM = -2,   /* host or device allocation failed */
+    BCAST_ERR_HIP = -3,     /* a HIP runtime call failed; see bcast_last_hip_error() */
+    BCAST_ERR_TIMEOUT = -4, /* a chain wave gave up waiting for its left neighbour */
+    BCAST_ERR_UNTUNED = -5  /* BCAST_ALGO_AUTO but the table has no entry for this nranks */
+} bcast_status_t;
+
+/* What a plan will launch for a given message size (host-side bookkeeping). */
+typedef struct {
+    int algo;              /* resolved bcast_algo_t (never AUTO) */
+    uint64_t chunk_bytes;  /* chunk size C in use (== bytes when unchunked) */
+    uint64_t nchunks;      /* ceil(bytes / C) */
+    int lanes;             /* chain: wavefronts per hop, each streaming its own slice of every chunk */
+    int grid_blocks;       /* workgroups of the (first) launch */
+    int block_threads;     /* threads per workgroup */
+    int vec_bytes;         /* widest access usable for these pointers: 16, 8, 4 or 1 */
+    int launches;          /* kernel launches per bcast_run */
+    uint64_t algorithmic_bytes; /* HBM bytes the schedule must move: reads + writes */
+} bcast_plan_info_t;
+
+/*
+ * bcast_plan_create -- reserve what a broadcast among `nranks` buffers of up
+ * to `bytes` bytes needs (Sec. IV-B: the chunked chain and its chunk size).
+ *   out         HOST pointer; receives the plan on success, NULL otherwise.
+ *   nranks      number of ranks P, 1..BCAST_MAX_RANKS (the paper's n).
+ *   bytes       largest message M this plan will carry (0 allowed).
+ *   chunk_bytes chunk size C for CHAIN: a positive multiple of 16; values
+ *               >= bytes give the unpipelined chain (Eq. 2).  0 = choose: the
+ *               tuning table's entry if one is loaded, else a built-in rule.
+ *               Ignored by DIRECT, BINOMIAL, FANOUT and SCATTER_ALLGATHER.
+ *   algo        a bcast_algo_t.  AUTO resolves per run from the tuning table and
+ *               fails with BCAST_ERR_UNTUNED if no table covers nranks.
+ * Allocates device memory for ready flags (zeroed once; they are never reset,
+ * runs are told apart by an epoch) and a pinned host status word.
+ * Errors: ERR_ARG (ranges, chunk not a multiple of 16), ERR_NOMEM, ERR_HIP.
+ */
+int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, size_t chunk_bytes, int algo);
+
+/*
+ * bcast_run -- enqueue one broadcast on `stream` (MPI_Bcast's statement of the
+ * problem, Sec. I and III-A; chain order per Sec. III-A "Chain and Ring").
+ *   plan       from bcast_plan_create.  One plan must not run on two streams
+ *              at once (not detected); back-to-back runs on one stream are fine.
+ *   rank_bufs  HOST array of plan.nranks DEVICE pointers, one per rank, on the
+ *              current device, pairwise non-overlapping over `bytes`.  Read
+ *              during the call only; the buffers must stay valid until the
+ *              stream has passed the run.  Any byte alignment is accepted;
+ *              the 128-bit path needs all pointers congruent mod 16.
+ *   root       rank whose buffer is the message; it is only read.
+ *   bytes      message size M, 0 <= M <= plan bytes.  Bytes at offsets >= M
+ *              are never written.
+ *   stream     hipStream_t to enqueue on.
+ * The chain position of rank r is (r - root) mod P: the root pushes chunks to
+ * rank root+1, which forwards to root+2, ... and rank root-1 only receives.
+ * Returns after enqueueing; completion follows stream order.
+ * bytes == 0 or nranks == 1 succeed without launching.
+ * Errors: ERR_ARG (NULL/duplicate/overlapping pointers, root or bytes out of
+ * range), ERR_UNTUNED, ERR_HIP.  A wave that waits longer than the plan's
+ * spin limit records ERR_TIMEOUT in the plan's status word (see below).
+ */
+int bcast_run(bcast_plan_t *plan, void *const *rank_bufs, int root, size_t bytes, bcast_stream_t stream);
+
+/*
+ * bcast_plan_status -- BCAST_OK, or BCAST_ERR_TIMEOUT if any run of this plan
+ * that has finished so far hit the wait limit.  Reads a pinned host word the
+ * kernels write; synchronises nothing (synchronise the stream first to cover a
+ * given run).  `detail` (HOST, nullable) receives hop << 32 | chunk of the
+ * first wave that gave up.  bcast_plan_clear_status resets the word.
+ */
+int bcast_plan_status(bcast_plan_t *plan, uint64_t *detail);
+int bcast_plan_clear_status(bcast_plan_t *plan);
+
+/* bcast_plan_info -- HOST-side description of what a run of `bytes` bytes over
+ * these pointers (nullable: then 16-byte alignment is assumed) would launch. */
+int bcast_plan_info(bcast_plan_t *plan, void *const *rank_bufs, size_t bytes, bcast_plan_info_t *info);
+
+/* bcast_plan_destroy -- waits for the device, then frees the plan's memory. */
+int bcast_plan_destroy(bcast_plan_t *plan);
+
+/* Knobs for experiments and tests.  lanes: wavefronts per chain hop (0 =
+ * automatic).  spin_limit_ticks: wait limit in 100 MHz ticks (0 = default,
+ * about 10 s).  mute_hop: chain position (1..P-2) that stores its chunks but
+ * never publishes them, so that its right neighbour runs into the wait limit;
+ * 0 = off.  Kernels always run to completion under these settings. */
+int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
+int bcast_plan_set_debug(bcast_plan_t *plan, uint64_t spin_limit_ticks, int mute_hop);
+
+/*
+ * Chain geometry as a pure HOST function (no GPU needed): how a chain of
+ * `nranks` ranks moving `bytes` bytes in chunks of `chunk_bytes` is laid over
+ * at most `max_waves` co-resident wavefronts.  lanes_request 0 = automatic.
+ * Fills nchunks, lanes, grid_blocks, block_threads, chunk_bytes.
+ */
+int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
+                         int lanes_request, bcast_plan_info_t *info);
+
+/*
+ * Tuning table (Sec. III-B "Discussion" and IV-B last paragraph: algorithm and
+ * chunk size are chosen per message-size range and process count from
+ * measurements).  Process-wide; entries are keyed by (nranks, floor(log2 bytes)).
+ *
+ * bcast_tune measures, on the current device and `stream`, every candidate
+ * (chain at chunk sizes 8 KiB..4 MiB, direct, binomial, and -- only if
+ * `algo_mask` has their bits -- the others) for message sizes that are powers
+ * of two in [min_bytes, max_bytes], keeps the fastest per size, installs the
+ * entries, and, if table_path (HOST, nullable) is given, appends them there as
+ * text.  It allocates nranks scratch buffers of max_bytes itself.
+ * algo_mask: bit (1 << algo) enables a candidate; 0 = chain|direct|binomial.
+ */
+int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsigned algo_mask,
+               bcast_stream_t stream, const char *table_path);
+int bcast_tune_load(const char *table_path);  /* HOST path; adds the file's entries */
+int bcast_tune_save(const char *table_path);  /* HOST path; writes all entries */
+int bcast_tune_clear(void);
+int bcast_tune_set(int nranks, size_t bytes, int algo, size_t chunk_bytes, double usec);
+/* Nearest entry for nranks at or below log2(bytes), else the nearest above.
+ * usec (nullable) = the time measured when the entry was made, 0 if unknown. */
+int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *chunk_bytes, double *usec);
+int bcast_tune_count(void);
+
+const char *bcast_strerror(int status);
+int bcast_last_hip_error(void);
+const char *bcast_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCAST_H */

@@ -1,0 +1,254 @@
+"""ctypes binding for the gfx950 broadcast library (``lib/libbcast.so``).
+
+Argument marshalling only: every byte is moved by the library's HIP kernels.
+Function names and argument order follow ``include/bcast.h``.  Buffers may be
+given as integers (device addresses) or as objects with ``data_ptr()`` (torch
+tensors); streams as integers (``torch.cuda.current_stream().cuda_stream``),
+objects with ``cuda_stream``, or None for the default stream.
+
+There is no CPU fallback: if the shared library is missing, importing this
+module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+from typing import Optional, Sequence, Tuple
+
+LIB_PATH = Path(__file__).resolve().parent / "lib" / "libbcast.so"
+
+BCAST_MAX_RANKS = 64
+
+BCAST_ALGO_AUTO = 0
+BCAST_ALGO_CHAIN = 1
+BCAST_ALGO_DIRECT = 2
+BCAST_ALGO_BINOMIAL = 3
+BCAST_ALGO_FANOUT = 4
+ALGO_NAMES = {0: "auto", 1: "chain", 2: "direct", 3: "binomial", 4: "fanout"}
+
+BCAST_OK = 0
+BCAST_ERR_ARG = -1
+BCAST_ERR_NOMEM = -2
+BCAST_ERR_HIP = -3
+BCAST_ERR_TIMEOUT = -4
+BCAST_ERR_UNTUNED = -5
+
+# every symbol include/bcast.h declares
+EXPORTS = [
+    "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_debug", "bcast_chain_geometry",
+    "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
+    "bcast_tune_lookup", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
+]
+
+
+class BcastError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        msg = "%s: %s (status %d)" % (what, _lib.bcast_strerror(status).decode(), status)
+        if status == BCAST_ERR_HIP:
+            msg += ", hipError %d" % _lib.bcast_last_hip_error()
+        super().__init__(msg)
+
+
+class PlanInfo(ctypes.Structure):
+    _fields_ = [
+        ("algo", ctypes.c_int),
+        ("chunk_bytes", ctypes.c_uint64),
+        ("nchunks", ctypes.c_uint64),
+        ("lanes", ctypes.c_int),
+        ("grid_blocks", ctypes.c_int),
+        ("block_threads", ctypes.c_int),
+        ("vec_bytes", ctypes.c_int),
+        ("launches", ctypes.c_int),
+        ("algorithmic_bytes", ctypes.c_uint64),
+    ]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+def _load():
+    if not LIB_PATH.exists():
+        raise ImportError(
+            "%s is missing: build it with `python -m paper_1707_09414_amd.build` "
+            "(there is no CPU fallback)" % LIB_PATH
+        )
+    lib = ctypes.CDLL(str(LIB_PATH))
+    vp, i, sz, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_uint64
+    pvp = ctypes.POINTER(ctypes.c_void_p)
+    sigs = {
+        "bcast_plan_create": ([pvp, i, sz, sz, i], i),
+        "bcast_run": ([vp, pvp, i, sz, vp], i),
+        "bcast_plan_status": ([vp, ctypes.POINTER(u64)], i),
+        "bcast_plan_clear_status": ([vp], i),
+        "bcast_plan_info": ([vp, pvp, sz, ctypes.POINTER(PlanInfo)], i),
+        "bcast_plan_destroy": ([vp], i),
+        "bcast_plan_set_lanes": ([vp, i], i),
+        "bcast_plan_set_debug": ([vp, u64, i], i),
+        "bcast_chain_geometry": ([i, sz, sz, i, i, ctypes.POINTER(PlanInfo)], i),
+        "bcast_tune": ([i, sz, sz, ctypes.c_uint, vp, ctypes.c_char_p], i),
+        "bcast_tune_load": ([ctypes.c_char_p], i),
+        "bcast_tune_save": ([ctypes.c_char_p], i),
+        "bcast_tune_clear": ([], i),
+        "bcast_tune_set": ([i, sz, i, sz, ctypes.c_double], i),
+        "bcast_tune_lookup": ([i, sz, ctypes.POINTER(i), ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_double)], i),
+        "bcast_tune_count": ([], i),
+        "bcast_strerror": ([i], ctypes.c_char_p),
+        "bcast_last_hip_error": ([], i),
+        "bcast_version": ([], ctypes.c_char_p),
+    }
+    for name, (args, res) in sigs.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = res
+    return lib
+
+
+_lib = _load()
+
+
+def _check(status: int, what: str) -> None:
+    if status != BCAST_OK:
+        raise BcastError(status, what)
+
+
+def _ptr(x) -> int:
+    return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return None
+    return int(s.cuda_stream) if hasattr(s, "cuda_stream") else int(s)
+
+
+def _ptr_array(rank_bufs: Sequence):
+    return (ctypes.c_void_p * len(rank_bufs))(*[_ptr(b) for b in rank_bufs])
+
+
+class Plan:
+    """Owner of one ``bcast_plan_t``; destroyed explicitly or when collected."""
+
+    def __init__(self, handle: int, nranks: int, bytes_: int, chunk_bytes: int, algo: int):
+        self.handle = handle
+        self.nranks = nranks
+        self.bytes = bytes_
+        self.chunk_bytes = chunk_bytes
+        self.algo = algo
+
+    def destroy(self) -> None:
+        if self.handle:
+            h, self.handle = self.handle, None
+            _check(_lib.bcast_plan_destroy(h), "bcast_plan_destroy")
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.destroy()
+
+
+def bcast_plan_create(nranks: int, bytes: int, chunk_bytes: int = 0, algo: int = BCAST_ALGO_CHAIN) -> Plan:
+    out = ctypes.c_void_p()
+    _check(_lib.bcast_plan_create(ctypes.byref(out), nranks, bytes, chunk_bytes, algo), "bcast_plan_create")
+    return Plan(out.value, nranks, bytes, chunk_bytes, algo)
+
+
+def bcast_run(plan: Plan, rank_bufs: Sequence, root: int, bytes: int, stream=None) -> None:
+    if len(rank_bufs) != plan.nranks:
+        raise BcastError(BCAST_ERR_ARG, "bcast_run: need %d buffers, got %d" % (plan.nranks, len(rank_bufs)))
+    _check(_lib.bcast_run(plan.handle, _ptr_array(rank_bufs), root, bytes, _stream(stream)), "bcast_run")
+
+
+def bcast_run_status(plan: Plan, rank_bufs: Sequence, root: int, bytes: int, stream=None) -> int:
+    """Like bcast_run but returns the status code instead of raising."""
+    arr = _ptr_array(rank_bufs) if rank_bufs is not None else None
+    return _lib.bcast_run(plan.handle, arr, root, bytes, _stream(stream))
+
+
+def bcast_plan_status(plan: Plan) -> Tuple[int, int]:
+    """(status, detail): detail is hop << 32 | chunk of the first wave that gave up."""
+    d = ctypes.c_uint64(0)
+    return _lib.bcast_plan_status(plan.handle, ctypes.byref(d)), d.value
+
+
+def bcast_plan_clear_status(plan: Plan) -> None:
+    _check(_lib.bcast_plan_clear_status(plan.handle), "bcast_plan_clear_status")
+
+
+def bcast_plan_info(plan: Plan, bytes: int, rank_bufs: Optional[Sequence] = None) -> dict:
+    info = PlanInfo()
+    arr = _ptr_array(rank_bufs) if rank_bufs is not None else None
+    _check(_lib.bcast_plan_info(plan.handle, arr, bytes, ctypes.byref(info)), "bcast_plan_info")
+    return info.as_dict()
+
+
+def bcast_plan_destroy(plan: Plan) -> None:
+    plan.destroy()
+
+
+def bcast_plan_set_lanes(plan: Plan, lanes: int) -> None:
+    _check(_lib.bcast_plan_set_lanes(plan.handle, lanes), "bcast_plan_set_lanes")
+
+
+def bcast_plan_set_debug(plan: Plan, spin_limit_ticks: int, mute_hop: int) -> None:
+    _check(_lib.bcast_plan_set_debug(plan.handle, spin_limit_ticks, mute_hop), "bcast_plan_set_debug")
+
+
+def bcast_chain_geometry(nranks: int, bytes: int, chunk_bytes: int, max_waves: int, lanes_request: int = 0) -> dict:
+    info = PlanInfo()
+    _check(_lib.bcast_chain_geometry(nranks, bytes, chunk_bytes, max_waves, lanes_request, ctypes.byref(info)),
+           "bcast_chain_geometry")
+    return info.as_dict()
+
+
+def bcast_tune(nranks: int, min_bytes: int, max_bytes: int, algo_mask: int = 0, stream=None,
+               table_path: Optional[str] = None) -> None:
+    path = table_path.encode() if table_path else None
+    _check(_lib.bcast_tune(nranks, min_bytes, max_bytes, algo_mask, _stream(stream), path), "bcast_tune")
+
+
+def bcast_tune_load(table_path: str) -> None:
+    _check(_lib.bcast_tune_load(str(table_path).encode()), "bcast_tune_load")
+
+
+def bcast_tune_save(table_path: str) -> None:
+    _check(_lib.bcast_tune_save(str(table_path).encode()), "bcast_tune_save")
+
+
+def bcast_tune_clear() -> None:
+    _check(_lib.bcast_tune_clear(), "bcast_tune_clear")
+
+
+def bcast_tune_set(nranks: int, bytes: int, algo: int, chunk_bytes: int, usec: float = 0.0) -> None:
+    _check(_lib.bcast_tune_set(nranks, bytes, algo, chunk_bytes, usec), "bcast_tune_set")
+
+
+def bcast_tune_lookup(nranks: int, bytes: int) -> Tuple[int, int, float]:
+    """(algo, chunk_bytes, usec) of the entry that AUTO would use."""
+    a, c, u = ctypes.c_int(0), ctypes.c_size_t(0), ctypes.c_double(0.0)
+    _check(_lib.bcast_tune_lookup(nranks, bytes, ctypes.byref(a), ctypes.byref(c), ctypes.byref(u)), "bcast_tune_lookup")
+    return a.value, c.value, u.value
+
+
+def bcast_tune_count() -> int:
+    return _lib.bcast_tune_count()
+
+
+def bcast_strerror(status: int) -> str:
+    return _lib.bcast_strerror(status).decode()
+
+
+def bcast_last_hip_error() -> int:
+    return _lib.bcast_last_hip_error()
+
+
+def bcast_version() -> str:
+    return _lib.bcast_version().decode()

@@ -1,0 +1,401 @@
+// Host side of the broadcast library: plans, argument checks, the mapping of
+// each algorithm onto kernel launches, and the C ABI declared in bcast.h.
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "bcast_internal.h"
+#include "tune_table.h"
+
+using namespace bcast;
+
+struct bcast_plan {
+    int nranks = 0;
+    size_t bytes = 0;
+    size_t chunk_bytes = 0;  // as requested; 0 = choose per run
+    int algo = BCAST_ALGO_AUTO;
+    int device = 0;
+    int cu_count = 0;
+    int max_waves = 0;       // wavefronts of the chain kernel the device holds at once
+    u64 *d_flags = nullptr;  // max_waves flags, kFlagStrideWords apart, plus the abort word
+    u64 *d_abort = nullptr;
+    u64 *h_status = nullptr; // pinned host: [0] timeout seen, [1] hop<<32|chunk
+    u64 *d_status = nullptr; // the same two words as the device sees them
+    u64 epoch = 0;
+    int lanes_request = 0;
+    u64 spin_ticks = kDefaultSpinTicks;
+    int mute_hop = 0;
+};
+
+static thread_local int g_last_hip_error = 0;
+
+static int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    (void)hipGetLastError();  // leave no sticky error behind for the caller's next HIP call
+    return e == hipErrorOutOfMemory ? BCAST_ERR_NOMEM : BCAST_ERR_HIP;
+}
+
+#define HIP_TRY(expr)                               \
+    do {                                            \
+        hipError_t e_ = (expr);                     \
+        if (e_ != hipSuccess) return hip_fail(e_);  \
+    } while (0)
+
+static u64 ceil_div(u64 a, u64 b) { return (a + b - 1) / b; }
+static u64 round_up(u64 a, u64 b) { return ceil_div(a, b) * b; }
+
+
+// Chunk size when the caller gives none and no tuning entry applies.  Eq. 5 is
+// minimised by C* = sqrt(M * ts * B / (n - 2)); with the start-up cost of one
+// flag hand-off and the per-hop stream rate folded into one constant this is
+// C ~ sqrt(M * 256 KiB / (n - 2)), kept within [16 KiB, 4 MiB] and a power of two.
+static u64 default_chunk(int nranks, u64 bytes)
+{
+    if (bytes == 0) return 16;
+    double fill = nranks > 2 ? (double)(nranks - 2) : 1.0;
+    double c = 1.0;
+    double target = (double)bytes * (256.0 * 1024.0) / fill;
+    while (c * c < target) c *= 2.0;
+    u64 C = (u64)c;
+    C = std::min<u64>(std::max<u64>(C, 16 * 1024), 4u << 20);
+    return C;
+}
+
+extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
+                                    int lanes_request, bcast_plan_info_t *info)
+{
+    if (!info || nranks < 1 || nranks > BCAST_MAX_RANKS || max_waves < 1 || lanes_request < 0) return BCAST_ERR_ARG;
+    if (chunk_bytes == 0 || chunk_bytes % 16 != 0) return BCAST_ERR_ARG;
+    memset(info, 0, sizeof *info);
+    info->algo = BCAST_ALGO_CHAIN;
+    info->block_threads = kBlockThreads;
+    info->vec_bytes = 16;
+    if (nranks < 2 || bytes == 0) {
+        info->chunk_bytes = chunk_bytes;
+        return BCAST_OK;
+    }
+    // C >= M is the unpipelined chain: one chunk that is the whole message
+    u64 C = std::min<u64>(chunk_bytes, round_up(bytes, 16));
+    u64 nchunks = ceil_div(bytes, C);
+    if (nchunks >= (1ull << 31)) return BCAST_ERR_ARG;
+    int hops = nranks - 1;
+    if (max_waves < hops) return BCAST_ERR_ARG;  // every hop needs a resident wavefront
+    int lanes_max = max_waves / hops;
+    // a lane should own at least one full 4 KiB trip of a chunk unless the chunk is smaller
+    u64 useful = std::max<u64>(1, ceil_div(C, kTileBytes));
+    int lanes = lanes_request > 0 ? lanes_request : (int)std::min<u64>(useful, (u64)lanes_max);
+    lanes = std::max(1, std::min(lanes, lanes_max));
+    u64 slice = round_up(ceil_div(C, (u64)lanes), 16);
+    info->chunk_bytes = C;
+    info->nchunks = nchunks;
+    info->lanes = lanes;
+    info->grid_blocks = (int)ceil_div((u64)hops * lanes, kWavesPerBlock);
+    info->launches = 1;
+    info->algorithmic_bytes = 2ull * hops * bytes;
+    // slice is recomputed by the launcher from (C, lanes) the same way
+    (void)slice;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, size_t chunk_bytes, int algo)
+{
+    if (!out) return BCAST_ERR_ARG;
+    *out = nullptr;
+    if (nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
+    if (algo < BCAST_ALGO_AUTO || algo > BCAST_ALGO_FANOUT) return BCAST_ERR_ARG;
+    if (chunk_bytes % 16 != 0) return BCAST_ERR_ARG;
+
+    bcast_plan *p = new (std::nothrow) bcast_plan;
+    if (!p) return BCAST_ERR_NOMEM;
+    p->nranks = nranks;
+    p->bytes = bytes;
+    p->chunk_bytes = chunk_bytes;
+    p->algo = algo;
+
+    int rc = BCAST_OK;
+    hipDeviceProp_t prop;
+    int per_cu = 0;
+    hipError_t e = hipGetDevice(&p->device);
+    if (e == hipSuccess) e = hipGetDeviceProperties(&prop, p->device);
+    if (e == hipSuccess) e = chain_max_blocks_per_cu(&per_cu);
+    if (e == hipSuccess) {
+        p->cu_count = prop.multiProcessorCount;
+        // keep the chain grid within half of what fits at once: room for the
+        // caller's other streams, and no reliance on the last wave slot
+        per_cu = std::max(1, std::min(per_cu, 8));
+        p->max_waves = std::max(nranks, p->cu_count * per_cu * kWavesPerBlock / 2);
+        size_t flag_bytes = ((size_t)p->max_waves + 1) * kFlagStrideWords * sizeof(u64);
+        e = hipMalloc((void **)&p->d_flags, flag_bytes);
+        if (e == hipSuccess) e = hipMemset(p->d_flags, 0, flag_bytes);
+        if (e == hipSuccess) p->d_abort = p->d_flags + (size_t)p->max_waves * kFlagStrideWords;
+    }
+    if (e == hipSuccess) e = hipHostMalloc((void **)&p->h_status, 2 * sizeof(u64), hipHostMallocMapped);
+    if (e == hipSuccess) {
+        p->h_status[0] = p->h_status[1] = 0;
+        e = hipHostGetDevicePointer((void **)&p->d_status, p->h_status, 0);
+    }
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        rc = hip_fail(e);
+        if (p->d_flags) (void)hipFree(p->d_flags);
+        if (p->h_status) (void)hipHostFree(p->h_status);
+        delete p;
+        return rc;
+    }
+    *out = p;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_destroy(bcast_plan_t *p)
+{
+    if (!p) return BCAST_ERR_ARG;
+    int rc = BCAST_OK;
+    hipError_t e = hipDeviceSynchronize();
+    if (e != hipSuccess) rc = hip_fail(e);
+    if (p->d_flags && (e = hipFree(p->d_flags)) != hipSuccess) rc = hip_fail(e);
+    if (p->h_status && (e = hipHostFree(p->h_status)) != hipSuccess) rc = hip_fail(e);
+    delete p;
+    return rc;
+}
+
+extern "C" int bcast_plan_set_lanes(bcast_plan_t *p, int lanes)
+{
+    if (!p || lanes < 0) return BCAST_ERR_ARG;
+    p->lanes_request = lanes;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_set_debug(bcast_plan_t *p, uint64_t spin_limit_ticks, int mute_hop)
+{
+    if (!p || mute_hop < 0 || mute_hop >= BCAST_MAX_RANKS) return BCAST_ERR_ARG;
+    p->spin_ticks = spin_limit_ticks ? spin_limit_ticks : kDefaultSpinTicks;
+    p->mute_hop = mute_hop;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_status(bcast_plan_t *p, uint64_t *detail)
+{
+    if (!p) return BCAST_ERR_ARG;
+    volatile u64 *st = p->h_status;
+    if (st[0] == 0) return BCAST_OK;
+    if (detail) *detail = st[1];
+    return BCAST_ERR_TIMEOUT;
+}
+
+extern "C" int bcast_plan_clear_status(bcast_plan_t *p)
+{
+    if (!p) return BCAST_ERR_ARG;
+    volatile u64 *st = p->h_status;
+    st[1] = 0;
+    st[0] = 0;
+    return BCAST_OK;
+}
+
+// Widest access every buffer supports together: all addresses must agree
+// modulo the vector size so that one head/body/tail split serves both sides
+// of every copy.
+static int common_vec_bytes(void *const *bufs, int n)
+{
+    if (!bufs) return 16;
+    uintptr_t diff = 0;
+    for (int i = 1; i < n; ++i) diff |= (uintptr_t)bufs[i] ^ (uintptr_t)bufs[0];
+    if ((diff & 15) == 0) return 16;
+    if ((diff & 7) == 0) return 8;
+    if ((diff & 3) == 0) return 4;
+    return 1;
+}
+
+struct Resolved {
+    int algo;
+    u64 chunk;
+};
+
+static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
+{
+    r->algo = p->algo;
+    r->chunk = p->chunk_bytes;
+    if (p->algo == BCAST_ALGO_AUTO) {
+        int algo = 0;
+        size_t chunk = 0;
+        if (bcast_tune_lookup(p->nranks, bytes, &algo, &chunk, nullptr) != BCAST_OK) return BCAST_ERR_UNTUNED;
+        r->algo = algo;
+        if (r->chunk == 0) r->chunk = chunk;
+    } else if (p->algo == BCAST_ALGO_CHAIN && r->chunk == 0) {
+        int algo = 0;
+        size_t chunk = 0;
+        if (bcast_tune_lookup(p->nranks, bytes, &algo, &chunk, nullptr) == BCAST_OK && algo == BCAST_ALGO_CHAIN)
+            r->chunk = chunk;
+    }
+    if (r->algo == BCAST_ALGO_CHAIN) {
+        if (r->chunk == 0) r->chunk = default_chunk(p->nranks, bytes);
+        r->chunk = round_up(r->chunk, 16);
+    }
+    return BCAST_OK;
+}
+
+// Grid for the plain copy kernels: enough 4-wave workgroups to cover the
+// bytes once, capped at a few workgroups per CU (waves stride beyond that).
+static int copy_grid(const bcast_plan *p, u64 bytes, int concurrent_copies)
+{
+    u64 need = std::max<u64>(1, ceil_div(bytes, kTileBytes * kWavesPerBlock));
+    u64 cap = std::max<u64>(1, (u64)p->cu_count * 8 / std::max(1, concurrent_copies));
+    return (int)std::min(need, cap);
+}
+
+static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_plan_info_t *info)
+{
+    Resolved r;
+    int rc = resolve(p, bytes, &r);
+    if (rc != BCAST_OK) return rc;
+    const int P = p->nranks;
+    const int vec = common_vec_bytes(rank_bufs, P);
+    if (r.algo == BCAST_ALGO_CHAIN) {
+        rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, p->max_waves, p->lanes_request, info);
+        if (rc != BCAST_OK) return rc;
+        info->vec_bytes = vec;
+        return BCAST_OK;
+    }
+    memset(info, 0, sizeof *info);
+    info->algo = r.algo;
+    info->chunk_bytes = bytes;
+    info->nchunks = bytes ? 1 : 0;
+    info->block_threads = kBlockThreads;
+    info->vec_bytes = vec;
+    if (P < 2 || bytes == 0) return BCAST_OK;
+    switch (r.algo) {
+    case BCAST_ALGO_DIRECT:
+        info->launches = P - 1;
+        info->grid_blocks = copy_grid(p, bytes, 1);
+        info->algorithmic_bytes = 2ull * (P - 1) * bytes;
+        break;
+    case BCAST_ALGO_BINOMIAL: {
+        int rounds = 0;
+        for (int reach = 1; reach < P; reach *= 2) ++rounds;
+        info->launches = rounds;
+        info->grid_blocks = copy_grid(p, bytes, 1);
+        info->algorithmic_bytes = 2ull * (P - 1) * bytes;
+        break;
+    }
+    case BCAST_ALGO_FANOUT:
+        info->launches = 1;
+        info->grid_blocks = copy_grid(p, bytes, 1);
+        info->algorithmic_bytes = (u64)P * bytes;
+        break;
+    default:
+        return BCAST_ERR_ARG;
+    }
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_info(bcast_plan_t *p, void *const *rank_bufs, size_t bytes, bcast_plan_info_t *info)
+{
+    if (!p || !info || bytes > p->bytes) return BCAST_ERR_ARG;
+    return describe(p, rank_bufs, bytes, info);
+}
+
+extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size_t bytes, bcast_stream_t stream)
+{
+    if (!p || !rank_bufs) return BCAST_ERR_ARG;
+    const int P = p->nranks;
+    if (root < 0 || root >= P || bytes > p->bytes) return BCAST_ERR_ARG;
+    for (int i = 0; i < P; ++i)
+        if (!rank_bufs[i]) return BCAST_ERR_ARG;
+    // buffers must not overlap over the message (duplicates included)
+    for (int i = 0; i < P; ++i)
+        for (int j = i + 1; j < P; ++j) {
+            uintptr_t a = (uintptr_t)rank_bufs[i], b = (uintptr_t)rank_bufs[j];
+            if (a == b) return BCAST_ERR_ARG;
+            uintptr_t lo = std::min(a, b), hi = std::max(a, b);
+            if (hi - lo < bytes) return BCAST_ERR_ARG;
+        }
+    if (P < 2 || bytes == 0) return BCAST_OK;
+
+    bcast_plan_info_t info;
+    int rc = describe(p, rank_bufs, bytes, &info);
+    if (rc != BCAST_OK) return rc;
+
+    // chain position k is rank (root + k) mod P: no wrap-around back to the root
+    char *by_pos[BCAST_MAX_RANKS];
+    for (int k = 0; k < P; ++k) by_pos[k] = (char *)rank_bufs[(root + k) % P];
+
+    if (info.algo == BCAST_ALGO_CHAIN) {
+        ChainArgs a;
+        memset(&a, 0, sizeof a);
+        memcpy(a.buf, by_pos, sizeof(char *) * P);
+        a.flags = p->d_flags;
+        a.abort_word = p->d_abort;
+        a.status = p->d_status;
+        a.base = (++p->epoch) << 32;
+        a.bytes = bytes;
+        a.chunk_bytes = info.chunk_bytes;
+        a.slice_bytes = round_up(ceil_div(info.chunk_bytes, (u64)info.lanes), 16);
+        a.spin_ticks = p->spin_ticks;
+        a.nchunks = (unsigned)info.nchunks;
+        a.lanes = (unsigned)info.lanes;
+        a.nranks = (unsigned)P;
+        a.mute_hop = (unsigned)p->mute_hop;
+        // the launch must match what the kernel indexes: (P-1)*lanes waves, each with its own flag
+        if ((u64)(P - 1) * a.lanes > (u64)p->max_waves) return BCAST_ERR_ARG;
+        if ((u64)info.grid_blocks * kWavesPerBlock < (u64)(P - 1) * a.lanes) return BCAST_ERR_ARG;
+        if (a.slice_bytes * a.lanes < a.chunk_bytes) return BCAST_ERR_ARG;
+        HIP_TRY(launch_chain(a, info.vec_bytes, info.grid_blocks, stream));
+        return BCAST_OK;
+    }
+
+    CopyArgs c;
+    memset(&c, 0, sizeof c);
+    memcpy(c.buf, by_pos, sizeof(char *) * P);
+    c.nranks = (unsigned)P;
+    c.lo = 0;
+    c.hi = bytes;
+    if (info.algo == BCAST_ALGO_DIRECT) {
+        // a serialized loop of point-to-point sends from the root (Eq. 1)
+        for (int k = 1; k < P; ++k) {
+            c.npairs = 1;
+            c.src_pos[0] = 0;
+            c.dst_pos[0] = (unsigned char)k;
+            HIP_TRY(launch_pair_copy(c, info.vec_bytes, info.grid_blocks, stream));
+        }
+        return BCAST_OK;
+    }
+    if (info.algo == BCAST_ALGO_BINOMIAL) {
+        // round j: every position q < 2^j sends to q + 2^j (Eq. 3, k = 2);
+        // stream order between launches is the round barrier
+        for (int reach = 1; reach < P; reach *= 2) {
+            unsigned n = 0;
+            for (int q = 0; q < reach && q + reach < P; ++q) {
+                c.src_pos[n] = (unsigned char)q;
+                c.dst_pos[n] = (unsigned char)(q + reach);
+                ++n;
+            }
+            c.npairs = n;
+            HIP_TRY(launch_pair_copy(c, info.vec_bytes, copy_grid(p, bytes, (int)n), stream));
+        }
+        return BCAST_OK;
+    }
+    if (info.algo == BCAST_ALGO_FANOUT) {
+        HIP_TRY(launch_fanout(c, info.vec_bytes, info.grid_blocks, stream));
+        return BCAST_OK;
+    }
+    return BCAST_ERR_ARG;
+}
+
+extern "C" const char *bcast_strerror(int status)
+{
+    switch (status) {
+    case BCAST_OK: return "ok";
+    case BCAST_ERR_ARG: return "invalid argument";
+    case BCAST_ERR_NOMEM: return "out of memory";
+    case BCAST_ERR_HIP: return "HIP runtime call failed";
+    case BCAST_ERR_TIMEOUT: return "chain wave gave up waiting for its left neighbour";
+    case BCAST_ERR_UNTUNED: return "no tuning table entry for this number of ranks";
+    default: return "unknown status";
+    }
+}
+
+extern "C" int bcast_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" const char *bcast_version(void) { return "bcast-gfx950 0.1"; }

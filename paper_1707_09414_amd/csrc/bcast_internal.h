@@ -1,0 +1,71 @@
+// Shared declarations between the host side (plan, validation, tuning) and
+// the gfx950 kernels of the broadcast library.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "bcast.h"
+
+namespace bcast {
+
+typedef unsigned long long u64;
+
+// Workgroups are 256 threads = 4 wavefronts of 64; every wavefront is an
+// independent copy engine (no workgroup barriers anywhere in the library).
+constexpr int kBlockThreads = 256;
+constexpr int kWaveSize = 64;
+constexpr int kWavesPerBlock = kBlockThreads / kWaveSize;
+
+// One ready flag per (hop, lane), each alone in a 128-byte line so that a
+// producer's store and other lanes' polls never share a line.
+constexpr int kFlagStrideWords = 16;
+
+// A wavefront moves kUnroll 16-byte vectors per lane per trip: 4 KiB in flight.
+constexpr int kUnroll = 4;
+constexpr u64 kTileBytes = (u64)kWaveSize * 16 * kUnroll;
+
+// Wait limit default: 10 s of the 100 MHz constant clock.
+constexpr u64 kDefaultSpinTicks = 1000000000ull;
+
+// Arguments of the persistent chain kernel (Sec. IV-B).  buf[] is indexed by
+// chain position: buf[0] is the root's buffer, buf[k] receives from buf[k-1].
+struct ChainArgs {
+    char *buf[BCAST_MAX_RANKS];
+    u64 *flags;        // device: [(nranks-1) * lanes] flags, kFlagStrideWords apart
+    u64 *abort_word;   // device: set to the run's epoch when a wave gives up
+    u64 *status;       // pinned host, device-visible: [0] = 1 on timeout, [1] = hop<<32|chunk
+    u64 base;          // epoch << 32; chunk c of this run is ready when flag >= base + c + 1
+    u64 bytes;         // M
+    u64 chunk_bytes;   // C (multiple of 16)
+    u64 slice_bytes;   // bytes of every chunk that one lane owns (multiple of 16)
+    u64 spin_ticks;    // wait limit in 100 MHz ticks
+    unsigned nchunks;
+    unsigned lanes;    // wavefronts per hop
+    unsigned nranks;
+    unsigned mute_hop; // debug: this position never publishes (0 = off)
+};
+
+// Arguments of the plain copy kernels: up to 32 simultaneous (src -> dst)
+// whole-message copies (one binomial round has at most 32 at P = 64; the
+// direct algorithm uses one per launch), or one source and nranks-1
+// destinations for the fan-out.
+struct CopyArgs {
+    char *buf[BCAST_MAX_RANKS]; // by chain position
+    unsigned char src_pos[BCAST_MAX_RANKS / 2];
+    unsigned char dst_pos[BCAST_MAX_RANKS / 2];
+    unsigned npairs;
+    unsigned nranks;
+    u64 lo;   // first byte offset to move
+    u64 hi;   // one past the last byte offset to move
+};
+
+// Launchers implemented in kernels.hip.  vec_bytes is 16, 8, 4 or 1: every
+// buffer address in the call is congruent modulo vec_bytes.
+hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
+hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
+hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
+hipError_t chain_max_blocks_per_cu(int *blocks);
+
+}  // namespace bcast

@@ -1,0 +1,105 @@
+"""Shared helpers for the GPU parity tests: allocate P rank buffers with guard
+bands, run the library through its C ABI (via the ctypes binding), and build the
+expected end state with the CPU oracle on the same seeded inputs."""
+import numpy as np
+import torch
+
+import oracle
+from paper_1707_09414_amd import binding as B
+from paper_1707_09414_amd import inputs
+
+GUARD = 256  # bytes of 0xFF kept before and after every rank buffer
+FILL = inputs.FILL_BYTE
+
+
+class RankBuffers:
+    """P device allocations of GUARD + offset_r + cap + GUARD bytes, all 0xFF;
+    rank r's buffer starts at GUARD + offset_r."""
+
+    def __init__(self, P, cap, offsets=None, device="cuda:0"):
+        self.P = P
+        self.cap = cap
+        self.offsets = list(offsets) if offsets is not None else [0] * P
+        assert len(self.offsets) == P and all(0 <= o < 64 for o in self.offsets)
+        self.total = GUARD + 64 + cap + GUARD
+        self.raw = [torch.full((self.total,), FILL, dtype=torch.uint8, device=device) for _ in range(P)]
+
+    def start(self, r):
+        return GUARD + self.offsets[r]
+
+    def ptrs(self):
+        return [self.raw[r].data_ptr() + self.start(r) for r in range(self.P)]
+
+    def reset(self, root, message):
+        for r in range(self.P):
+            self.raw[r].fill_(FILL)
+        self.set_message(root, message)
+
+    def set_message(self, root, message):
+        m = torch.from_numpy(np.ascontiguousarray(message))
+        self.raw[root][self.start(root): self.start(root) + m.numel()].copy_(m)
+
+    def to_host(self):
+        torch.cuda.synchronize()
+        return [t.cpu().numpy() for t in self.raw]
+
+
+def expected_with_oracle(bufs_host, starts, root, M, schedule):
+    """Apply `schedule` (a function over a [P, M] uint8 array) with the oracle to
+    the message region of each host buffer; everything else must stay as it was."""
+    P = len(bufs_host)
+    region = np.stack([bufs_host[r][starts[r]: starts[r] + M] for r in range(P)]) if M else np.zeros((P, 0), np.uint8)
+    region = np.ascontiguousarray(region)
+    res = schedule(region)
+    exp = [b.copy() for b in bufs_host]
+    for r in range(P):
+        exp[r][starts[r]: starts[r] + M] = region[r]
+    return exp, res
+
+
+def oracle_schedule(algo, P, root, M, C):
+    if algo == B.BCAST_ALGO_CHAIN:
+        return lambda a: oracle.chain_bcast(a, P, root, M, max(1, C))
+    if algo == B.BCAST_ALGO_DIRECT:
+        return lambda a: oracle.direct_bcast(a, P, root, M)
+    if algo == B.BCAST_ALGO_BINOMIAL:
+        return lambda a: oracle.binomial_bcast(a, P, root, M)
+    if algo == B.BCAST_ALGO_FANOUT:
+        # the fan-out has no schedule of its own in the paper: its result is the definition
+        return lambda a: oracle.naive_bcast(a, root, M)
+    raise ValueError(algo)
+
+
+def assert_same(got, exp, what):
+    for r, (g, e) in enumerate(zip(got, exp)):
+        if not np.array_equal(g, e):
+            bad = np.flatnonzero(g != e)
+            raise AssertionError("%s: rank %d differs at %d bytes, first at allocation offset %d (got %d, want %d)"
+                                 % (what, r, bad.size, bad[0], g[bad[0]], e[bad[0]]))
+
+
+def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0, stream=None, plan=None):
+    """One broadcast on the GPU, compared byte for byte (guards included) with
+    the oracle's end state.  Returns the plan info used."""
+    cap = M if cap is None else cap
+    rb = RankBuffers(P, max(cap, 1), offsets)
+    rb.reset(root, message[:M])
+    before = rb.to_host()
+    own = plan is None
+    if own:
+        plan = B.bcast_plan_create(P, cap, C, algo)
+    try:
+        if lanes:
+            B.bcast_plan_set_lanes(plan, lanes)
+        info = B.bcast_plan_info(plan, M, rb.ptrs())
+        B.bcast_run(plan, rb.ptrs(), root, M, stream)
+        got = rb.to_host()
+        st, detail = B.bcast_plan_status(plan)
+        assert st == B.BCAST_OK, "plan status %d detail %x" % (st, detail)
+    finally:
+        if own:
+            plan.destroy()
+    starts = [rb.start(r) for r in range(P)]
+    exp, _ = expected_with_oracle(before, starts, root, M, oracle_schedule(info["algo"], P, root, M, info["chunk_bytes"]))
+    assert_same(got, exp, "P=%d root=%d M=%d C=%d algo=%d offsets=%s" % (P, root, M, C, algo, offsets))
+    return info

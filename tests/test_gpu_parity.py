@@ -1,0 +1,198 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU
+oracle on the same seeded inputs -- byte for byte, guard bands included.
+Integer/byte work: the bar is bit-exact equality, nothing less."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1707_09414_amd import binding as B
+from paper_1707_09414_amd import inputs
+from gpu_harness import RankBuffers, run_and_check, assert_same, expected_with_oracle, oracle_schedule, FILL
+
+pytestmark = pytest.mark.gpu
+
+KiB, MiB = inputs.KiB, inputs.MiB
+ALGOS = [B.BCAST_ALGO_CHAIN, B.BCAST_ALGO_DIRECT, B.BCAST_ALGO_BINOMIAL, B.BCAST_ALGO_FANOUT]
+
+
+@pytest.fixture(scope="module")
+def noise():
+    return inputs.random_bytes(1, 8 * MiB + 64)
+
+
+def test_config1_chain_1mib_p4_c64k():
+    """1 MiB of fp32 uniform[-1,1) from seed 0, P=4, root 0, 64 KiB chunks."""
+    msg = inputs.uniform_fp32_message(0, 262144)
+    assert msg.nbytes == MiB
+    info = run_and_check(4, 0, MiB, 64 * KiB, B.BCAST_ALGO_CHAIN, msg)
+    assert info["nchunks"] == 16 and info["algo"] == B.BCAST_ALGO_CHAIN
+    # the oracle's schedule for this case takes chunks + P - 2 = 18 steps (Eq. 5)
+    assert oracle.chain_bcast(None, 4, 0, MiB, 64 * KiB).steps == 18
+
+
+@pytest.mark.parametrize("P", [2, 3, 8, 17, 64])
+@pytest.mark.parametrize("M,C", [
+    (1, 16), (4, 16), (12, 16), (15, 16), (16, 16), (17, 16), (33, 16), (1000, 112), (4096, 8192),
+    (65536 + 3, 8192), (MiB + 17, 64 * KiB), (5 * MiB + 4096 + 5, 256 * KiB), (3 * MiB, 4 * MiB),
+])
+def test_chain_sizes_and_ranks(noise, P, M, C):
+    run_and_check(P, (5 * P) // 7 % P, M, C, B.BCAST_ALGO_CHAIN, noise)
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("offsets_kind", ["same4", "same1", "mixed4", "mixed1", "mixed8"])
+@pytest.mark.parametrize("M", [5, 16, 4099, 300 * KiB + 7])
+def test_misaligned_pointers(noise, algo, offsets_kind, M):
+    P = 5
+    offsets = {
+        "same4": [4] * P, "same1": [1] * P, "mixed4": [0, 4, 8, 12, 20],
+        "mixed1": [0, 1, 2, 3, 5], "mixed8": [0, 8, 16, 24, 40],
+    }[offsets_kind]
+    info = run_and_check(P, 2, M, 64 * KiB, algo, noise, offsets=offsets)
+    assert info["vec_bytes"] == {"same4": 16, "same1": 16, "mixed4": 4, "mixed1": 1, "mixed8": 8}[offsets_kind]
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("P,root,M", [(2, 1, 100), (4, 3, 70000), (7, 0, 2 * MiB + 1), (9, 4, 12345), (33, 32, 8192), (64, 17, 64 * KiB + 16)])
+def test_every_algorithm_matches_its_oracle_schedule(noise, algo, P, root, M):
+    run_and_check(P, root, M, 32 * KiB, algo, noise)
+
+
+@pytest.mark.parametrize("lanes", [1, 2, 3, 7, 64])
+def test_chain_lane_counts(noise, lanes):
+    """Slices per chunk that do not divide the chunk evenly, including empty ones."""
+    info = run_and_check(6, 1, 200 * KiB + 3, 16 * KiB, B.BCAST_ALGO_CHAIN, noise, lanes=lanes)
+    assert info["lanes"] == lanes
+
+
+def test_degenerate_cases(noise):
+    # one rank, empty message, message shorter than the plan's size
+    for algo in ALGOS:
+        run_and_check(1, 0, 4096, 4096, algo, noise)
+        run_and_check(4, 2, 0, 4096, algo, noise, cap=4096)
+        run_and_check(4, 2, 1000, 4096, algo, noise, cap=1 * MiB)
+
+
+def test_argument_errors_launch_nothing(noise):
+    P, M = 4, 4096
+    rb = RankBuffers(P, M)
+    rb.reset(0, noise[:M])
+    before = rb.to_host()
+    plan = B.bcast_plan_create(P, M, 1024, B.BCAST_ALGO_CHAIN)
+    ptrs = rb.ptrs()
+    assert B.bcast_run_status(plan, ptrs, P, M) == B.BCAST_ERR_ARG        # root out of range
+    assert B.bcast_run_status(plan, ptrs, -1, M) == B.BCAST_ERR_ARG
+    assert B.bcast_run_status(plan, ptrs, 0, M + 1) == B.BCAST_ERR_ARG    # longer than the plan
+    assert B.bcast_run_status(plan, [ptrs[0], ptrs[1], ptrs[1], ptrs[3]], 0, M) == B.BCAST_ERR_ARG  # duplicate
+    assert B.bcast_run_status(plan, [ptrs[0], 0, ptrs[2], ptrs[3]], 0, M) == B.BCAST_ERR_ARG        # NULL
+    assert B.bcast_run_status(plan, [ptrs[0], ptrs[0] + 100, ptrs[2], ptrs[3]], 0, M) == B.BCAST_ERR_ARG  # overlap
+    assert B.bcast_run_status(plan, None, 0, M) == B.BCAST_ERR_ARG
+    assert_same(rb.to_host(), before, "after rejected calls")
+    # AUTO without a table entry
+    B.bcast_tune_clear()
+    auto = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_AUTO)
+    assert B.bcast_run_status(auto, ptrs, 0, M) == B.BCAST_ERR_UNTUNED
+    assert_same(rb.to_host(), before, "after untuned AUTO")
+    auto.destroy()
+    plan.destroy()
+
+
+def test_burst_of_small_broadcasts_reuses_flags(noise):
+    """1000 back-to-back 4 KiB broadcasts at P=64, root 17, a different message
+    each time and no flag reset in between: a stale flag from an earlier run
+    would let a wave forward the previous message."""
+    P, root, M, N = 64, 17, 4 * KiB, 1000
+    msgs = inputs.random_bytes(4, N * M).reshape(N, M)
+    d_msgs = torch.from_numpy(msgs).cuda()
+    rb = RankBuffers(P, M)
+    rb.reset(root, msgs[0])
+    last = (root + P - 1) % P
+    mid = (root + 31) % P
+    out_last = torch.empty((N, M), dtype=torch.uint8, device="cuda")
+    out_mid = torch.empty((N, M), dtype=torch.uint8, device="cuda")
+    plan = B.bcast_plan_create(P, M, 8 * KiB, B.BCAST_ALGO_CHAIN)
+    ptrs = rb.ptrs()
+    s0 = rb.start(root)
+    stream = torch.cuda.current_stream()
+    for i in range(N):
+        rb.raw[root][s0: s0 + M].copy_(d_msgs[i])
+        B.bcast_run(plan, ptrs, root, M, stream)
+        out_last[i].copy_(rb.raw[last][rb.start(last): rb.start(last) + M])
+        out_mid[i].copy_(rb.raw[mid][rb.start(mid): rb.start(mid) + M])
+    torch.cuda.synchronize()
+    assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+    assert np.array_equal(out_last.cpu().numpy(), msgs)
+    assert np.array_equal(out_mid.cpu().numpy(), msgs)
+    got = rb.to_host()
+    for r in range(P):
+        assert np.array_equal(got[r][rb.start(r): rb.start(r) + M], msgs[N - 1]), r
+    plan.destroy()
+
+
+def test_two_plans_alternating_and_moving_root(noise):
+    P, M = 8, 512 * KiB + 48
+    rb = RankBuffers(P, M)
+    plan_a = B.bcast_plan_create(P, M, 32 * KiB, B.BCAST_ALGO_CHAIN)
+    plan_b = B.bcast_plan_create(P, M, 128 * KiB, B.BCAST_ALGO_CHAIN)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for it in range(12):
+            root = (3 * it + 1) % P
+            msg = noise[it * 1000: it * 1000 + M]
+            rb.reset(root, msg)
+            B.bcast_run(plan_a if it % 2 == 0 else plan_b, rb.ptrs(), root, M, stream)
+            stream.synchronize()
+            got = rb.to_host()
+            for r in range(P):
+                assert np.array_equal(got[r][rb.start(r): rb.start(r) + M], msg), (it, r)
+                assert (got[r][: rb.start(r)] == FILL).all() and (got[r][rb.start(r) + M:] == FILL).all()
+    assert B.bcast_plan_status(plan_a)[0] == B.BCAST_OK and B.bcast_plan_status(plan_b)[0] == B.BCAST_OK
+    plan_a.destroy()
+    plan_b.destroy()
+
+
+def test_wait_limit_reports_timeout_and_plan_recovers(noise):
+    """Position 2 never publishes (debug knob) and the wait limit is tiny, so
+    position 3's waves give up: the kernel must still run to completion and the
+    plan must report the timeout, then work again once the knob is off."""
+    P, M = 6, 256 * KiB
+    rb = RankBuffers(P, M)
+    rb.reset(0, noise[:M])
+    plan = B.bcast_plan_create(P, M, 16 * KiB, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_debug(plan, 200000, 2)  # 2 ms of the 100 MHz clock
+    B.bcast_run(plan, rb.ptrs(), 0, M)
+    torch.cuda.synchronize()
+    st, detail = B.bcast_plan_status(plan)
+    assert st == B.BCAST_ERR_TIMEOUT
+    assert detail >> 32 in (3, 4, 5) and (detail & 0xFFFFFFFF) == 0, hex(detail)
+    got = rb.to_host()
+    # positions 1 and 2 were fed normally
+    for r in (1, 2):
+        assert np.array_equal(got[r][rb.start(r): rb.start(r) + M], noise[:M])
+    B.bcast_plan_clear_status(plan)
+    B.bcast_plan_set_debug(plan, 0, 0)
+    rb.reset(0, noise[7: 7 + M])
+    B.bcast_run(plan, rb.ptrs(), 0, M)
+    got = rb.to_host()
+    assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+    for r in range(P):
+        assert np.array_equal(got[r][rb.start(r): rb.start(r) + M], noise[7: 7 + M]), r
+    plan.destroy()
+
+
+def test_tune_then_auto(noise, tmp_path):
+    P = 4
+    B.bcast_tune_clear()
+    path = tmp_path / "tuned.txt"
+    B.bcast_tune(P, 1 * KiB, 2 * MiB, 0, None, str(path))
+    assert B.bcast_tune_count() == 12
+    for M in (1 * KiB, 100 * KiB, 2 * MiB, 3 * MiB + 5, 17):
+        algo, chunk, usec = B.bcast_tune_lookup(P, M)
+        assert algo in (B.BCAST_ALGO_CHAIN, B.BCAST_ALGO_DIRECT, B.BCAST_ALGO_BINOMIAL) and usec > 0
+        info = run_and_check(P, 1, M, 0, B.BCAST_ALGO_AUTO, noise)
+        assert info["algo"] == algo
+    B.bcast_tune_clear()
+    B.bcast_tune_load(str(path))
+    assert B.bcast_tune_count() == 12
+    B.bcast_tune_clear()

@@ -1,0 +1,107 @@
+"""CPU-only checks of the native library's host side: it loads, exports every
+symbol the header declares, rejects bad arguments before touching the GPU, and
+its chain geometry and tuning table behave as documented.  No kernel runs."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1707_09414_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "bcast.h")).read()
+    # strip comments, then collect identifiers followed by '(' at declaration level
+    code = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(bcast_[a-z_0-9]+)\s*\(", code))
+    assert declared, "no declarations found"
+    lib = ctypes.CDLL(str(B.LIB_PATH))
+    for name in sorted(declared):
+        assert hasattr(lib, name), "library does not export %s" % name
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+
+
+def test_strerror_and_version():
+    assert B.bcast_strerror(B.BCAST_OK) == "ok"
+    for code in (B.BCAST_ERR_ARG, B.BCAST_ERR_NOMEM, B.BCAST_ERR_HIP, B.BCAST_ERR_TIMEOUT, B.BCAST_ERR_UNTUNED):
+        assert B.bcast_strerror(code) not in ("ok", "unknown status")
+    assert "gfx950" in B.bcast_version()
+
+
+def test_plan_create_rejects_bad_arguments_without_gpu():
+    for nranks, bytes_, chunk, algo in [(0, 1024, 64, 1), (65, 1024, 64, 1), (4, 1024, 24, 1), (4, 1024, 64, 9), (4, 1024, 64, -1)]:
+        with pytest.raises(B.BcastError) as e:
+            B.bcast_plan_create(nranks, bytes_, chunk, algo)
+        assert e.value.status == B.BCAST_ERR_ARG
+
+
+def test_chain_geometry_matches_eq5_chunking():
+    # 1 MiB in 64 KiB chunks over 4 ranks: 16 chunks (Sec. IV-B)
+    g = B.bcast_chain_geometry(4, 1 << 20, 64 << 10, 4096)
+    assert g["nchunks"] == 16 and g["chunk_bytes"] == 64 << 10
+    assert g["lanes"] * 3 <= 4096 and g["grid_blocks"] * 4 >= g["lanes"] * 3
+    assert g["algorithmic_bytes"] == 2 * 3 * (1 << 20)
+    # ragged tail counts as a chunk
+    assert B.bcast_chain_geometry(3, 1001, 112, 64)["nchunks"] == 9
+    # C >= M is the unpipelined chain: one chunk
+    g = B.bcast_chain_geometry(8, 4096, 1 << 20, 4096)
+    assert g["nchunks"] == 1 and g["chunk_bytes"] == 4096
+    # tiny message
+    g = B.bcast_chain_geometry(64, 4, 8192, 4096)
+    assert g["nchunks"] == 1 and g["lanes"] == 1 and g["grid_blocks"] == 16
+    # lanes never exceed what fits at once, whatever is requested
+    g = B.bcast_chain_geometry(64, 1 << 30, 4 << 20, 2048, lanes_request=1000)
+    assert g["lanes"] == 2048 // 63
+    # no-ops
+    assert B.bcast_chain_geometry(1, 1 << 20, 4096, 64)["nchunks"] == 0
+    assert B.bcast_chain_geometry(4, 0, 4096, 64)["nchunks"] == 0
+    for bad in [(4, 100, 0, 64), (4, 100, 8, 64), (65, 100, 16, 64), (4, 100, 16, 2)]:
+        with pytest.raises(B.BcastError):
+            B.bcast_chain_geometry(*bad)
+
+
+def test_tuning_table_lookup_rules(tmp_path):
+    B.bcast_tune_clear()
+    assert B.bcast_tune_count() == 0
+    with pytest.raises(B.BcastError) as e:
+        B.bcast_tune_lookup(8, 4096)
+    assert e.value.status == B.BCAST_ERR_UNTUNED
+    B.bcast_tune_set(8, 1 << 12, B.BCAST_ALGO_BINOMIAL, 0, 11.0)
+    B.bcast_tune_set(8, 1 << 20, B.BCAST_ALGO_CHAIN, 64 << 10, 50.0)
+    B.bcast_tune_set(16, 1 << 20, B.BCAST_ALGO_DIRECT, 0, 70.0)
+    # same bucket, anywhere inside it
+    assert B.bcast_tune_lookup(8, (1 << 12) + 5)[0] == B.BCAST_ALGO_BINOMIAL
+    # between entries: nearest at or below
+    assert B.bcast_tune_lookup(8, 1 << 19)[0] == B.BCAST_ALGO_BINOMIAL
+    assert B.bcast_tune_lookup(8, 1 << 26) == (B.BCAST_ALGO_CHAIN, 64 << 10, 50.0)
+    # below the smallest entry: nearest above
+    assert B.bcast_tune_lookup(8, 16)[0] == B.BCAST_ALGO_BINOMIAL
+    # other rank counts are separate
+    assert B.bcast_tune_lookup(16, 4)[0] == B.BCAST_ALGO_DIRECT
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_lookup(4, 4096)
+    # chain entries need a valid chunk
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_set(8, 1 << 20, B.BCAST_ALGO_CHAIN, 0)
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_set(8, 1 << 20, 7, 0)
+
+    path = tmp_path / "table.txt"
+    B.bcast_tune_save(str(path))
+    B.bcast_tune_clear()
+    B.bcast_tune_load(str(path))
+    assert B.bcast_tune_count() == 3
+    assert B.bcast_tune_lookup(8, 1 << 20) == (B.BCAST_ALGO_CHAIN, 64 << 10, 50.0)
+
+    bad = tmp_path / "bad.txt"
+    bad.write_text("8 20 1 65536 1.0\n8 21 1 7 1.0\n")
+    B.bcast_tune_clear()
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_load(str(bad))
+    assert B.bcast_tune_count() == 0, "a malformed file must install nothing"
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_load(str(tmp_path / "missing.txt"))
+    B.bcast_tune_clear()
