@@ -62,6 +62,7 @@ typedef struct {
     uint64_t chunk_bytes;  /* chunk size C in use (== bytes when unchunked) */
     uint64_t nchunks;      /* ceil(bytes / C) */
     int lanes;             /* chain: wavefronts per hop, each streaming its own slice of every chunk */
+    uint64_t slice_bytes;  /* chain: bytes of every chunk owned by one lane (lanes * slice_bytes >= chunk_bytes) */
     int grid_blocks;       /* workgroups of the (first) launch */
     int block_threads;     /* threads per workgroup */
     int vec_bytes;         /* widest access usable for these pointers: 16, 8, 4 or 1 */
@@ -136,11 +137,19 @@ int bcast_plan_destroy(bcast_plan_t *plan);
 int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
 int bcast_plan_set_debug(bcast_plan_t *plan, uint64_t spin_limit_ticks, int mute_hop);
 
+/* Chain kernel modes (bit mask).  BCAST_MODE_COUNT: count the hand-offs whose
+ * producer and consumer waves ran on the same XCD (one L2) and on different
+ * XCDs; read back (after a device synchronise) by bcast_plan_handoff_counts.
+ * The counts accumulate over runs.  Diagnostic: it slows the kernel down. */
+#define BCAST_MODE_COUNT 2u
+int bcast_plan_set_mode(bcast_plan_t *plan, unsigned mode);
+int bcast_plan_handoff_counts(bcast_plan_t *plan, uint64_t *same_xcd, uint64_t *cross_xcd);
+
 /*
  * Chain geometry as a pure HOST function (no GPU needed): how a chain of
  * `nranks` ranks moving `bytes` bytes in chunks of `chunk_bytes` is laid over
  * at most `max_waves` co-resident wavefronts.  lanes_request 0 = automatic.
- * Fills nchunks, lanes, grid_blocks, block_threads, chunk_bytes.
+ * Fills nchunks, lanes, slice_bytes, grid_blocks, block_threads, chunk_bytes.
  */
 int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
                          int lanes_request, bcast_plan_info_t *info);

@@ -36,7 +36,8 @@ BCAST_ERR_UNTUNED = -5
 # every symbol include/bcast.h declares
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_debug", "bcast_chain_geometry",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_debug", "bcast_plan_set_mode",
+    "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
 ]
@@ -57,6 +58,7 @@ class PlanInfo(ctypes.Structure):
         ("chunk_bytes", ctypes.c_uint64),
         ("nchunks", ctypes.c_uint64),
         ("lanes", ctypes.c_int),
+        ("slice_bytes", ctypes.c_uint64),
         ("grid_blocks", ctypes.c_int),
         ("block_threads", ctypes.c_int),
         ("vec_bytes", ctypes.c_int),
@@ -86,6 +88,8 @@ def _load():
         "bcast_plan_destroy": ([vp], i),
         "bcast_plan_set_lanes": ([vp, i], i),
         "bcast_plan_set_debug": ([vp, u64, i], i),
+        "bcast_plan_set_mode": ([vp, ctypes.c_uint], i),
+        "bcast_plan_handoff_counts": ([vp, ctypes.POINTER(u64), ctypes.POINTER(u64)], i),
         "bcast_chain_geometry": ([i, sz, sz, i, i, ctypes.POINTER(PlanInfo)], i),
         "bcast_tune": ([i, sz, sz, ctypes.c_uint, vp, ctypes.c_char_p], i),
         "bcast_tune_load": ([ctypes.c_char_p], i),
@@ -200,6 +204,20 @@ def bcast_plan_set_lanes(plan: Plan, lanes: int) -> None:
 
 def bcast_plan_set_debug(plan: Plan, spin_limit_ticks: int, mute_hop: int) -> None:
     _check(_lib.bcast_plan_set_debug(plan.handle, spin_limit_ticks, mute_hop), "bcast_plan_set_debug")
+
+
+BCAST_MODE_COUNT = 2
+
+
+def bcast_plan_set_mode(plan: Plan, mode: int) -> None:
+    _check(_lib.bcast_plan_set_mode(plan.handle, mode), "bcast_plan_set_mode")
+
+
+def bcast_plan_handoff_counts(plan: Plan) -> Tuple[int, int]:
+    """(same-XCD, cross-XCD) chain hand-offs counted so far (needs BCAST_MODE_COUNT)."""
+    a, b = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    _check(_lib.bcast_plan_handoff_counts(plan.handle, ctypes.byref(a), ctypes.byref(b)), "bcast_plan_handoff_counts")
+    return a.value, b.value
 
 
 def bcast_chain_geometry(nranks: int, bytes: int, chunk_bytes: int, max_waves: int, lanes_request: int = 0) -> dict:

@@ -25,6 +25,11 @@ constexpr int kFlagStrideWords = 16;
 // A wavefront moves kUnroll 16-byte vectors per lane per trip: 4 KiB in flight.
 constexpr int kUnroll = 4;
 constexpr u64 kTileBytes = (u64)kWaveSize * 16 * kUnroll;
+// The chain kernel keeps more in flight per wave: its waves also wait on flags.
+#ifndef BCAST_CHAIN_UNROLL
+#define BCAST_CHAIN_UNROLL 8
+#endif
+constexpr int kChainUnroll = BCAST_CHAIN_UNROLL;
 
 // Wait limit default: 10 s of the 100 MHz constant clock.
 constexpr u64 kDefaultSpinTicks = 1000000000ull;
@@ -36,7 +41,8 @@ struct ChainArgs {
     u64 *flags;        // device: [(nranks-1) * lanes] flags, kFlagStrideWords apart
     u64 *abort_word;   // device: set to the run's epoch when a wave gives up
     u64 *status;       // pinned host, device-visible: [0] = 1 on timeout, [1] = hop<<32|chunk
-    u64 base;          // epoch << 32; chunk c of this run is ready when flag >= base + c + 1
+    u64 *counters;     // device: [0] hand-offs within an XCD, [1] across XCDs (kModeCount)
+    u64 base;          // epoch << 32; chunk c of this run is ready when flag >= base + ((c + 1) << 4)
     u64 bytes;         // M
     u64 chunk_bytes;   // C (multiple of 16)
     u64 slice_bytes;   // bytes of every chunk that one lane owns (multiple of 16)
@@ -45,7 +51,14 @@ struct ChainArgs {
     unsigned lanes;    // wavefronts per hop
     unsigned nranks;
     unsigned mute_hop; // debug: this position never publishes (0 = off)
+    unsigned mode;     // kMode* bits
 };
+
+// ChainArgs::mode
+// Count hand-offs whose two waves ran on the same XCD / on different XCDs.
+// Diagnostic only: every wave ends with two atomics on one cache line, which
+// costs tens of microseconds at full occupancy.
+constexpr unsigned kModeCount = 2;
 
 // Arguments of the plain copy kernels: up to 32 simultaneous (src -> dst)
 // whole-message copies (one binomial round has at most 32 at P = 64; the

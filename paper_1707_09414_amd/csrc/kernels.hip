@@ -51,6 +51,86 @@ __device__ __forceinline__ void copy_span(char *__restrict__ dst, const char *__
     if (lane < tail) d[done + lane] = s[done + lane];
 }
 
+// ---------------------------------------------------------------------------
+// Agent-scope coherent accesses for payload that another wavefront, possibly on
+// another XCD (each XCD has its own L2), reads or wrote during the same kernel.
+// On gfx940-class targets the cache-policy bit sc1 marks an access as
+// agent-scope: a load with sc1 is not served from a line that may be stale in
+// this CU's L1 or this XCD's L2, and a store with sc1 is written through, so
+// that once it has completed (vmcnt reaches 0) any sc1 load on the device sees
+// it.  These are the bits the compiler itself emits for relaxed agent-scope
+// atomic loads and stores; the buffer intrinsics let 16-byte payload accesses
+// carry them too.  With every payload access of the chain kernel marked this
+// way there is nothing stale to invalidate and nothing dirty to write back, so
+// the hand-off needs no L2 write-back / invalidate (which cost microseconds
+// per wave and serialise on the L2).
+// ---------------------------------------------------------------------------
+constexpr int kAuxAgent = 16;               // sc1: agent scope
+constexpr int kRsrcWord3 = 0x00020000;      // raw buffer, 32-bit data format
+
+template <int V> struct AgentIO;
+template <> struct AgentIO<16> {
+    typedef VecOf<16>::type T;
+    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, kAuxAgent); }
+    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, kAuxAgent); }
+};
+template <> struct AgentIO<8> {
+    typedef VecOf<8>::type T;
+    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, kAuxAgent); }
+    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b64(v, r, off, 0, kAuxAgent); }
+};
+template <> struct AgentIO<4> {
+    typedef VecOf<4>::type T;
+    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, kAuxAgent); }
+    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b32(v, r, off, 0, kAuxAgent); }
+};
+template <> struct AgentIO<1> {
+    typedef VecOf<1>::type T;
+    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b8(r, off, 0, kAuxAgent); }
+    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b8(v, r, off, 0, kAuxAgent); }
+};
+
+// copy_span with agent-scope accesses.  The span must be shorter than 2 GiB
+// (offsets inside a buffer descriptor are 32-bit); the host guarantees it.
+// The vector body runs a wave-uniform loop of kChainUnroll loads then
+// kChainUnroll stores per lane with no remainder loop: the body's descriptors
+// end exactly at the last whole vector, so a lane whose offset lies beyond it
+// is range-checked by the hardware (the load returns zero, the store is
+// dropped).  A short slice therefore costs one memory round trip, not one per
+// kilobyte.
+template <int V>
+__device__ __forceinline__ void copy_span_agent(char *dst, const char *src, u64 lo, u64 hi, unsigned lane)
+{
+    typedef AgentIO<V> IO;
+    typedef AgentIO<1> IO1;
+    typedef typename IO::T T;
+    const unsigned n = (unsigned)(hi - lo);
+    unsigned head = (V - (unsigned)((uintptr_t)(src + lo) & (V - 1))) & (V - 1);
+    if (head > n) head = n;
+    const unsigned nvec = (n - head) / V;
+    const unsigned body_end = head + nvec * V;
+
+    if (head != 0 || body_end != n) {  // ragged ends: at most V-1 bytes each
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(src + lo), 0, n, kRsrcWord3);
+        const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(dst + lo, 0, n, kRsrcWord3);
+        if (lane < head) IO1::st(IO1::ld(rs, lane), rd, lane);
+        if (lane < n - body_end) IO1::st(IO1::ld(rs, body_end + lane), rd, body_end + lane);
+    }
+    if (nvec == 0) return;
+
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(src + lo), 0, body_end, kRsrcWord3);
+    const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(dst + lo, 0, body_end, kRsrcWord3);
+    const unsigned trip = kChainUnroll * kWaveSize * V;  // bytes per wave per trip
+    unsigned off = head + lane * V;
+    for (unsigned base = head; base < body_end; base += trip, off += trip) {
+        T r[kChainUnroll];
+#pragma unroll
+        for (int u = 0; u < kChainUnroll; ++u) r[u] = IO::ld(rs, off + u * kWaveSize * V);
+#pragma unroll
+        for (int u = 0; u < kChainUnroll; ++u) IO::st(r[u], rd, off + u * kWaveSize * V);
+    }
+}
+
 // Same span, one source, many destinations: each vector is read once and
 // stored to every dst (the one-die fan-out).
 template <int V>
@@ -103,11 +183,13 @@ __device__ __forceinline__ void fanout_span(const CopyArgs &a, u64 lo, u64 hi, u
 //
 // Hand-off protocol.  flag(hop, lane) counts the chunks of this run that
 // position `hop` has stored for `lane`, as base + count with base = epoch<<32;
-// flags only grow, so nothing is reset between runs.  Producer: all lanes'
-// stores are drained and written back (agent-scope release fence, executed by
-// the whole wave so it covers every lane's stores), then lane 0 stores the
-// flag.  Consumer: polls the flag with relaxed agent-scope loads (one address
-// per wave), then an agent-scope acquire fence before touching the payload.
+// flags only grow, so nothing is reset between runs.  Producer: the wave waits
+// until all of its (write-through, agent-scope) payload stores have completed
+// -- one s_waitcnt for the whole wave, so it covers every lane's stores -- and
+// then lane 0 stores the flag (agent scope).  Consumer: polls the flag with
+// agent-scope loads (one address per wave); the payload loads are issued only
+// after a poll has returned the awaited value, and, being agent-scope
+// themselves, cannot be served from a stale cache line.
 //
 // Forward progress.  Wavefronts are numbered hop-major, so a wave only ever
 // waits for a wave with a lower workgroup index; the host also keeps the grid
@@ -126,7 +208,7 @@ __device__ __forceinline__ void report_timeout(const ChainArgs &a, unsigned hop,
 }
 
 __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const ChainArgs &a, unsigned hop,
-                                           unsigned chunk, unsigned lane)
+                                           unsigned chunk, unsigned lane, u64 *seen)
 {
     u64 v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (v < want) {
@@ -147,7 +229,10 @@ __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const Chai
             }
         }
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    // the branch on v has already waited for the poll to return; keep the
+    // compiler from hoisting payload loads above it
+    asm volatile("" ::: "memory");
+    *seen = v;
     return true;
 }
 
@@ -160,6 +245,8 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
     if (gw >= nwaves) return;
     const unsigned hop = gw / a.lanes + 1;  // this wave fills chain position `hop`
     const unsigned s = gw - (hop - 1) * a.lanes;
+    // which XCD (L2 domain) this wave runs on: HW_REG_XCC_ID, bits 3:0
+    const unsigned xcd = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u;
 
     const char *src = a.buf[hop - 1];
     char *dst = a.buf[hop];
@@ -167,6 +254,7 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
     u64 *out_flag = (hop + 1 < a.nranks && hop != a.mute_hop)
                         ? a.flags + ((u64)(hop - 1) * a.lanes + s) * kFlagStrideWords
                         : nullptr;
+    unsigned near = 0, far = 0;  // hand-offs received from the same / another XCD
 
     u64 chunk_lo = 0;
     for (unsigned c = 0; c < a.nchunks; ++c, chunk_lo += a.chunk_bytes) {
@@ -176,13 +264,29 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
         u64 hi = lo + a.slice_bytes;
         if (hi > chunk_hi) hi = chunk_hi;
 
-        if (in_flag && !wait_ready(in_flag, a.base + c + 1, a, hop, c, lane)) return;
-        if (lo < hi) copy_span<V>(dst, src, lo, hi, lane);
-        if (out_flag) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-            if (lane == 0)
-                __hip_atomic_store(out_flag, a.base + c + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // flag value: base + (chunks stored << 4) + producer's XCD
+        bool same_xcd = false;
+        if (in_flag) {
+            u64 seen;
+            if (!wait_ready(in_flag, a.base + ((u64)(c + 1) << 4), a, hop, c, lane, &seen)) return;
+            same_xcd = (unsigned)(seen & 15u) == xcd;
+            near += same_xcd;
+            far += !same_xcd;
         }
+        if (lo < hi) {
+            copy_span_agent<V>(dst, src, lo, hi, lane);
+        }
+        if (out_flag) {
+            // every payload store of this wave has completed (and, being
+            // write-through, is visible device-wide) before the flag is raised
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0)
+                __hip_atomic_store(out_flag, a.base + ((u64)(c + 1) << 4) + xcd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    if ((a.mode & kModeCount) && lane == 0) {
+        __hip_atomic_fetch_add(&a.counters[0], (u64)near, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(&a.counters[1], (u64)far, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 

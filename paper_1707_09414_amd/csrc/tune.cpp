@@ -132,14 +132,14 @@ struct Scratch {
     }
 };
 
-// Average microseconds per run of one candidate: `reps` runs between two
-// events, best of three batches (the first batch doubles as warm-up).
+// Microseconds per run of one candidate.  One timed run warms up and sizes
+// the batches (about 20 ms each, 2..40 runs); the best of three batches counts.
 int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, Scratch &sc, hipStream_t stream, double *usec)
 {
     bcast_plan_t *plan = nullptr;
     int rc = bcast_plan_create(&plan, nranks, bytes, chunk, algo);
     if (rc != BCAST_OK) return rc;
-    const int reps = bytes >= (1u << 20) ? 10 : 40;
+    int reps = 1;
     double best = 1e30;
     for (int batch = 0; batch < 4 && rc == BCAST_OK; ++batch) {
         if (hipEventRecord(sc.e0, stream) != hipSuccess) { rc = BCAST_ERR_HIP; break; }
@@ -148,7 +148,11 @@ int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, Scratch &sc
         if (hipEventRecord(sc.e1, stream) != hipSuccess || hipEventSynchronize(sc.e1) != hipSuccess) { rc = BCAST_ERR_HIP; break; }
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, sc.e0, sc.e1) != hipSuccess) { rc = BCAST_ERR_HIP; break; }
-        if (batch > 0) best = std::min(best, (double)ms * 1000.0 / reps);
+        const double us = (double)ms * 1000.0 / reps;
+        if (batch == 0)
+            reps = (int)std::min(40.0, std::max(2.0, 20000.0 / std::max(us, 1.0)));
+        else
+            best = std::min(best, us);
     }
     if (rc == BCAST_OK && bcast_plan_status(plan, nullptr) != BCAST_OK) rc = BCAST_ERR_TIMEOUT;
     int rd = bcast_plan_destroy(plan);
@@ -193,9 +197,11 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
             if (rc == BCAST_OK && us < best.usec) best = TuneEntry{algo, chunk, us};
         };
         // chain: the whole message as one chunk (Eq. 2), then every power-of-two
-        // chunk size from 8 KiB to 4 MiB that actually splits the message (Eq. 5)
+        // chunk size from 8 KiB to 64 MiB that splits the message into at most
+        // 4096 chunks (Eq. 5); smaller chunks than that only add hand-offs
         consider(BCAST_ALGO_CHAIN, std::max<size_t>(16, (M + 15) / 16 * 16));
-        for (size_t C = 8u << 10; C <= (4u << 20) && C < M; C <<= 1) consider(BCAST_ALGO_CHAIN, C);
+        for (size_t C = 8u << 10; C <= (64u << 20) && C < M; C <<= 1)
+            if (M / C <= 4096) consider(BCAST_ALGO_CHAIN, C);
         consider(BCAST_ALGO_DIRECT, 0);
         consider(BCAST_ALGO_BINOMIAL, 0);
         consider(BCAST_ALGO_FANOUT, 0);

@@ -1,0 +1,48 @@
+"""Measure the tuning table on the GPU in this machine and write it as text.
+
+    python -m paper_1707_09414_amd.tuned.make_table [--out PATH] [--ranks 2,4,8,...]
+                                                    [--min-bytes N] [--max-bytes N] [--with-fanout]
+
+For every rank count it runs ``bcast_tune`` (chain over chunk sizes, direct,
+binomial; the one-die fan-out only on request) over power-of-two message sizes
+and writes the winners.  The file it produces is what ``load_default_table``
+installs.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+import time
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--out", default=os.path.join(os.path.dirname(os.path.abspath(__file__)), "mi355x.txt"))
+    ap.add_argument("--ranks", default="2,4,8,16,32,64")
+    ap.add_argument("--min-bytes", type=int, default=4)
+    ap.add_argument("--max-bytes", type=int, default=1 << 30)
+    ap.add_argument("--with-fanout", action="store_true")
+    args = ap.parse_args()
+
+    import torch  # device context and stream only
+
+    from .. import binding as B
+
+    torch.cuda.set_device(0)
+    mask = (1 << B.BCAST_ALGO_CHAIN) | (1 << B.BCAST_ALGO_DIRECT) | (1 << B.BCAST_ALGO_BINOMIAL)
+    if args.with_fanout:
+        mask |= 1 << B.BCAST_ALGO_FANOUT
+    B.bcast_tune_clear()
+    stream = torch.cuda.current_stream()
+    for P in [int(x) for x in args.ranks.split(",")]:
+        t0 = time.time()
+        B.bcast_tune(P, args.min_bytes, args.max_bytes, mask, stream, None)
+        print("tuned P=%d in %.1f s (%d entries so far)" % (P, time.time() - t0, B.bcast_tune_count()), flush=True)
+    B.bcast_tune_save(args.out)
+    print("wrote", args.out)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -196,3 +196,21 @@ def test_tune_then_auto(noise, tmp_path):
     B.bcast_tune_load(str(path))
     assert B.bcast_tune_count() == 12
     B.bcast_tune_clear()
+
+
+def test_handoff_counts_and_xcd_placement(noise):
+    """Every wave of positions 2..P-1 receives each chunk through one flag
+    hand-off; the diagnostic counters must account for all of them."""
+    P, M, C, lanes = 8, 2 * MiB, 256 * KiB, 32
+    rb = RankBuffers(P, M)
+    rb.reset(0, noise[:M])
+    plan = B.bcast_plan_create(P, M, C, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_lanes(plan, lanes)
+    B.bcast_plan_set_mode(plan, B.BCAST_MODE_COUNT)
+    B.bcast_run(plan, rb.ptrs(), 0, M)
+    near, far = B.bcast_plan_handoff_counts(plan)
+    assert near + far == (P - 2) * lanes * (M // C)
+    got = rb.to_host()
+    for r in range(P):
+        assert np.array_equal(got[r][rb.start(r): rb.start(r) + M], noise[:M])
+    plan.destroy()
