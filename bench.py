@@ -40,9 +40,11 @@ WORKLOADS = {
 MEASURED_TRAFFIC_BYTES = {}
 
 
-def make_message(name, seed, nbytes):
+def make_message(name, seed, nbytes, custom=False):
     from paper_1707_09414_amd import inputs
 
+    if custom:
+        return inputs.random_bytes(seed, nbytes)
     if name == "cfg1":
         return inputs.uniform_fp32_message(seed, nbytes // 4)
     if name == "cfg3":
@@ -59,6 +61,8 @@ def main() -> int:
     ap.add_argument("--algo", default="chain", choices=["chain", "direct", "binomial", "fanout", "auto"])
     ap.add_argument("--chunk", type=int, default=0, help="chain chunk bytes (0 = tuned table / built-in rule)")
     ap.add_argument("--lanes", type=int, default=0, help="wavefronts per chain hop (0 = automatic)")
+    ap.add_argument("--ranks", type=int, default=0, help="override the workload's P (experiments)")
+    ap.add_argument("--bytes", type=int, default=0, help="override the workload's message size (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true")
     args = ap.parse_args()
@@ -80,12 +84,17 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     P, root, M, seed, what = WORKLOADS[args.workload]
+    if args.ranks or args.bytes:
+        P = args.ranks or P
+        M = args.bytes or M
+        root = root % P
+        what = "custom: %d random bytes, P=%d" % (M, P)
     algo = {"chain": B.BCAST_ALGO_CHAIN, "direct": B.BCAST_ALGO_DIRECT, "binomial": B.BCAST_ALGO_BINOMIAL,
             "fanout": B.BCAST_ALGO_FANOUT, "auto": B.BCAST_ALGO_AUTO}[args.algo]
 
     table = tuned.load_default_table()  # installs the shipped MI355X table if present
 
-    msg = make_message(args.workload, seed, M)
+    msg = make_message(args.workload, seed, M, custom=bool(args.ranks or args.bytes))
     assert msg.nbytes == M
     d_msg = torch.from_numpy(msg).cuda()
     bufs = []

@@ -62,7 +62,7 @@ typedef struct {
     uint64_t chunk_bytes;  /* chunk size C in use (== bytes when unchunked) */
     uint64_t nchunks;      /* ceil(bytes / C) */
     int lanes;             /* chain: wavefronts per hop, each streaming its own slice of every chunk */
-    uint64_t slice_bytes;  /* chain: bytes of every chunk owned by one lane (lanes * slice_bytes >= chunk_bytes) */
+    uint64_t slice_bytes;  /* chain: bytes of every chunk owned by one lane, in 8 KiB trips dealt round-robin over the lanes */
     int grid_blocks;       /* workgroups of the (first) launch */
     int block_threads;     /* threads per workgroup */
     int vec_bytes;         /* widest access usable for these pointers: 16, 8, 4 or 1 */
@@ -176,6 +176,11 @@ int bcast_tune_set(int nranks, size_t bytes, int algo, size_t chunk_bytes, doubl
 /* Nearest entry for nranks at or below log2(bytes), else the nearest above.
  * usec (nullable) = the time measured when the entry was made, 0 if unknown. */
 int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *chunk_bytes, double *usec);
+/* The table also keeps, per entry, the best chunk size found for the chain even
+ * where another algorithm won; a CHAIN plan with chunk_bytes == 0 uses it.
+ * bcast_tune_set_chain needs the entry to exist (bcast_tune_set first). */
+int bcast_tune_set_chain(int nranks, size_t bytes, size_t chunk_bytes, double usec);
+int bcast_tune_lookup_chain(int nranks, size_t bytes, size_t *chunk_bytes, double *usec);
 int bcast_tune_count(void);
 
 const char *bcast_strerror(int status);

@@ -39,7 +39,7 @@ EXPORTS = [
     "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_debug", "bcast_plan_set_mode",
     "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
-    "bcast_tune_lookup", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
+    "bcast_tune_lookup", "bcast_tune_set_chain", "bcast_tune_lookup_chain", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
 ]
 
 
@@ -97,6 +97,8 @@ def _load():
         "bcast_tune_clear": ([], i),
         "bcast_tune_set": ([i, sz, i, sz, ctypes.c_double], i),
         "bcast_tune_lookup": ([i, sz, ctypes.POINTER(i), ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_double)], i),
+        "bcast_tune_set_chain": ([i, sz, sz, ctypes.c_double], i),
+        "bcast_tune_lookup_chain": ([i, sz, ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_double)], i),
         "bcast_tune_count": ([], i),
         "bcast_strerror": ([i], ctypes.c_char_p),
         "bcast_last_hip_error": ([], i),
@@ -254,6 +256,17 @@ def bcast_tune_lookup(nranks: int, bytes: int) -> Tuple[int, int, float]:
     a, c, u = ctypes.c_int(0), ctypes.c_size_t(0), ctypes.c_double(0.0)
     _check(_lib.bcast_tune_lookup(nranks, bytes, ctypes.byref(a), ctypes.byref(c), ctypes.byref(u)), "bcast_tune_lookup")
     return a.value, c.value, u.value
+
+
+def bcast_tune_set_chain(nranks: int, bytes: int, chunk_bytes: int, usec: float = 0.0) -> None:
+    _check(_lib.bcast_tune_set_chain(nranks, bytes, chunk_bytes, usec), "bcast_tune_set_chain")
+
+
+def bcast_tune_lookup_chain(nranks: int, bytes: int) -> Tuple[int, float]:
+    """(chunk_bytes, usec): the best chain chunk size measured for this bucket."""
+    c, u = ctypes.c_size_t(0), ctypes.c_double(0.0)
+    _check(_lib.bcast_tune_lookup_chain(nranks, bytes, ctypes.byref(c), ctypes.byref(u)), "bcast_tune_lookup_chain")
+    return c.value, u.value
 
 
 def bcast_tune_count() -> int:

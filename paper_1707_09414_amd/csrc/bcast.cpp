@@ -53,7 +53,7 @@ static u64 round_up(u64 a, u64 b) { return ceil_div(a, b) * b; }
 // A lane (one wavefront per hop) is fed well by 16 KiB of every chunk: two
 // trips of its copy loop per hand-off.  8 KiB is the least worth a lane.
 constexpr u64 kSliceTarget = 16 * 1024;
-constexpr u64 kSliceMin = 8 * 1024;
+constexpr u64 kSliceMin = (u64)kChainUnroll * kWaveSize * 16;  // one trip
 
 // Chunk size when the caller gives none and no tuning entry applies.  On one
 // die every hop shares the same HBM, so Eq. 5's fill term (n - 2 idle links)
@@ -102,11 +102,9 @@ extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes
     u64 lanes = lanes_request > 0 ? std::min<u64>((u64)lanes_request, (u64)(max_waves / hops))
                                   : shape(std::min(useful, lanes_max));
     lanes = std::max<u64>(1, lanes);
-    // slices are whole kilobytes (one vector instruction of a wave) when the
-    // chunk is big enough, so that neighbouring lanes never share a cache line
-    u64 slice = ceil_div(C, lanes);
-    slice = round_up(slice, slice >= 1024 ? 1024 : 16);
-    info->slice_bytes = slice;
+    // a lane takes every lanes-th 8 KiB trip of a chunk
+    const u64 trip = (u64)kChainUnroll * kWaveSize * 16;
+    info->slice_bytes = ceil_div(C, lanes * trip) * trip;
     info->chunk_bytes = C;
     info->nchunks = nchunks;
     info->lanes = (int)lanes;
@@ -262,10 +260,8 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
         r->algo = algo;
         if (r->chunk == 0) r->chunk = chunk;
     } else if (p->algo == BCAST_ALGO_CHAIN && r->chunk == 0) {
-        int algo = 0;
         size_t chunk = 0;
-        if (bcast_tune_lookup(p->nranks, bytes, &algo, &chunk, nullptr) == BCAST_OK && algo == BCAST_ALGO_CHAIN)
-            r->chunk = chunk;
+        if (bcast_tune_lookup_chain(p->nranks, bytes, &chunk, nullptr) == BCAST_OK) r->chunk = chunk;
     }
     if (r->algo == BCAST_ALGO_CHAIN) {
         if (r->chunk == 0) r->chunk = default_chunk(p->nranks, p->max_waves);
@@ -371,7 +367,6 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         a.base = (++p->epoch) << 32;
         a.bytes = bytes;
         a.chunk_bytes = info.chunk_bytes;
-        a.slice_bytes = info.slice_bytes;
         a.spin_ticks = p->spin_ticks;
         a.nchunks = (unsigned)info.nchunks;
         a.lanes = (unsigned)info.lanes;
@@ -380,9 +375,8 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         // the launch must match what the kernel indexes: (P-1)*lanes waves, each with its own flag
         if ((u64)(P - 1) * a.lanes > (u64)p->max_waves) return BCAST_ERR_ARG;
         if ((u64)info.grid_blocks * kWavesPerBlock < (u64)(P - 1) * a.lanes) return BCAST_ERR_ARG;
-        if (a.slice_bytes * a.lanes < a.chunk_bytes) return BCAST_ERR_ARG;
-        if (a.slice_bytes >= (1ull << 31)) return BCAST_ERR_ARG;  // a wave addresses its slice with 32-bit offsets
-        if (a.nchunks == 0 || a.lanes == 0 || a.slice_bytes == 0 || a.chunk_bytes == 0) return BCAST_ERR_ARG;
+        if (a.nchunks == 0 || a.lanes == 0 || a.chunk_bytes == 0) return BCAST_ERR_ARG;
+        if ((u64)a.nchunks * a.chunk_bytes < a.bytes) return BCAST_ERR_ARG;
         HIP_TRY(launch_chain(a, info.vec_bytes, info.grid_blocks, stream));
         return BCAST_OK;
     }

@@ -45,7 +45,6 @@ struct ChainArgs {
     u64 base;          // epoch << 32; chunk c of this run is ready when flag >= base + ((c + 1) << 4)
     u64 bytes;         // M
     u64 chunk_bytes;   // C (multiple of 16)
-    u64 slice_bytes;   // bytes of every chunk that one lane owns (multiple of 16)
     u64 spin_ticks;    // wait limit in 100 MHz ticks
     unsigned nchunks;
     unsigned lanes;    // wavefronts per hop

@@ -90,9 +90,9 @@ template <> struct AgentIO<1> {
     static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b8(v, r, off, 0, kAuxAgent); }
 };
 
-// copy_span with agent-scope accesses.  The span must be shorter than 2 GiB
-// (offsets inside a buffer descriptor are 32-bit); the host guarantees it.
-// The vector body runs a wave-uniform loop of kChainUnroll loads then
+// copy_span with agent-scope accesses for a span of at most a few trips (the
+// chain kernel passes one trip at a time; offsets inside a buffer descriptor
+// are 32-bit).  The vector body runs a wave-uniform loop of kChainUnroll loads then
 // kChainUnroll stores per lane with no remainder loop: the body's descriptors
 // end exactly at the last whole vector, so a lane whose offset lies beyond it
 // is range-checked by the hardware (the load returns zero, the store is
@@ -207,21 +207,33 @@ __device__ __forceinline__ void report_timeout(const ChainArgs &a, unsigned hop,
     }
 }
 
+// One agent-scope read of a flag for the whole wave: only lane 0 issues the
+// load (64 lanes reading one address still cost one request per group of
+// lanes, and a device full of polling waves then eats a large share of the
+// memory system's request rate), the value is broadcast through an SGPR.
+__device__ __forceinline__ u64 read_flag(const u64 *flag, unsigned lane)
+{
+    u64 v = 0;
+    if (lane == 0) v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return ((u64)hi << 32) | lo;
+}
+
 __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const ChainArgs &a, unsigned hop,
                                            unsigned chunk, unsigned lane, u64 *seen)
 {
-    u64 v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    u64 v = read_flag(flag, lane);
     if (v < want) {
         const u64 t0 = wall_clock64();
         const u64 epoch = a.base >> 32;
         unsigned spins = 0;
         for (;;) {
-            __builtin_amdgcn_s_sleep(1);
-            v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_s_sleep(2);
+            v = read_flag(flag, lane);
             if (v >= want) break;
             if ((++spins & 31u) == 0) {
-                if (__hip_atomic_load(a.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= epoch)
-                    return false;
+                if (read_flag(a.abort_word, lane) >= epoch) return false;
                 if (wall_clock64() - t0 > a.spin_ticks) {
                     if (lane == 0) report_timeout(a, hop, chunk);
                     return false;
@@ -256,26 +268,35 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
                         : nullptr;
     unsigned near = 0, far = 0;  // hand-offs received from the same / another XCD
 
+    // A lane's share of a chunk is every lanes-th trip (one trip = kChainUnroll
+    // vector instructions of the wave, 8 KiB at 16 bytes per lane), so at any
+    // moment the lanes of a hop sweep one contiguous window of the chunk: DRAM
+    // sees a few wide streams per hop, not one narrow stream per wave.
+    const u64 trip = (u64)kChainUnroll * kWaveSize * V;
+    const u64 stride = trip * a.lanes;
+
+    u64 seen = 0;  // newest value read from in_flag
     u64 chunk_lo = 0;
     for (unsigned c = 0; c < a.nchunks; ++c, chunk_lo += a.chunk_bytes) {
         u64 chunk_hi = chunk_lo + a.chunk_bytes;
         if (chunk_hi > a.bytes) chunk_hi = a.bytes;
-        u64 lo = chunk_lo + (u64)s * a.slice_bytes;
-        u64 hi = lo + a.slice_bytes;
-        if (hi > chunk_hi) hi = chunk_hi;
 
         // flag value: base + (chunks stored << 4) + producer's XCD
-        bool same_xcd = false;
         if (in_flag) {
-            u64 seen;
-            if (!wait_ready(in_flag, a.base + ((u64)(c + 1) << 4), a, hop, c, lane, &seen)) return;
-            same_xcd = (unsigned)(seen & 15u) == xcd;
+            const u64 want = a.base + ((u64)(c + 1) << 4);
+            if (seen < want && !wait_ready(in_flag, want, a, hop, c, lane, &seen)) return;
+            const bool same_xcd = (unsigned)(seen & 15u) == xcd;
             near += same_xcd;
             far += !same_xcd;
         }
-        if (lo < hi) {
+        for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
+            const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
             copy_span_agent<V>(dst, src, lo, hi, lane);
         }
+        // Look at the next chunk's flag while this chunk's stores drain: in
+        // steady state the left neighbour is ahead and the next wait is free.
+        if (in_flag && c + 1 < a.nchunks)
+            seen = read_flag(in_flag, lane);
         if (out_flag) {
             // every payload store of this wave has completed (and, being
             // write-through, is visible device-wide) before the flag is raised

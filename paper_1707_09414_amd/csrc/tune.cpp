@@ -48,23 +48,47 @@ extern "C" int bcast_tune_set(int nranks, size_t bytes, int algo, size_t chunk_b
     if (nranks < 1 || nranks > BCAST_MAX_RANKS || !valid_algo(algo) || bytes == 0) return BCAST_ERR_ARG;
     if (algo == BCAST_ALGO_CHAIN && (chunk_bytes == 0 || chunk_bytes % 16 != 0)) return BCAST_ERR_ARG;
     std::lock_guard<std::mutex> g(g_mu);
-    g_table[{nranks, log2_bucket(bytes)}] = TuneEntry{algo, chunk_bytes, usec};
+    TuneEntry &e = g_table[{nranks, log2_bucket(bytes)}];
+    e.algo = algo;
+    e.chunk_bytes = chunk_bytes;
+    e.usec = usec;
+    if (algo == BCAST_ALGO_CHAIN) {
+        e.chain_chunk = chunk_bytes;
+        e.chain_usec = usec;
+    }
     return BCAST_OK;
+}
+
+extern "C" int bcast_tune_set_chain(int nranks, size_t bytes, size_t chunk_bytes, double usec)
+{
+    if (nranks < 1 || nranks > BCAST_MAX_RANKS || bytes == 0 || chunk_bytes == 0 || chunk_bytes % 16 != 0) return BCAST_ERR_ARG;
+    std::lock_guard<std::mutex> g(g_mu);
+    auto it = g_table.find({nranks, log2_bucket(bytes)});
+    if (it == g_table.end()) return BCAST_ERR_UNTUNED;  // the bucket's winner must be set first
+    it->second.chain_chunk = chunk_bytes;
+    it->second.chain_usec = usec;
+    return BCAST_OK;
+}
+
+// nearest bucket at or below, else the nearest above, among this nranks' entries
+// (caller holds g_mu)
+static const TuneEntry *nearest(int nranks, size_t bytes)
+{
+    const int want = log2_bucket(bytes);
+    auto it = g_table.upper_bound({nranks, want});
+    if (it != g_table.begin()) {
+        auto below = std::prev(it);
+        if (below->first.first == nranks) return &below->second;
+    }
+    if (it != g_table.end() && it->first.first == nranks) return &it->second;
+    return nullptr;
 }
 
 extern "C" int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *chunk_bytes, double *usec)
 {
     if (!algo || !chunk_bytes || nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
     std::lock_guard<std::mutex> g(g_mu);
-    const int want = log2_bucket(bytes);
-    // nearest bucket at or below, else the nearest above, among this nranks' entries
-    const TuneEntry *best = nullptr;
-    auto it = g_table.upper_bound({nranks, want});
-    if (it != g_table.begin()) {
-        auto below = std::prev(it);
-        if (below->first.first == nranks) best = &below->second;
-    }
-    if (!best && it != g_table.end() && it->first.first == nranks) best = &it->second;
+    const TuneEntry *best = nearest(nranks, bytes);
     if (!best) return BCAST_ERR_UNTUNED;
     *algo = best->algo;
     *chunk_bytes = best->chunk_bytes;
@@ -72,18 +96,33 @@ extern "C" int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *ch
     return BCAST_OK;
 }
 
-// Text format, one entry per line:  nranks log2_bytes algo chunk_bytes usec
+extern "C" int bcast_tune_lookup_chain(int nranks, size_t bytes, size_t *chunk_bytes, double *usec)
+{
+    if (!chunk_bytes || nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
+    std::lock_guard<std::mutex> g(g_mu);
+    const TuneEntry *best = nearest(nranks, bytes);
+    if (!best || best->chain_chunk == 0) return BCAST_ERR_UNTUNED;
+    *chunk_bytes = best->chain_chunk;
+    if (usec) *usec = best->chain_usec;
+    return BCAST_OK;
+}
+
+// Text format, one entry per line:
+//   nranks log2_bytes algo chunk_bytes usec [chain_chunk_bytes chain_usec]
 // Lines starting with '#' are comments.
+static const char kHeaderLine[] =
+    "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout) chunk_bytes usec chain_chunk_bytes chain_usec\n";
+
 extern "C" int bcast_tune_save(const char *path)
 {
     if (!path) return BCAST_ERR_ARG;
     FILE *f = fopen(path, "w");
     if (!f) return BCAST_ERR_ARG;
-    fprintf(f, "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout) chunk_bytes usec\n");
+    fprintf(f, "%s", kHeaderLine);
     std::lock_guard<std::mutex> g(g_mu);
     for (const auto &kv : g_table)
-        fprintf(f, "%d %d %d %zu %.3f\n", kv.first.first, kv.first.second, kv.second.algo,
-                kv.second.chunk_bytes, kv.second.usec);
+        fprintf(f, "%d %d %d %zu %.3f %zu %.3f\n", kv.first.first, kv.first.second, kv.second.algo,
+                kv.second.chunk_bytes, kv.second.usec, kv.second.chain_chunk, kv.second.chain_usec);
     fclose(f);
     return BCAST_OK;
 }
@@ -101,15 +140,16 @@ extern "C" int bcast_tune_load(const char *path)
         while (*s == ' ' || *s == '\t') ++s;
         if (*s == '#' || *s == '\n' || *s == '\0') continue;
         int nranks, bucket, algo;
-        unsigned long long chunk;
-        double usec = 0.0;
-        int got = sscanf(s, "%d %d %d %llu %lf", &nranks, &bucket, &algo, &chunk, &usec);
+        unsigned long long chunk, cchunk = 0;
+        double usec = 0.0, cusec = 0.0;
+        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf", &nranks, &bucket, &algo, &chunk, &usec, &cchunk, &cusec);
         if (got < 4 || nranks < 1 || nranks > BCAST_MAX_RANKS || bucket < 0 || bucket > 62 || !valid_algo(algo) ||
-            (algo == BCAST_ALGO_CHAIN && (chunk == 0 || chunk % 16 != 0))) {
+            (algo == BCAST_ALGO_CHAIN && (chunk == 0 || chunk % 16 != 0)) || cchunk % 16 != 0) {
             rc = BCAST_ERR_ARG;
             break;
         }
-        rows.push_back({{nranks, bucket}, TuneEntry{algo, (size_t)chunk, usec}});
+        if (algo == BCAST_ALGO_CHAIN && cchunk == 0) { cchunk = chunk; cusec = usec; }
+        rows.push_back({{nranks, bucket}, TuneEntry{algo, (size_t)chunk, usec, (size_t)cchunk, cusec}});
     }
     fclose(f);
     if (rc != BCAST_OK) return rc;  // a malformed file installs nothing
@@ -182,19 +222,28 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
     if (table_path) {
         f = fopen(table_path, "a");
         if (!f) return BCAST_ERR_ARG;
-        fprintf(f, "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout) chunk_bytes usec\n");
+        fprintf(f, "%s", kHeaderLine);
     }
 
     int rc = BCAST_OK;
     size_t M = (size_t)1 << log2_bucket(min_bytes);
     if (M < min_bytes) M <<= 1;
     for (; M <= max_bytes && rc == BCAST_OK; M <<= 1) {
-        TuneEntry best{0, 0, 1e30};
+        TuneEntry best{0, 0, 1e30, 0, 1e30};
         auto consider = [&](int algo, size_t chunk) {
             if (rc != BCAST_OK || !(algo_mask & (1u << algo))) return;
             double us = 0.0;
             rc = time_candidate(nranks, M, algo, chunk, sc, stream, &us);
-            if (rc == BCAST_OK && us < best.usec) best = TuneEntry{algo, chunk, us};
+            if (rc != BCAST_OK) return;
+            if (algo == BCAST_ALGO_CHAIN && us < best.chain_usec) {
+                best.chain_chunk = chunk;
+                best.chain_usec = us;
+            }
+            if (us < best.usec) {
+                best.algo = algo;
+                best.chunk_bytes = chunk;
+                best.usec = us;
+            }
         };
         // chain: the whole message as one chunk (Eq. 2), then every power-of-two
         // chunk size from 8 KiB to 64 MiB that splits the message into at most
@@ -207,7 +256,9 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         consider(BCAST_ALGO_FANOUT, 0);
         if (rc != BCAST_OK) break;
         rc = bcast_tune_set(nranks, M, best.algo, best.chunk_bytes, best.usec);
-        if (f) fprintf(f, "%d %d %d %zu %.3f\n", nranks, log2_bucket(M), best.algo, best.chunk_bytes, best.usec);
+        if (rc == BCAST_OK && best.chain_chunk) rc = bcast_tune_set_chain(nranks, M, best.chain_chunk, best.chain_usec);
+        if (f) fprintf(f, "%d %d %d %zu %.3f %zu %.3f\n", nranks, log2_bucket(M), best.algo, best.chunk_bytes, best.usec,
+                       best.chain_chunk, best.chain_chunk ? best.chain_usec : 0.0);
         if (M > (max_bytes >> 1)) break;  // next doubling would overflow or pass max
     }
     if (f) fclose(f);

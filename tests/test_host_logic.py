@@ -89,12 +89,28 @@ def test_tuning_table_lookup_rules(tmp_path):
     with pytest.raises(B.BcastError):
         B.bcast_tune_set(8, 1 << 20, 7, 0)
 
+    # the chain's own best chunk is kept beside the winner
+    assert B.bcast_tune_lookup_chain(8, 1 << 20) == (64 << 10, 50.0)
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_lookup_chain(16, 1 << 20)  # direct won there and no chain chunk is recorded
+    B.bcast_tune_set_chain(16, 1 << 20, 128 << 10, 90.0)
+    assert B.bcast_tune_lookup_chain(16, 1 << 21) == (128 << 10, 90.0)
+    assert B.bcast_tune_lookup(16, 1 << 20)[0] == B.BCAST_ALGO_DIRECT
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_set_chain(32, 1 << 20, 128 << 10, 90.0)  # no such entry yet
+
     path = tmp_path / "table.txt"
     B.bcast_tune_save(str(path))
     B.bcast_tune_clear()
     B.bcast_tune_load(str(path))
     assert B.bcast_tune_count() == 3
     assert B.bcast_tune_lookup(8, 1 << 20) == (B.BCAST_ALGO_CHAIN, 64 << 10, 50.0)
+    assert B.bcast_tune_lookup_chain(16, 1 << 20) == (128 << 10, 90.0)
+    # the older five-column format still loads
+    old = tmp_path / "old.txt"
+    old.write_text("4 20 1 65536 12.5\n4 10 3 0 5.0\n")
+    B.bcast_tune_load(str(old))
+    assert B.bcast_tune_lookup_chain(4, 1 << 20) == (65536, 12.5)
 
     bad = tmp_path / "bad.txt"
     bad.write_text("8 20 1 65536 1.0\n8 21 1 7 1.0\n")
