@@ -35,9 +35,16 @@ WORKLOADS = {
     "cfg5": (64, 17, 1 * GiB, 4, "1 GiB random bytes, P=64, root 17"),
 }
 
-# HBM traffic per launch of the chain kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM traffic per launch of the dominant kernel, measured with rocprofv3 --pmc
+# FETCH_SIZE and --pmc WRITE_SIZE (KiB per dispatch; summaries under profiles/).
+# FETCH_SIZE is scaled by the factor a plain copy of known size shows in the same
+# run (a 64 MiB copy reads 32786.9 KiB on the counter: factor 1.999); WRITE_SIZE
+# reads the true size (factor 1.000).  Workloads without a profile report null.
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg2", "chain"): int((232620.7 * (65536.0 / 32786.9) + 460288.0) * 1024),
+    ("cfg2", "direct"): int((32784.5 * (65536.0 / 32786.9) + 65536.0) * 1024),
+    ("cfg4", "chain"): int((8148345.0 * (524288.0 / 262167.1) + 16260608.0) * 1024),
+}
 
 
 def make_message(name, seed, nbytes, custom=False):
@@ -151,7 +158,8 @@ def main() -> int:
     algorithmic = int(info["algorithmic_bytes"])
     value = algorithmic / (wall_ms * 1e-3) / 1e9
     achieved = algorithmic / (avg_launch_ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo))
+    custom = bool(args.ranks or args.bytes or args.chunk or args.lanes)
+    traffic = None if custom else MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo))
 
     cpu = None
     if not args.no_cpu_baseline:
