@@ -61,7 +61,9 @@ typedef struct {
     int algo;              /* resolved bcast_algo_t (never AUTO) */
     uint64_t chunk_bytes;  /* chunk size C in use (== bytes when unchunked) */
     uint64_t nchunks;      /* ceil(bytes / C) */
-    int lanes;             /* chain: wavefronts per hop, each streaming its own slice of every chunk */
+    int stages;            /* chain: groups of consecutive hops; each stage has its own wavefronts and flags */
+    int hops_per_stage;    /* chain: hops a stage's wavefront plays one after the other (1 = a stage per rank) */
+    int lanes;             /* chain: wavefronts per stage, each streaming its own share of every chunk */
     uint64_t slice_bytes;  /* chain: bytes of every chunk owned by one lane, in 8 KiB trips dealt round-robin over the lanes */
     int grid_blocks;       /* workgroups of the (first) launch */
     int block_threads;     /* threads per workgroup */
@@ -129,12 +131,16 @@ int bcast_plan_info(bcast_plan_t *plan, void *const *rank_bufs, size_t bytes, bc
 /* bcast_plan_destroy -- waits for the device, then frees the plan's memory. */
 int bcast_plan_destroy(bcast_plan_t *plan);
 
-/* Knobs for experiments and tests.  lanes: wavefronts per chain hop (0 =
- * automatic).  spin_limit_ticks: wait limit in 100 MHz ticks (0 = default,
+/* Knobs for experiments and tests.  lanes: wavefronts per chain stage (0 =
+ * automatic).  stages: how many groups of consecutive hops get wavefronts of
+ * their own (0 = automatic; nranks-1 = one stage per receiving rank; fewer =
+ * a wavefront plays several consecutive ranks in turn, re-reading from each
+ * rank's buffer what it stored there, and flags are only used between stages).  spin_limit_ticks: wait limit in 100 MHz ticks (0 = default,
  * about 10 s).  mute_hop: chain position (1..P-2) that stores its chunks but
  * never publishes them, so that its right neighbour runs into the wait limit;
  * 0 = off.  Kernels always run to completion under these settings. */
 int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
+int bcast_plan_set_stages(bcast_plan_t *plan, int stages);
 int bcast_plan_set_debug(bcast_plan_t *plan, uint64_t spin_limit_ticks, int mute_hop);
 
 /* Chain kernel modes (bit mask).  BCAST_MODE_COUNT: count the hand-offs whose
@@ -148,11 +154,11 @@ int bcast_plan_handoff_counts(bcast_plan_t *plan, uint64_t *same_xcd, uint64_t *
 /*
  * Chain geometry as a pure HOST function (no GPU needed): how a chain of
  * `nranks` ranks moving `bytes` bytes in chunks of `chunk_bytes` is laid over
- * at most `max_waves` co-resident wavefronts.  lanes_request 0 = automatic.
- * Fills nchunks, lanes, slice_bytes, grid_blocks, block_threads, chunk_bytes.
+ * at most `max_waves` co-resident wavefronts.  lanes_request, stages_request:
+ * 0 = automatic.  Fills nchunks, stages, hops_per_stage, lanes, slice_bytes, grid_blocks, block_threads, chunk_bytes.
  */
 int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
-                         int lanes_request, bcast_plan_info_t *info);
+                         int lanes_request, int stages_request, bcast_plan_info_t *info);
 
 /*
  * Tuning table (Sec. III-B "Discussion" and IV-B last paragraph: algorithm and
@@ -160,27 +166,42 @@ int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_w
  * measurements).  Process-wide; entries are keyed by (nranks, floor(log2 bytes)).
  *
  * bcast_tune measures, on the current device and `stream`, every candidate
- * (chain at chunk sizes 8 KiB..4 MiB, direct, binomial, and -- only if
- * `algo_mask` has their bits -- the others) for message sizes that are powers
- * of two in [min_bytes, max_bytes], keeps the fastest per size, installs the
- * entries, and, if table_path (HOST, nullable) is given, appends them there as
- * text.  It allocates nranks scratch buffers of max_bytes itself.
+ * (chain over chunk sizes 8 KiB..64 MiB and stage counts, direct, binomial, and
+ * -- only if `algo_mask` has its bit -- the fan-out) for message sizes that are
+ * powers of two in [min_bytes, max_bytes], keeps the fastest per size, installs
+ * the entries, and, if table_path (HOST, nullable) is given, appends them there
+ * as text.  It allocates nranks scratch buffers of max_bytes itself.
  * algo_mask: bit (1 << algo) enables a candidate; 0 = chain|direct|binomial.
  */
 int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsigned algo_mask,
                bcast_stream_t stream, const char *table_path);
+/* algo_mask flag: also try the chain with a single stage (one wavefront plays
+ * every rank of its share in turn; no flag hand-off is left). */
+#define BCAST_TUNE_FOLDED (1u << 16)
+
+/* One table entry: the fastest candidate for the bucket and, beside it, the
+ * chain's own best setting (whoever won), which a CHAIN plan with
+ * chunk_bytes == 0 uses.  stages: 0 = automatic. */
+typedef struct {
+    int algo;                   /* winner: bcast_algo_t */
+    uint64_t chunk_bytes;       /* winner's chunk size (chain only) */
+    int stages;                 /* winner's stage count (chain only) */
+    double usec;                /* winner's measured time */
+    uint64_t chain_chunk_bytes; /* chain: best chunk size (0 = not measured) */
+    int chain_stages;           /* chain: best stage count */
+    double chain_usec;          /* chain: time at that setting */
+} bcast_tune_entry_t;
+
 int bcast_tune_load(const char *table_path);  /* HOST path; adds the file's entries */
 int bcast_tune_save(const char *table_path);  /* HOST path; writes all entries */
 int bcast_tune_clear(void);
+int bcast_tune_put(int nranks, size_t bytes, const bcast_tune_entry_t *entry);
+/* Nearest entry for nranks at or below log2(bytes), else the nearest above;
+ * BCAST_ERR_UNTUNED if the table has none for nranks. */
+int bcast_tune_get(int nranks, size_t bytes, bcast_tune_entry_t *entry);
+/* Shorthands: set / look up the winner only. */
 int bcast_tune_set(int nranks, size_t bytes, int algo, size_t chunk_bytes, double usec);
-/* Nearest entry for nranks at or below log2(bytes), else the nearest above.
- * usec (nullable) = the time measured when the entry was made, 0 if unknown. */
 int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *chunk_bytes, double *usec);
-/* The table also keeps, per entry, the best chunk size found for the chain even
- * where another algorithm won; a CHAIN plan with chunk_bytes == 0 uses it.
- * bcast_tune_set_chain needs the entry to exist (bcast_tune_set first). */
-int bcast_tune_set_chain(int nranks, size_t bytes, size_t chunk_bytes, double usec);
-int bcast_tune_lookup_chain(int nranks, size_t bytes, size_t *chunk_bytes, double *usec);
 int bcast_tune_count(void);
 
 const char *bcast_strerror(int status);

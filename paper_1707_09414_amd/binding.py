@@ -36,10 +36,10 @@ BCAST_ERR_UNTUNED = -5
 # every symbol include/bcast.h declares
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_debug", "bcast_plan_set_mode",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_debug", "bcast_plan_set_mode",
     "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
-    "bcast_tune_lookup", "bcast_tune_set_chain", "bcast_tune_lookup_chain", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
+    "bcast_tune_lookup", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
 ]
 
 
@@ -57,6 +57,8 @@ class PlanInfo(ctypes.Structure):
         ("algo", ctypes.c_int),
         ("chunk_bytes", ctypes.c_uint64),
         ("nchunks", ctypes.c_uint64),
+        ("stages", ctypes.c_int),
+        ("hops_per_stage", ctypes.c_int),
         ("lanes", ctypes.c_int),
         ("slice_bytes", ctypes.c_uint64),
         ("grid_blocks", ctypes.c_int),
@@ -68,6 +70,24 @@ class PlanInfo(ctypes.Structure):
 
     def as_dict(self):
         return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class TuneEntry(ctypes.Structure):
+    _fields_ = [
+        ("algo", ctypes.c_int),
+        ("chunk_bytes", ctypes.c_uint64),
+        ("stages", ctypes.c_int),
+        ("usec", ctypes.c_double),
+        ("chain_chunk_bytes", ctypes.c_uint64),
+        ("chain_stages", ctypes.c_int),
+        ("chain_usec", ctypes.c_double),
+    ]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+BCAST_TUNE_FOLDED = 1 << 16
 
 
 def _load():
@@ -87,18 +107,19 @@ def _load():
         "bcast_plan_info": ([vp, pvp, sz, ctypes.POINTER(PlanInfo)], i),
         "bcast_plan_destroy": ([vp], i),
         "bcast_plan_set_lanes": ([vp, i], i),
+        "bcast_plan_set_stages": ([vp, i], i),
         "bcast_plan_set_debug": ([vp, u64, i], i),
         "bcast_plan_set_mode": ([vp, ctypes.c_uint], i),
         "bcast_plan_handoff_counts": ([vp, ctypes.POINTER(u64), ctypes.POINTER(u64)], i),
-        "bcast_chain_geometry": ([i, sz, sz, i, i, ctypes.POINTER(PlanInfo)], i),
+        "bcast_chain_geometry": ([i, sz, sz, i, i, i, ctypes.POINTER(PlanInfo)], i),
         "bcast_tune": ([i, sz, sz, ctypes.c_uint, vp, ctypes.c_char_p], i),
         "bcast_tune_load": ([ctypes.c_char_p], i),
         "bcast_tune_save": ([ctypes.c_char_p], i),
         "bcast_tune_clear": ([], i),
         "bcast_tune_set": ([i, sz, i, sz, ctypes.c_double], i),
         "bcast_tune_lookup": ([i, sz, ctypes.POINTER(i), ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_double)], i),
-        "bcast_tune_set_chain": ([i, sz, sz, ctypes.c_double], i),
-        "bcast_tune_lookup_chain": ([i, sz, ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_double)], i),
+        "bcast_tune_put": ([i, sz, ctypes.POINTER(TuneEntry)], i),
+        "bcast_tune_get": ([i, sz, ctypes.POINTER(TuneEntry)], i),
         "bcast_tune_count": ([], i),
         "bcast_strerror": ([i], ctypes.c_char_p),
         "bcast_last_hip_error": ([], i),
@@ -204,6 +225,10 @@ def bcast_plan_set_lanes(plan: Plan, lanes: int) -> None:
     _check(_lib.bcast_plan_set_lanes(plan.handle, lanes), "bcast_plan_set_lanes")
 
 
+def bcast_plan_set_stages(plan: Plan, stages: int) -> None:
+    _check(_lib.bcast_plan_set_stages(plan.handle, stages), "bcast_plan_set_stages")
+
+
 def bcast_plan_set_debug(plan: Plan, spin_limit_ticks: int, mute_hop: int) -> None:
     _check(_lib.bcast_plan_set_debug(plan.handle, spin_limit_ticks, mute_hop), "bcast_plan_set_debug")
 
@@ -222,9 +247,11 @@ def bcast_plan_handoff_counts(plan: Plan) -> Tuple[int, int]:
     return a.value, b.value
 
 
-def bcast_chain_geometry(nranks: int, bytes: int, chunk_bytes: int, max_waves: int, lanes_request: int = 0) -> dict:
+def bcast_chain_geometry(nranks: int, bytes: int, chunk_bytes: int, max_waves: int, lanes_request: int = 0,
+                         stages_request: int = 0) -> dict:
     info = PlanInfo()
-    _check(_lib.bcast_chain_geometry(nranks, bytes, chunk_bytes, max_waves, lanes_request, ctypes.byref(info)),
+    _check(_lib.bcast_chain_geometry(nranks, bytes, chunk_bytes, max_waves, lanes_request, stages_request,
+                                     ctypes.byref(info)),
            "bcast_chain_geometry")
     return info.as_dict()
 
@@ -258,15 +285,17 @@ def bcast_tune_lookup(nranks: int, bytes: int) -> Tuple[int, int, float]:
     return a.value, c.value, u.value
 
 
-def bcast_tune_set_chain(nranks: int, bytes: int, chunk_bytes: int, usec: float = 0.0) -> None:
-    _check(_lib.bcast_tune_set_chain(nranks, bytes, chunk_bytes, usec), "bcast_tune_set_chain")
+def bcast_tune_put(nranks: int, bytes: int, **fields) -> None:
+    """Install one entry; fields are those of bcast_tune_entry_t."""
+    e = TuneEntry(**fields)
+    _check(_lib.bcast_tune_put(nranks, bytes, ctypes.byref(e)), "bcast_tune_put")
 
 
-def bcast_tune_lookup_chain(nranks: int, bytes: int) -> Tuple[int, float]:
-    """(chunk_bytes, usec): the best chain chunk size measured for this bucket."""
-    c, u = ctypes.c_size_t(0), ctypes.c_double(0.0)
-    _check(_lib.bcast_tune_lookup_chain(nranks, bytes, ctypes.byref(c), ctypes.byref(u)), "bcast_tune_lookup_chain")
-    return c.value, u.value
+def bcast_tune_get(nranks: int, bytes: int) -> dict:
+    """The entry AUTO / chunk 0 would use for this size (nearest bucket)."""
+    e = TuneEntry()
+    _check(_lib.bcast_tune_get(nranks, bytes, ctypes.byref(e)), "bcast_tune_get")
+    return e.as_dict()
 
 
 def bcast_tune_count() -> int:

@@ -27,6 +27,7 @@ struct bcast_plan {
     u64 *d_status = nullptr; // the same two words as the device sees them
     u64 epoch = 0;
     int lanes_request = 0;
+    int stages_request = 0;
     u64 spin_ticks = kDefaultSpinTicks;
     int mute_hop = 0;
 };
@@ -50,7 +51,15 @@ static u64 ceil_div(u64 a, u64 b) { return (a + b - 1) / b; }
 static u64 round_up(u64 a, u64 b) { return ceil_div(a, b) * b; }
 
 
-// A lane (one wavefront per hop) is fed well by 16 KiB of every chunk: two
+// Stages for `hops` chain hops when the caller asks for `request` (0 = one per hop).
+static void stage_shape(int hops, int request, int *stages, int *hops_per_stage)
+{
+    int want = request > 0 ? std::min(request, hops) : hops;
+    *hops_per_stage = (hops + want - 1) / want;
+    *stages = (hops + *hops_per_stage - 1) / *hops_per_stage;
+}
+
+// A lane (one wavefront per stage) is fed well by 16 KiB of every chunk: two
 // trips of its copy loop per hand-off.  8 KiB is the least worth a lane.
 constexpr u64 kSliceTarget = 16 * 1024;
 constexpr u64 kSliceMin = (u64)kChainUnroll * kWaveSize * 16;  // one trip
@@ -59,18 +68,21 @@ constexpr u64 kSliceMin = (u64)kChainUnroll * kWaveSize * 16;  // one trip
 // die every hop shares the same HBM, so Eq. 5's fill term (n - 2 idle links)
 // costs little and the hand-off cost per chunk dominates: the best chunk is
 // the one that gives every lane the device can hold about kSliceTarget bytes.
-static u64 default_chunk(int nranks, int max_waves)
+static u64 default_chunk(int nranks, int max_waves, int stages_request)
 {
-    u64 lanes_max = std::max(1, max_waves / std::max(1, nranks - 1));
+    int stages = 1, hps = 1;
+    stage_shape(std::max(1, nranks - 1), stages_request, &stages, &hps);
+    u64 lanes_max = std::max(1, max_waves / stages);
     u64 C = 16 * 1024;
     while (C * 2 <= lanes_max * kSliceTarget) C *= 2;
     return C;
 }
 
 extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
-                                    int lanes_request, bcast_plan_info_t *info)
+                                    int lanes_request, int stages_request, bcast_plan_info_t *info)
 {
-    if (!info || nranks < 1 || nranks > BCAST_MAX_RANKS || max_waves < 1 || lanes_request < 0) return BCAST_ERR_ARG;
+    if (!info || nranks < 1 || nranks > BCAST_MAX_RANKS || max_waves < 1 || lanes_request < 0 || stages_request < 0)
+        return BCAST_ERR_ARG;
     if (chunk_bytes == 0 || chunk_bytes % 16 != 0) return BCAST_ERR_ARG;
     memset(info, 0, sizeof *info);
     info->algo = BCAST_ALGO_CHAIN;
@@ -85,7 +97,9 @@ extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes
     u64 nchunks = ceil_div(bytes, C);
     if (nchunks >= (1ull << 27)) return BCAST_ERR_ARG;  // the flag word keeps the count in 28 bits
     int hops = nranks - 1;
-    if (max_waves < hops) return BCAST_ERR_ARG;  // every hop needs a resident wavefront
+    int stages = 0, hps = 0;
+    stage_shape(hops, stages_request, &stages, &hps);
+    if (max_waves < stages) return BCAST_ERR_ARG;  // every stage needs a resident wavefront
     // Lanes per hop: a power of two.  Measured on MI355X, 2^k lanes per hop run
     // 15-20 % faster than nearby counts: with 4-wave workgroups dealt round-robin
     // over 8 XCDs and then over each XCD's CUs, every hop's workgroups then
@@ -96,10 +110,10 @@ extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes
         while (p * 2 <= l) p *= 2;
         return p;
     };
-    u64 lanes_max = shape((u64)(max_waves / hops));
+    u64 lanes_max = shape((u64)(max_waves / stages));
     // a lane should own at least kSliceMin bytes of a chunk unless the chunk is smaller
     u64 useful = std::max<u64>(1, ceil_div(C, kSliceMin));
-    u64 lanes = lanes_request > 0 ? std::min<u64>((u64)lanes_request, (u64)(max_waves / hops))
+    u64 lanes = lanes_request > 0 ? std::min<u64>((u64)lanes_request, (u64)(max_waves / stages))
                                   : shape(std::min(useful, lanes_max));
     lanes = std::max<u64>(1, lanes);
     // a lane takes every lanes-th 8 KiB trip of a chunk
@@ -108,7 +122,9 @@ extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes
     info->chunk_bytes = C;
     info->nchunks = nchunks;
     info->lanes = (int)lanes;
-    info->grid_blocks = (int)ceil_div((u64)hops * lanes, kWavesPerBlock);
+    info->stages = stages;
+    info->hops_per_stage = hps;
+    info->grid_blocks = (int)ceil_div((u64)stages * lanes, kWavesPerBlock);
     info->launches = 1;
     info->algorithmic_bytes = 2ull * hops * bytes;
     return BCAST_OK;
@@ -186,6 +202,13 @@ extern "C" int bcast_plan_set_lanes(bcast_plan_t *p, int lanes)
     return BCAST_OK;
 }
 
+extern "C" int bcast_plan_set_stages(bcast_plan_t *p, int stages)
+{
+    if (!p || stages < 0) return BCAST_ERR_ARG;
+    p->stages_request = stages;
+    return BCAST_OK;
+}
+
 extern "C" int bcast_plan_set_debug(bcast_plan_t *p, uint64_t spin_limit_ticks, int mute_hop)
 {
     if (!p || mute_hop < 0 || mute_hop >= BCAST_MAX_RANKS) return BCAST_ERR_ARG;
@@ -247,24 +270,36 @@ static int common_vec_bytes(void *const *bufs, int n)
 struct Resolved {
     int algo;
     u64 chunk;
+    int stages;  // 0 = built-in rule
 };
+
+// Without a measurement: two stages (hops 1..h | h+1..P-1).  On one die the
+// fewer, larger stages run faster (a wave re-reads what it just stored from the
+// Infinity Cache, and DRAM sees few streams), and two is the fewest that still
+// hands every chunk over through a flag.
+static int default_stages(int nranks) { return std::min(std::max(1, nranks - 1), 2); }
 
 static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
 {
     r->algo = p->algo;
     r->chunk = p->chunk_bytes;
+    r->stages = p->stages_request;
+    bcast_tune_entry_t e;
+    const bool tuned = bcast_tune_get(p->nranks, bytes, &e) == BCAST_OK;
     if (p->algo == BCAST_ALGO_AUTO) {
-        int algo = 0;
-        size_t chunk = 0;
-        if (bcast_tune_lookup(p->nranks, bytes, &algo, &chunk, nullptr) != BCAST_OK) return BCAST_ERR_UNTUNED;
-        r->algo = algo;
-        if (r->chunk == 0) r->chunk = chunk;
-    } else if (p->algo == BCAST_ALGO_CHAIN && r->chunk == 0) {
-        size_t chunk = 0;
-        if (bcast_tune_lookup_chain(p->nranks, bytes, &chunk, nullptr) == BCAST_OK) r->chunk = chunk;
+        if (!tuned) return BCAST_ERR_UNTUNED;
+        r->algo = e.algo;
+        if (r->chunk == 0) {
+            r->chunk = e.chunk_bytes;
+            if (r->stages == 0) r->stages = e.stages;
+        }
+    } else if (p->algo == BCAST_ALGO_CHAIN && r->chunk == 0 && tuned && e.chain_chunk_bytes != 0) {
+        r->chunk = e.chain_chunk_bytes;
+        if (r->stages == 0) r->stages = e.chain_stages;
     }
     if (r->algo == BCAST_ALGO_CHAIN) {
-        if (r->chunk == 0) r->chunk = default_chunk(p->nranks, p->max_waves);
+        if (r->stages == 0) r->stages = default_stages(p->nranks);
+        if (r->chunk == 0) r->chunk = default_chunk(p->nranks, p->max_waves, r->stages);
         r->chunk = round_up(r->chunk, 16);
     }
     return BCAST_OK;
@@ -287,7 +322,7 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
     const int P = p->nranks;
     const int vec = common_vec_bytes(rank_bufs, P);
     if (r.algo == BCAST_ALGO_CHAIN) {
-        rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, p->max_waves, p->lanes_request, info);
+        rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, p->max_waves, p->lanes_request, r.stages, info);
         if (rc != BCAST_OK) return rc;
         info->vec_bytes = vec;
         return BCAST_OK;
@@ -370,11 +405,17 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         a.spin_ticks = p->spin_ticks;
         a.nchunks = (unsigned)info.nchunks;
         a.lanes = (unsigned)info.lanes;
+        a.stages = (unsigned)info.stages;
+        a.hops_per_stage = (unsigned)info.hops_per_stage;
         a.nranks = (unsigned)P;
         a.mute_hop = (unsigned)p->mute_hop;
-        // the launch must match what the kernel indexes: (P-1)*lanes waves, each with its own flag
-        if ((u64)(P - 1) * a.lanes > (u64)p->max_waves) return BCAST_ERR_ARG;
-        if ((u64)info.grid_blocks * kWavesPerBlock < (u64)(P - 1) * a.lanes) return BCAST_ERR_ARG;
+        // the launch must match what the kernel indexes: stages*lanes waves, each with its own flag,
+        // and the stages together cover exactly the P-1 hops
+        if ((u64)a.stages * a.lanes > (u64)p->max_waves) return BCAST_ERR_ARG;
+        if ((u64)info.grid_blocks * kWavesPerBlock < (u64)a.stages * a.lanes) return BCAST_ERR_ARG;
+        if (a.stages == 0 || a.hops_per_stage == 0) return BCAST_ERR_ARG;
+        if ((u64)a.stages * a.hops_per_stage < (u64)(P - 1) || (u64)(a.stages - 1) * a.hops_per_stage >= (u64)(P - 1))
+            return BCAST_ERR_ARG;
         if (a.nchunks == 0 || a.lanes == 0 || a.chunk_bytes == 0) return BCAST_ERR_ARG;
         if ((u64)a.nchunks * a.chunk_bytes < a.bytes) return BCAST_ERR_ARG;
         HIP_TRY(launch_chain(a, info.vec_bytes, info.grid_blocks, stream));

@@ -47,7 +47,9 @@ struct ChainArgs {
     u64 chunk_bytes;   // C (multiple of 16)
     u64 spin_ticks;    // wait limit in 100 MHz ticks
     unsigned nchunks;
-    unsigned lanes;    // wavefronts per hop
+    unsigned lanes;    // wavefronts per stage
+    unsigned stages;   // groups of consecutive chain positions, each served by its own waves
+    unsigned hops_per_stage;
     unsigned nranks;
     unsigned mute_hop; // debug: this position never publishes (0 = off)
     unsigned mode;     // kMode* bits

@@ -253,25 +253,29 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 {
     const unsigned lane = threadIdx.x & (kWaveSize - 1);
     const unsigned gw = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
-    const unsigned nwaves = (a.nranks - 1) * a.lanes;
-    if (gw >= nwaves) return;
-    const unsigned hop = gw / a.lanes + 1;  // this wave fills chain position `hop`
-    const unsigned s = gw - (hop - 1) * a.lanes;
+    if (gw >= a.stages * a.lanes) return;
+    // Stage g serves the consecutive chain positions first_hop .. last_hop: its
+    // waves play those ranks one after the other for every chunk (hops_per_stage
+    // == 1 is one stage per rank).  Hand-offs between stages go through flags;
+    // inside a stage the same wave stored what it reads next, so its own
+    // s_waitcnt orders the two.
+    const unsigned g = gw / a.lanes;
+    const unsigned s = gw - g * a.lanes;
+    const unsigned first_hop = g * a.hops_per_stage + 1;
+    unsigned last_hop = first_hop + a.hops_per_stage - 1;
+    if (last_hop > a.nranks - 1) last_hop = a.nranks - 1;
     // which XCD (L2 domain) this wave runs on: HW_REG_XCC_ID, bits 3:0
     const unsigned xcd = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u;
 
-    const char *src = a.buf[hop - 1];
-    char *dst = a.buf[hop];
-    const u64 *in_flag = hop > 1 ? a.flags + ((u64)(hop - 2) * a.lanes + s) * kFlagStrideWords : nullptr;
-    u64 *out_flag = (hop + 1 < a.nranks && hop != a.mute_hop)
-                        ? a.flags + ((u64)(hop - 1) * a.lanes + s) * kFlagStrideWords
-                        : nullptr;
+    const u64 *in_flag = g > 0 ? a.flags + ((u64)(g - 1) * a.lanes + s) * kFlagStrideWords : nullptr;
+    const bool muted = a.mute_hop >= first_hop && a.mute_hop <= last_hop;
+    u64 *out_flag = (g + 1 < a.stages && !muted) ? a.flags + ((u64)g * a.lanes + s) * kFlagStrideWords : nullptr;
     unsigned near = 0, far = 0;  // hand-offs received from the same / another XCD
 
     // A lane's share of a chunk is every lanes-th trip (one trip = kChainUnroll
     // vector instructions of the wave, 8 KiB at 16 bytes per lane), so at any
-    // moment the lanes of a hop sweep one contiguous window of the chunk: DRAM
-    // sees a few wide streams per hop, not one narrow stream per wave.
+    // moment the lanes of a stage sweep one contiguous window of the chunk: DRAM
+    // sees a few wide streams per stage, not one narrow stream per wave.
     const u64 trip = (u64)kChainUnroll * kWaveSize * V;
     const u64 stride = trip * a.lanes;
 
@@ -284,19 +288,25 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
         // flag value: base + (chunks stored << 4) + producer's XCD
         if (in_flag) {
             const u64 want = a.base + ((u64)(c + 1) << 4);
-            if (seen < want && !wait_ready(in_flag, want, a, hop, c, lane, &seen)) return;
+            if (seen < want && !wait_ready(in_flag, want, a, first_hop, c, lane, &seen)) return;
             const bool same_xcd = (unsigned)(seen & 15u) == xcd;
             near += same_xcd;
             far += !same_xcd;
         }
-        for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
-            const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
-            copy_span_agent<V>(dst, src, lo, hi, lane);
+        for (unsigned hop = first_hop; hop <= last_hop; ++hop) {
+            const char *src = a.buf[hop - 1];
+            char *dst = a.buf[hop];
+            // what this wave stored for position hop-1 must have completed
+            // before it is read back for position hop
+            if (hop != first_hop) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
+                const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
+                copy_span_agent<V>(dst, src, lo, hi, lane);
+            }
         }
         // Look at the next chunk's flag while this chunk's stores drain: in
         // steady state the left neighbour is ahead and the next wait is free.
-        if (in_flag && c + 1 < a.nchunks)
-            seen = read_flag(in_flag, lane);
+        if (in_flag && c + 1 < a.nchunks) seen = read_flag(in_flag, lane);
         if (out_flag) {
             // every payload store of this wave has completed (and, being
             // write-through, is visible device-wide) before the flag is raised

@@ -22,13 +22,22 @@ int log2_bucket(size_t bytes)
 }
 
 static std::mutex g_mu;
-static std::map<std::pair<int, int>, TuneEntry> g_table;  // (nranks, bucket)
+static std::map<std::pair<int, int>, bcast_tune_entry_t> g_table;  // (nranks, bucket)
 
 }  // namespace bcast
 
 using namespace bcast;
 
 static bool valid_algo(int algo) { return algo >= BCAST_ALGO_CHAIN && algo <= BCAST_ALGO_FANOUT; }
+
+static bool valid_entry(int nranks, const bcast_tune_entry_t &e)
+{
+    if (nranks < 1 || nranks > BCAST_MAX_RANKS || !valid_algo(e.algo)) return false;
+    if (e.algo == BCAST_ALGO_CHAIN && (e.chunk_bytes == 0 || e.chunk_bytes % 16 != 0)) return false;
+    if (e.chain_chunk_bytes % 16 != 0) return false;
+    if (e.stages < 0 || e.stages > BCAST_MAX_RANKS || e.chain_stages < 0 || e.chain_stages > BCAST_MAX_RANKS) return false;
+    return true;
+}
 
 extern "C" int bcast_tune_clear(void)
 {
@@ -43,36 +52,23 @@ extern "C" int bcast_tune_count(void)
     return (int)g_table.size();
 }
 
-extern "C" int bcast_tune_set(int nranks, size_t bytes, int algo, size_t chunk_bytes, double usec)
+extern "C" int bcast_tune_put(int nranks, size_t bytes, const bcast_tune_entry_t *entry)
 {
-    if (nranks < 1 || nranks > BCAST_MAX_RANKS || !valid_algo(algo) || bytes == 0) return BCAST_ERR_ARG;
-    if (algo == BCAST_ALGO_CHAIN && (chunk_bytes == 0 || chunk_bytes % 16 != 0)) return BCAST_ERR_ARG;
-    std::lock_guard<std::mutex> g(g_mu);
-    TuneEntry &e = g_table[{nranks, log2_bucket(bytes)}];
-    e.algo = algo;
-    e.chunk_bytes = chunk_bytes;
-    e.usec = usec;
-    if (algo == BCAST_ALGO_CHAIN) {
-        e.chain_chunk = chunk_bytes;
-        e.chain_usec = usec;
+    if (!entry || bytes == 0 || !valid_entry(nranks, *entry)) return BCAST_ERR_ARG;
+    bcast_tune_entry_t e = *entry;
+    if (e.algo == BCAST_ALGO_CHAIN && e.chain_chunk_bytes == 0) {  // the winner is the chain: it is its own best
+        e.chain_chunk_bytes = e.chunk_bytes;
+        e.chain_stages = e.stages;
+        e.chain_usec = e.usec;
     }
-    return BCAST_OK;
-}
-
-extern "C" int bcast_tune_set_chain(int nranks, size_t bytes, size_t chunk_bytes, double usec)
-{
-    if (nranks < 1 || nranks > BCAST_MAX_RANKS || bytes == 0 || chunk_bytes == 0 || chunk_bytes % 16 != 0) return BCAST_ERR_ARG;
     std::lock_guard<std::mutex> g(g_mu);
-    auto it = g_table.find({nranks, log2_bucket(bytes)});
-    if (it == g_table.end()) return BCAST_ERR_UNTUNED;  // the bucket's winner must be set first
-    it->second.chain_chunk = chunk_bytes;
-    it->second.chain_usec = usec;
+    g_table[{nranks, log2_bucket(bytes)}] = e;
     return BCAST_OK;
 }
 
 // nearest bucket at or below, else the nearest above, among this nranks' entries
 // (caller holds g_mu)
-static const TuneEntry *nearest(int nranks, size_t bytes)
+static const bcast_tune_entry_t *nearest(int nranks, size_t bytes)
 {
     const int want = log2_bucket(bytes);
     auto it = g_table.upper_bound({nranks, want});
@@ -84,34 +80,50 @@ static const TuneEntry *nearest(int nranks, size_t bytes)
     return nullptr;
 }
 
+extern "C" int bcast_tune_get(int nranks, size_t bytes, bcast_tune_entry_t *entry)
+{
+    if (!entry || nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
+    std::lock_guard<std::mutex> g(g_mu);
+    const bcast_tune_entry_t *best = nearest(nranks, bytes);
+    if (!best) return BCAST_ERR_UNTUNED;
+    *entry = *best;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_tune_set(int nranks, size_t bytes, int algo, size_t chunk_bytes, double usec)
+{
+    bcast_tune_entry_t e;
+    memset(&e, 0, sizeof e);
+    e.algo = algo;
+    e.chunk_bytes = chunk_bytes;
+    e.usec = usec;
+    return bcast_tune_put(nranks, bytes, &e);
+}
+
 extern "C" int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *chunk_bytes, double *usec)
 {
-    if (!algo || !chunk_bytes || nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
-    std::lock_guard<std::mutex> g(g_mu);
-    const TuneEntry *best = nearest(nranks, bytes);
-    if (!best) return BCAST_ERR_UNTUNED;
-    *algo = best->algo;
-    *chunk_bytes = best->chunk_bytes;
-    if (usec) *usec = best->usec;
+    if (!algo || !chunk_bytes) return BCAST_ERR_ARG;
+    bcast_tune_entry_t e;
+    int rc = bcast_tune_get(nranks, bytes, &e);
+    if (rc != BCAST_OK) return rc;
+    *algo = e.algo;
+    *chunk_bytes = (size_t)e.chunk_bytes;
+    if (usec) *usec = e.usec;
     return BCAST_OK;
 }
 
-extern "C" int bcast_tune_lookup_chain(int nranks, size_t bytes, size_t *chunk_bytes, double *usec)
-{
-    if (!chunk_bytes || nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
-    std::lock_guard<std::mutex> g(g_mu);
-    const TuneEntry *best = nearest(nranks, bytes);
-    if (!best || best->chain_chunk == 0) return BCAST_ERR_UNTUNED;
-    *chunk_bytes = best->chain_chunk;
-    if (usec) *usec = best->chain_usec;
-    return BCAST_OK;
-}
-
-// Text format, one entry per line:
-//   nranks log2_bytes algo chunk_bytes usec [chain_chunk_bytes chain_usec]
-// Lines starting with '#' are comments.
 static const char kHeaderLine[] =
-    "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout) chunk_bytes usec chain_chunk_bytes chain_usec\n";
+    "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout) chunk_bytes usec "
+    "chain_chunk_bytes chain_usec stages chain_stages\n";
+
+// Text format, one entry per line (the last four columns are optional):
+//   nranks log2_bytes algo chunk_bytes usec [chain_chunk_bytes chain_usec [stages chain_stages]]
+// Lines starting with '#' are comments.
+static void print_entry(FILE *f, int nranks, int bucket, const bcast_tune_entry_t &e)
+{
+    fprintf(f, "%d %d %d %llu %.3f %llu %.3f %d %d\n", nranks, bucket, e.algo, (unsigned long long)e.chunk_bytes, e.usec,
+            (unsigned long long)e.chain_chunk_bytes, e.chain_usec, e.stages, e.chain_stages);
+}
 
 extern "C" int bcast_tune_save(const char *path)
 {
@@ -120,9 +132,7 @@ extern "C" int bcast_tune_save(const char *path)
     if (!f) return BCAST_ERR_ARG;
     fprintf(f, "%s", kHeaderLine);
     std::lock_guard<std::mutex> g(g_mu);
-    for (const auto &kv : g_table)
-        fprintf(f, "%d %d %d %zu %.3f %zu %.3f\n", kv.first.first, kv.first.second, kv.second.algo,
-                kv.second.chunk_bytes, kv.second.usec, kv.second.chain_chunk, kv.second.chain_usec);
+    for (const auto &kv : g_table) print_entry(f, kv.first.first, kv.first.second, kv.second);
     fclose(f);
     return BCAST_OK;
 }
@@ -134,22 +144,29 @@ extern "C" int bcast_tune_load(const char *path)
     if (!f) return BCAST_ERR_ARG;
     char line[256];
     int rc = BCAST_OK;
-    std::vector<std::pair<std::pair<int, int>, TuneEntry>> rows;
+    std::vector<std::pair<std::pair<int, int>, bcast_tune_entry_t>> rows;
     while (fgets(line, sizeof line, f)) {
         const char *s = line;
         while (*s == ' ' || *s == '\t') ++s;
         if (*s == '#' || *s == '\n' || *s == '\0') continue;
-        int nranks, bucket, algo;
-        unsigned long long chunk, cchunk = 0;
-        double usec = 0.0, cusec = 0.0;
-        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf", &nranks, &bucket, &algo, &chunk, &usec, &cchunk, &cusec);
-        if (got < 4 || nranks < 1 || nranks > BCAST_MAX_RANKS || bucket < 0 || bucket > 62 || !valid_algo(algo) ||
-            (algo == BCAST_ALGO_CHAIN && (chunk == 0 || chunk % 16 != 0)) || cchunk % 16 != 0) {
+        int nranks, bucket;
+        unsigned long long chunk = 0, cchunk = 0;
+        bcast_tune_entry_t e;
+        memset(&e, 0, sizeof e);
+        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf %d %d", &nranks, &bucket, &e.algo, &chunk, &e.usec, &cchunk,
+                         &e.chain_usec, &e.stages, &e.chain_stages);
+        e.chunk_bytes = chunk;
+        e.chain_chunk_bytes = cchunk;
+        if (got < 4 || bucket < 0 || bucket > 62 || !valid_entry(nranks, e)) {
             rc = BCAST_ERR_ARG;
             break;
         }
-        if (algo == BCAST_ALGO_CHAIN && cchunk == 0) { cchunk = chunk; cusec = usec; }
-        rows.push_back({{nranks, bucket}, TuneEntry{algo, (size_t)chunk, usec, (size_t)cchunk, cusec}});
+        if (e.algo == BCAST_ALGO_CHAIN && e.chain_chunk_bytes == 0) {
+            e.chain_chunk_bytes = e.chunk_bytes;
+            e.chain_stages = e.stages;
+            e.chain_usec = e.usec;
+        }
+        rows.push_back({{nranks, bucket}, e});
     }
     fclose(f);
     if (rc != BCAST_OK) return rc;  // a malformed file installs nothing
@@ -174,11 +191,13 @@ struct Scratch {
 
 // Microseconds per run of one candidate.  One timed run warms up and sizes
 // the batches (about 20 ms each, 2..40 runs); the best of three batches counts.
-int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, Scratch &sc, hipStream_t stream, double *usec)
+int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages, Scratch &sc, hipStream_t stream,
+                   double *usec)
 {
     bcast_plan_t *plan = nullptr;
     int rc = bcast_plan_create(&plan, nranks, bytes, chunk, algo);
     if (rc != BCAST_OK) return rc;
+    rc = bcast_plan_set_stages(plan, stages);
     int reps = 1;
     double best = 1e30;
     for (int batch = 0; batch < 4 && rc == BCAST_OK; ++batch) {
@@ -207,7 +226,8 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
                           bcast_stream_t stream, const char *table_path)
 {
     if (nranks < 2 || nranks > BCAST_MAX_RANKS || min_bytes == 0 || max_bytes < min_bytes) return BCAST_ERR_ARG;
-    if (algo_mask == 0) algo_mask = (1u << BCAST_ALGO_CHAIN) | (1u << BCAST_ALGO_DIRECT) | (1u << BCAST_ALGO_BINOMIAL);
+    if ((algo_mask & ~BCAST_TUNE_FOLDED) == 0)
+        algo_mask |= (1u << BCAST_ALGO_CHAIN) | (1u << BCAST_ALGO_DIRECT) | (1u << BCAST_ALGO_BINOMIAL);
 
     Scratch sc;
     sc.bufs.assign(nranks, nullptr);
@@ -225,40 +245,63 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         fprintf(f, "%s", kHeaderLine);
     }
 
+    // Stage counts to try for the chain: one stage per receiving rank (every
+    // rank has wavefronts of its own), then fewer, larger stages.  A single
+    // stage has no flag hand-off at all and is only tried on request.
+    const int hops = nranks - 1;
+    std::vector<int> stage_counts;
+    for (int s : {hops, 16, 8, 4, 2, 1}) {
+        if (s > hops || (s == 1 && hops > 1 && !(algo_mask & BCAST_TUNE_FOLDED))) continue;
+        const int hps = (hops + s - 1) / s;
+        const int eff = (hops + hps - 1) / hps;
+        if (std::find(stage_counts.begin(), stage_counts.end(), eff) == stage_counts.end()) stage_counts.push_back(eff);
+    }
+
     int rc = BCAST_OK;
     size_t M = (size_t)1 << log2_bucket(min_bytes);
     if (M < min_bytes) M <<= 1;
     for (; M <= max_bytes && rc == BCAST_OK; M <<= 1) {
-        TuneEntry best{0, 0, 1e30, 0, 1e30};
-        auto consider = [&](int algo, size_t chunk) {
+        bcast_tune_entry_t best;
+        memset(&best, 0, sizeof best);
+        best.usec = best.chain_usec = 1e30;
+        auto consider = [&](int algo, size_t chunk, int stages) {
             if (rc != BCAST_OK || !(algo_mask & (1u << algo))) return;
             double us = 0.0;
-            rc = time_candidate(nranks, M, algo, chunk, sc, stream, &us);
+            rc = time_candidate(nranks, M, algo, chunk, stages, sc, stream, &us);
             if (rc != BCAST_OK) return;
             if (algo == BCAST_ALGO_CHAIN && us < best.chain_usec) {
-                best.chain_chunk = chunk;
+                best.chain_chunk_bytes = chunk;
+                best.chain_stages = stages;
                 best.chain_usec = us;
             }
             if (us < best.usec) {
                 best.algo = algo;
                 best.chunk_bytes = chunk;
+                best.stages = algo == BCAST_ALGO_CHAIN ? stages : 0;
                 best.usec = us;
             }
         };
-        // chain: the whole message as one chunk (Eq. 2), then every power-of-two
-        // chunk size from 8 KiB to 64 MiB that splits the message into at most
-        // 4096 chunks (Eq. 5); smaller chunks than that only add hand-offs
-        consider(BCAST_ALGO_CHAIN, std::max<size_t>(16, (M + 15) / 16 * 16));
-        for (size_t C = 8u << 10; C <= (64u << 20) && C < M; C <<= 1)
-            if (M / C <= 4096) consider(BCAST_ALGO_CHAIN, C);
-        consider(BCAST_ALGO_DIRECT, 0);
-        consider(BCAST_ALGO_BINOMIAL, 0);
-        consider(BCAST_ALGO_FANOUT, 0);
+        // chain: for every stage count, the whole message as one chunk (Eq. 2)
+        // and the power-of-two chunk sizes from 8 KiB to 64 MiB (Eq. 5) that give
+        // a lane between 4 KiB and 128 KiB of a chunk (outside that range the
+        // hand-off cost or the idle lanes dominate), at most 4096 chunks
+        for (int stages : stage_counts) {
+            size_t lanes_max = 1;
+            while (lanes_max * 2 * stages <= 8192) lanes_max *= 2;
+            consider(BCAST_ALGO_CHAIN, std::max<size_t>(16, (M + 15) / 16 * 16), stages);
+            for (size_t C = 8u << 10; C <= (64u << 20) && C < M; C <<= 1) {
+                if (M / C > 4096 || C > lanes_max * (128u << 10)) continue;
+                if (C < lanes_max * (4u << 10) && C < M / 8) continue;
+                consider(BCAST_ALGO_CHAIN, C, stages);
+            }
+        }
+        consider(BCAST_ALGO_DIRECT, 0, 0);
+        consider(BCAST_ALGO_BINOMIAL, 0, 0);
+        consider(BCAST_ALGO_FANOUT, 0, 0);
         if (rc != BCAST_OK) break;
-        rc = bcast_tune_set(nranks, M, best.algo, best.chunk_bytes, best.usec);
-        if (rc == BCAST_OK && best.chain_chunk) rc = bcast_tune_set_chain(nranks, M, best.chain_chunk, best.chain_usec);
-        if (f) fprintf(f, "%d %d %d %zu %.3f %zu %.3f\n", nranks, log2_bucket(M), best.algo, best.chunk_bytes, best.usec,
-                       best.chain_chunk, best.chain_chunk ? best.chain_usec : 0.0);
+        if (best.chain_chunk_bytes == 0) best.chain_usec = 0.0;
+        rc = bcast_tune_put(nranks, M, &best);
+        if (f) print_entry(f, nranks, log2_bucket(M), best);
         if (M > (max_bytes >> 1)) break;  // next doubling would overflow or pass max
     }
     if (f) fclose(f);

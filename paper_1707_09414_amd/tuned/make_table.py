@@ -1,10 +1,10 @@
 """Measure the tuning table on the GPU in this machine and write it as text.
 
     python -m paper_1707_09414_amd.tuned.make_table [--out PATH] [--ranks 2,4,8,...]
-                                                    [--min-bytes N] [--max-bytes N] [--with-fanout]
+                                                    [--min-bytes N] [--max-bytes N] [--with-fanout] [--folded]
 
-For every rank count it runs ``bcast_tune`` (chain over chunk sizes, direct,
-binomial; the one-die fan-out only on request) over power-of-two message sizes
+For every rank count it runs ``bcast_tune`` (chain over chunk sizes and stage counts,
+direct, binomial; the one-die fan-out and the single-stage chain only on request) over power-of-two message sizes
 and writes the winners.  The file it produces is what ``load_default_table``
 installs.
 """
@@ -23,6 +23,7 @@ def main() -> int:
     ap.add_argument("--min-bytes", type=int, default=4)
     ap.add_argument("--max-bytes", type=int, default=1 << 30)
     ap.add_argument("--with-fanout", action="store_true")
+    ap.add_argument("--folded", action="store_true", help="also try the chain with a single stage (no flag hand-off)")
     args = ap.parse_args()
 
     import torch  # device context and stream only
@@ -33,6 +34,8 @@ def main() -> int:
     mask = (1 << B.BCAST_ALGO_CHAIN) | (1 << B.BCAST_ALGO_DIRECT) | (1 << B.BCAST_ALGO_BINOMIAL)
     if args.with_fanout:
         mask |= 1 << B.BCAST_ALGO_FANOUT
+    if args.folded:
+        mask |= B.BCAST_TUNE_FOLDED
     B.bcast_tune_clear()
     stream = torch.cuda.current_stream()
     for P in [int(x) for x in args.ranks.split(",")]:

@@ -78,7 +78,7 @@ def assert_same(got, exp, what):
                                  % (what, r, bad.size, bad[0], g[bad[0]], e[bad[0]]))
 
 
-def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0, stream=None, plan=None):
+def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0, stream=None, plan=None, stages=0):
     """One broadcast on the GPU, compared byte for byte (guards included) with
     the oracle's end state.  Returns the plan info used."""
     cap = M if cap is None else cap
@@ -91,6 +91,8 @@ def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0,
     try:
         if lanes:
             B.bcast_plan_set_lanes(plan, lanes)
+        if stages:
+            B.bcast_plan_set_stages(plan, stages)
         info = B.bcast_plan_info(plan, M, rb.ptrs())
         B.bcast_run(plan, rb.ptrs(), root, M, stream)
         got = rb.to_host()

@@ -66,6 +66,17 @@ def test_chain_lane_counts(noise, lanes):
     assert info["lanes"] == lanes
 
 
+@pytest.mark.parametrize("P,stages", [(2, 1), (5, 1), (5, 2), (5, 3), (9, 3), (17, 4), (33, 5), (64, 1), (64, 8), (64, 9), (64, 63), (64, 100)])
+@pytest.mark.parametrize("M,C", [(7, 16), (70000, 8192), (3 * MiB + 5, 256 * KiB)])
+def test_chain_stages(noise, P, stages, M, C):
+    """A stage's wavefront plays several consecutive ranks in turn; every rank's
+    buffer must still end up with the root's bytes, whatever the grouping."""
+    info = run_and_check(P, P // 3, M, C, B.BCAST_ALGO_CHAIN, noise, stages=stages)
+    want = min(stages, P - 1)
+    hps = -(-(P - 1) // want)
+    assert info["hops_per_stage"] == hps and info["stages"] == -(-(P - 1) // hps)
+
+
 def test_degenerate_cases(noise):
     # one rank, empty message, message shorter than the plan's size
     for algo in ALGOS:
@@ -160,6 +171,7 @@ def test_wait_limit_reports_timeout_and_plan_recovers(noise):
     rb = RankBuffers(P, M)
     rb.reset(0, noise[:M])
     plan = B.bcast_plan_create(P, M, 16 * KiB, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_stages(plan, P - 1)     # every position has waves of its own
     B.bcast_plan_set_debug(plan, 200000, 2)  # 2 ms of the 100 MHz clock
     B.bcast_run(plan, rb.ptrs(), 0, M)
     torch.cuda.synchronize()
@@ -206,10 +218,15 @@ def test_handoff_counts_and_xcd_placement(noise):
     rb.reset(0, noise[:M])
     plan = B.bcast_plan_create(P, M, C, B.BCAST_ALGO_CHAIN)
     B.bcast_plan_set_lanes(plan, lanes)
+    B.bcast_plan_set_stages(plan, P - 1)
     B.bcast_plan_set_mode(plan, B.BCAST_MODE_COUNT)
     B.bcast_run(plan, rb.ptrs(), 0, M)
     near, far = B.bcast_plan_handoff_counts(plan)
     assert near + far == (P - 2) * lanes * (M // C)
+    B.bcast_plan_set_stages(plan, 3)  # hops 1-3 | 4-6 | 7: two flag hand-offs per lane and chunk
+    B.bcast_run(plan, rb.ptrs(), 0, M)
+    near2, far2 = B.bcast_plan_handoff_counts(plan)
+    assert (near2 + far2) - (near + far) == 2 * lanes * (M // C)
     got = rb.to_host()
     for r in range(P):
         assert np.array_equal(got[r][rb.start(r): rb.start(r) + M], noise[:M])

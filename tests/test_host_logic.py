@@ -54,7 +54,16 @@ def test_chain_geometry_matches_eq5_chunking():
     assert g["nchunks"] == 1 and g["lanes"] == 1 and g["grid_blocks"] == 16
     # lanes never exceed what fits at once, whatever is requested
     g = B.bcast_chain_geometry(64, 1 << 30, 4 << 20, 2048, lanes_request=1000)
-    assert g["lanes"] == 2048 // 63
+    assert g["lanes"] == 2048 // 63 and g["stages"] == 63 and g["hops_per_stage"] == 1
+    # stages: consecutive hops grouped as evenly as possible
+    g = B.bcast_chain_geometry(64, 1 << 30, 4 << 20, 8192, stages_request=8)
+    assert (g["stages"], g["hops_per_stage"], g["lanes"]) == (8, 8, 512)
+    g = B.bcast_chain_geometry(64, 1 << 30, 4 << 20, 8192, stages_request=5)
+    assert (g["stages"], g["hops_per_stage"]) == (5, 13)
+    g = B.bcast_chain_geometry(8, 1 << 26, 8 << 20, 8192, stages_request=100)
+    assert (g["stages"], g["hops_per_stage"], g["lanes"]) == (7, 1, 1024)
+    g = B.bcast_chain_geometry(8, 1 << 26, 8 << 20, 8192, stages_request=1)
+    assert (g["stages"], g["hops_per_stage"], g["grid_blocks"]) == (1, 7, 256)
     # no-ops
     assert B.bcast_chain_geometry(1, 1 << 20, 4096, 64)["nchunks"] == 0
     assert B.bcast_chain_geometry(4, 0, 4096, 64)["nchunks"] == 0
@@ -89,15 +98,17 @@ def test_tuning_table_lookup_rules(tmp_path):
     with pytest.raises(B.BcastError):
         B.bcast_tune_set(8, 1 << 20, 7, 0)
 
-    # the chain's own best chunk is kept beside the winner
-    assert B.bcast_tune_lookup_chain(8, 1 << 20) == (64 << 10, 50.0)
+    # the chain's own best setting is kept beside the winner
+    e = B.bcast_tune_get(8, 1 << 20)
+    assert (e["chain_chunk_bytes"], e["chain_usec"], e["algo"]) == (64 << 10, 50.0, B.BCAST_ALGO_CHAIN)
+    assert B.bcast_tune_get(16, 1 << 20)["chain_chunk_bytes"] == 0  # direct won and no chain setting is recorded
+    B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_DIRECT, usec=70.0, chain_chunk_bytes=128 << 10, chain_stages=4, chain_usec=90.0)
+    e = B.bcast_tune_get(16, 1 << 21)
+    assert (e["algo"], e["chain_chunk_bytes"], e["chain_stages"], e["chain_usec"]) == (B.BCAST_ALGO_DIRECT, 128 << 10, 4, 90.0)
     with pytest.raises(B.BcastError):
-        B.bcast_tune_lookup_chain(16, 1 << 20)  # direct won there and no chain chunk is recorded
-    B.bcast_tune_set_chain(16, 1 << 20, 128 << 10, 90.0)
-    assert B.bcast_tune_lookup_chain(16, 1 << 21) == (128 << 10, 90.0)
-    assert B.bcast_tune_lookup(16, 1 << 20)[0] == B.BCAST_ALGO_DIRECT
+        B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=24)  # not a multiple of 16
     with pytest.raises(B.BcastError):
-        B.bcast_tune_set_chain(32, 1 << 20, 128 << 10, 90.0)  # no such entry yet
+        B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_DIRECT, chain_stages=65)
 
     path = tmp_path / "table.txt"
     B.bcast_tune_save(str(path))
@@ -105,12 +116,15 @@ def test_tuning_table_lookup_rules(tmp_path):
     B.bcast_tune_load(str(path))
     assert B.bcast_tune_count() == 3
     assert B.bcast_tune_lookup(8, 1 << 20) == (B.BCAST_ALGO_CHAIN, 64 << 10, 50.0)
-    assert B.bcast_tune_lookup_chain(16, 1 << 20) == (128 << 10, 90.0)
-    # the older five-column format still loads
+    e = B.bcast_tune_get(16, 1 << 20)
+    assert (e["chain_chunk_bytes"], e["chain_stages"], e["chain_usec"]) == (128 << 10, 4, 90.0)
+    # files with only the first five or seven columns still load
     old = tmp_path / "old.txt"
-    old.write_text("4 20 1 65536 12.5\n4 10 3 0 5.0\n")
+    old.write_text("4 20 1 65536 12.5\n4 10 3 0 5.0\n4 12 2 0 5.0 8192 7.5\n")
     B.bcast_tune_load(str(old))
-    assert B.bcast_tune_lookup_chain(4, 1 << 20) == (65536, 12.5)
+    e = B.bcast_tune_get(4, 1 << 20)
+    assert (e["chain_chunk_bytes"], e["chain_usec"], e["stages"]) == (65536, 12.5, 0)
+    assert B.bcast_tune_get(4, 1 << 12)["chain_chunk_bytes"] == 8192
 
     bad = tmp_path / "bad.txt"
     bad.write_text("8 20 1 65536 1.0\n8 21 1 7 1.0\n")
