@@ -41,9 +41,10 @@ WORKLOADS = {
 # run (a 64 MiB copy reads 32786.9 KiB on the counter: factor 1.999); WRITE_SIZE
 # reads the true size (factor 1.000).  Workloads without a profile report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "chain"): int((232620.7 * (65536.0 / 32786.9) + 460288.0) * 1024),
+    ("cfg2", "chain"): int((230279.8 * (65536.0 / 32786.8) + 459008.0) * 1024),
     ("cfg2", "direct"): int((32784.5 * (65536.0 / 32786.9) + 65536.0) * 1024),
-    ("cfg4", "chain"): int((8148345.0 * (524288.0 / 262167.1) + 16260608.0) * 1024),
+    ("cfg4", "chain"): int((8134392.3 * (524288.0 / 262167.6) + 16256000.0) * 1024),
+    ("cfg5", "chain"): int((33045440.4 * (1048576.0 / 524313.7) + 66066432.0) * 1024),
 }
 
 
