@@ -19,6 +19,7 @@ struct bcast_plan {
     int device = 0;
     int cu_count = 0;
     int max_waves = 0;       // wavefronts of the chain kernel the device holds at once
+    int max_waves_cached = 0;  // the same for its small-message (stage-cached) variant
     u64 *d_flags = nullptr;  // max_waves flags, kFlagStrideWords apart, plus the abort word
     u64 *d_abort = nullptr;
     u64 *d_counters = nullptr; // two words after the abort word
@@ -147,17 +148,19 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
 
     int rc = BCAST_OK;
     hipDeviceProp_t prop;
-    int per_cu = 0;
+    int per_cu = 0, per_cu_cached = 0;
     hipError_t e = hipGetDevice(&p->device);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, p->device);
-    if (e == hipSuccess) e = chain_max_blocks_per_cu(&per_cu);
+    if (e == hipSuccess) e = chain_max_blocks_per_cu(&per_cu, &per_cu_cached);
     if (e == hipSuccess) {
         p->cu_count = prop.multiProcessorCount;
         // the chain grid never exceeds what the device holds at once, so every
         // wave a waiter depends on is resident (hop-major numbering alone already
         // makes waits point at earlier-dispatched workgroups)
         per_cu = std::max(1, std::min(per_cu, 8));
+        per_cu_cached = std::max(1, std::min(per_cu_cached, per_cu));
         p->max_waves = std::max(nranks, p->cu_count * per_cu * kWavesPerBlock);
+        p->max_waves_cached = std::max(nranks, p->cu_count * per_cu_cached * kWavesPerBlock);
         size_t flag_bytes = ((size_t)p->max_waves + 2) * kFlagStrideWords * sizeof(u64);
         e = hipMalloc((void **)&p->d_flags, flag_bytes);
         if (e == hipSuccess) e = hipMemset(p->d_flags, 0, flag_bytes);
@@ -279,6 +282,12 @@ struct Resolved {
 // hands every chunk over through a flag.
 static int default_stages(int nranks) { return std::min(std::max(1, nranks - 1), 2); }
 
+// Co-residency limit of the kernel variant a message of `bytes` bytes will use.
+static int waves_for(const bcast_plan *p, size_t bytes)
+{
+    return bytes <= kStageCachedMaxBytes ? p->max_waves_cached : p->max_waves;
+}
+
 static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
 {
     r->algo = p->algo;
@@ -299,7 +308,7 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
     }
     if (r->algo == BCAST_ALGO_CHAIN) {
         if (r->stages == 0) r->stages = default_stages(p->nranks);
-        if (r->chunk == 0) r->chunk = default_chunk(p->nranks, p->max_waves, r->stages);
+        if (r->chunk == 0) r->chunk = default_chunk(p->nranks, waves_for(p, bytes), r->stages);
         r->chunk = round_up(r->chunk, 16);
     }
     return BCAST_OK;
@@ -322,7 +331,7 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
     const int P = p->nranks;
     const int vec = common_vec_bytes(rank_bufs, P);
     if (r.algo == BCAST_ALGO_CHAIN) {
-        rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, p->max_waves, p->lanes_request, r.stages, info);
+        rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, waves_for(p, bytes), p->lanes_request, r.stages, info);
         if (rc != BCAST_OK) return rc;
         info->vec_bytes = vec;
         return BCAST_OK;
@@ -398,6 +407,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         a.abort_word = p->d_abort;
         a.counters = p->d_counters;
         a.mode = p->mode;
+        if (bytes <= kStageCachedMaxBytes) a.mode |= kModeStageCached;
         a.status = p->d_status;
         a.base = (++p->epoch) << 32;
         a.bytes = bytes;
@@ -411,7 +421,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         a.mute_hop = (unsigned)p->mute_hop;
         // the launch must match what the kernel indexes: stages*lanes waves, each with its own flag,
         // and the stages together cover exactly the P-1 hops
-        if ((u64)a.stages * a.lanes > (u64)p->max_waves) return BCAST_ERR_ARG;
+        if ((u64)a.stages * a.lanes > (u64)waves_for(p, bytes)) return BCAST_ERR_ARG;
         if ((u64)info.grid_blocks * kWavesPerBlock < (u64)a.stages * a.lanes) return BCAST_ERR_ARG;
         if (a.stages == 0 || a.hops_per_stage == 0) return BCAST_ERR_ARG;
         if ((u64)a.stages * a.hops_per_stage < (u64)(P - 1) || (u64)(a.stages - 1) * a.hops_per_stage >= (u64)(P - 1))

@@ -60,6 +60,10 @@ struct ChainArgs {
 // Diagnostic only: every wave ends with two atomics on one cache line, which
 // costs tens of microseconds at full occupancy.
 constexpr unsigned kModeCount = 2;
+// Chosen by the host per run (small messages): cached accesses inside a stage.
+constexpr unsigned kModeStageCached = 4;
+// Largest message that uses it (measured crossover on MI355X: 2-4 MiB).
+constexpr u64 kStageCachedMaxBytes = 2u << 20;
 
 // Arguments of the plain copy kernels: up to 32 simultaneous (src -> dst)
 // whole-message copies (one binomial round has at most 32 at P = 64; the
@@ -80,6 +84,6 @@ struct CopyArgs {
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
-hipError_t chain_max_blocks_per_cu(int *blocks);
+hipError_t chain_max_blocks_per_cu(int *blocks, int *blocks_stage_cached);
 
 }  // namespace bcast

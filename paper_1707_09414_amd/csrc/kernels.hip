@@ -66,28 +66,30 @@ __device__ __forceinline__ void copy_span(char *__restrict__ dst, const char *__
 // per wave and serialise on the L2).
 // ---------------------------------------------------------------------------
 constexpr int kAuxAgent = 16;               // sc1: agent scope
+constexpr int kAuxCached = 0;               // ordinary cached access
 constexpr int kRsrcWord3 = 0x00020000;      // raw buffer, 32-bit data format
 
-template <int V> struct AgentIO;
-template <> struct AgentIO<16> {
+// LD / ST: cache-policy bits of the loads / stores (kAuxAgent or kAuxCached).
+template <int V, int LD, int ST> struct AgentIO;
+template <int LD, int ST> struct AgentIO<16, LD, ST> {
     typedef VecOf<16>::type T;
-    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, kAuxAgent); }
-    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, kAuxAgent); }
+    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, LD); }
+    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b128(v, r, off, 0, ST); }
 };
-template <> struct AgentIO<8> {
+template <int LD, int ST> struct AgentIO<8, LD, ST> {
     typedef VecOf<8>::type T;
-    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, kAuxAgent); }
-    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b64(v, r, off, 0, kAuxAgent); }
+    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, LD); }
+    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b64(v, r, off, 0, ST); }
 };
-template <> struct AgentIO<4> {
+template <int LD, int ST> struct AgentIO<4, LD, ST> {
     typedef VecOf<4>::type T;
-    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, kAuxAgent); }
-    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b32(v, r, off, 0, kAuxAgent); }
+    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, LD); }
+    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b32(v, r, off, 0, ST); }
 };
-template <> struct AgentIO<1> {
+template <int LD, int ST> struct AgentIO<1, LD, ST> {
     typedef VecOf<1>::type T;
-    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b8(r, off, 0, kAuxAgent); }
-    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b8(v, r, off, 0, kAuxAgent); }
+    static __device__ __forceinline__ T ld(__amdgpu_buffer_rsrc_t r, unsigned off) { return __builtin_amdgcn_raw_buffer_load_b8(r, off, 0, LD); }
+    static __device__ __forceinline__ void st(T v, __amdgpu_buffer_rsrc_t r, unsigned off) { __builtin_amdgcn_raw_buffer_store_b8(v, r, off, 0, ST); }
 };
 
 // copy_span with agent-scope accesses for a span of at most a few trips (the
@@ -98,11 +100,11 @@ template <> struct AgentIO<1> {
 // is range-checked by the hardware (the load returns zero, the store is
 // dropped).  A short slice therefore costs one memory round trip, not one per
 // kilobyte.
-template <int V>
+template <int V, int LD = kAuxAgent, int ST = kAuxAgent>
 __device__ __forceinline__ void copy_span_agent(char *dst, const char *src, u64 lo, u64 hi, unsigned lane)
 {
-    typedef AgentIO<V> IO;
-    typedef AgentIO<1> IO1;
+    typedef AgentIO<V, LD, ST> IO;
+    typedef AgentIO<1, LD, ST> IO1;
     typedef typename IO::T T;
     const unsigned n = (unsigned)(hi - lo);
     unsigned head = (V - (unsigned)((uintptr_t)(src + lo) & (V - 1))) & (V - 1);
@@ -248,7 +250,17 @@ __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const Chai
     return true;
 }
 
-template <int V>
+// STAGE_CACHED (small messages): inside a stage, a buffer that only this wave
+// touches during the kernel -- it stores it as position h and reads it back
+// for position h+1, or it is the chain's last position -- is accessed with
+// ordinary cached loads and stores instead of agent-scope ones: a wave always
+// sees its own earlier stores (after s_waitcnt), whatever cache they sit in,
+// and the end of the kernel writes the dirty lines back like for any kernel.
+// The L2 round trip is about half the memory one, which is what a small
+// broadcast over many hops consists of; for large messages the write-back
+// traffic makes this slower than write-through, so the host only selects it
+// up to a couple of MiB.  Buffers handed from stage to stage stay agent-scope.
+template <int V, bool STAGE_CACHED>
 __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 {
     const unsigned lane = threadIdx.x & (kWaveSize - 1);
@@ -299,9 +311,14 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
             // what this wave stored for position hop-1 must have completed
             // before it is read back for position hop
             if (hop != first_hop) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            const bool ld_cached = STAGE_CACHED && hop != first_hop;
+            const bool st_cached = STAGE_CACHED && (hop != last_hop || g + 1 == a.stages);
             for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
                 const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
-                copy_span_agent<V>(dst, src, lo, hi, lane);
+                if (STAGE_CACHED && ld_cached && st_cached) copy_span_agent<V, kAuxCached, kAuxCached>(dst, src, lo, hi, lane);
+                else if (STAGE_CACHED && ld_cached) copy_span_agent<V, kAuxCached, kAuxAgent>(dst, src, lo, hi, lane);
+                else if (STAGE_CACHED && st_cached) copy_span_agent<V, kAuxAgent, kAuxCached>(dst, src, lo, hi, lane);
+                else copy_span_agent<V>(dst, src, lo, hi, lane);
             }
         }
         // Look at the next chunk's flag while this chunk's stores drain: in
@@ -356,20 +373,24 @@ __global__ void __launch_bounds__(kBlockThreads) fanout_kernel(const CopyArgs a)
     }
 }
 
-// Launch KERNEL<V> for the vector width the host found usable.
-#define BCAST_LAUNCH_V(KERNEL, vec_bytes, grid, stream, args)                              \
-    switch (vec_bytes) {                                                                   \
-    case 16: KERNEL<16><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break;            \
-    case 8: KERNEL<8><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break;              \
-    case 4: KERNEL<4><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break;              \
-    case 1: KERNEL<1><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break;              \
-    default: return hipErrorInvalidValue;                                                  \
+// Launch KERNEL<V, ...> for the vector width the host found usable.
+#define BCAST_LAUNCH_V(KERNEL, vec_bytes, grid, stream, args, ...)                                      \
+    switch (vec_bytes) {                                                                                \
+    case 16: KERNEL<16 __VA_OPT__(,) __VA_ARGS__><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break; \
+    case 8: KERNEL<8 __VA_OPT__(,) __VA_ARGS__><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break;   \
+    case 4: KERNEL<4 __VA_OPT__(,) __VA_ARGS__><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break;   \
+    case 1: KERNEL<1 __VA_OPT__(,) __VA_ARGS__><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break;   \
+    default: return hipErrorInvalidValue;                                                               \
     }
 
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream)
 {
     if (grid_blocks < 1) return hipErrorInvalidValue;
-    BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a);
+    if (a.mode & kModeStageCached) {
+        BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, true);
+    } else {
+        BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, false);
+    }
     return hipGetLastError();
 }
 
@@ -387,9 +408,12 @@ hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream
     return hipGetLastError();
 }
 
-hipError_t chain_max_blocks_per_cu(int *blocks)
+hipError_t chain_max_blocks_per_cu(int *blocks, int *blocks_stage_cached)
 {
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, chain_kernel<16>, kBlockThreads, 0);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, chain_kernel<16, false>, kBlockThreads, 0);
+    if (e == hipSuccess)
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_stage_cached, chain_kernel<16, true>, kBlockThreads, 0);
+    return e;
 }
 
 }  // namespace bcast
