@@ -192,6 +192,10 @@ typedef struct {
     double chain_usec;          /* chain: time at that setting */
 } bcast_tune_entry_t;
 
+/* While a log path (HOST, NULL = off) is set, bcast_tune appends one line per
+ * candidate it times: "nranks bytes algo chunk_bytes stages usec" -- the raw
+ * material for fitting the cost models of Sec. III-A / IV-B. */
+int bcast_tune_set_log(const char *log_path);
 int bcast_tune_load(const char *table_path);  /* HOST path; adds the file's entries */
 int bcast_tune_save(const char *table_path);  /* HOST path; writes all entries */
 int bcast_tune_clear(void);

@@ -39,7 +39,7 @@ EXPORTS = [
     "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_debug", "bcast_plan_set_mode",
     "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
-    "bcast_tune_lookup", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
+    "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
 ]
 
 
@@ -118,6 +118,7 @@ def _load():
         "bcast_tune_clear": ([], i),
         "bcast_tune_set": ([i, sz, i, sz, ctypes.c_double], i),
         "bcast_tune_lookup": ([i, sz, ctypes.POINTER(i), ctypes.POINTER(sz), ctypes.POINTER(ctypes.c_double)], i),
+        "bcast_tune_set_log": ([ctypes.c_char_p], i),
         "bcast_tune_put": ([i, sz, ctypes.POINTER(TuneEntry)], i),
         "bcast_tune_get": ([i, sz, ctypes.POINTER(TuneEntry)], i),
         "bcast_tune_count": ([], i),
@@ -283,6 +284,10 @@ def bcast_tune_lookup(nranks: int, bytes: int) -> Tuple[int, int, float]:
     a, c, u = ctypes.c_int(0), ctypes.c_size_t(0), ctypes.c_double(0.0)
     _check(_lib.bcast_tune_lookup(nranks, bytes, ctypes.byref(a), ctypes.byref(c), ctypes.byref(u)), "bcast_tune_lookup")
     return a.value, c.value, u.value
+
+
+def bcast_tune_set_log(log_path: Optional[str]) -> None:
+    _check(_lib.bcast_tune_set_log(log_path.encode() if log_path else None), "bcast_tune_set_log")
 
 
 def bcast_tune_put(nranks: int, bytes: int, **fields) -> None:

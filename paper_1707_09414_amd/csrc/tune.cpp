@@ -6,6 +6,7 @@
 #include <cstring>
 #include <map>
 #include <mutex>
+#include <string>
 #include <utility>
 #include <vector>
 
@@ -23,6 +24,7 @@ int log2_bucket(size_t bytes)
 
 static std::mutex g_mu;
 static std::map<std::pair<int, int>, bcast_tune_entry_t> g_table;  // (nranks, bucket)
+static std::string g_log_path;  // if set, bcast_tune appends every candidate it times
 
 }  // namespace bcast
 
@@ -50,6 +52,13 @@ extern "C" int bcast_tune_count(void)
 {
     std::lock_guard<std::mutex> g(g_mu);
     return (int)g_table.size();
+}
+
+extern "C" int bcast_tune_set_log(const char *path)
+{
+    std::lock_guard<std::mutex> g(g_mu);
+    g_log_path = path ? path : "";
+    return BCAST_OK;
 }
 
 extern "C" int bcast_tune_put(int nranks, size_t bytes, const bcast_tune_entry_t *entry)
@@ -238,6 +247,17 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
     }
     if (hipEventCreate(&sc.e0) != hipSuccess || hipEventCreate(&sc.e1) != hipSuccess) return BCAST_ERR_HIP;
 
+    FILE *log = nullptr;
+    {
+        std::lock_guard<std::mutex> g(g_mu);
+        if (!g_log_path.empty()) log = fopen(g_log_path.c_str(), "a");
+    }
+    if (log) fprintf(log, "# nranks bytes algo chunk_bytes stages usec\n");
+    struct LogCloser {
+        FILE *f;
+        ~LogCloser() { if (f) fclose(f); }
+    } log_closer{log};
+
     FILE *f = nullptr;
     if (table_path) {
         f = fopen(table_path, "a");
@@ -269,6 +289,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
             double us = 0.0;
             rc = time_candidate(nranks, M, algo, chunk, stages, sc, stream, &us);
             if (rc != BCAST_OK) return;
+            if (log) fprintf(log, "%d %zu %d %zu %d %.3f\n", nranks, M, algo, chunk, stages, us);
             if (algo == BCAST_ALGO_CHAIN && us < best.chain_usec) {
                 best.chain_chunk_bytes = chunk;
                 best.chain_stages = stages;

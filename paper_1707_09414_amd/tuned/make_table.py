@@ -23,6 +23,7 @@ def main() -> int:
     ap.add_argument("--min-bytes", type=int, default=4)
     ap.add_argument("--max-bytes", type=int, default=1 << 30)
     ap.add_argument("--with-fanout", action="store_true")
+    ap.add_argument("--log", default=None, help="also append every timed candidate to this file")
     ap.add_argument("--folded", action="store_true", help="also try the chain with a single stage (no flag hand-off)")
     args = ap.parse_args()
 
@@ -37,11 +38,13 @@ def main() -> int:
     if args.folded:
         mask |= B.BCAST_TUNE_FOLDED
     B.bcast_tune_clear()
+    B.bcast_tune_set_log(args.log)
     stream = torch.cuda.current_stream()
     for P in [int(x) for x in args.ranks.split(",")]:
         t0 = time.time()
         B.bcast_tune(P, args.min_bytes, args.max_bytes, mask, stream, None)
         print("tuned P=%d in %.1f s (%d entries so far)" % (P, time.time() - t0, B.bcast_tune_count()), flush=True)
+    B.bcast_tune_set_log(None)
     B.bcast_tune_save(args.out)
     print("wrote", args.out)
     return 0
