@@ -6,7 +6,8 @@
  * every buffer holds the root's bytes) for P "virtual ranks" that are P
  * distinct device buffers in one GPU's HBM.  The flagship algorithm is the
  * pipelined chain of Sec. IV-B (Eq. 5); the direct algorithm (Eq. 1), the
- * binomial tree (Eq. 3, k = 2), a one-die fan-out and a tuning table that picks
+ * binomial tree (Eq. 3, k = 2), scatter + ring allgather (Eq. 4), a one-die
+ * fan-out and a tuning table that picks
  * algorithm and chunk size per (message bytes, ranks) (Sec. III-B, IV-B) sit
  * beside it.
  *
@@ -81,7 +82,8 @@ typedef struct {
  *   chunk_bytes chunk size C for CHAIN: a positive multiple of 16; values
  *               >= bytes give the unpipelined chain (Eq. 2).  0 = choose: the
  *               tuning table's entry if one is loaded, else a built-in rule.
- *               Ignored by DIRECT, BINOMIAL, FANOUT and SCATTER_ALLGATHER.
+ *               Ignored by DIRECT, BINOMIAL, FANOUT and SCATTER_ALLGATHER
+ *               (whose piece size is ceil(bytes / nranks)).
  *   algo        a bcast_algo_t.  AUTO resolves per run from the tuning table and
  *               fails with BCAST_ERR_UNTUNED if no table covers nranks.
  * Allocates device memory for ready flags (zeroed once; they are never reset,
@@ -167,7 +169,7 @@ int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_w
  *
  * bcast_tune measures, on the current device and `stream`, every candidate
  * (chain over chunk sizes 8 KiB..64 MiB and stage counts, direct, binomial, and
- * -- only if `algo_mask` has its bit -- the fan-out) for message sizes that are
+ * -- only if `algo_mask` has their bits -- the fan-out and scatter + allgather) for message sizes that are
  * powers of two in [min_bytes, max_bytes], keeps the fastest per size, installs
  * the entries, and, if table_path (HOST, nullable) is given, appends them there
  * as text.  It allocates nranks scratch buffers of max_bytes itself.

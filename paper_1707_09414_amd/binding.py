@@ -24,7 +24,8 @@ BCAST_ALGO_CHAIN = 1
 BCAST_ALGO_DIRECT = 2
 BCAST_ALGO_BINOMIAL = 3
 BCAST_ALGO_FANOUT = 4
-ALGO_NAMES = {0: "auto", 1: "chain", 2: "direct", 3: "binomial", 4: "fanout"}
+BCAST_ALGO_SCATTER_ALLGATHER = 5
+ALGO_NAMES = {0: "auto", 1: "chain", 2: "direct", 3: "binomial", 4: "fanout", 5: "scatter_allgather"}
 
 BCAST_OK = 0
 BCAST_ERR_ARG = -1

@@ -136,7 +136,7 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
     if (!out) return BCAST_ERR_ARG;
     *out = nullptr;
     if (nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
-    if (algo < BCAST_ALGO_AUTO || algo > BCAST_ALGO_FANOUT) return BCAST_ERR_ARG;
+    if (algo < BCAST_ALGO_AUTO || algo > BCAST_ALGO_SCATTER_ALLGATHER) return BCAST_ERR_ARG;
     if (chunk_bytes % 16 != 0) return BCAST_ERR_ARG;
 
     bcast_plan *p = new (std::nothrow) bcast_plan;
@@ -323,6 +323,58 @@ static int copy_grid(const bcast_plan *p, u64 bytes, int concurrent_copies)
     return (int)std::min(need, cap);
 }
 
+// Scatter + ring allgather (Sec. III-A, Eq. 4) as a list of launches, each a set
+// of (src position, dst position, byte range) copies.  Pieces: position q owns
+// bytes [q * piece, (q+1) * piece) clipped to the message, piece = ceil(M / P).
+// Binomial scatter: strides from the top power of two down; a position that is
+// a multiple of 2*stride hands the upper half of the pieces it holds to position
+// + stride.  Ring: in step t position q passes piece (q - t) mod P to q + 1,
+// with wrap-around; the copy that would land in the root (which already owns
+// everything and is input only) is left out.
+struct SagLaunch {
+    RangedCopyArgs args;
+    u64 max_range;
+};
+
+template <typename F>
+static void walk_scatter_allgather(int P, u64 M, F &&emit)
+{
+    const u64 piece = ceil_div(M, (u64)P);
+    auto piece_lo = [&](u64 q) { return std::min(q * piece, M); };
+    int top = 1;
+    while (top < P) top *= 2;
+    for (int stride = top / 2; stride >= 1; stride /= 2) {
+        SagLaunch l;
+        memset(&l, 0, sizeof l);
+        for (int q = 0; q + stride < P; q += 2 * stride) {
+            const int last = std::min(q + 2 * stride, P);
+            const unsigned n = l.args.npairs++;
+            l.args.src_pos[n] = (unsigned char)q;
+            l.args.dst_pos[n] = (unsigned char)(q + stride);
+            l.args.lo[n] = piece_lo((u64)(q + stride));
+            l.args.hi[n] = piece_lo((u64)last);
+            l.max_range = std::max(l.max_range, l.args.hi[n] - l.args.lo[n]);
+        }
+        emit(l);
+    }
+    for (int t = 0; t < P - 1; ++t) {
+        SagLaunch l;
+        memset(&l, 0, sizeof l);
+        for (int q = 0; q < P; ++q) {
+            const int dst = (q + 1) % P;
+            if (dst == 0) continue;
+            const int pc = ((q - t) % P + P) % P;
+            const unsigned n = l.args.npairs++;
+            l.args.src_pos[n] = (unsigned char)q;
+            l.args.dst_pos[n] = (unsigned char)dst;
+            l.args.lo[n] = piece_lo((u64)pc);
+            l.args.hi[n] = piece_lo((u64)pc + 1);
+            l.max_range = std::max(l.max_range, l.args.hi[n] - l.args.lo[n]);
+        }
+        emit(l);
+    }
+}
+
 static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_plan_info_t *info)
 {
     Resolved r;
@@ -362,6 +414,20 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
         info->grid_blocks = copy_grid(p, bytes, 1);
         info->algorithmic_bytes = (u64)P * bytes;
         break;
+    case BCAST_ALGO_SCATTER_ALLGATHER: {
+        u64 moved = 0;
+        int launches = 0;
+        walk_scatter_allgather(P, bytes, [&](const SagLaunch &l) {
+            ++launches;
+            for (unsigned i = 0; i < l.args.npairs; ++i) moved += l.args.hi[i] - l.args.lo[i];
+        });
+        info->launches = launches;
+        info->chunk_bytes = ceil_div(bytes, (u64)P);  // the piece size
+        info->nchunks = (u64)P;
+        info->grid_blocks = copy_grid(p, info->chunk_bytes, P - 1);
+        info->algorithmic_bytes = 2 * moved;
+        break;
+    }
     default:
         return BCAST_ERR_ARG;
     }
@@ -465,6 +531,16 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
     }
     if (info.algo == BCAST_ALGO_FANOUT) {
         HIP_TRY(launch_fanout(c, info.vec_bytes, info.grid_blocks, stream));
+        return BCAST_OK;
+    }
+    if (info.algo == BCAST_ALGO_SCATTER_ALLGATHER) {
+        hipError_t err = hipSuccess;
+        walk_scatter_allgather(P, bytes, [&](SagLaunch &l) {
+            if (err != hipSuccess || l.max_range == 0) return;  // a round of empty pieces moves nothing
+            memcpy(l.args.buf, by_pos, sizeof(char *) * P);
+            err = launch_ranged_copy(l.args, info.vec_bytes, copy_grid(p, l.max_range, (int)l.args.npairs), stream);
+        });
+        HIP_TRY(err);
         return BCAST_OK;
     }
     return BCAST_ERR_ARG;

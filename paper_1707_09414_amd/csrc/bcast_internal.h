@@ -79,11 +79,24 @@ struct CopyArgs {
     u64 hi;   // one past the last byte offset to move
 };
 
+// Arguments of the ranged copy kernel: up to 64 simultaneous copies, each of its
+// own byte range [lo, hi) (same offsets on both sides): one round of the
+// binomial scatter or one step of the ring allgather (Sec. III-A, Eq. 4).
+struct RangedCopyArgs {
+    char *buf[BCAST_MAX_RANKS]; // by chain position
+    u64 lo[BCAST_MAX_RANKS];
+    u64 hi[BCAST_MAX_RANKS];
+    unsigned char src_pos[BCAST_MAX_RANKS];
+    unsigned char dst_pos[BCAST_MAX_RANKS];
+    unsigned npairs;
+};
+
 // Launchers implemented in kernels.hip.  vec_bytes is 16, 8, 4 or 1: every
 // buffer address in the call is congruent modulo vec_bytes.
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
+hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t chain_max_blocks_per_cu(int *blocks, int *blocks_stage_cached);
 
 }  // namespace bcast

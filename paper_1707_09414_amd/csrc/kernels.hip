@@ -359,6 +359,26 @@ __global__ void __launch_bounds__(kBlockThreads) pair_copy_kernel(const CopyArgs
     }
 }
 
+// Copies with a byte range per pair (blockIdx.y picks the pair): the pieces
+// moved by one round of the binomial scatter or one step of the ring allgather
+// (Sec. III-A, Eq. 4).  Empty ranges are skipped.
+template <int V>
+__global__ void __launch_bounds__(kBlockThreads) ranged_copy_kernel(const RangedCopyArgs a)
+{
+    const unsigned lane = threadIdx.x & (kWaveSize - 1);
+    const unsigned pair = blockIdx.y;
+    const char *src = a.buf[a.src_pos[pair]];
+    char *dst = a.buf[a.dst_pos[pair]];
+    const u64 end = a.hi[pair];
+    const u64 nwaves = (u64)gridDim.x * kWavesPerBlock;
+    u64 w = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    for (u64 lo = a.lo[pair] + w * kTileBytes; lo < end; lo += nwaves * kTileBytes) {
+        u64 hi = lo + kTileBytes;
+        if (hi > end) hi = end;
+        copy_span<V>(dst, src, lo, hi, lane);
+    }
+}
+
 // One-die fan-out: buf[0] is read once, every other position is written.
 template <int V>
 __global__ void __launch_bounds__(kBlockThreads) fanout_kernel(const CopyArgs a)
@@ -405,6 +425,13 @@ hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream
 {
     if (grid_x < 1) return hipErrorInvalidValue;
     BCAST_LAUNCH_V(fanout_kernel, vec_bytes, dim3(grid_x), stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream)
+{
+    if (grid_x < 1 || a.npairs < 1 || a.npairs > BCAST_MAX_RANKS) return hipErrorInvalidValue;
+    BCAST_LAUNCH_V(ranged_copy_kernel, vec_bytes, dim3(grid_x, a.npairs), stream, a);
     return hipGetLastError();
 }
 

@@ -30,7 +30,7 @@ static std::string g_log_path;  // if set, bcast_tune appends every candidate it
 
 using namespace bcast;
 
-static bool valid_algo(int algo) { return algo >= BCAST_ALGO_CHAIN && algo <= BCAST_ALGO_FANOUT; }
+static bool valid_algo(int algo) { return algo >= BCAST_ALGO_CHAIN && algo <= BCAST_ALGO_SCATTER_ALLGATHER; }
 
 static bool valid_entry(int nranks, const bcast_tune_entry_t &e)
 {
@@ -122,7 +122,7 @@ extern "C" int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *ch
 }
 
 static const char kHeaderLine[] =
-    "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout) chunk_bytes usec "
+    "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout 5=scatter-allgather) chunk_bytes usec "
     "chain_chunk_bytes chain_usec stages chain_stages\n";
 
 // Text format, one entry per line (the last four columns are optional):
@@ -319,6 +319,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         consider(BCAST_ALGO_DIRECT, 0, 0);
         consider(BCAST_ALGO_BINOMIAL, 0, 0);
         consider(BCAST_ALGO_FANOUT, 0, 0);
+        consider(BCAST_ALGO_SCATTER_ALLGATHER, 0, 0);
         if (rc != BCAST_OK) break;
         if (best.chain_chunk_bytes == 0) best.chain_usec = 0.0;
         rc = bcast_tune_put(nranks, M, &best);

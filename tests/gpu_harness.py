@@ -64,6 +64,8 @@ def oracle_schedule(algo, P, root, M, C):
         return lambda a: oracle.direct_bcast(a, P, root, M)
     if algo == B.BCAST_ALGO_BINOMIAL:
         return lambda a: oracle.binomial_bcast(a, P, root, M)
+    if algo == B.BCAST_ALGO_SCATTER_ALLGATHER:
+        return lambda a: oracle.scatter_allgather_bcast(a, P, root, M)
     if algo == B.BCAST_ALGO_FANOUT:
         # the fan-out has no schedule of its own in the paper: its result is the definition
         return lambda a: oracle.naive_bcast(a, root, M)

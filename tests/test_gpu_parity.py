@@ -13,7 +13,8 @@ from gpu_harness import RankBuffers, run_and_check, assert_same, expected_with_o
 pytestmark = pytest.mark.gpu
 
 KiB, MiB = inputs.KiB, inputs.MiB
-ALGOS = [B.BCAST_ALGO_CHAIN, B.BCAST_ALGO_DIRECT, B.BCAST_ALGO_BINOMIAL, B.BCAST_ALGO_FANOUT]
+ALGOS = [B.BCAST_ALGO_CHAIN, B.BCAST_ALGO_DIRECT, B.BCAST_ALGO_BINOMIAL, B.BCAST_ALGO_FANOUT,
+         B.BCAST_ALGO_SCATTER_ALLGATHER]
 
 
 @pytest.fixture(scope="module")
@@ -75,6 +76,17 @@ def test_chain_stages(noise, P, stages, M, C):
     want = min(stages, P - 1)
     hps = -(-(P - 1) // want)
     assert info["hops_per_stage"] == hps and info["stages"] == -(-(P - 1) // hps)
+
+
+@pytest.mark.parametrize("P", [2, 3, 5, 8, 13, 64])
+@pytest.mark.parametrize("M", [1, 3, 63, 64, 65, 1000, 64 * KiB + 1, 2 * MiB + 77])
+def test_scatter_allgather_piece_edges(noise, P, M):
+    """Pieces of ceil(M/P) bytes: short last pieces, empty pieces (M < P), odd sizes."""
+    info = run_and_check(P, P - 1, M, 0, B.BCAST_ALGO_SCATTER_ALLGATHER, noise)
+    rounds = (P - 1).bit_length()
+    assert info["launches"] == rounds + P - 1 and info["chunk_bytes"] == -(-M // P)
+    # the traffic the library accounts for equals what the oracle's schedule moves
+    assert info["algorithmic_bytes"] == 2 * oracle.scatter_allgather_bcast(None, P, P - 1, M).bytes_copied
 
 
 def test_degenerate_cases(noise):
