@@ -97,6 +97,8 @@ def _bind(path):
     lib.oracle_direct_bcast.restype = ctypes.c_long
     lib.oracle_binomial_bcast.argtypes = [pp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, tp]
     lib.oracle_binomial_bcast.restype = ctypes.c_long
+    lib.oracle_knomial_bcast.argtypes = [pp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, tp]
+    lib.oracle_knomial_bcast.restype = ctypes.c_long
     lp = ctypes.POINTER(ctypes.c_long)
     lib.oracle_scatter_allgather_bcast.argtypes = [pp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, lp, lp, tp]
     lib.oracle_scatter_allgather_bcast.restype = ctypes.c_long
@@ -197,6 +199,13 @@ def binomial_bcast(bufs: Optional[np.ndarray], P: int, root: int, M: int, trace:
     """Binomial tree (Sec. III-A, Eq. 3 with k = 2)."""
     tb = _TraceBuf(P, trace, P, 1)
     n = _check(_load().oracle_binomial_bcast(_row_pointers(bufs, P, M), P, root, M, ctypes.byref(tb.c)), "binomial_bcast")
+    return tb.result(n)
+
+
+def knomial_bcast(bufs: Optional[np.ndarray], P: int, root: int, M: int, k: int, trace: bool = False) -> Result:
+    """K-nomial tree (Sec. III-A, Eq. 3) with radix k."""
+    tb = _TraceBuf(P, trace, P, 1)
+    n = _check(_load().oracle_knomial_bcast(_row_pointers(bufs, P, M), P, root, M, k, ctypes.byref(tb.c)), "knomial_bcast")
     return tb.result(n)
 
 

@@ -124,6 +124,25 @@ long oracle_binomial_bcast(unsigned char **bufs, int P, int root, size_t M, orac
     return rounds;
 }
 
+long oracle_knomial_bcast(unsigned char **bufs, int P, int root, size_t M, int k, oracle_trace_t *tr)
+{
+    if (bad_common(P, root) || k < 2) return -1;
+    trace_reset(tr);
+    long rounds = 0;
+    /* before round j the holders are exactly positions 0 .. reach - 1, reach = k^j */
+    for (long reach = 1; reach < P; reach *= k) {
+        for (long q = 0; q < reach; q++)
+            for (long i = 1; i < k; i++) {
+                long child = q + i * reach;
+                if (child < P)
+                    transfer(bufs, tr, rounds, rank_at(root, (int)q, P), rank_at(root, (int)child, P),
+                             0, 0, M);
+            }
+        rounds++;
+    }
+    return rounds;
+}
+
 long oracle_scatter_allgather_bcast(unsigned char **bufs, int P, int root, size_t M,
                                     long *scatter_rounds, long *ring_steps, oracle_trace_t *tr)
 {

@@ -75,6 +75,14 @@ long oracle_direct_bcast(unsigned char **bufs, int P, int root, size_t M,
 long oracle_binomial_bcast(unsigned char **bufs, int P, int root, size_t M,
                            oracle_trace_t *tr);
 
+/* K-nomial tree (Sec. III-A, Eq. 3, general radix k >= 2): before round j the
+ * holders are chain positions 0 .. k^j - 1; in round j every holder q sends the
+ * whole message to q + i * k^j for i = 1 .. k-1 (where that position exists).
+ * All sends of a round count as one step of Eq. 3.  k = 2 is the binomial tree.
+ * Returns the number of rounds, ceil(log_k P), or -1 on bad arguments. */
+long oracle_knomial_bcast(unsigned char **bufs, int P, int root, size_t M, int k,
+                          oracle_trace_t *tr);
+
 /* Scatter + ring allgather (Sec. III-A, Eq. 4): the message is cut into P
  * pieces of ceil(M/P) bytes (piece q may be short or empty); a binomial
  * scatter leaves position q holding piece q, then P - 1 ring steps pass

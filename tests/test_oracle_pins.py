@@ -129,6 +129,8 @@ def pin_golden_counts():
             got = oracle.direct_bcast(None, n, 0, M).steps
         elif kind == "scatter_allgather":
             got = oracle.scatter_allgather_bcast(None, n, 0, M).steps
+        elif kind.startswith("knomial"):
+            got = oracle.knomial_bcast(None, n, 0, M, int(kind[len("knomial"):])).steps
         else:
             raise AssertionError(kind)
         assert got == want, (kind, n, M, C, got, want)
@@ -161,6 +163,28 @@ def pin_variants_end_state_and_counts(maxP=9):
                 for k in range(1, P):
                     j = k.bit_length() - 1  # floor(log2 k): the round in which k is reached
                     assert got_from[k] == (k - (1 << j), j), (P, k, got_from[k])
+
+                for k in (2, 3, 4, 8):
+                    b = before.copy()
+                    r = oracle.knomial_bcast(b, P, root, M, k, trace=True)
+                    assert np.array_equal(b, exp), (P, root, M, k)
+                    rounds, reach = 0, 1
+                    while reach < P:
+                        reach *= k
+                        rounds += 1
+                    assert r.steps == rounds and r.bytes_copied == (P - 1) * M
+                    got_from = {}
+                    for t in r.transfers:
+                        q = (t.dst_rank - root) % P
+                        assert q not in got_from and q != 0
+                        got_from[q] = ((t.src_rank - root) % P, t.step)
+                    for q in range(1, P):
+                        j, top = 0, 1  # top = k^j with k^j <= q < k^(j+1)
+                        while top * k <= q:
+                            top *= k
+                            j += 1
+                        # the parent is q without its leading base-k digit; reached in round j
+                        assert got_from[q] == (q % top, j), (P, k, q, got_from[q])
 
                 b = before.copy()
                 r = oracle.scatter_allgather_bcast(b, P, root, M, trace=True)
@@ -273,6 +297,9 @@ MUTANTS = [
     ("wrong_chunk_offset", "size_t lo = (size_t)c * C;", "size_t lo = (size_t)(c + 1) * C;"),
     ("binomial_wrong_child", "long child = q + reach;", "long child = q + reach + 1;"),
     ("binomial_linear_rounds", "for (long reach = 1; reach < P; reach *= 2) {", "for (long reach = 1; reach < P; reach += 1) {"),
+    ("knomial_skips_last_child", "for (long i = 1; i < k; i++) {", "for (long i = 1; i < k - 1; i++) {"),
+    ("knomial_wrong_stride", "long child = q + i * reach;", "long child = q + i * (reach + 1);"),
+    ("knomial_reach_doubles", "for (long reach = 1; reach < P; reach *= k) {", "for (long reach = 1; reach < P; reach *= 2) {"),
     ("direct_skips_last", "for (int k = 1; k < P; k++) {\n        transfer(bufs, tr, sends, root,",
      "for (int k = 1; k < P - 1; k++) {\n        transfer(bufs, tr, sends, root,"),
     ("ring_wrong_piece", "long pc = ((q - t) % P + P) % P;", "long pc = ((q + t) % P + P) % P;"),
