@@ -45,7 +45,8 @@ typedef enum {
     BCAST_ALGO_DIRECT = 2,   /* root copies to each other rank in turn, Sec. III-A Eq. 1 */
     BCAST_ALGO_BINOMIAL = 3, /* binomial tree, Sec. III-A Eq. 3 with k = 2 */
     BCAST_ALGO_FANOUT = 4,   /* one-die shortcut: read root once, store to all ranks (no paper equivalent) */
-    BCAST_ALGO_SCATTER_ALLGATHER = 5 /* binomial scatter + ring allgather, Sec. III-A Eq. 4 */
+    BCAST_ALGO_SCATTER_ALLGATHER = 5, /* binomial scatter + ring allgather, Sec. III-A Eq. 4 */
+    BCAST_ALGO_KNOMIAL = 6   /* k-nomial tree, Sec. III-A Eq. 3, radix from bcast_plan_set_radix (default 4) */
 } bcast_algo_t;
 
 typedef enum {
@@ -82,7 +83,7 @@ typedef struct {
  *   chunk_bytes chunk size C for CHAIN: a positive multiple of 16; values
  *               >= bytes give the unpipelined chain (Eq. 2).  0 = choose: the
  *               tuning table's entry if one is loaded, else a built-in rule.
- *               Ignored by DIRECT, BINOMIAL, FANOUT and SCATTER_ALLGATHER
+ *               Ignored by DIRECT, BINOMIAL, KNOMIAL, FANOUT and SCATTER_ALLGATHER
  *               (whose piece size is ceil(bytes / nranks)).
  *   algo        a bcast_algo_t.  AUTO resolves per run from the tuning table and
  *               fails with BCAST_ERR_UNTUNED if no table covers nranks.
@@ -143,6 +144,9 @@ int bcast_plan_destroy(bcast_plan_t *plan);
  * 0 = off.  Kernels always run to completion under these settings. */
 int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
 int bcast_plan_set_stages(bcast_plan_t *plan, int stages);
+/* Radix k of BCAST_ALGO_KNOMIAL, 2..nranks (0 = the tuning table's, else 4):
+ * in round j every position q < k^j sends to q + i k^j, i = 1..k-1. */
+int bcast_plan_set_radix(bcast_plan_t *plan, int radix);
 int bcast_plan_set_debug(bcast_plan_t *plan, uint64_t spin_limit_ticks, int mute_hop);
 
 /* Chain kernel modes (bit mask).  BCAST_MODE_COUNT: count the hand-offs whose
@@ -169,7 +173,8 @@ int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_w
  *
  * bcast_tune measures, on the current device and `stream`, every candidate
  * (chain over chunk sizes 8 KiB..64 MiB and stage counts, direct, binomial, and
- * -- only if `algo_mask` has their bits -- the fan-out and scatter + allgather) for message sizes that are
+ * -- only if `algo_mask` has their bits -- the fan-out, scatter + allgather and
+ * the k-nomial tree at radix 4 and 8) for message sizes that are
  * powers of two in [min_bytes, max_bytes], keeps the fastest per size, installs
  * the entries, and, if table_path (HOST, nullable) is given, appends them there
  * as text.  It allocates nranks scratch buffers of max_bytes itself.
@@ -187,7 +192,7 @@ int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsigned algo_mas
 typedef struct {
     int algo;                   /* winner: bcast_algo_t */
     uint64_t chunk_bytes;       /* winner's chunk size (chain only) */
-    int stages;                 /* winner's stage count (chain only) */
+    int stages;                 /* winner's stage count (chain) or radix (k-nomial) */
     double usec;                /* winner's measured time */
     uint64_t chain_chunk_bytes; /* chain: best chunk size (0 = not measured) */
     int chain_stages;           /* chain: best stage count */

@@ -25,7 +25,8 @@ BCAST_ALGO_DIRECT = 2
 BCAST_ALGO_BINOMIAL = 3
 BCAST_ALGO_FANOUT = 4
 BCAST_ALGO_SCATTER_ALLGATHER = 5
-ALGO_NAMES = {0: "auto", 1: "chain", 2: "direct", 3: "binomial", 4: "fanout", 5: "scatter_allgather"}
+BCAST_ALGO_KNOMIAL = 6
+ALGO_NAMES = {0: "auto", 1: "chain", 2: "direct", 3: "binomial", 4: "fanout", 5: "scatter_allgather", 6: "knomial"}
 
 BCAST_OK = 0
 BCAST_ERR_ARG = -1
@@ -37,7 +38,7 @@ BCAST_ERR_UNTUNED = -5
 # every symbol include/bcast.h declares
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_debug", "bcast_plan_set_mode",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_set_mode",
     "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
@@ -109,6 +110,7 @@ def _load():
         "bcast_plan_destroy": ([vp], i),
         "bcast_plan_set_lanes": ([vp, i], i),
         "bcast_plan_set_stages": ([vp, i], i),
+        "bcast_plan_set_radix": ([vp, i], i),
         "bcast_plan_set_debug": ([vp, u64, i], i),
         "bcast_plan_set_mode": ([vp, ctypes.c_uint], i),
         "bcast_plan_handoff_counts": ([vp, ctypes.POINTER(u64), ctypes.POINTER(u64)], i),
@@ -229,6 +231,10 @@ def bcast_plan_set_lanes(plan: Plan, lanes: int) -> None:
 
 def bcast_plan_set_stages(plan: Plan, stages: int) -> None:
     _check(_lib.bcast_plan_set_stages(plan.handle, stages), "bcast_plan_set_stages")
+
+
+def bcast_plan_set_radix(plan: Plan, radix: int) -> None:
+    _check(_lib.bcast_plan_set_radix(plan.handle, radix), "bcast_plan_set_radix")
 
 
 def bcast_plan_set_debug(plan: Plan, spin_limit_ticks: int, mute_hop: int) -> None:

@@ -29,6 +29,7 @@ struct bcast_plan {
     u64 epoch = 0;
     int lanes_request = 0;
     int stages_request = 0;
+    int radix_request = 0;
     u64 spin_ticks = kDefaultSpinTicks;
     int mute_hop = 0;
 };
@@ -136,7 +137,7 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
     if (!out) return BCAST_ERR_ARG;
     *out = nullptr;
     if (nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
-    if (algo < BCAST_ALGO_AUTO || algo > BCAST_ALGO_SCATTER_ALLGATHER) return BCAST_ERR_ARG;
+    if (algo < BCAST_ALGO_AUTO || algo > BCAST_ALGO_KNOMIAL) return BCAST_ERR_ARG;
     if (chunk_bytes % 16 != 0) return BCAST_ERR_ARG;
 
     bcast_plan *p = new (std::nothrow) bcast_plan;
@@ -212,6 +213,13 @@ extern "C" int bcast_plan_set_stages(bcast_plan_t *p, int stages)
     return BCAST_OK;
 }
 
+extern "C" int bcast_plan_set_radix(bcast_plan_t *p, int radix)
+{
+    if (!p || radix < 0 || radix == 1 || radix > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
+    p->radix_request = radix;
+    return BCAST_OK;
+}
+
 extern "C" int bcast_plan_set_debug(bcast_plan_t *p, uint64_t spin_limit_ticks, int mute_hop)
 {
     if (!p || mute_hop < 0 || mute_hop >= BCAST_MAX_RANKS) return BCAST_ERR_ARG;
@@ -274,6 +282,7 @@ struct Resolved {
     int algo;
     u64 chunk;
     int stages;  // 0 = built-in rule
+    int radix;   // k-nomial only
 };
 
 // Without a measurement: two stages (hops 1..h | h+1..P-1).  On one die the
@@ -305,6 +314,14 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
     } else if (p->algo == BCAST_ALGO_CHAIN && r->chunk == 0 && tuned && e.chain_chunk_bytes != 0) {
         r->chunk = e.chain_chunk_bytes;
         if (r->stages == 0) r->stages = e.chain_stages;
+    }
+    r->radix = p->radix_request;
+    if (r->algo == BCAST_ALGO_KNOMIAL) {
+        // an AUTO plan takes the radix the table recorded (in the stages column)
+        if (r->radix == 0 && p->algo == BCAST_ALGO_AUTO && tuned && e.algo == BCAST_ALGO_KNOMIAL) r->radix = e.stages;
+        if (r->radix < 2) r->radix = 4;
+        r->radix = std::min(r->radix, std::max(2, p->nranks));
+        r->stages = 0;
     }
     if (r->algo == BCAST_ALGO_CHAIN) {
         if (r->stages == 0) r->stages = default_stages(p->nranks);
@@ -405,6 +422,15 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
         int rounds = 0;
         for (int reach = 1; reach < P; reach *= 2) ++rounds;
         info->launches = rounds;
+        info->grid_blocks = copy_grid(p, bytes, 1);
+        info->algorithmic_bytes = 2ull * (P - 1) * bytes;
+        break;
+    }
+    case BCAST_ALGO_KNOMIAL: {
+        int rounds = 0;
+        for (long reach = 1; reach < P; reach *= r.radix) ++rounds;
+        info->launches = rounds;
+        info->stages = r.radix;  // reported here: the tree's radix
         info->grid_blocks = copy_grid(p, bytes, 1);
         info->algorithmic_bytes = 2ull * (P - 1) * bytes;
         break;
@@ -531,6 +557,29 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
     }
     if (info.algo == BCAST_ALGO_FANOUT) {
         HIP_TRY(launch_fanout(c, info.vec_bytes, info.grid_blocks, stream));
+        return BCAST_OK;
+    }
+    if (info.algo == BCAST_ALGO_KNOMIAL) {
+        // round j: every holder q < k^j sends to q + i k^j, i = 1..k-1 (Eq. 3); all
+        // copies of a round go out in one launch, stream order is the round barrier
+        const int k = info.stages;
+        if (k < 2) return BCAST_ERR_ARG;
+        for (long reach = 1; reach < P; reach *= k) {
+            RangedCopyArgs ra;
+            memset(&ra, 0, sizeof ra);
+            memcpy(ra.buf, by_pos, sizeof(char *) * P);
+            for (long q = 0; q < reach; ++q)
+                for (long i = 1; i < k; ++i) {
+                    const long child = q + i * reach;
+                    if (child >= P) continue;
+                    const unsigned n = ra.npairs++;
+                    ra.src_pos[n] = (unsigned char)q;
+                    ra.dst_pos[n] = (unsigned char)child;
+                    ra.lo[n] = 0;
+                    ra.hi[n] = bytes;
+                }
+            HIP_TRY(launch_ranged_copy(ra, info.vec_bytes, copy_grid(p, bytes, (int)ra.npairs), stream));
+        }
         return BCAST_OK;
     }
     if (info.algo == BCAST_ALGO_SCATTER_ALLGATHER) {

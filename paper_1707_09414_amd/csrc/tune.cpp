@@ -30,7 +30,7 @@ static std::string g_log_path;  // if set, bcast_tune appends every candidate it
 
 using namespace bcast;
 
-static bool valid_algo(int algo) { return algo >= BCAST_ALGO_CHAIN && algo <= BCAST_ALGO_SCATTER_ALLGATHER; }
+static bool valid_algo(int algo) { return algo >= BCAST_ALGO_CHAIN && algo <= BCAST_ALGO_KNOMIAL; }
 
 static bool valid_entry(int nranks, const bcast_tune_entry_t &e)
 {
@@ -122,10 +122,11 @@ extern "C" int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *ch
 }
 
 static const char kHeaderLine[] =
-    "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout 5=scatter-allgather) chunk_bytes usec "
+    "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout 5=scatter-allgather 6=knomial) chunk_bytes usec "
     "chain_chunk_bytes chain_usec stages chain_stages\n";
 
-// Text format, one entry per line (the last four columns are optional):
+// Text format, one entry per line (the last four columns are optional; for a
+// k-nomial winner the stages column holds the radix):
 //   nranks log2_bytes algo chunk_bytes usec [chain_chunk_bytes chain_usec [stages chain_stages]]
 // Lines starting with '#' are comments.
 static void print_entry(FILE *f, int nranks, int bucket, const bcast_tune_entry_t &e)
@@ -206,7 +207,7 @@ int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages,
     bcast_plan_t *plan = nullptr;
     int rc = bcast_plan_create(&plan, nranks, bytes, chunk, algo);
     if (rc != BCAST_OK) return rc;
-    rc = bcast_plan_set_stages(plan, stages);
+    rc = algo == BCAST_ALGO_KNOMIAL ? bcast_plan_set_radix(plan, stages) : bcast_plan_set_stages(plan, stages);
     int reps = 1;
     double best = 1e30;
     for (int batch = 0; batch < 4 && rc == BCAST_OK; ++batch) {
@@ -298,7 +299,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
             if (us < best.usec) {
                 best.algo = algo;
                 best.chunk_bytes = chunk;
-                best.stages = algo == BCAST_ALGO_CHAIN ? stages : 0;
+                best.stages = (algo == BCAST_ALGO_CHAIN || algo == BCAST_ALGO_KNOMIAL) ? stages : 0;
                 best.usec = us;
             }
         };
@@ -320,6 +321,8 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         consider(BCAST_ALGO_BINOMIAL, 0, 0);
         consider(BCAST_ALGO_FANOUT, 0, 0);
         consider(BCAST_ALGO_SCATTER_ALLGATHER, 0, 0);
+        for (int k : {4, 8})
+            if (k < nranks) consider(BCAST_ALGO_KNOMIAL, 0, k);  // radix travels in the stages column
         if (rc != BCAST_OK) break;
         if (best.chain_chunk_bytes == 0) best.chain_usec = 0.0;
         rc = bcast_tune_put(nranks, M, &best);

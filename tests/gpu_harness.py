@@ -80,7 +80,7 @@ def assert_same(got, exp, what):
                                  % (what, r, bad.size, bad[0], g[bad[0]], e[bad[0]]))
 
 
-def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0, stream=None, plan=None, stages=0):
+def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0, stream=None, plan=None, stages=0, radix=0):
     """One broadcast on the GPU, compared byte for byte (guards included) with
     the oracle's end state.  Returns the plan info used."""
     cap = M if cap is None else cap
@@ -95,6 +95,8 @@ def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0,
             B.bcast_plan_set_lanes(plan, lanes)
         if stages:
             B.bcast_plan_set_stages(plan, stages)
+        if radix:
+            B.bcast_plan_set_radix(plan, radix)
         info = B.bcast_plan_info(plan, M, rb.ptrs())
         B.bcast_run(plan, rb.ptrs(), root, M, stream)
         got = rb.to_host()
@@ -104,6 +106,12 @@ def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0,
         if own:
             plan.destroy()
     starts = [rb.start(r) for r in range(P)]
-    exp, _ = expected_with_oracle(before, starts, root, M, oracle_schedule(info["algo"], P, root, M, info["chunk_bytes"]))
+    if info["algo"] == B.BCAST_ALGO_KNOMIAL:
+        schedule = lambda a: oracle.knomial_bcast(a, P, root, M, max(2, info["stages"]))
+    else:
+        schedule = oracle_schedule(info["algo"], P, root, M, info["chunk_bytes"])
+    exp, res = expected_with_oracle(before, starts, root, M, schedule)
+    if info["algo"] == B.BCAST_ALGO_KNOMIAL and P > 1 and M > 0:
+        assert info["launches"] == res.steps, "one launch per k-nomial round"
     assert_same(got, exp, "P=%d root=%d M=%d C=%d algo=%d offsets=%s" % (P, root, M, C, algo, offsets))
     return info

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 KiB, MiB = inputs.KiB, inputs.MiB
 ALGOS = [B.BCAST_ALGO_CHAIN, B.BCAST_ALGO_DIRECT, B.BCAST_ALGO_BINOMIAL, B.BCAST_ALGO_FANOUT,
-         B.BCAST_ALGO_SCATTER_ALLGATHER]
+         B.BCAST_ALGO_SCATTER_ALLGATHER, B.BCAST_ALGO_KNOMIAL]
 
 
 @pytest.fixture(scope="module")
@@ -87,6 +87,13 @@ def test_scatter_allgather_piece_edges(noise, P, M):
     assert info["launches"] == rounds + P - 1 and info["chunk_bytes"] == -(-M // P)
     # the traffic the library accounts for equals what the oracle's schedule moves
     assert info["algorithmic_bytes"] == 2 * oracle.scatter_allgather_bcast(None, P, P - 1, M).bytes_copied
+
+
+@pytest.mark.parametrize("P,radix", [(2, 2), (5, 3), (9, 3), (10, 3), (16, 4), (17, 4), (64, 4), (64, 8), (64, 64), (33, 2), (7, 9)])
+@pytest.mark.parametrize("M", [9, 4096, MiB + 3])
+def test_knomial_radices(noise, P, radix, M):
+    info = run_and_check(P, P // 2, M, 0, B.BCAST_ALGO_KNOMIAL, noise, radix=radix)
+    assert info["stages"] == min(radix, max(2, P))
 
 
 def test_degenerate_cases(noise):
