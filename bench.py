@@ -33,6 +33,7 @@ WORKLOADS = {
     "cfg3": (16, 0, 553430176, 2, "VGG-16 parameters packed (138M fp32, N(0,0.01)), P=16"),
     "cfg4": (32, 0, 512 * MiB, 3, "512 MiB random bytes, P=32"),
     "cfg5": (64, 17, 1 * GiB, 4, "1 GiB random bytes, P=64, root 17"),
+    "cfg5b": (64, 17, 4 * KiB, 4, "4 KiB random bytes back to back, P=64, root 17 (use --steps 1000)"),
 }
 
 # HBM traffic per launch of the dominant kernel, measured with rocprofv3 --pmc

@@ -98,7 +98,7 @@ template <int LD, int ST> struct AgentIO<1, LD, ST> {
 // kChainUnroll stores per lane with no remainder loop: the body's descriptors
 // end exactly at the last whole vector, so a lane whose offset lies beyond it
 // is range-checked by the hardware (the load returns zero, the store is
-// dropped).  A short slice therefore costs one memory round trip, not one per
+// dropped).  A short span therefore costs one memory round trip, not one per
 // kilobyte.
 template <int V, int LD = kAuxAgent, int ST = kAuxAgent>
 __device__ __forceinline__ void copy_span_agent(char *dst, const char *src, u64 lo, u64 hi, unsigned lane)
@@ -177,27 +177,31 @@ __device__ __forceinline__ void fanout_span(const CopyArgs &a, u64 lo, u64 hi, u
 }
 
 // ---------------------------------------------------------------------------
-// Pipelined chain (Sec. IV-B).  Wavefront (hop, lane) receives lane's slice of
-// every chunk from position hop-1 into position hop and then publishes it to
-// position hop+1 -- the receive / store / forward loop of a middle rank.
+// Pipelined chain (Sec. IV-B).  The P-1 hops are grouped into stages of
+// consecutive hops; wavefront (stage, lane) receives lane's share of every
+// chunk into the first position of its stage from the position before it,
+// carries it through the stage's positions (each read out of the previous
+// position's buffer), and publishes it to the next stage -- the receive /
+// store / forward loop of a middle rank, with one wave playing the ranks of
+// its stage in turn.  With one hop per stage every rank has waves of its own.
 // Position 0 (the root) only sends: nobody writes its buffer.  The last
-// position only receives: it publishes nothing.
+// position only receives: its stage publishes nothing.
 //
-// Hand-off protocol.  flag(hop, lane) counts the chunks of this run that
-// position `hop` has stored for `lane`, as base + count with base = epoch<<32;
-// flags only grow, so nothing is reset between runs.  Producer: the wave waits
-// until all of its (write-through, agent-scope) payload stores have completed
-// -- one s_waitcnt for the whole wave, so it covers every lane's stores -- and
-// then lane 0 stores the flag (agent scope).  Consumer: polls the flag with
-// agent-scope loads (one address per wave); the payload loads are issued only
-// after a poll has returned the awaited value, and, being agent-scope
-// themselves, cannot be served from a stale cache line.
+// Hand-off protocol.  flag(stage, lane) counts the chunks of this run that the
+// stage's last position has stored for `lane`, as base + (count << 4) + xcd
+// with base = epoch << 32; flags only grow, so nothing is reset between runs.
+// Producer: the wave waits until all of its (write-through, agent-scope)
+// payload stores have completed -- one s_waitcnt for the whole wave, so it
+// covers every lane's stores -- and then lane 0 stores the flag (agent scope).
+// Consumer: lane 0 polls the flag with agent-scope loads; the payload loads are
+// issued only after a poll has returned the awaited value, and, being
+// agent-scope themselves, cannot be served from a stale cache line.
 //
-// Forward progress.  Wavefronts are numbered hop-major, so a wave only ever
+// Forward progress.  Wavefronts are numbered stage-major, so a wave only ever
 // waits for a wave with a lower workgroup index; the host also keeps the grid
 // within what the device can hold at once.  Every wait is bounded by a clock
-// limit: a wave that gives up records (hop, chunk), raises the abort word so
-// that the others stop waiting too, and returns.
+// limit: a wave that gives up records (first hop of its stage, chunk), raises
+// the abort word so that the others stop waiting too, and returns.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void report_timeout(const ChainArgs &a, unsigned hop, unsigned chunk)
 {
