@@ -73,6 +73,7 @@ def main() -> int:
     ap.add_argument("--stages", type=int, default=0, help="chain stages (0 = tuned table / built-in rule)")
     ap.add_argument("--ranks", type=int, default=0, help="override the workload's P (experiments)")
     ap.add_argument("--bytes", type=int, default=0, help="override the workload's message size (experiments)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the per-message-size latency table (cfg2 only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true")
     args = ap.parse_args()
@@ -166,6 +167,10 @@ def main() -> int:
     custom = bool(args.ranks or args.bytes or args.chunk or args.lanes or args.stages)
     traffic = None if custom else MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo))
 
+    sweep = None
+    if args.workload == "cfg2" and not custom and not args.no_sweep:
+        sweep = size_sweep(B, torch, bufs, P, root, M, stream)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(P, root, M, int(info["chunk_bytes"]) or M, msg)
@@ -207,10 +212,48 @@ def main() -> int:
             "median_launch_ms": round(med_launch_ms, 5),
         },
         "cpu_baseline": cpu,
+        "sweep": sweep,
     }
     print(json.dumps(out))
     plan.destroy()
     return 0
+
+
+def size_sweep(B, torch, bufs, P, root, max_bytes, stream):
+    """Latency per message size (4 B .. the workload's size, powers of two) at the
+    workload's P, measured live: the tuned choice (AUTO) and the chain, each as
+    the mean of a batch of back-to-back runs between two HIP events."""
+    rows = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def time_plan(plan, M):
+        reps = 200 if M <= (1 << 20) else 20
+        for _ in range(3):
+            B.bcast_run(plan, bufs, root, M, stream)
+        e0.record(stream)
+        for _ in range(reps):
+            B.bcast_run(plan, bufs, root, M, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps  # microseconds
+
+    M = 4
+    while M <= max_bytes:
+        auto = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_AUTO)
+        chain = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_CHAIN)
+        ai = B.bcast_plan_info(auto, M, bufs)
+        ci = B.bcast_plan_info(chain, M, bufs)
+        a_us, c_us = time_plan(auto, M), time_plan(chain, M)
+        rows.append({
+            "bytes": M, "auto_algo": B.ALGO_NAMES[ai["algo"]], "auto_us": round(a_us, 2),
+            "chain_us": round(c_us, 2), "chain_chunk_bytes": int(ci["chunk_bytes"]), "chain_stages": ci["stages"],
+            "chain_GBps": round(2 * (P - 1) * M / c_us / 1e3, 1),
+            "chain_frac_of_peak": round(2 * (P - 1) * M / c_us / 1e3 / HBM_PEAK_GBS, 4),
+        })
+        auto.destroy()
+        chain.destroy()
+        M *= 2
+    return rows
 
 
 def cpu_baseline(P, root, M, C, msg):

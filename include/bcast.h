@@ -155,6 +155,17 @@ int bcast_plan_set_debug(bcast_plan_t *plan, uint64_t spin_limit_ticks, int mute
  * The counts accumulate over runs.  Diagnostic: it slows the kernel down. */
 #define BCAST_MODE_COUNT 2u
 int bcast_plan_set_mode(bcast_plan_t *plan, unsigned mode);
+
+/* Pipeline trace (diagnostic).  After bcast_plan_enable_trace(plan, entries),
+ * every chain run records, for the first `entries` (stage, chunk) pairs in
+ * stage-major order (index = stage * nchunks + chunk), the 100 MHz device
+ * clock at which lane 0's wavefront of the stage began copying the chunk (after
+ * its wait) and at which all its stores for the chunk had completed.
+ * bcast_plan_read_trace synchronises the device and copies `entries` pairs
+ * [begin, end] into `out` (HOST, 2 * entries words).  entries == 0 turns the
+ * trace off.  Each run overwrites the previous one's record. */
+int bcast_plan_enable_trace(bcast_plan_t *plan, size_t entries);
+int bcast_plan_read_trace(bcast_plan_t *plan, uint64_t *out, size_t entries);
 int bcast_plan_handoff_counts(bcast_plan_t *plan, uint64_t *same_xcd, uint64_t *cross_xcd);
 
 /*

@@ -38,7 +38,7 @@ BCAST_ERR_UNTUNED = -5
 # every symbol include/bcast.h declares
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_set_mode",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
     "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
@@ -113,6 +113,8 @@ def _load():
         "bcast_plan_set_radix": ([vp, i], i),
         "bcast_plan_set_debug": ([vp, u64, i], i),
         "bcast_plan_set_mode": ([vp, ctypes.c_uint], i),
+        "bcast_plan_enable_trace": ([vp, sz], i),
+        "bcast_plan_read_trace": ([vp, ctypes.POINTER(u64), sz], i),
         "bcast_plan_handoff_counts": ([vp, ctypes.POINTER(u64), ctypes.POINTER(u64)], i),
         "bcast_chain_geometry": ([i, sz, sz, i, i, i, ctypes.POINTER(PlanInfo)], i),
         "bcast_tune": ([i, sz, sz, ctypes.c_uint, vp, ctypes.c_char_p], i),
@@ -246,6 +248,17 @@ BCAST_MODE_COUNT = 2
 
 def bcast_plan_set_mode(plan: Plan, mode: int) -> None:
     _check(_lib.bcast_plan_set_mode(plan.handle, mode), "bcast_plan_set_mode")
+
+
+def bcast_plan_enable_trace(plan: Plan, entries: int) -> None:
+    _check(_lib.bcast_plan_enable_trace(plan.handle, entries), "bcast_plan_enable_trace")
+
+
+def bcast_plan_read_trace(plan: Plan, entries: int):
+    """[(begin, end)] device-clock ticks (100 MHz) per (stage, chunk), stage-major."""
+    buf = (ctypes.c_uint64 * (2 * entries))()
+    _check(_lib.bcast_plan_read_trace(plan.handle, buf, entries), "bcast_plan_read_trace")
+    return [(buf[2 * i], buf[2 * i + 1]) for i in range(entries)]
 
 
 def bcast_plan_handoff_counts(plan: Plan) -> Tuple[int, int]:

@@ -23,6 +23,8 @@ struct bcast_plan {
     u64 *d_flags = nullptr;  // max_waves flags, kFlagStrideWords apart, plus the abort word
     u64 *d_abort = nullptr;
     u64 *d_counters = nullptr; // two words after the abort word
+    u64 *d_trace = nullptr;    // optional (bcast_plan_enable_trace)
+    size_t trace_entries = 0;
     unsigned mode = 0;
     u64 *h_status = nullptr; // pinned host: [0] timeout seen, [1] hop<<32|chunk
     u64 *d_status = nullptr; // the same two words as the device sees them
@@ -194,6 +196,7 @@ extern "C" int bcast_plan_destroy(bcast_plan_t *p)
     hipError_t e = hipDeviceSynchronize();
     if (e != hipSuccess) rc = hip_fail(e);
     if (p->d_flags && (e = hipFree(p->d_flags)) != hipSuccess) rc = hip_fail(e);
+    if (p->d_trace && (e = hipFree(p->d_trace)) != hipSuccess) rc = hip_fail(e);
     if (p->h_status && (e = hipHostFree(p->h_status)) != hipSuccess) rc = hip_fail(e);
     delete p;
     return rc;
@@ -232,6 +235,30 @@ extern "C" int bcast_plan_set_mode(bcast_plan_t *p, unsigned mode)
 {
     if (!p || (mode & ~kModeCount)) return BCAST_ERR_ARG;
     p->mode = mode;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_enable_trace(bcast_plan_t *p, size_t entries)
+{
+    if (!p || entries > ((size_t)1 << 24)) return BCAST_ERR_ARG;
+    HIP_TRY(hipDeviceSynchronize());
+    if (p->d_trace) {
+        HIP_TRY(hipFree(p->d_trace));
+        p->d_trace = nullptr;
+        p->trace_entries = 0;
+    }
+    if (entries == 0) return BCAST_OK;
+    HIP_TRY(hipMalloc((void **)&p->d_trace, entries * 2 * sizeof(u64)));
+    HIP_TRY(hipMemset(p->d_trace, 0, entries * 2 * sizeof(u64)));
+    p->trace_entries = entries;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_read_trace(bcast_plan_t *p, uint64_t *out, size_t entries)
+{
+    if (!p || !out || !p->d_trace || entries > p->trace_entries) return BCAST_ERR_ARG;
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(out, p->d_trace, entries * 2 * sizeof(u64), hipMemcpyDeviceToHost));
     return BCAST_OK;
 }
 
@@ -498,8 +525,11 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         a.flags = p->d_flags;
         a.abort_word = p->d_abort;
         a.counters = p->d_counters;
+        a.trace = p->d_trace;
+        a.trace_entries = p->trace_entries;
         a.mode = p->mode;
         if (bytes <= kStageCachedMaxBytes) a.mode |= kModeStageCached;
+        if (p->d_trace) a.mode |= kModeTrace;
         a.status = p->d_status;
         a.base = (++p->epoch) << 32;
         a.bytes = bytes;

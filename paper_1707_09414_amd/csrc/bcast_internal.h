@@ -41,6 +41,8 @@ struct ChainArgs {
     u64 *flags;        // device: [(nranks-1) * lanes] flags, kFlagStrideWords apart
     u64 *abort_word;   // device: set to the run's epoch when a wave gives up
     u64 *status;       // pinned host, device-visible: [0] = 1 on timeout, [1] = hop<<32|chunk
+    u64 *trace;        // device: [stage][chunk][begin, end] clock values of lane 0's wave (kModeTrace)
+    u64 trace_entries; // (stage, chunk) pairs the trace buffer holds
     u64 *counters;     // device: [0] hand-offs within an XCD, [1] across XCDs (kModeCount)
     u64 base;          // epoch << 32; chunk c of this run is ready when flag >= base + ((c + 1) << 4)
     u64 bytes;         // M
@@ -60,6 +62,8 @@ struct ChainArgs {
 // Diagnostic only: every wave ends with two atomics on one cache line, which
 // costs tens of microseconds at full occupancy.
 constexpr unsigned kModeCount = 2;
+// Lane 0's wave of every stage records when it begins and ends each chunk.
+constexpr unsigned kModeTrace = 8;
 // Chosen by the host per run (small messages): cached accesses inside a stage.
 constexpr unsigned kModeStageCached = 4;
 // Largest message that uses it (measured crossover on MI355X: 2-4 MiB).

@@ -309,6 +309,8 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
             near += same_xcd;
             far += !same_xcd;
         }
+        const bool traced = (a.mode & kModeTrace) && s == 0 && (u64)g * a.nchunks + c < a.trace_entries;
+        if (traced && lane == 0) a.trace[((u64)g * a.nchunks + c) * 2] = wall_clock64();
         for (unsigned hop = first_hop; hop <= last_hop; ++hop) {
             const char *src = a.buf[hop - 1];
             char *dst = a.buf[hop];
@@ -328,10 +330,13 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
         // Look at the next chunk's flag while this chunk's stores drain: in
         // steady state the left neighbour is ahead and the next wait is free.
         if (in_flag && c + 1 < a.nchunks) seen = read_flag(in_flag, lane);
-        if (out_flag) {
+        if (out_flag || traced) {
             // every payload store of this wave has completed (and, being
             // write-through, is visible device-wide) before the flag is raised
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (traced && lane == 0) a.trace[((u64)g * a.nchunks + c) * 2 + 1] = wall_clock64();
+        }
+        if (out_flag) {
             if (lane == 0)
                 __hip_atomic_store(out_flag, a.base + ((u64)(c + 1) << 4) + xcd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }

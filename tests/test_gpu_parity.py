@@ -250,3 +250,38 @@ def test_handoff_counts_and_xcd_placement(noise):
     for r in range(P):
         assert np.array_equal(got[r][rb.start(r): rb.start(r) + M], noise[:M])
     plan.destroy()
+
+
+@pytest.mark.parametrize("stages", [7, 2])
+def test_chunks_overlap_across_stages_on_the_device(noise, stages):
+    """The point of the pipelined chain (Sec. IV-B): chunk c+1 is received while
+    chunk c is forwarded.  Device timestamps of lane 0's waves must show (a)
+    causality -- a stage begins chunk c only after the stage before it finished
+    storing it -- and (b) overlap -- every stage begins its first chunk before
+    the stage before it has finished its last."""
+    P, M, C = 8, 8 * MiB, 256 * KiB
+    nchunks = M // C
+    rb = RankBuffers(P, M)
+    rb.reset(0, noise[:M])
+    plan = B.bcast_plan_create(P, M, C, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_stages(plan, stages)
+    B.bcast_plan_enable_trace(plan, stages * nchunks)
+    B.bcast_run(plan, rb.ptrs(), 0, M)
+    t = B.bcast_plan_read_trace(plan, stages * nchunks)
+    got = rb.to_host()
+    plan.destroy()
+    for r in range(P):
+        assert np.array_equal(got[r][rb.start(r): rb.start(r) + M], noise[:M])
+    begin = [[t[g * nchunks + c][0] for c in range(nchunks)] for g in range(stages)]
+    end = [[t[g * nchunks + c][1] for c in range(nchunks)] for g in range(stages)]
+    for g in range(stages):
+        for c in range(nchunks):
+            assert 0 < begin[g][c] <= end[g][c]
+            if c:
+                assert end[g][c - 1] <= begin[g][c]
+            if g:
+                assert end[g - 1][c] <= begin[g][c], "stage %d began chunk %d before it was published" % (g, c)
+        if g:
+            assert begin[g][0] < end[g - 1][nchunks - 1], "stage %d did not overlap with stage %d" % (g, g - 1)
+    # Eq. 5's picture: the last stage finishes its first chunk long before the first stage finishes its last
+    assert end[stages - 1][0] < end[0][nchunks - 1]
