@@ -19,7 +19,7 @@ struct bcast_plan {
     int device = 0;
     int cu_count = 0;
     int max_waves = 0;       // wavefronts of the chain kernel the device holds at once
-    int max_waves_cached = 0;  // the same for its small-message (stage-cached) variant
+    int max_waves_cached = 0;  // the same for its small-message (write-back) variant
     u64 *d_flags = nullptr;  // max_waves flags, kFlagStrideWords apart, plus the abort word
     u64 *d_abort = nullptr;
     u64 *d_counters = nullptr; // two words after the abort word
@@ -63,23 +63,25 @@ static void stage_shape(int hops, int request, int *stages, int *hops_per_stage)
     *stages = (hops + *hops_per_stage - 1) / *hops_per_stage;
 }
 
-// A lane (one wavefront per stage) is fed well by 16 KiB of every chunk: two
-// trips of its copy loop per hand-off.  8 KiB is the least worth a lane.
-constexpr u64 kSliceTarget = 16 * 1024;
+// 8 KiB (one trip of the copy loop) is the least worth a lane.
 constexpr u64 kSliceMin = (u64)kChainUnroll * kWaveSize * 16;  // one trip
 
 // Chunk size when the caller gives none and no tuning entry applies.  On one
 // die every hop shares the same HBM, so Eq. 5's fill term (n - 2 idle links)
-// costs little and the hand-off cost per chunk dominates: the best chunk is
-// the one that gives every lane the device can hold about kSliceTarget bytes.
+// costs little.  What matters is how many waves run: a lane gets one 8 KiB
+// trip per chunk, and about 1024 waves in total keep what a wave re-reads
+// inside its stage in the L2 (see chain_kernel).  So: chunk = lanes * 8 KiB
+// with lanes = 1024 / stages, but never more lanes than the device holds.
+constexpr u64 kWavesTarget = 1024;
+
 static u64 default_chunk(int nranks, int max_waves, int stages_request)
 {
     int stages = 1, hps = 1;
     stage_shape(std::max(1, nranks - 1), stages_request, &stages, &hps);
-    u64 lanes_max = std::max(1, max_waves / stages);
-    u64 C = 16 * 1024;
-    while (C * 2 <= lanes_max * kSliceTarget) C *= 2;
-    return C;
+    u64 lanes = std::max<u64>(1, std::min<u64>(kWavesTarget, (u64)max_waves) / (u64)stages);
+    u64 p = 1;
+    while (p * 2 <= lanes) p *= 2;
+    return p * kSliceMin;
 }
 
 extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
@@ -321,7 +323,7 @@ static int default_stages(int nranks) { return std::min(std::max(1, nranks - 1),
 // Co-residency limit of the kernel variant a message of `bytes` bytes will use.
 static int waves_for(const bcast_plan *p, size_t bytes)
 {
-    return bytes <= kStageCachedMaxBytes ? p->max_waves_cached : p->max_waves;
+    return bytes <= kStageWriteBackMaxBytes ? p->max_waves_cached : p->max_waves;
 }
 
 static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
@@ -528,7 +530,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         a.trace = p->d_trace;
         a.trace_entries = p->trace_entries;
         a.mode = p->mode;
-        if (bytes <= kStageCachedMaxBytes) a.mode |= kModeStageCached;
+        if (bytes <= kStageWriteBackMaxBytes) a.mode |= kModeStageWriteBack;
         if (p->d_trace) a.mode |= kModeTrace;
         a.status = p->d_status;
         a.base = (++p->epoch) << 32;

@@ -64,10 +64,10 @@ struct ChainArgs {
 constexpr unsigned kModeCount = 2;
 // Lane 0's wave of every stage records when it begins and ends each chunk.
 constexpr unsigned kModeTrace = 8;
-// Chosen by the host per run (small messages): cached accesses inside a stage.
-constexpr unsigned kModeStageCached = 4;
+// Chosen by the host per run (small messages): write-back stores inside a stage.
+constexpr unsigned kModeStageWriteBack = 4;
 // Largest message that uses it (measured crossover on MI355X: 2-4 MiB).
-constexpr u64 kStageCachedMaxBytes = 2u << 20;
+constexpr u64 kStageWriteBackMaxBytes = 2u << 20;
 
 // Arguments of the plain copy kernels: up to 32 simultaneous (src -> dst)
 // whole-message copies (one binomial round has at most 32 at P = 64; the
@@ -101,6 +101,6 @@ hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, hipS
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
-hipError_t chain_max_blocks_per_cu(int *blocks, int *blocks_stage_cached);
+hipError_t chain_max_blocks_per_cu(int *blocks, int *blocks_write_back);
 
 }  // namespace bcast

@@ -304,16 +304,16 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
             }
         };
         // chain: for every stage count, the whole message as one chunk (Eq. 2)
-        // and the power-of-two chunk sizes from 8 KiB to 64 MiB (Eq. 5) that give
-        // a lane between 4 KiB and 128 KiB of a chunk (outside that range the
-        // hand-off cost or the idle lanes dominate), at most 4096 chunks
+        // and the power-of-two chunk sizes from 8 KiB to 64 MiB (Eq. 5), at most
+        // 4096 chunks and at most 128 KiB of a chunk per lane.  The chunk size
+        // also sets the number of lanes (one 8 KiB trip per lane and chunk until
+        // the device is full), so this sweep covers wave counts as well.
         for (int stages : stage_counts) {
             size_t lanes_max = 1;
             while (lanes_max * 2 * stages <= 8192) lanes_max *= 2;
             consider(BCAST_ALGO_CHAIN, std::max<size_t>(16, (M + 15) / 16 * 16), stages);
             for (size_t C = 8u << 10; C <= (64u << 20) && C < M; C <<= 1) {
                 if (M / C > 4096 || C > lanes_max * (128u << 10)) continue;
-                if (C < lanes_max * (4u << 10) && C < M / 8) continue;
                 consider(BCAST_ALGO_CHAIN, C, stages);
             }
         }
