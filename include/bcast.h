@@ -66,7 +66,7 @@ typedef struct {
     int stages;            /* chain: groups of consecutive hops; each stage has its own wavefronts and flags */
     int hops_per_stage;    /* chain: hops a stage's wavefront plays one after the other (1 = a stage per rank) */
     int lanes;             /* chain: wavefronts per stage, each streaming its own share of every chunk */
-    uint64_t slice_bytes;  /* chain: bytes of every chunk owned by one lane, in 8 KiB trips dealt round-robin over the lanes */
+    uint64_t slice_bytes;  /* chain: bytes of every chunk owned by one lane, in 4 KiB trips dealt round-robin over the lanes */
     int grid_blocks;       /* workgroups of the (first) launch */
     int block_threads;     /* threads per workgroup */
     int vec_bytes;         /* widest access usable for these pointers: 16, 8, 4 or 1 */

@@ -63,16 +63,17 @@ static void stage_shape(int hops, int request, int *stages, int *hops_per_stage)
     *stages = (hops + *hops_per_stage - 1) / *hops_per_stage;
 }
 
-// 8 KiB (one trip of the copy loop) is the least worth a lane.
+// One trip of the copy loop (4 KiB) is the least worth a lane.
 constexpr u64 kSliceMin = (u64)kChainUnroll * kWaveSize * 16;  // one trip
 
 // Chunk size when the caller gives none and no tuning entry applies.  On one
 // die every hop shares the same HBM, so Eq. 5's fill term (n - 2 idle links)
-// costs little.  What matters is how many waves run: a lane gets one 8 KiB
-// trip per chunk, and about 1024 waves in total keep what a wave re-reads
-// inside its stage in the L2 (see chain_kernel).  So: chunk = lanes * 8 KiB
-// with lanes = 1024 / stages, but never more lanes than the device holds.
-constexpr u64 kWavesTarget = 1024;
+// costs little.  What matters is how many waves run: a lane gets one 4 KiB
+// trip per chunk, and about 2048 waves in total (8 MiB of trips in flight) keep
+// what a wave re-reads inside its stage in the L2 (see chain_kernel).  So:
+// chunk = lanes * 4 KiB with lanes = 2048 / stages, but never more lanes than
+// the device holds.
+constexpr u64 kWavesTarget = 2048;
 
 static u64 default_chunk(int nranks, int max_waves, int stages_request)
 {
@@ -122,7 +123,7 @@ extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes
     u64 lanes = lanes_request > 0 ? std::min<u64>((u64)lanes_request, (u64)(max_waves / stages))
                                   : shape(std::min(useful, lanes_max));
     lanes = std::max<u64>(1, lanes);
-    // a lane takes every lanes-th 8 KiB trip of a chunk
+    // a lane takes every lanes-th trip (4 KiB) of a chunk
     const u64 trip = (u64)kChainUnroll * kWaveSize * 16;
     info->slice_bytes = ceil_div(C, lanes * trip) * trip;
     info->chunk_bytes = C;

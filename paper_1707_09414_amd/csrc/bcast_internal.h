@@ -25,9 +25,12 @@ constexpr int kFlagStrideWords = 16;
 // A wavefront moves kUnroll 16-byte vectors per lane per trip: 4 KiB in flight.
 constexpr int kUnroll = 4;
 constexpr u64 kTileBytes = (u64)kWaveSize * 16 * kUnroll;
-// The chain kernel keeps more in flight per wave: its waves also wait on flags.
+// The chain kernel's trip: 4 vector instructions per lane = 4 KiB per wave.
+// Measured on MI355X against 2 and 8: with the trips of all resident waves
+// summing to 4-8 MiB (what the L2s keep hot between a wave's store and its
+// read-back) 4 KiB trips let twice the waves hide the store latency.
 #ifndef BCAST_CHAIN_UNROLL
-#define BCAST_CHAIN_UNROLL 8
+#define BCAST_CHAIN_UNROLL 4
 #endif
 constexpr int kChainUnroll = BCAST_CHAIN_UNROLL;
 

@@ -259,8 +259,8 @@ __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const Chai
 // a wave always sees its own earlier stores once s_waitcnt has passed, whatever
 // cache they sit in.  So the read-back is an ordinary cached load: the
 // write-through store left the line in this XCD's L2, and if few enough waves
-// share the XCD (about 128, i.e. 1 MiB of trips in flight) it is still there --
-// measured 8.2-8.8 TB/s instead of 7.3 TB/s when every load goes to memory.
+// share the XCD (128-256, i.e. 0.5-1 MiB of trips in flight) it is still there
+// -- measured 8-10 TB/s instead of 7.3 TB/s when every load goes to memory.
 // STAGE_WRITE_BACK (small messages): these buffers, and the chain's last
 // position, are also *stored* with ordinary cached stores; the end of the
 // kernel writes the dirty lines back like for any kernel.  The L2 round trip is
@@ -293,7 +293,7 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
     unsigned near = 0, far = 0;  // hand-offs received from the same / another XCD
 
     // A lane's share of a chunk is every lanes-th trip (one trip = kChainUnroll
-    // vector instructions of the wave, 8 KiB at 16 bytes per lane), so at any
+    // vector instructions of the wave, 4 KiB at 16 bytes per lane), so at any
     // moment the lanes of a stage sweep one contiguous window of the chunk: DRAM
     // sees a few wide streams per stage, not one narrow stream per wave.
     const u64 trip = (u64)kChainUnroll * kWaveSize * V;

@@ -306,7 +306,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         // chain: for every stage count, the whole message as one chunk (Eq. 2)
         // and the power-of-two chunk sizes from 8 KiB to 64 MiB (Eq. 5), at most
         // 4096 chunks and at most 128 KiB of a chunk per lane.  The chunk size
-        // also sets the number of lanes (one 8 KiB trip per lane and chunk until
+        // also sets the number of lanes (one 4 KiB trip per lane and chunk until
         // the device is full), so this sweep covers wave counts as well.
         for (int stages : stage_counts) {
             size_t lanes_max = 1;

@@ -57,13 +57,13 @@ def test_chain_geometry_matches_eq5_chunking():
     assert g["lanes"] == 2048 // 63 and g["stages"] == 63 and g["hops_per_stage"] == 1
     # stages: consecutive hops grouped as evenly as possible
     g = B.bcast_chain_geometry(64, 1 << 30, 4 << 20, 8192, stages_request=8)
-    assert (g["stages"], g["hops_per_stage"], g["lanes"]) == (8, 8, 512)
+    assert (g["stages"], g["hops_per_stage"], g["lanes"]) == (8, 8, 1024)  # 4 MiB = 1024 trips of 4 KiB
     g = B.bcast_chain_geometry(64, 1 << 30, 4 << 20, 8192, stages_request=5)
     assert (g["stages"], g["hops_per_stage"]) == (5, 13)
     g = B.bcast_chain_geometry(8, 1 << 26, 8 << 20, 8192, stages_request=100)
     assert (g["stages"], g["hops_per_stage"], g["lanes"]) == (7, 1, 1024)
     g = B.bcast_chain_geometry(8, 1 << 26, 8 << 20, 8192, stages_request=1)
-    assert (g["stages"], g["hops_per_stage"], g["grid_blocks"]) == (1, 7, 256)
+    assert (g["stages"], g["hops_per_stage"], g["grid_blocks"]) == (1, 7, 512)
     # no-ops
     assert B.bcast_chain_geometry(1, 1 << 20, 4096, 64)["nchunks"] == 0
     assert B.bcast_chain_geometry(4, 0, 4096, 64)["nchunks"] == 0
