@@ -44,10 +44,10 @@ WORKLOADS = {
 # The chain's traffic is BELOW its algorithmic bytes: part of what a wave reads
 # back inside a stage is served by the L2 and never reaches the fabric.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "chain"): int((169046.6 * (65536.0 / 32786.7) + 459008.0) * 1024),
+    ("cfg2", "chain"): int((155408.1 * (65536.0 / 32786.8) + 459264.0) * 1024),
     ("cfg2", "direct"): int((32784.5 * (65536.0 / 32786.9) + 65536.0) * 1024),
-    ("cfg4", "chain"): int((5424523.7 * (524288.0 / 262167.3) + 16259072.0) * 1024),
-    ("cfg5", "chain"): int((17427303.3 * (1048576.0 / 524313.6) + 66088960.0) * 1024),
+    ("cfg4", "chain"): int((4003527.3 * (524288.0 / 262167.0) + 16265216.0) * 1024),
+    ("cfg5", "chain"): int((15327635.5 * (1048576.0 / 524315.7) + 66084864.0) * 1024),
 }
 
 
