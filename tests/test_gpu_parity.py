@@ -285,3 +285,79 @@ def test_chunks_overlap_across_stages_on_the_device(noise, stages):
             assert begin[g][0] < end[g - 1][nchunks - 1], "stage %d did not overlap with stage %d" % (g, g - 1)
     # Eq. 5's picture: the last stage finishes its first chunk long before the first stage finishes its last
     assert end[stages - 1][0] < end[0][nchunks - 1]
+
+
+def test_random_configurations(noise):
+    """Seeded sweep over the whole parameter space at small sizes: ranks, root,
+    message and chunk size, stage and lane counts, pointer offsets, algorithm."""
+    rng = np.random.default_rng(20240607)
+    algos = ALGOS
+    for case in range(150):
+        P = int(rng.integers(1, 65)) if case % 3 else int(rng.integers(1, 9))
+        root = int(rng.integers(0, P))
+        M = int(rng.choice([0, 1, 7, 16, 100, 4095, 4096, 65537, 300000, int(rng.integers(1, 3 * MiB))]))
+        C = int(rng.choice([0, 16, 112, 4096, 65536, 1 << 20])) if rng.random() < 0.8 else 16 * int(rng.integers(1, 70000))
+        algo = int(algos[int(rng.integers(0, len(algos)))])
+        stages = int(rng.integers(0, 70)) if algo == B.BCAST_ALGO_CHAIN else 0
+        lanes = int(rng.choice([0, 0, 1, 3, 32, 100]))
+        kind = int(rng.integers(0, 4))
+        offsets = [[0] * P, [int(rng.integers(0, 16))] * P, [int(x) for x in rng.integers(0, 4, P) * 4],
+                   [int(x) for x in rng.integers(0, 33, P)]][kind]
+        radix = int(rng.integers(2, 10)) if algo == B.BCAST_ALGO_KNOMIAL else 0
+        try:
+            run_and_check(P, root, M, C, algo, noise, offsets=offsets, lanes=lanes, stages=stages, radix=radix)
+        except Exception as e:
+            raise AssertionError("case %d: P=%d root=%d M=%d C=%d algo=%d stages=%d lanes=%d offsets=%s radix=%d: %s"
+                                 % (case, P, root, M, C, algo, stages, lanes, kind, radix, e))
+
+
+def test_two_plans_on_two_streams_at_once(noise):
+    """Different plans (own flags) with different buffers may run concurrently:
+    two persistent kernels share the device without starving each other."""
+    P, M = 16, 6 * MiB + 40
+    rb1, rb2 = RankBuffers(P, M), RankBuffers(P, M)
+    m1, m2 = noise[:M], noise[1234: 1234 + M]
+    rb1.reset(3, m1)
+    rb2.reset(9, m2)
+    torch.cuda.synchronize()
+    p1 = B.bcast_plan_create(P, M, 512 * KiB, B.BCAST_ALGO_CHAIN)
+    p2 = B.bcast_plan_create(P, M, 256 * KiB, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_stages(p1, 15)
+    B.bcast_plan_set_stages(p2, 3)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for _ in range(20):
+        B.bcast_run(p1, rb1.ptrs(), 3, M, s1)
+        B.bcast_run(p2, rb2.ptrs(), 9, M, s2)
+    s1.synchronize()
+    s2.synchronize()
+    assert B.bcast_plan_status(p1)[0] == B.BCAST_OK and B.bcast_plan_status(p2)[0] == B.BCAST_OK
+    g1, g2 = rb1.to_host(), rb2.to_host()
+    for r in range(P):
+        assert np.array_equal(g1[r][rb1.start(r): rb1.start(r) + M], m1), r
+        assert np.array_equal(g2[r][rb2.start(r): rb2.start(r) + M], m2), r
+    p1.destroy()
+    p2.destroy()
+
+
+def test_tune_with_every_candidate(noise, tmp_path):
+    """The tuner with the optional candidates switched on (single-stage chain,
+    fan-out, scatter + allgather, k-nomial) still yields runnable entries."""
+    P = 8
+    B.bcast_tune_clear()
+    mask = sum(1 << a for a in ALGOS) | B.BCAST_TUNE_FOLDED
+    log = tmp_path / "log.txt"
+    B.bcast_tune_set_log(str(log))
+    B.bcast_tune(P, 64 * KiB, 1 * MiB, mask, None, None)
+    B.bcast_tune_set_log(None)
+    assert B.bcast_tune_count() == 5
+    seen_algos = set()
+    for line in log.read_text().splitlines():
+        if not line.startswith("#"):
+            seen_algos.add(int(line.split()[2]))
+    assert seen_algos == set(ALGOS)
+    for M in (64 * KiB, 300 * KiB, 1 * MiB):
+        e = B.bcast_tune_get(P, M)
+        assert e["usec"] > 0 and e["chain_usec"] > 0 and e["chain_chunk_bytes"] > 0
+        run_and_check(P, 5, M, 0, B.BCAST_ALGO_AUTO, noise)
+        run_and_check(P, 5, M, 0, B.BCAST_ALGO_CHAIN, noise)
+    B.bcast_tune_clear()
