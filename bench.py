@@ -132,15 +132,18 @@ def main() -> int:
         B.bcast_run(plan, bufs, root, M, stream)
     torch.cuda.synchronize()
 
-    # timed region: exactly --steps broadcasts, each bracketed by HIP events on
-    # the launch stream (torch's current stream is the stream we launch on)
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    # timed region: exactly --steps broadcasts back to back, bracketed by
+    # synchronize + wall clock (the whole-job figure) and by one pair of HIP
+    # events recorded on the launch stream (torch's current stream is the stream
+    # we launch on): elapsed / steps is the average launch duration, gaps between
+    # consecutive launches included
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for e0, e1 in ev:
-        e0.record(stream)
+    e0.record(stream)
+    for _ in range(args.steps):
         B.bcast_run(plan, bufs, root, M, stream)
-        e1.record(stream)
+    e1.record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     status, detail = B.bcast_plan_status(plan)
@@ -148,9 +151,7 @@ def main() -> int:
         print("bench.py: plan status %d detail %x" % (status, detail), file=sys.stderr)
         return 1
     wall_ms = (t1 - t0) * 1e3 / args.steps
-    launch_ms = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
-    avg_launch_ms = sum(launch_ms) / len(launch_ms)
-    med_launch_ms = launch_ms[len(launch_ms) // 2]
+    avg_launch_ms = e0.elapsed_time(e1) / args.steps
 
     # every rank must now hold the root's message: one rank at a time over PCIe
     verified = None
@@ -208,10 +209,10 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
             "traffic": traffic,
-            "kernel": "chain_kernel<16>" if info["algo"] == B.BCAST_ALGO_CHAIN else B.ALGO_NAMES[info["algo"]],
+            "kernel": ("bcast::chain_kernel<%d, %s>" % (info["vec_bytes"], "true" if M <= (2 << 20) else "false"))
+            if info["algo"] == B.BCAST_ALGO_CHAIN else B.ALGO_NAMES[info["algo"]],
             "algorithmic_bytes_per_launch": algorithmic,
             "avg_launch_ms": round(avg_launch_ms, 5),
-            "median_launch_ms": round(med_launch_ms, 5),
         },
         "cpu_baseline": cpu,
         "sweep": sweep,

@@ -109,7 +109,9 @@ int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, size_t chunk
  *   stream     hipStream_t to enqueue on.
  * The chain position of rank r is (r - root) mod P: the root pushes chunks to
  * rank root+1, which forwards to root+2, ... and rank root-1 only receives.
- * Returns after enqueueing; completion follows stream order.
+ * Returns after enqueueing; completion follows stream order.  Every run gets a
+ * fresh epoch from the host as a kernel argument, so a bcast_run recorded into
+ * a HIP graph must not be replayed: call it directly.
  * bytes == 0 or nranks == 1 succeed without launching.
  * Errors: ERR_ARG (NULL/duplicate/overlapping pointers, root or bytes out of
  * range), ERR_UNTUNED, ERR_HIP.  A wave that waits longer than the plan's
