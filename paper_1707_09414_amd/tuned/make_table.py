@@ -1,7 +1,8 @@
 """Measure the tuning table on the GPU in this machine and write it as text.
 
     python -m paper_1707_09414_amd.tuned.make_table [--out PATH] [--ranks 2,4,8,...]
-                                                    [--min-bytes N] [--max-bytes N] [--with-fanout] [--folded]
+                                                    [--min-bytes N] [--max-bytes N] [--with-fanout] [--with-knomial]
+                                                    [--with-scatter-allgather] [--folded]
 
 For every rank count it runs ``bcast_tune`` (chain over chunk sizes and stage counts,
 direct, binomial; the one-die fan-out and the single-stage chain only on request) over power-of-two message sizes
@@ -23,6 +24,8 @@ def main() -> int:
     ap.add_argument("--min-bytes", type=int, default=4)
     ap.add_argument("--max-bytes", type=int, default=1 << 30)
     ap.add_argument("--with-fanout", action="store_true")
+    ap.add_argument("--with-knomial", action="store_true", help="also try the k-nomial tree at radix 4 and 8")
+    ap.add_argument("--with-scatter-allgather", action="store_true")
     ap.add_argument("--log", default=None, help="also append every timed candidate to this file")
     ap.add_argument("--folded", action="store_true", help="also try the chain with a single stage (no flag hand-off)")
     args = ap.parse_args()
@@ -35,6 +38,10 @@ def main() -> int:
     mask = (1 << B.BCAST_ALGO_CHAIN) | (1 << B.BCAST_ALGO_DIRECT) | (1 << B.BCAST_ALGO_BINOMIAL)
     if args.with_fanout:
         mask |= 1 << B.BCAST_ALGO_FANOUT
+    if args.with_knomial:
+        mask |= 1 << B.BCAST_ALGO_KNOMIAL
+    if args.with_scatter_allgather:
+        mask |= 1 << B.BCAST_ALGO_SCATTER_ALLGATHER
     if args.folded:
         mask |= B.BCAST_TUNE_FOLDED
     B.bcast_tune_clear()
