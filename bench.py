@@ -42,7 +42,7 @@ WORKLOADS = {
 # run (a 64 MiB copy reads 32786.9 KiB on the counter: factor 1.999); WRITE_SIZE
 # reads the true size (factor 1.000).  Workloads without a profile report null.
 # The chain's traffic is BELOW its algorithmic bytes: part of what a wave reads
-# back inside a stage is served by the L2 and never reaches the fabric.
+# back inside a stage is served by the CU's vector L1 and never reaches the fabric.
 MEASURED_TRAFFIC_BYTES = {
     ("cfg2", "chain"): int((155408.1 * (65536.0 / 32786.8) + 459264.0) * 1024),
     ("cfg2", "direct"): int((32784.5 * (65536.0 / 32786.9) + 65536.0) * 1024),

@@ -69,8 +69,9 @@ constexpr u64 kSliceMin = (u64)kChainUnroll * kWaveSize * 16;  // one trip
 // Chunk size when the caller gives none and no tuning entry applies.  On one
 // die every hop shares the same HBM, so Eq. 5's fill term (n - 2 idle links)
 // costs little.  What matters is how many waves run: a lane gets one 4 KiB
-// trip per chunk, and about 2048 waves in total (8 MiB of trips in flight) keep
-// what a wave re-reads inside its stage in the L2 (see chain_kernel).  So:
+// trip per chunk, and about 2048 waves in total (8 per CU, 32 KiB of trips) keep
+// half of what a wave re-reads inside its stage in the CU's L1 while hiding the
+// store latency (see chain_kernel).  So:
 // chunk = lanes * 4 KiB with lanes = 2048 / stages, but never more lanes than
 // the device holds.
 constexpr u64 kWavesTarget = 2048;

@@ -26,9 +26,9 @@ constexpr int kFlagStrideWords = 16;
 constexpr int kUnroll = 4;
 constexpr u64 kTileBytes = (u64)kWaveSize * 16 * kUnroll;
 // The chain kernel's trip: 4 vector instructions per lane = 4 KiB per wave.
-// Measured on MI355X against 2 and 8: with the trips of all resident waves
-// summing to 4-8 MiB (what the L2s keep hot between a wave's store and its
-// read-back) 4 KiB trips let twice the waves hide the store latency.
+// Measured on MI355X against 2 and 8: the trips of a CU's resident waves must
+// fit its 32 KiB vector L1 to be read back from it, and 4 KiB trips let twice
+// the waves of 8 KiB trips hide the store latency within that budget.
 #ifndef BCAST_CHAIN_UNROLL
 #define BCAST_CHAIN_UNROLL 4
 #endif

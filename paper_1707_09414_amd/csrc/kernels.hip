@@ -258,9 +258,9 @@ __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const Chai
 // reads back for position h+1 is touched by no other wave during the kernel, and
 // a wave always sees its own earlier stores once s_waitcnt has passed, whatever
 // cache they sit in.  So the read-back is an ordinary cached load: the
-// write-through store left the line in this XCD's L2, and if few enough waves
-// share the XCD (128-256, i.e. 0.5-1 MiB of trips in flight) it is still there
-// -- measured 8-10 TB/s instead of 7.3 TB/s when every load goes to memory.
+// write-through store left the line in this CU's 32 KiB vector L1, and with 4-8
+// waves per CU (16-32 KiB of 4 KiB trips) all or half of it is still there --
+// measured 8-10 TB/s instead of 7.3 TB/s when every load goes to memory.
 // STAGE_WRITE_BACK (small messages): these buffers, and the chain's last
 // position, are also *stored* with ordinary cached stores; the end of the
 // kernel writes the dirty lines back like for any kernel.  The L2 round trip is
@@ -318,7 +318,7 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
         // One trip at a time is carried through all positions of the stage
         // before the next trip starts: what the wave reads back for position
         // h+1 it stored for position h one memory round trip earlier, so with
-        // few enough waves per XCD it is still in that XCD's L2.
+        // few enough waves per CU it is still in that CU's vector L1.
         for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
             const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
             for (unsigned hop = first_hop; hop <= last_hop; ++hop) {
