@@ -2,7 +2,7 @@
 """Benchmark of the broadcast hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
-                    [--algo chain|direct|binomial|fanout|auto] [--chunk BYTES] [--lanes N] [--stages N]
+                    [--algo chain|direct|binomial|fanout|auto] [--chunk BYTES] [--lanes N] [--stages N] [--trip BYTES]
 
 A "step" is one whole broadcast (every chunk over every hop) of the workload's
 message to all P virtual ranks, with all buffers already resident in HBM.
@@ -73,6 +73,7 @@ def main() -> int:
     ap.add_argument("--chunk", type=int, default=0, help="chain chunk bytes (0 = tuned table / built-in rule)")
     ap.add_argument("--lanes", type=int, default=0, help="wavefronts per chain hop (0 = automatic)")
     ap.add_argument("--stages", type=int, default=0, help="chain stages (0 = tuned table / built-in rule)")
+    ap.add_argument("--trip", type=int, default=0, help="chain trip bytes, 3072 or 4096 (0 = tuned table / 4096)")
     ap.add_argument("--ranks", type=int, default=0, help="override the workload's P (experiments)")
     ap.add_argument("--bytes", type=int, default=0, help="override the workload's message size (experiments)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-message-size latency table (cfg2 only)")
@@ -125,6 +126,8 @@ def main() -> int:
         B.bcast_plan_set_lanes(plan, args.lanes)
     if args.stages:
         B.bcast_plan_set_stages(plan, args.stages)
+    if args.trip:
+        B.bcast_plan_set_trip(plan, args.trip)
     info = B.bcast_plan_info(plan, M, bufs)
     stream = torch.cuda.current_stream()
 
@@ -167,7 +170,7 @@ def main() -> int:
     algorithmic = int(info["algorithmic_bytes"])
     value = algorithmic / (wall_ms * 1e-3) / 1e9
     achieved = algorithmic / (avg_launch_ms * 1e-3) / 1e9
-    custom = bool(args.ranks or args.bytes or args.chunk or args.lanes or args.stages)
+    custom = bool(args.ranks or args.bytes or args.chunk or args.lanes or args.stages or args.trip)
     traffic = None if custom else MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo))
 
     sweep = None
@@ -195,7 +198,7 @@ def main() -> int:
         "config": {
             "workload": "%s: %s, root %d" % (args.workload, what, root),
             "P": P, "message_bytes": M, "algo": B.ALGO_NAMES[info["algo"]],
-            "chunk_bytes": int(info["chunk_bytes"]), "nchunks": int(info["nchunks"]), "stages": info["stages"], "hops_per_stage": info["hops_per_stage"],
+            "chunk_bytes": int(info["chunk_bytes"]), "nchunks": int(info["nchunks"]), "stages": info["stages"], "hops_per_stage": info["hops_per_stage"], "trip_bytes": info["trip_bytes"],
             "lanes": info["lanes"],
             "grid_blocks": info["grid_blocks"], "vec_bytes": info["vec_bytes"], "launches_per_step": info["launches"],
             "tuning_table": table,

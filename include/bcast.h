@@ -66,7 +66,8 @@ typedef struct {
     int stages;            /* chain: groups of consecutive hops; each stage has its own wavefronts and flags */
     int hops_per_stage;    /* chain: hops a stage's wavefront plays one after the other (1 = a stage per rank) */
     int lanes;             /* chain: wavefronts per stage, each streaming its own share of every chunk */
-    uint64_t slice_bytes;  /* chain: bytes of every chunk owned by one lane, in 4 KiB trips dealt round-robin over the lanes */
+    int trip_bytes;        /* chain: bytes a wavefront moves per trip at 16-byte accesses (3072 or 4096) */
+    uint64_t slice_bytes;  /* chain: bytes of every chunk owned by one lane, in trips dealt round-robin over the lanes */
     int grid_blocks;       /* workgroups of the (first) launch */
     int block_threads;     /* threads per workgroup */
     int vec_bytes;         /* widest access usable for these pointers: 16, 8, 4 or 1 */
@@ -146,6 +147,9 @@ int bcast_plan_destroy(bcast_plan_t *plan);
  * 0 = off.  Kernels always run to completion under these settings. */
 int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
 int bcast_plan_set_stages(bcast_plan_t *plan, int stages);
+/* Bytes a chain wavefront moves per trip (16-byte accesses): 4096 or 3072,
+ * 0 = the tuning table's choice, else 4096. */
+int bcast_plan_set_trip(bcast_plan_t *plan, int trip_bytes);
 /* Radix k of BCAST_ALGO_KNOMIAL, 2..nranks (0 = the tuning table's, else 4):
  * in round j every position q < k^j sends to q + i k^j, i = 1..k-1. */
 int bcast_plan_set_radix(bcast_plan_t *plan, int radix);
@@ -173,11 +177,12 @@ int bcast_plan_handoff_counts(bcast_plan_t *plan, uint64_t *same_xcd, uint64_t *
 /*
  * Chain geometry as a pure HOST function (no GPU needed): how a chain of
  * `nranks` ranks moving `bytes` bytes in chunks of `chunk_bytes` is laid over
- * at most `max_waves` co-resident wavefronts.  lanes_request, stages_request:
- * 0 = automatic.  Fills nchunks, stages, hops_per_stage, lanes, slice_bytes, grid_blocks, block_threads, chunk_bytes.
+ * at most `max_waves` co-resident wavefronts.  lanes_request, stages_request,
+ * trip_request: 0 = automatic.  Fills nchunks, stages, hops_per_stage, lanes, slice_bytes, grid_blocks, block_threads, chunk_bytes.
  */
 int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
-                         int lanes_request, int stages_request, bcast_plan_info_t *info);
+                         int lanes_request, int stages_request, int trip_request,
+                         bcast_plan_info_t *info);
 
 /*
  * Tuning table (Sec. III-B "Discussion" and IV-B last paragraph: algorithm and
@@ -206,9 +211,11 @@ typedef struct {
     int algo;                   /* winner: bcast_algo_t */
     uint64_t chunk_bytes;       /* winner's chunk size (chain only) */
     int stages;                 /* winner's stage count (chain) or radix (k-nomial) */
+    int trip_bytes;             /* winner's trip size (chain only; 0 = default) */
     double usec;                /* winner's measured time */
     uint64_t chain_chunk_bytes; /* chain: best chunk size (0 = not measured) */
     int chain_stages;           /* chain: best stage count */
+    int chain_trip_bytes;       /* chain: best trip size (0 = default) */
     double chain_usec;          /* chain: time at that setting */
 } bcast_tune_entry_t;
 

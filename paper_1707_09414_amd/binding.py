@@ -38,7 +38,7 @@ BCAST_ERR_UNTUNED = -5
 # every symbol include/bcast.h declares
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
     "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
@@ -62,6 +62,7 @@ class PlanInfo(ctypes.Structure):
         ("stages", ctypes.c_int),
         ("hops_per_stage", ctypes.c_int),
         ("lanes", ctypes.c_int),
+        ("trip_bytes", ctypes.c_int),
         ("slice_bytes", ctypes.c_uint64),
         ("grid_blocks", ctypes.c_int),
         ("block_threads", ctypes.c_int),
@@ -79,9 +80,11 @@ class TuneEntry(ctypes.Structure):
         ("algo", ctypes.c_int),
         ("chunk_bytes", ctypes.c_uint64),
         ("stages", ctypes.c_int),
+        ("trip_bytes", ctypes.c_int),
         ("usec", ctypes.c_double),
         ("chain_chunk_bytes", ctypes.c_uint64),
         ("chain_stages", ctypes.c_int),
+        ("chain_trip_bytes", ctypes.c_int),
         ("chain_usec", ctypes.c_double),
     ]
 
@@ -111,12 +114,13 @@ def _load():
         "bcast_plan_set_lanes": ([vp, i], i),
         "bcast_plan_set_stages": ([vp, i], i),
         "bcast_plan_set_radix": ([vp, i], i),
+        "bcast_plan_set_trip": ([vp, i], i),
         "bcast_plan_set_debug": ([vp, u64, i], i),
         "bcast_plan_set_mode": ([vp, ctypes.c_uint], i),
         "bcast_plan_enable_trace": ([vp, sz], i),
         "bcast_plan_read_trace": ([vp, ctypes.POINTER(u64), sz], i),
         "bcast_plan_handoff_counts": ([vp, ctypes.POINTER(u64), ctypes.POINTER(u64)], i),
-        "bcast_chain_geometry": ([i, sz, sz, i, i, i, ctypes.POINTER(PlanInfo)], i),
+        "bcast_chain_geometry": ([i, sz, sz, i, i, i, i, ctypes.POINTER(PlanInfo)], i),
         "bcast_tune": ([i, sz, sz, ctypes.c_uint, vp, ctypes.c_char_p], i),
         "bcast_tune_load": ([ctypes.c_char_p], i),
         "bcast_tune_save": ([ctypes.c_char_p], i),
@@ -235,6 +239,10 @@ def bcast_plan_set_stages(plan: Plan, stages: int) -> None:
     _check(_lib.bcast_plan_set_stages(plan.handle, stages), "bcast_plan_set_stages")
 
 
+def bcast_plan_set_trip(plan: Plan, trip_bytes: int) -> None:
+    _check(_lib.bcast_plan_set_trip(plan.handle, trip_bytes), "bcast_plan_set_trip")
+
+
 def bcast_plan_set_radix(plan: Plan, radix: int) -> None:
     _check(_lib.bcast_plan_set_radix(plan.handle, radix), "bcast_plan_set_radix")
 
@@ -269,10 +277,10 @@ def bcast_plan_handoff_counts(plan: Plan) -> Tuple[int, int]:
 
 
 def bcast_chain_geometry(nranks: int, bytes: int, chunk_bytes: int, max_waves: int, lanes_request: int = 0,
-                         stages_request: int = 0) -> dict:
+                         stages_request: int = 0, trip_request: int = 0) -> dict:
     info = PlanInfo()
     _check(_lib.bcast_chain_geometry(nranks, bytes, chunk_bytes, max_waves, lanes_request, stages_request,
-                                     ctypes.byref(info)),
+                                     trip_request, ctypes.byref(info)),
            "bcast_chain_geometry")
     return info.as_dict()
 

@@ -32,6 +32,7 @@ struct bcast_plan {
     int lanes_request = 0;
     int stages_request = 0;
     int radix_request = 0;
+    int trip_request = 0;  // bytes at 16-byte vectors: 0 = choose, else 3072 or 4096
     u64 spin_ticks = kDefaultSpinTicks;
     int mute_hop = 0;
 };
@@ -63,34 +64,37 @@ static void stage_shape(int hops, int request, int *stages, int *hops_per_stage)
     *stages = (hops + *hops_per_stage - 1) / *hops_per_stage;
 }
 
-// One trip of the copy loop (4 KiB) is the least worth a lane.
-constexpr u64 kSliceMin = (u64)kChainUnroll * kWaveSize * 16;  // one trip
+// Bytes of one trip of the copy loop at 16-byte vectors: the least worth a lane.
+static u64 trip_bytes_of(int unroll) { return (u64)unroll * kWaveSize * 16; }
+static bool valid_trip(u64 t) { return t == trip_bytes_of(kTripUnrollDefault) || t == trip_bytes_of(kTripUnrollSmall); }
 
 // Chunk size when the caller gives none and no tuning entry applies.  On one
 // die every hop shares the same HBM, so Eq. 5's fill term (n - 2 idle links)
-// costs little.  What matters is how many waves run: a lane gets one 4 KiB
-// trip per chunk, and about 2048 waves in total (8 per CU, 32 KiB of trips) keep
-// half of what a wave re-reads inside its stage in the CU's L1 while hiding the
-// store latency (see chain_kernel).  So:
-// chunk = lanes * 4 KiB with lanes = 2048 / stages, but never more lanes than
-// the device holds.
+// costs little.  What matters is how many waves run: a lane gets one trip per
+// chunk, and about 2048 waves in total (8 per CU) keep what a wave re-reads
+// inside its stage in the CU's L1 while hiding the store latency (see
+// chain_kernel).  So: chunk = lanes * trip with lanes = 2048 / stages, but never
+// more lanes than the device holds.
 constexpr u64 kWavesTarget = 2048;
 
-static u64 default_chunk(int nranks, int max_waves, int stages_request)
+static u64 default_chunk(int nranks, int max_waves, int stages_request, u64 trip)
 {
     int stages = 1, hps = 1;
     stage_shape(std::max(1, nranks - 1), stages_request, &stages, &hps);
     u64 lanes = std::max<u64>(1, std::min<u64>(kWavesTarget, (u64)max_waves) / (u64)stages);
     u64 p = 1;
     while (p * 2 <= lanes) p *= 2;
-    return p * kSliceMin;
+    return p * trip;
 }
 
 extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
-                                    int lanes_request, int stages_request, bcast_plan_info_t *info)
+                                    int lanes_request, int stages_request, int trip_request,
+                                    bcast_plan_info_t *info)
 {
     if (!info || nranks < 1 || nranks > BCAST_MAX_RANKS || max_waves < 1 || lanes_request < 0 || stages_request < 0)
         return BCAST_ERR_ARG;
+    const u64 trip = trip_request ? (u64)trip_request : trip_bytes_of(kTripUnrollDefault);
+    if (!valid_trip(trip)) return BCAST_ERR_ARG;
     if (chunk_bytes == 0 || chunk_bytes % 16 != 0) return BCAST_ERR_ARG;
     memset(info, 0, sizeof *info);
     info->algo = BCAST_ALGO_CHAIN;
@@ -119,13 +123,13 @@ extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes
         return p;
     };
     u64 lanes_max = shape((u64)(max_waves / stages));
-    // a lane should own at least kSliceMin bytes of a chunk unless the chunk is smaller
-    u64 useful = std::max<u64>(1, ceil_div(C, kSliceMin));
+    // a lane should own at least one trip of a chunk unless the chunk is smaller
+    u64 useful = std::max<u64>(1, ceil_div(C, trip));
     u64 lanes = lanes_request > 0 ? std::min<u64>((u64)lanes_request, (u64)(max_waves / stages))
                                   : shape(std::min(useful, lanes_max));
     lanes = std::max<u64>(1, lanes);
-    // a lane takes every lanes-th trip (4 KiB) of a chunk
-    const u64 trip = (u64)kChainUnroll * kWaveSize * 16;
+    // a lane takes every lanes-th trip of a chunk
+    info->trip_bytes = (int)trip;
     info->slice_bytes = ceil_div(C, lanes * trip) * trip;
     info->chunk_bytes = C;
     info->nchunks = nchunks;
@@ -217,6 +221,13 @@ extern "C" int bcast_plan_set_stages(bcast_plan_t *p, int stages)
 {
     if (!p || stages < 0) return BCAST_ERR_ARG;
     p->stages_request = stages;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_set_trip(bcast_plan_t *p, int trip_bytes)
+{
+    if (!p || (trip_bytes != 0 && !valid_trip((u64)trip_bytes))) return BCAST_ERR_ARG;
+    p->trip_request = trip_bytes;
     return BCAST_OK;
 }
 
@@ -314,6 +325,7 @@ struct Resolved {
     u64 chunk;
     int stages;  // 0 = built-in rule
     int radix;   // k-nomial only
+    int trip;    // chain: bytes per trip
 };
 
 // Without a measurement: two stages (hops 1..h | h+1..P-1).  On one die the
@@ -333,6 +345,7 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
     r->algo = p->algo;
     r->chunk = p->chunk_bytes;
     r->stages = p->stages_request;
+    r->trip = p->trip_request;
     bcast_tune_entry_t e;
     const bool tuned = bcast_tune_get(p->nranks, bytes, &e) == BCAST_OK;
     if (p->algo == BCAST_ALGO_AUTO) {
@@ -341,10 +354,12 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
         if (r->chunk == 0) {
             r->chunk = e.chunk_bytes;
             if (r->stages == 0) r->stages = e.stages;
+            if (r->trip == 0 && e.algo == BCAST_ALGO_CHAIN) r->trip = e.trip_bytes;
         }
     } else if (p->algo == BCAST_ALGO_CHAIN && r->chunk == 0 && tuned && e.chain_chunk_bytes != 0) {
         r->chunk = e.chain_chunk_bytes;
         if (r->stages == 0) r->stages = e.chain_stages;
+        if (r->trip == 0) r->trip = e.chain_trip_bytes;
     }
     r->radix = p->radix_request;
     if (r->algo == BCAST_ALGO_KNOMIAL) {
@@ -356,7 +371,8 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
     }
     if (r->algo == BCAST_ALGO_CHAIN) {
         if (r->stages == 0) r->stages = default_stages(p->nranks);
-        if (r->chunk == 0) r->chunk = default_chunk(p->nranks, waves_for(p, bytes), r->stages);
+        if (!valid_trip((u64)r->trip)) r->trip = (int)trip_bytes_of(kTripUnrollDefault);
+        if (r->chunk == 0) r->chunk = default_chunk(p->nranks, waves_for(p, bytes), r->stages, (u64)r->trip);
         r->chunk = round_up(r->chunk, 16);
     }
     return BCAST_OK;
@@ -431,7 +447,7 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
     const int P = p->nranks;
     const int vec = common_vec_bytes(rank_bufs, P);
     if (r.algo == BCAST_ALGO_CHAIN) {
-        rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, waves_for(p, bytes), p->lanes_request, r.stages, info);
+        rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, waves_for(p, bytes), p->lanes_request, r.stages, r.trip, info);
         if (rc != BCAST_OK) return rc;
         info->vec_bytes = vec;
         return BCAST_OK;
@@ -543,6 +559,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         a.lanes = (unsigned)info.lanes;
         a.stages = (unsigned)info.stages;
         a.hops_per_stage = (unsigned)info.hops_per_stage;
+        a.unroll = (unsigned)(info.trip_bytes / (kWaveSize * 16));
         a.nranks = (unsigned)P;
         a.mute_hop = (unsigned)p->mute_hop;
         // the launch must match what the kernel indexes: stages*lanes waves, each with its own flag,

@@ -25,14 +25,13 @@ constexpr int kFlagStrideWords = 16;
 // A wavefront moves kUnroll 16-byte vectors per lane per trip: 4 KiB in flight.
 constexpr int kUnroll = 4;
 constexpr u64 kTileBytes = (u64)kWaveSize * 16 * kUnroll;
-// The chain kernel's trip: 4 vector instructions per lane = 4 KiB per wave.
-// Measured on MI355X against 2 and 8: the trips of a CU's resident waves must
-// fit its 32 KiB vector L1 to be read back from it, and 4 KiB trips let twice
-// the waves of 8 KiB trips hide the store latency within that budget.
-#ifndef BCAST_CHAIN_UNROLL
-#define BCAST_CHAIN_UNROLL 4
-#endif
-constexpr int kChainUnroll = BCAST_CHAIN_UNROLL;
+// The chain kernel's trip: `unroll` vector instructions per lane, unroll KiB
+// per wave at 16 bytes per lane.  The trips of a CU's resident waves must fit
+// its 32 KiB vector L1 to be read back from it (see chain_kernel); measured on
+// MI355X, 8 waves per CU with 3 KiB trips (24 KiB) is best for many ranks and
+// 4 KiB trips for few, so both are built and the tuner chooses.
+constexpr int kTripUnrollDefault = 4;
+constexpr int kTripUnrollSmall = 3;
 
 // Wait limit default: 10 s of the 100 MHz constant clock.
 constexpr u64 kDefaultSpinTicks = 1000000000ull;
@@ -55,6 +54,7 @@ struct ChainArgs {
     unsigned lanes;    // wavefronts per stage
     unsigned stages;   // groups of consecutive chain positions, each served by its own waves
     unsigned hops_per_stage;
+    unsigned unroll;   // vector instructions per lane and trip: kTripUnrollDefault or kTripUnrollSmall
     unsigned nranks;
     unsigned mute_hop; // debug: this position never publishes (0 = off)
     unsigned mode;     // kMode* bits

@@ -94,13 +94,13 @@ template <int LD, int ST> struct AgentIO<1, LD, ST> {
 
 // copy_span with agent-scope accesses for a span of at most a few trips (the
 // chain kernel passes one trip at a time; offsets inside a buffer descriptor
-// are 32-bit).  The vector body runs a wave-uniform loop of kChainUnroll loads then
-// kChainUnroll stores per lane with no remainder loop: the body's descriptors
+// are 32-bit).  The vector body runs a wave-uniform loop of U loads then U
+// stores per lane with no remainder loop: the body's descriptors
 // end exactly at the last whole vector, so a lane whose offset lies beyond it
 // is range-checked by the hardware (the load returns zero, the store is
 // dropped).  A short span therefore costs one memory round trip, not one per
 // kilobyte.
-template <int V, int LD = kAuxAgent, int ST = kAuxAgent>
+template <int V, int U, int LD = kAuxAgent, int ST = kAuxAgent>
 __device__ __forceinline__ void copy_span_agent(char *dst, const char *src, u64 lo, u64 hi, unsigned lane)
 {
     typedef AgentIO<V, LD, ST> IO;
@@ -122,14 +122,14 @@ __device__ __forceinline__ void copy_span_agent(char *dst, const char *src, u64 
 
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(src + lo), 0, body_end, kRsrcWord3);
     const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(dst + lo, 0, body_end, kRsrcWord3);
-    const unsigned trip = kChainUnroll * kWaveSize * V;  // bytes per wave per trip
+    const unsigned trip = U * kWaveSize * V;  // bytes per wave per trip
     unsigned off = head + lane * V;
     for (unsigned base = head; base < body_end; base += trip, off += trip) {
-        T r[kChainUnroll];
+        T r[U];
 #pragma unroll
-        for (int u = 0; u < kChainUnroll; ++u) r[u] = IO::ld(rs, off + u * kWaveSize * V);
+        for (int u = 0; u < U; ++u) r[u] = IO::ld(rs, off + u * kWaveSize * V);
 #pragma unroll
-        for (int u = 0; u < kChainUnroll; ++u) IO::st(r[u], rd, off + u * kWaveSize * V);
+        for (int u = 0; u < U; ++u) IO::st(r[u], rd, off + u * kWaveSize * V);
     }
 }
 
@@ -258,9 +258,10 @@ __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const Chai
 // reads back for position h+1 is touched by no other wave during the kernel, and
 // a wave always sees its own earlier stores once s_waitcnt has passed, whatever
 // cache they sit in.  So the read-back is an ordinary cached load: the
-// write-through store left the line in this CU's 32 KiB vector L1, and with 4-8
-// waves per CU (16-32 KiB of 4 KiB trips) all or half of it is still there --
-// measured 8-10 TB/s instead of 7.3 TB/s when every load goes to memory.
+// write-through store left the line in this CU's 32 KiB vector L1, and while the
+// trips of the CU's resident waves fit there (8 waves of 3 KiB, 4-8 of 4 KiB)
+// all or most of it is still there -- measured 8-10 TB/s instead of 7.3 TB/s
+// when every load goes to memory.  U (3 or 4 KiB trips) is the host's choice.
 // STAGE_WRITE_BACK (small messages): these buffers, and the chain's last
 // position, are also *stored* with ordinary cached stores; the end of the
 // kernel writes the dirty lines back like for any kernel.  The L2 round trip is
@@ -268,7 +269,7 @@ __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const Chai
 // consists of; for large messages write-back is slower than write-through, so
 // the host only selects it up to a couple of MiB.  Buffers handed from stage to
 // stage are always loaded and stored at agent scope.
-template <int V, bool STAGE_WRITE_BACK>
+template <int V, int U, bool STAGE_WRITE_BACK>
 __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 {
     const unsigned lane = threadIdx.x & (kWaveSize - 1);
@@ -292,11 +293,11 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
     u64 *out_flag = (g + 1 < a.stages && !muted) ? a.flags + ((u64)g * a.lanes + s) * kFlagStrideWords : nullptr;
     unsigned near = 0, far = 0;  // hand-offs received from the same / another XCD
 
-    // A lane's share of a chunk is every lanes-th trip (one trip = kChainUnroll
-    // vector instructions of the wave, 4 KiB at 16 bytes per lane), so at any
+    // A lane's share of a chunk is every lanes-th trip (one trip = U vector
+    // instructions of the wave, U KiB at 16 bytes per lane), so at any
     // moment the lanes of a stage sweep one contiguous window of the chunk: DRAM
     // sees a few wide streams per stage, not one narrow stream per wave.
-    const u64 trip = (u64)kChainUnroll * kWaveSize * V;
+    const u64 trip = (u64)U * kWaveSize * V;
     const u64 stride = trip * a.lanes;
 
     u64 seen = 0;  // newest value read from in_flag
@@ -329,10 +330,10 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
                 if (hop != first_hop) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 const bool ld_cached = hop != first_hop;
                 const bool st_cached = STAGE_WRITE_BACK && (hop != last_hop || g + 1 == a.stages);
-                if (ld_cached && st_cached) copy_span_agent<V, kAuxCached, kAuxCached>(dst, src, lo, hi, lane);
-                else if (ld_cached) copy_span_agent<V, kAuxCached, kAuxAgent>(dst, src, lo, hi, lane);
-                else if (st_cached) copy_span_agent<V, kAuxAgent, kAuxCached>(dst, src, lo, hi, lane);
-                else copy_span_agent<V>(dst, src, lo, hi, lane);
+                if (ld_cached && st_cached) copy_span_agent<V, U, kAuxCached, kAuxCached>(dst, src, lo, hi, lane);
+                else if (ld_cached) copy_span_agent<V, U, kAuxCached, kAuxAgent>(dst, src, lo, hi, lane);
+                else if (st_cached) copy_span_agent<V, U, kAuxAgent, kAuxCached>(dst, src, lo, hi, lane);
+                else copy_span_agent<V, U>(dst, src, lo, hi, lane);
             }
         }
         // Look at the next chunk's flag while this chunk's stores drain: in
@@ -423,10 +424,21 @@ __global__ void __launch_bounds__(kBlockThreads) fanout_kernel(const CopyArgs a)
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream)
 {
     if (grid_blocks < 1) return hipErrorInvalidValue;
-    if (a.mode & kModeStageWriteBack) {
-        BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, true);
+    const bool wb = (a.mode & kModeStageWriteBack) != 0;
+    if (a.unroll == (unsigned)kTripUnrollSmall) {
+        if (wb) {
+            BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, kTripUnrollSmall, true);
+        } else {
+            BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, kTripUnrollSmall, false);
+        }
+    } else if (a.unroll == (unsigned)kTripUnrollDefault) {
+        if (wb) {
+            BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, kTripUnrollDefault, true);
+        } else {
+            BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, kTripUnrollDefault, false);
+        }
     } else {
-        BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, false);
+        return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
@@ -454,9 +466,9 @@ hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x
 
 hipError_t chain_max_blocks_per_cu(int *blocks, int *blocks_write_back)
 {
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, chain_kernel<16, false>, kBlockThreads, 0);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, chain_kernel<16, kTripUnrollDefault, false>, kBlockThreads, 0);
     if (e == hipSuccess)
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_write_back, chain_kernel<16, true>, kBlockThreads, 0);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_write_back, chain_kernel<16, kTripUnrollDefault, true>, kBlockThreads, 0);
     return e;
 }
 

@@ -38,6 +38,8 @@ static bool valid_entry(int nranks, const bcast_tune_entry_t &e)
     if (e.algo == BCAST_ALGO_CHAIN && (e.chunk_bytes == 0 || e.chunk_bytes % 16 != 0)) return false;
     if (e.chain_chunk_bytes % 16 != 0) return false;
     if (e.stages < 0 || e.stages > BCAST_MAX_RANKS || e.chain_stages < 0 || e.chain_stages > BCAST_MAX_RANKS) return false;
+    for (int t : {e.trip_bytes, e.chain_trip_bytes})
+        if (t != 0 && t != 3072 && t != 4096) return false;
     return true;
 }
 
@@ -68,6 +70,7 @@ extern "C" int bcast_tune_put(int nranks, size_t bytes, const bcast_tune_entry_t
     if (e.algo == BCAST_ALGO_CHAIN && e.chain_chunk_bytes == 0) {  // the winner is the chain: it is its own best
         e.chain_chunk_bytes = e.chunk_bytes;
         e.chain_stages = e.stages;
+        e.chain_trip_bytes = e.trip_bytes;
         e.chain_usec = e.usec;
     }
     std::lock_guard<std::mutex> g(g_mu);
@@ -123,16 +126,18 @@ extern "C" int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *ch
 
 static const char kHeaderLine[] =
     "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout 5=scatter-allgather 6=knomial) chunk_bytes usec "
-    "chain_chunk_bytes chain_usec stages chain_stages\n";
+    "chain_chunk_bytes chain_usec stages chain_stages trip_bytes chain_trip_bytes\n";
 
-// Text format, one entry per line (the last four columns are optional; for a
+// Text format, one entry per line (columns after usec are optional; for a
 // k-nomial winner the stages column holds the radix):
-//   nranks log2_bytes algo chunk_bytes usec [chain_chunk_bytes chain_usec [stages chain_stages]]
+//   nranks log2_bytes algo chunk_bytes usec [chain_chunk_bytes chain_usec [stages chain_stages
+//   [trip_bytes chain_trip_bytes]]]
 // Lines starting with '#' are comments.
 static void print_entry(FILE *f, int nranks, int bucket, const bcast_tune_entry_t &e)
 {
-    fprintf(f, "%d %d %d %llu %.3f %llu %.3f %d %d\n", nranks, bucket, e.algo, (unsigned long long)e.chunk_bytes, e.usec,
-            (unsigned long long)e.chain_chunk_bytes, e.chain_usec, e.stages, e.chain_stages);
+    fprintf(f, "%d %d %d %llu %.3f %llu %.3f %d %d %d %d\n", nranks, bucket, e.algo, (unsigned long long)e.chunk_bytes,
+            e.usec, (unsigned long long)e.chain_chunk_bytes, e.chain_usec, e.stages, e.chain_stages, e.trip_bytes,
+            e.chain_trip_bytes);
 }
 
 extern "C" int bcast_tune_save(const char *path)
@@ -163,8 +168,8 @@ extern "C" int bcast_tune_load(const char *path)
         unsigned long long chunk = 0, cchunk = 0;
         bcast_tune_entry_t e;
         memset(&e, 0, sizeof e);
-        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf %d %d", &nranks, &bucket, &e.algo, &chunk, &e.usec, &cchunk,
-                         &e.chain_usec, &e.stages, &e.chain_stages);
+        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf %d %d %d %d", &nranks, &bucket, &e.algo, &chunk, &e.usec, &cchunk,
+                         &e.chain_usec, &e.stages, &e.chain_stages, &e.trip_bytes, &e.chain_trip_bytes);
         e.chunk_bytes = chunk;
         e.chain_chunk_bytes = cchunk;
         if (got < 4 || bucket < 0 || bucket > 62 || !valid_entry(nranks, e)) {
@@ -174,6 +179,7 @@ extern "C" int bcast_tune_load(const char *path)
         if (e.algo == BCAST_ALGO_CHAIN && e.chain_chunk_bytes == 0) {
             e.chain_chunk_bytes = e.chunk_bytes;
             e.chain_stages = e.stages;
+            e.chain_trip_bytes = e.trip_bytes;
             e.chain_usec = e.usec;
         }
         rows.push_back({{nranks, bucket}, e});
@@ -201,13 +207,14 @@ struct Scratch {
 
 // Microseconds per run of one candidate.  One timed run warms up and sizes
 // the batches (about 20 ms each, 2..40 runs); the best of three batches counts.
-int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages, Scratch &sc, hipStream_t stream,
-                   double *usec)
+int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages, int trip, Scratch &sc,
+                   hipStream_t stream, double *usec)
 {
     bcast_plan_t *plan = nullptr;
     int rc = bcast_plan_create(&plan, nranks, bytes, chunk, algo);
     if (rc != BCAST_OK) return rc;
     rc = algo == BCAST_ALGO_KNOMIAL ? bcast_plan_set_radix(plan, stages) : bcast_plan_set_stages(plan, stages);
+    if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN) rc = bcast_plan_set_trip(plan, trip);
     int reps = 1;
     double best = 1e30;
     for (int batch = 0; batch < 4 && rc == BCAST_OK; ++batch) {
@@ -253,7 +260,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         std::lock_guard<std::mutex> g(g_mu);
         if (!g_log_path.empty()) log = fopen(g_log_path.c_str(), "a");
     }
-    if (log) fprintf(log, "# nranks bytes algo chunk_bytes stages usec\n");
+    if (log) fprintf(log, "# nranks bytes algo chunk_bytes stages usec trip_bytes\n");
     struct LogCloser {
         FILE *f;
         ~LogCloser() { if (f) fclose(f); }
@@ -285,36 +292,45 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         bcast_tune_entry_t best;
         memset(&best, 0, sizeof best);
         best.usec = best.chain_usec = 1e30;
-        auto consider = [&](int algo, size_t chunk, int stages) {
+        auto consider = [&](int algo, size_t chunk, int stages, int trip = 0) {
             if (rc != BCAST_OK || !(algo_mask & (1u << algo))) return;
             double us = 0.0;
-            rc = time_candidate(nranks, M, algo, chunk, stages, sc, stream, &us);
+            rc = time_candidate(nranks, M, algo, chunk, stages, trip, sc, stream, &us);
             if (rc != BCAST_OK) return;
-            if (log) fprintf(log, "%d %zu %d %zu %d %.3f\n", nranks, M, algo, chunk, stages, us);
+            if (log) fprintf(log, "%d %zu %d %zu %d %.3f %d\n", nranks, M, algo, chunk, stages, us, trip);
             if (algo == BCAST_ALGO_CHAIN && us < best.chain_usec) {
                 best.chain_chunk_bytes = chunk;
                 best.chain_stages = stages;
+                best.chain_trip_bytes = trip;
                 best.chain_usec = us;
             }
             if (us < best.usec) {
                 best.algo = algo;
                 best.chunk_bytes = chunk;
                 best.stages = (algo == BCAST_ALGO_CHAIN || algo == BCAST_ALGO_KNOMIAL) ? stages : 0;
+                best.trip_bytes = algo == BCAST_ALGO_CHAIN ? trip : 0;
                 best.usec = us;
             }
         };
         // chain: for every stage count, the whole message as one chunk (Eq. 2)
-        // and the power-of-two chunk sizes from 8 KiB to 64 MiB (Eq. 5), at most
-        // 4096 chunks and at most 128 KiB of a chunk per lane.  The chunk size
-        // also sets the number of lanes (one 4 KiB trip per lane and chunk until
-        // the device is full), so this sweep covers wave counts as well.
+        // and chunk sizes lanes * trip for power-of-two lane counts (Eq. 5): a
+        // chunk gives every lane one trip, so the chunk size is also the number
+        // of waves that run, and that is what has an optimum (see chain_kernel).
+        // 4 KiB trips span 8 KiB .. 64 MiB chunks; 3 KiB trips are only tried
+        // where they can matter (messages of a few MiB and more).  At most 4096
+        // chunks per message.
         for (int stages : stage_counts) {
             size_t lanes_max = 1;
             while (lanes_max * 2 * stages <= 8192) lanes_max *= 2;
-            consider(BCAST_ALGO_CHAIN, std::max<size_t>(16, (M + 15) / 16 * 16), stages);
-            for (size_t C = 8u << 10; C <= (64u << 20) && C < M; C <<= 1) {
-                if (M / C > 4096 || C > lanes_max * (128u << 10)) continue;
-                consider(BCAST_ALGO_CHAIN, C, stages);
+            consider(BCAST_ALGO_CHAIN, std::max<size_t>(16, (M + 15) / 16 * 16), stages, 4096);
+            for (int trip : {4096, 3072}) {
+                if (trip == 3072 && M < (4u << 20)) continue;
+                for (size_t lanes = 2; lanes <= lanes_max * 32; lanes <<= 1) {
+                    const size_t C = lanes * (size_t)trip;
+                    if (C >= M || M / C > 4096 || C > (64u << 20)) continue;
+                    if (trip == 3072 && lanes * (size_t)stages < 512) continue;
+                    consider(BCAST_ALGO_CHAIN, C, stages, trip);
+                }
             }
         }
         consider(BCAST_ALGO_DIRECT, 0, 0);

@@ -5,7 +5,7 @@ to measured broadcast times.
 
 `SWEEP.txt` is what ``bcast_tune`` writes while a log path is set
 (``make_table --log``): one line per timed candidate,
-``nranks bytes algo chunk_bytes stages usec``.  For every rank count the start-up
+``nranks bytes algo chunk_bytes stages usec [trip_bytes]``.  For every rank count the start-up
 time t_s and the bandwidth B of Table I are estimated per algorithm by linear
 least squares (each model is linear in t_s and 1/B), the model's prediction is
 compared with every measurement, and the chunk size that minimises Eq. 5,
@@ -114,7 +114,7 @@ def read_log(path: str) -> Dict[int, List[Tuple[int, int, int, int, float]]]:
         for line in f:
             if not line.strip() or line.startswith("#"):
                 continue
-            n, M, algo, C, stages, us = line.split()
+            n, M, algo, C, stages, us = line.split()[:6]
             out[int(n)].append((int(M), int(algo), int(C), int(stages), float(us) * 1e-6))
     return out
 

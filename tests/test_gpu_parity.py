@@ -89,6 +89,16 @@ def test_scatter_allgather_piece_edges(noise, P, M):
     assert info["algorithmic_bytes"] == 2 * oracle.scatter_allgather_bcast(None, P, P - 1, M).bytes_copied
 
 
+@pytest.mark.parametrize("offsets", [None, [4] * 9, [1, 0, 3, 16, 8, 2, 5, 7, 12]])
+@pytest.mark.parametrize("stages,M,C", [(1, 3072, 3072), (2, 3073, 3072), (3, 70000, 6144), (8, 3 * MiB + 5, 96 * KiB),
+                                        (2, 5 * MiB + 1000, 768 * KiB), (4, 100000, 1 << 20)])
+def test_chain_three_kib_trips(noise, stages, M, C, offsets):
+    """The 3 KiB-trip build of the chain kernel: chunk sizes that are and are
+    not whole trips, ragged tails, pointers of every alignment."""
+    info = run_and_check(9, 2, M, C, B.BCAST_ALGO_CHAIN, noise, stages=stages, trip=3072, offsets=offsets)
+    assert info["trip_bytes"] == 3072 and info["slice_bytes"] % 3072 == 0
+
+
 @pytest.mark.parametrize("P,radix", [(2, 2), (5, 3), (9, 3), (10, 3), (16, 4), (17, 4), (64, 4), (64, 8), (64, 64), (33, 2), (7, 9)])
 @pytest.mark.parametrize("M", [9, 4096, MiB + 3])
 def test_knomial_radices(noise, P, radix, M):
@@ -304,11 +314,12 @@ def test_random_configurations(noise):
         offsets = [[0] * P, [int(rng.integers(0, 16))] * P, [int(x) for x in rng.integers(0, 4, P) * 4],
                    [int(x) for x in rng.integers(0, 33, P)]][kind]
         radix = int(rng.integers(2, 10)) if algo == B.BCAST_ALGO_KNOMIAL else 0
+        trip = int(rng.choice([0, 3072, 4096])) if algo == B.BCAST_ALGO_CHAIN else 0
         try:
-            run_and_check(P, root, M, C, algo, noise, offsets=offsets, lanes=lanes, stages=stages, radix=radix)
+            run_and_check(P, root, M, C, algo, noise, offsets=offsets, lanes=lanes, stages=stages, radix=radix, trip=trip)
         except Exception as e:
-            raise AssertionError("case %d: P=%d root=%d M=%d C=%d algo=%d stages=%d lanes=%d offsets=%s radix=%d: %s"
-                                 % (case, P, root, M, C, algo, stages, lanes, kind, radix, e))
+            raise AssertionError("case %d: P=%d root=%d M=%d C=%d algo=%d stages=%d lanes=%d offsets=%s radix=%d trip=%d: %s"
+                                 % (case, P, root, M, C, algo, stages, lanes, kind, radix, trip, e))
 
 
 def test_two_plans_on_two_streams_at_once(noise):

@@ -64,6 +64,14 @@ def test_chain_geometry_matches_eq5_chunking():
     assert (g["stages"], g["hops_per_stage"], g["lanes"]) == (7, 1, 1024)
     g = B.bcast_chain_geometry(8, 1 << 26, 8 << 20, 8192, stages_request=1)
     assert (g["stages"], g["hops_per_stage"], g["grid_blocks"]) == (1, 7, 512)
+    # trip size: 4 KiB unless 3 KiB is asked for; a lane owns whole trips
+    assert g["trip_bytes"] == 4096 and g["slice_bytes"] == 4096
+    g = B.bcast_chain_geometry(64, 1 << 30, 3 << 20, 8192, stages_request=2, trip_request=3072)
+    assert (g["trip_bytes"], g["lanes"], g["slice_bytes"], g["nchunks"]) == (3072, 1024, 3072, 342)
+    g = B.bcast_chain_geometry(64, 1 << 30, 3 << 20, 8192, stages_request=2, trip_request=4096)
+    assert (g["lanes"], g["slice_bytes"]) == (512, 8192)  # 768 trips: the next power of two below
+    with pytest.raises(B.BcastError):
+        B.bcast_chain_geometry(8, 1 << 20, 4096, 64, trip_request=2048)
     # no-ops
     assert B.bcast_chain_geometry(1, 1 << 20, 4096, 64)["nchunks"] == 0
     assert B.bcast_chain_geometry(4, 0, 4096, 64)["nchunks"] == 0
@@ -109,22 +117,29 @@ def test_tuning_table_lookup_rules(tmp_path):
         B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=24)  # not a multiple of 16
     with pytest.raises(B.BcastError):
         B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_DIRECT, chain_stages=65)
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=4096, trip_bytes=2048)
+    B.bcast_tune_put(16, 1 << 24, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=3 << 20, stages=2, trip_bytes=3072, usec=80.0)
 
     path = tmp_path / "table.txt"
     B.bcast_tune_save(str(path))
     B.bcast_tune_clear()
     B.bcast_tune_load(str(path))
-    assert B.bcast_tune_count() == 3
+    assert B.bcast_tune_count() == 4
+    e = B.bcast_tune_get(16, 1 << 24)
+    assert (e["trip_bytes"], e["chain_trip_bytes"], e["chain_chunk_bytes"], e["stages"]) == (3072, 3072, 3 << 20, 2)
     assert B.bcast_tune_lookup(8, 1 << 20) == (B.BCAST_ALGO_CHAIN, 64 << 10, 50.0)
     e = B.bcast_tune_get(16, 1 << 20)
     assert (e["chain_chunk_bytes"], e["chain_stages"], e["chain_usec"]) == (128 << 10, 4, 90.0)
-    # files with only the first five or seven columns still load
+    # files with only the first five, seven or nine columns still load
     old = tmp_path / "old.txt"
-    old.write_text("4 20 1 65536 12.5\n4 10 3 0 5.0\n4 12 2 0 5.0 8192 7.5\n")
+    old.write_text("4 20 1 65536 12.5\n4 10 3 0 5.0\n4 12 2 0 5.0 8192 7.5\n4 24 1 1048576 9.0 1048576 9.0 2 2\n")
     B.bcast_tune_load(str(old))
     e = B.bcast_tune_get(4, 1 << 20)
     assert (e["chain_chunk_bytes"], e["chain_usec"], e["stages"]) == (65536, 12.5, 0)
     assert B.bcast_tune_get(4, 1 << 12)["chain_chunk_bytes"] == 8192
+    e = B.bcast_tune_get(4, 1 << 24)
+    assert (e["stages"], e["chain_stages"], e["trip_bytes"], e["chain_trip_bytes"]) == (2, 2, 0, 0)
 
     bad = tmp_path / "bad.txt"
     bad.write_text("8 20 1 65536 1.0\n8 21 1 7 1.0\n")
