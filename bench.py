@@ -2,7 +2,8 @@
 """Benchmark of the broadcast hot path on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
-                    [--algo chain|direct|binomial|fanout|auto] [--chunk BYTES] [--lanes N] [--stages N] [--trip BYTES]
+                    [--algo chain|direct|binomial|fanout|auto] [--chunk BYTES] [--lanes N] [--stages N] [--trip BYTES] [--block THREADS]
+                    [--rank-stride BYTES]
 
 A "step" is one whole broadcast (every chunk over every hop) of the workload's
 message to all P virtual ranks, with all buffers already resident in HBM.
@@ -44,10 +45,11 @@ WORKLOADS = {
 # The chain's traffic is BELOW its algorithmic bytes: part of what a wave reads
 # back inside a stage is served by the CU's vector L1 and never reaches the fabric.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "chain"): int((155408.1 * (65536.0 / 32786.8) + 459264.0) * 1024),
+    ("cfg2", "chain"): int((155526.3 * (65536.0 / 32786.3) + 459264.0) * 1024),
     ("cfg2", "direct"): int((32784.5 * (65536.0 / 32786.9) + 65536.0) * 1024),
-    ("cfg4", "chain"): int((4003527.3 * (524288.0 / 262167.0) + 16265216.0) * 1024),
-    ("cfg5", "chain"): int((15327635.5 * (1048576.0 / 524315.7) + 66084864.0) * 1024),
+    ("cfg3", "chain"): int((993754.3 * (540459.2 / 270255.1) + 8112519.3) * 1024),
+    ("cfg4", "chain"): int((1542330.8 * (524288.0 / 262167.2) + 16258400.0) * 1024),
+    ("cfg5", "chain"): int((5636280.7 * (1048576.0 / 524313.2) + 66071232.0) * 1024),
 }
 
 
@@ -73,6 +75,10 @@ def main() -> int:
     ap.add_argument("--chunk", type=int, default=0, help="chain chunk bytes (0 = tuned table / built-in rule)")
     ap.add_argument("--lanes", type=int, default=0, help="wavefronts per chain hop (0 = automatic)")
     ap.add_argument("--stages", type=int, default=0, help="chain stages (0 = tuned table / built-in rule)")
+    ap.add_argument("--rank-stride", type=int, default=0,
+                    help="place the rank buffers in one allocation this many bytes apart (>= message bytes, multiple of 256; "
+                         "0 = one allocation per rank)")
+    ap.add_argument("--block", type=int, default=0, help="chain workgroup size, 64, 128 or 256 (0 = default)")
     ap.add_argument("--trip", type=int, default=0, help="chain trip bytes, 3072 or 4096 (0 = tuned table / 4096)")
     ap.add_argument("--ranks", type=int, default=0, help="override the workload's P (experiments)")
     ap.add_argument("--bytes", type=int, default=0, help="override the workload's message size (experiments)")
@@ -112,8 +118,14 @@ def main() -> int:
     assert msg.nbytes == M
     d_msg = torch.from_numpy(msg).cuda()
     bufs = []
+    arena = None
+    if args.rank_stride:
+        if args.rank_stride < M or args.rank_stride % 256:
+            print("bench.py: --rank-stride must be >= the message size and a multiple of 256", file=sys.stderr)
+            return 2
+        arena = torch.empty(args.rank_stride * (P - 1) + M, dtype=torch.uint8, device="cuda")
     for r in range(P):
-        t = torch.empty(M, dtype=torch.uint8, device="cuda")
+        t = arena[r * args.rank_stride: r * args.rank_stride + M] if arena is not None else torch.empty(M, dtype=torch.uint8, device="cuda")
         if r == root:
             t.copy_(d_msg)
         else:
@@ -128,6 +140,8 @@ def main() -> int:
         B.bcast_plan_set_stages(plan, args.stages)
     if args.trip:
         B.bcast_plan_set_trip(plan, args.trip)
+    if args.block:
+        B.bcast_plan_set_block_threads(plan, args.block)
     info = B.bcast_plan_info(plan, M, bufs)
     stream = torch.cuda.current_stream()
 
@@ -170,7 +184,7 @@ def main() -> int:
     algorithmic = int(info["algorithmic_bytes"])
     value = algorithmic / (wall_ms * 1e-3) / 1e9
     achieved = algorithmic / (avg_launch_ms * 1e-3) / 1e9
-    custom = bool(args.ranks or args.bytes or args.chunk or args.lanes or args.stages or args.trip)
+    custom = bool(args.ranks or args.bytes or args.chunk or args.lanes or args.stages or args.trip or args.block or args.rank_stride)
     traffic = None if custom else MEASURED_TRAFFIC_BYTES.get((args.workload, args.algo))
 
     sweep = None
@@ -198,7 +212,7 @@ def main() -> int:
         "config": {
             "workload": "%s: %s, root %d" % (args.workload, what, root),
             "P": P, "message_bytes": M, "algo": B.ALGO_NAMES[info["algo"]],
-            "chunk_bytes": int(info["chunk_bytes"]), "nchunks": int(info["nchunks"]), "stages": info["stages"], "hops_per_stage": info["hops_per_stage"], "trip_bytes": info["trip_bytes"],
+            "chunk_bytes": int(info["chunk_bytes"]), "nchunks": int(info["nchunks"]), "stages": info["stages"], "hops_per_stage": info["hops_per_stage"], "trip_bytes": info["trip_bytes"], "block_threads": info["block_threads"], "rank_stride": args.rank_stride,
             "lanes": info["lanes"],
             "grid_blocks": info["grid_blocks"], "vec_bytes": info["vec_bytes"], "launches_per_step": info["launches"],
             "tuning_table": table,
@@ -212,7 +226,7 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
             "traffic": traffic,
-            "kernel": ("bcast::chain_kernel<%d, %s>" % (info["vec_bytes"], "true" if M <= (2 << 20) else "false"))
+            "kernel": ("bcast::chain_kernel<%d, %d, %s>" % (info["vec_bytes"], info["trip_bytes"] // 1024, "true" if M <= (2 << 20) else "false"))
             if info["algo"] == B.BCAST_ALGO_CHAIN else B.ALGO_NAMES[info["algo"]],
             "algorithmic_bytes_per_launch": algorithmic,
             "avg_launch_ms": round(avg_launch_ms, 5),

@@ -150,6 +150,10 @@ int bcast_plan_set_stages(bcast_plan_t *plan, int stages);
 /* Bytes a chain wavefront moves per trip (16-byte accesses): 4096 or 3072,
  * 0 = the tuning table's choice, else 4096. */
 int bcast_plan_set_trip(bcast_plan_t *plan, int trip_bytes);
+/* Threads per workgroup of the chain kernel: 64, 128 or 256 (1, 2 or 4
+ * wavefronts; they never synchronise, the workgroup is only the unit placed on
+ * a compute unit), 0 = default. */
+int bcast_plan_set_block_threads(bcast_plan_t *plan, int block_threads);
 /* Radix k of BCAST_ALGO_KNOMIAL, 2..nranks (0 = the tuning table's, else 4):
  * in round j every position q < k^j sends to q + i k^j, i = 1..k-1. */
 int bcast_plan_set_radix(bcast_plan_t *plan, int radix);
@@ -174,15 +178,22 @@ int bcast_plan_enable_trace(bcast_plan_t *plan, size_t entries);
 int bcast_plan_read_trace(bcast_plan_t *plan, uint64_t *out, size_t entries);
 int bcast_plan_handoff_counts(bcast_plan_t *plan, uint64_t *same_xcd, uint64_t *cross_xcd);
 
+/* Launch-shape requests for the chain kernel; 0 = automatic in every field. */
+typedef struct {
+    int lanes;         /* wavefronts per stage */
+    int stages;        /* groups of consecutive chain positions served by one set of wavefronts */
+    int trip_bytes;    /* 3072 or 4096 */
+    int block_threads; /* 64, 128 or 256 */
+} bcast_chain_request_t;
+
 /*
  * Chain geometry as a pure HOST function (no GPU needed): how a chain of
  * `nranks` ranks moving `bytes` bytes in chunks of `chunk_bytes` is laid over
- * at most `max_waves` co-resident wavefronts.  lanes_request, stages_request,
- * trip_request: 0 = automatic.  Fills nchunks, stages, hops_per_stage, lanes, slice_bytes, grid_blocks, block_threads, chunk_bytes.
+ * at most `max_waves` co-resident wavefronts.  `request` (nullable = all
+ * automatic) carries what the plan setters would.  Fills nchunks, stages, hops_per_stage, lanes, slice_bytes, grid_blocks, block_threads, chunk_bytes.
  */
 int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
-                         int lanes_request, int stages_request, int trip_request,
-                         bcast_plan_info_t *info);
+                         const bcast_chain_request_t *request, bcast_plan_info_t *info);
 
 /*
  * Tuning table (Sec. III-B "Discussion" and IV-B last paragraph: algorithm and

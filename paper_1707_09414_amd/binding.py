@@ -38,7 +38,7 @@ BCAST_ERR_UNTUNED = -5
 # every symbol include/bcast.h declares
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
     "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
@@ -52,6 +52,10 @@ class BcastError(RuntimeError):
         if status == BCAST_ERR_HIP:
             msg += ", hipError %d" % _lib.bcast_last_hip_error()
         super().__init__(msg)
+
+
+class ChainRequest(ctypes.Structure):
+    _fields_ = [("lanes", ctypes.c_int), ("stages", ctypes.c_int), ("trip_bytes", ctypes.c_int), ("block_threads", ctypes.c_int)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -115,12 +119,13 @@ def _load():
         "bcast_plan_set_stages": ([vp, i], i),
         "bcast_plan_set_radix": ([vp, i], i),
         "bcast_plan_set_trip": ([vp, i], i),
+        "bcast_plan_set_block_threads": ([vp, i], i),
         "bcast_plan_set_debug": ([vp, u64, i], i),
         "bcast_plan_set_mode": ([vp, ctypes.c_uint], i),
         "bcast_plan_enable_trace": ([vp, sz], i),
         "bcast_plan_read_trace": ([vp, ctypes.POINTER(u64), sz], i),
         "bcast_plan_handoff_counts": ([vp, ctypes.POINTER(u64), ctypes.POINTER(u64)], i),
-        "bcast_chain_geometry": ([i, sz, sz, i, i, i, i, ctypes.POINTER(PlanInfo)], i),
+        "bcast_chain_geometry": ([i, sz, sz, i, ctypes.POINTER(ChainRequest), ctypes.POINTER(PlanInfo)], i),
         "bcast_tune": ([i, sz, sz, ctypes.c_uint, vp, ctypes.c_char_p], i),
         "bcast_tune_load": ([ctypes.c_char_p], i),
         "bcast_tune_save": ([ctypes.c_char_p], i),
@@ -243,6 +248,10 @@ def bcast_plan_set_trip(plan: Plan, trip_bytes: int) -> None:
     _check(_lib.bcast_plan_set_trip(plan.handle, trip_bytes), "bcast_plan_set_trip")
 
 
+def bcast_plan_set_block_threads(plan: Plan, block_threads: int) -> None:
+    _check(_lib.bcast_plan_set_block_threads(plan.handle, block_threads), "bcast_plan_set_block_threads")
+
+
 def bcast_plan_set_radix(plan: Plan, radix: int) -> None:
     _check(_lib.bcast_plan_set_radix(plan.handle, radix), "bcast_plan_set_radix")
 
@@ -277,10 +286,10 @@ def bcast_plan_handoff_counts(plan: Plan) -> Tuple[int, int]:
 
 
 def bcast_chain_geometry(nranks: int, bytes: int, chunk_bytes: int, max_waves: int, lanes_request: int = 0,
-                         stages_request: int = 0, trip_request: int = 0) -> dict:
+                         stages_request: int = 0, trip_request: int = 0, block_request: int = 0) -> dict:
     info = PlanInfo()
-    _check(_lib.bcast_chain_geometry(nranks, bytes, chunk_bytes, max_waves, lanes_request, stages_request,
-                                     trip_request, ctypes.byref(info)),
+    req = ChainRequest(lanes_request, stages_request, trip_request, block_request)
+    _check(_lib.bcast_chain_geometry(nranks, bytes, chunk_bytes, max_waves, ctypes.byref(req), ctypes.byref(info)),
            "bcast_chain_geometry")
     return info.as_dict()
 

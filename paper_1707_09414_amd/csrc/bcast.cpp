@@ -18,8 +18,11 @@ struct bcast_plan {
     int algo = BCAST_ALGO_AUTO;
     int device = 0;
     int cu_count = 0;
-    int max_waves = 0;       // wavefronts of the chain kernel the device holds at once
-    int max_waves_cached = 0;  // the same for its small-message (write-back) variant
+    // wavefronts of the chain kernel the device holds at once, per workgroup
+    // size (index: 0 = 64, 1 = 128, 2 = 256 threads)
+    int max_waves[3] = {0, 0, 0};
+    int max_waves_cached[3] = {0, 0, 0};  // the same for its small-message (write-back) variant
+    int max_flags = 0;                    // flags allocated: the largest of the above
     u64 *d_flags = nullptr;  // max_waves flags, kFlagStrideWords apart, plus the abort word
     u64 *d_abort = nullptr;
     u64 *d_counters = nullptr; // two words after the abort word
@@ -33,6 +36,7 @@ struct bcast_plan {
     int stages_request = 0;
     int radix_request = 0;
     int trip_request = 0;  // bytes at 16-byte vectors: 0 = choose, else 3072 or 4096
+    int block_request = 0; // chain workgroup size: 0 = choose, else 64, 128 or 256
     u64 spin_ticks = kDefaultSpinTicks;
     int mute_hop = 0;
 };
@@ -87,18 +91,24 @@ static u64 default_chunk(int nranks, int max_waves, int stages_request, u64 trip
     return p * trip;
 }
 
+static int block_index(int block_threads) { return block_threads == 64 ? 0 : block_threads == 128 ? 1 : 2; }
+
 extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
-                                    int lanes_request, int stages_request, int trip_request,
-                                    bcast_plan_info_t *info)
+                                    const bcast_chain_request_t *req, bcast_plan_info_t *info)
 {
+    const bcast_chain_request_t none = {0, 0, 0, 0};
+    if (!req) req = &none;
+    const int lanes_request = req->lanes, stages_request = req->stages;
     if (!info || nranks < 1 || nranks > BCAST_MAX_RANKS || max_waves < 1 || lanes_request < 0 || stages_request < 0)
         return BCAST_ERR_ARG;
-    const u64 trip = trip_request ? (u64)trip_request : trip_bytes_of(kTripUnrollDefault);
+    const u64 trip = req->trip_bytes ? (u64)req->trip_bytes : trip_bytes_of(kTripUnrollDefault);
     if (!valid_trip(trip)) return BCAST_ERR_ARG;
+    const int block = req->block_threads ? req->block_threads : kBlockThreads;
+    if (!valid_chain_block(block)) return BCAST_ERR_ARG;
     if (chunk_bytes == 0 || chunk_bytes % 16 != 0) return BCAST_ERR_ARG;
     memset(info, 0, sizeof *info);
     info->algo = BCAST_ALGO_CHAIN;
-    info->block_threads = kBlockThreads;
+    info->block_threads = block;
     info->vec_bytes = 16;
     if (nranks < 2 || bytes == 0) {
         info->chunk_bytes = chunk_bytes;
@@ -136,7 +146,7 @@ extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes
     info->lanes = (int)lanes;
     info->stages = stages;
     info->hops_per_stage = hps;
-    info->grid_blocks = (int)ceil_div((u64)stages * lanes, kWavesPerBlock);
+    info->grid_blocks = (int)ceil_div((u64)stages * lanes, (u64)(block / kWaveSize));
     info->launches = 1;
     info->algorithmic_bytes = 2ull * hops * bytes;
     return BCAST_OK;
@@ -159,24 +169,31 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
 
     int rc = BCAST_OK;
     hipDeviceProp_t prop;
-    int per_cu = 0, per_cu_cached = 0;
     hipError_t e = hipGetDevice(&p->device);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, p->device);
-    if (e == hipSuccess) e = chain_max_blocks_per_cu(&per_cu, &per_cu_cached);
     if (e == hipSuccess) {
         p->cu_count = prop.multiProcessorCount;
         // the chain grid never exceeds what the device holds at once, so every
-        // wave a waiter depends on is resident (hop-major numbering alone already
-        // makes waits point at earlier-dispatched workgroups)
-        per_cu = std::max(1, std::min(per_cu, 8));
-        per_cu_cached = std::max(1, std::min(per_cu_cached, per_cu));
-        p->max_waves = std::max(nranks, p->cu_count * per_cu * kWavesPerBlock);
-        p->max_waves_cached = std::max(nranks, p->cu_count * per_cu_cached * kWavesPerBlock);
-        size_t flag_bytes = ((size_t)p->max_waves + 2) * kFlagStrideWords * sizeof(u64);
+        // wave a waiter depends on is resident (stage-major numbering alone
+        // already makes waits point at earlier-dispatched workgroups); at most
+        // 32 waves per CU are counted on
+        for (int b = 0; b < 3 && e == hipSuccess; ++b) {
+            const int threads = kWaveSize << b, waves = 1 << b;
+            int per_cu = 0, per_cu_cached = 0;
+            e = chain_max_blocks_per_cu(threads, &per_cu, &per_cu_cached);
+            per_cu = std::max(1, std::min(per_cu * waves, 32) / waves);
+            per_cu_cached = std::max(1, std::min(per_cu_cached, per_cu));
+            p->max_waves[b] = std::max(nranks, p->cu_count * per_cu * waves);
+            p->max_waves_cached[b] = std::max(nranks, p->cu_count * per_cu_cached * waves);
+            p->max_flags = std::max(p->max_flags, p->max_waves[b]);
+        }
+    }
+    if (e == hipSuccess) {
+        size_t flag_bytes = ((size_t)p->max_flags + 2) * kFlagStrideWords * sizeof(u64);
         e = hipMalloc((void **)&p->d_flags, flag_bytes);
         if (e == hipSuccess) e = hipMemset(p->d_flags, 0, flag_bytes);
         if (e == hipSuccess) {
-            p->d_abort = p->d_flags + (size_t)p->max_waves * kFlagStrideWords;
+            p->d_abort = p->d_flags + (size_t)p->max_flags * kFlagStrideWords;
             p->d_counters = p->d_abort + kFlagStrideWords;
         }
     }
@@ -228,6 +245,13 @@ extern "C" int bcast_plan_set_trip(bcast_plan_t *p, int trip_bytes)
 {
     if (!p || (trip_bytes != 0 && !valid_trip((u64)trip_bytes))) return BCAST_ERR_ARG;
     p->trip_request = trip_bytes;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_set_block_threads(bcast_plan_t *p, int block_threads)
+{
+    if (!p || (block_threads != 0 && !valid_chain_block(block_threads))) return BCAST_ERR_ARG;
+    p->block_request = block_threads;
     return BCAST_OK;
 }
 
@@ -337,7 +361,8 @@ static int default_stages(int nranks) { return std::min(std::max(1, nranks - 1),
 // Co-residency limit of the kernel variant a message of `bytes` bytes will use.
 static int waves_for(const bcast_plan *p, size_t bytes)
 {
-    return bytes <= kStageWriteBackMaxBytes ? p->max_waves_cached : p->max_waves;
+    const int b = block_index(p->block_request ? p->block_request : kBlockThreads);
+    return bytes <= kStageWriteBackMaxBytes ? p->max_waves_cached[b] : p->max_waves[b];
 }
 
 static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
@@ -447,7 +472,8 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
     const int P = p->nranks;
     const int vec = common_vec_bytes(rank_bufs, P);
     if (r.algo == BCAST_ALGO_CHAIN) {
-        rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, waves_for(p, bytes), p->lanes_request, r.stages, r.trip, info);
+        const bcast_chain_request_t req = {p->lanes_request, r.stages, r.trip, p->block_request};
+        rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, waves_for(p, bytes), &req, info);
         if (rc != BCAST_OK) return rc;
         info->vec_bytes = vec;
         return BCAST_OK;
@@ -571,7 +597,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
             return BCAST_ERR_ARG;
         if (a.nchunks == 0 || a.lanes == 0 || a.chunk_bytes == 0) return BCAST_ERR_ARG;
         if ((u64)a.nchunks * a.chunk_bytes < a.bytes) return BCAST_ERR_ARG;
-        HIP_TRY(launch_chain(a, info.vec_bytes, info.grid_blocks, stream));
+        HIP_TRY(launch_chain(a, info.vec_bytes, info.grid_blocks, info.block_threads, stream));
         return BCAST_OK;
     }
 

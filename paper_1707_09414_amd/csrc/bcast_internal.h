@@ -12,8 +12,9 @@ namespace bcast {
 
 typedef unsigned long long u64;
 
-// Workgroups are 256 threads = 4 wavefronts of 64; every wavefront is an
-// independent copy engine (no workgroup barriers anywhere in the library).
+// Workgroups are 256 threads = 4 wavefronts of 64 (the chain kernel can also be
+// launched with 1 or 2); every wavefront is an independent copy engine (no
+// workgroup barriers anywhere in the library).
 constexpr int kBlockThreads = 256;
 constexpr int kWaveSize = 64;
 constexpr int kWavesPerBlock = kBlockThreads / kWaveSize;
@@ -100,10 +101,11 @@ struct RangedCopyArgs {
 
 // Launchers implemented in kernels.hip.  vec_bytes is 16, 8, 4 or 1: every
 // buffer address in the call is congruent modulo vec_bytes.
-hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
+hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream);
+bool valid_chain_block(int block_threads);  // 64, 128 or 256
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
-hipError_t chain_max_blocks_per_cu(int *blocks, int *blocks_write_back);
+hipError_t chain_max_blocks_per_cu(int block_threads, int *blocks, int *blocks_write_back);
 
 }  // namespace bcast

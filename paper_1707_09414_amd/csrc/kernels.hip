@@ -273,7 +273,9 @@ template <int V, int U, bool STAGE_WRITE_BACK>
 __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 {
     const unsigned lane = threadIdx.x & (kWaveSize - 1);
-    const unsigned gw = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    // workgroups of 1, 2 or 4 waves: no wave ever meets another at a barrier,
+    // the workgroup is only the unit the dispatcher places on a CU
+    const unsigned gw = __builtin_amdgcn_readfirstlane(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
     if (gw >= a.stages * a.lanes) return;
     // Stage g serves the consecutive chain positions first_hop .. last_hop: its
     // waves play those ranks one after the other for every chunk (hops_per_stage
@@ -325,8 +327,11 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
             for (unsigned hop = first_hop; hop <= last_hop; ++hop) {
                 const char *src = a.buf[hop - 1];
                 char *dst = a.buf[hop];
-                // what this wave stored for position hop-1 must have completed
-                // before it is read back for position hop
+                // What this wave stored for position hop-1 must have completed
+                // before it is read back for position hop.  (Same-address order
+                // alone would make the read-back correct without this wait, but
+                // measured it is 10-25 % slower with 3 KiB trips: loads issued
+                // behind stores still in flight miss the L1.)
                 if (hop != first_hop) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 const bool ld_cached = hop != first_hop;
                 const bool st_cached = STAGE_WRITE_BACK && (hop != last_hop || g + 1 == a.stages);
@@ -412,30 +417,36 @@ __global__ void __launch_bounds__(kBlockThreads) fanout_kernel(const CopyArgs a)
 }
 
 // Launch KERNEL<V, ...> for the vector width the host found usable.
-#define BCAST_LAUNCH_V(KERNEL, vec_bytes, grid, stream, args, ...)                                      \
-    switch (vec_bytes) {                                                                                \
-    case 16: KERNEL<16 __VA_OPT__(,) __VA_ARGS__><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break; \
-    case 8: KERNEL<8 __VA_OPT__(,) __VA_ARGS__><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break;   \
-    case 4: KERNEL<4 __VA_OPT__(,) __VA_ARGS__><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break;   \
-    case 1: KERNEL<1 __VA_OPT__(,) __VA_ARGS__><<<grid, dim3(kBlockThreads), 0, stream>>>(args); break;   \
-    default: return hipErrorInvalidValue;                                                               \
+#define BCAST_LAUNCH_VB(KERNEL, vec_bytes, grid, block, stream, args, ...)                      \
+    switch (vec_bytes) {                                                                        \
+    case 16: KERNEL<16 __VA_OPT__(,) __VA_ARGS__><<<grid, block, 0, stream>>>(args); break;     \
+    case 8: KERNEL<8 __VA_OPT__(,) __VA_ARGS__><<<grid, block, 0, stream>>>(args); break;       \
+    case 4: KERNEL<4 __VA_OPT__(,) __VA_ARGS__><<<grid, block, 0, stream>>>(args); break;       \
+    case 1: KERNEL<1 __VA_OPT__(,) __VA_ARGS__><<<grid, block, 0, stream>>>(args); break;       \
+    default: return hipErrorInvalidValue;                                                       \
     }
+#define BCAST_LAUNCH_V(KERNEL, vec_bytes, grid, stream, args, ...) \
+    BCAST_LAUNCH_VB(KERNEL, vec_bytes, grid, dim3(kBlockThreads), stream, args __VA_OPT__(,) __VA_ARGS__)
 
-hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream)
+bool valid_chain_block(int block_threads) { return block_threads == 64 || block_threads == 128 || block_threads == 256; }
+
+hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream)
 {
-    if (grid_blocks < 1) return hipErrorInvalidValue;
+    if (grid_blocks < 1 || !valid_chain_block(block_threads)) return hipErrorInvalidValue;
+    if ((u64)grid_blocks * (unsigned)(block_threads / kWaveSize) < (u64)a.stages * a.lanes) return hipErrorInvalidValue;
+    const dim3 grid(grid_blocks), block(block_threads);
     const bool wb = (a.mode & kModeStageWriteBack) != 0;
     if (a.unroll == (unsigned)kTripUnrollSmall) {
         if (wb) {
-            BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, kTripUnrollSmall, true);
+            BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, kTripUnrollSmall, true);
         } else {
-            BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, kTripUnrollSmall, false);
+            BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, kTripUnrollSmall, false);
         }
     } else if (a.unroll == (unsigned)kTripUnrollDefault) {
         if (wb) {
-            BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, kTripUnrollDefault, true);
+            BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, kTripUnrollDefault, true);
         } else {
-            BCAST_LAUNCH_V(chain_kernel, vec_bytes, dim3(grid_blocks), stream, a, kTripUnrollDefault, false);
+            BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, kTripUnrollDefault, false);
         }
     } else {
         return hipErrorInvalidValue;
@@ -464,11 +475,11 @@ hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x
     return hipGetLastError();
 }
 
-hipError_t chain_max_blocks_per_cu(int *blocks, int *blocks_write_back)
+hipError_t chain_max_blocks_per_cu(int block_threads, int *blocks, int *blocks_write_back)
 {
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, chain_kernel<16, kTripUnrollDefault, false>, kBlockThreads, 0);
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, chain_kernel<16, kTripUnrollDefault, false>, block_threads, 0);
     if (e == hipSuccess)
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_write_back, chain_kernel<16, kTripUnrollDefault, true>, kBlockThreads, 0);
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_write_back, chain_kernel<16, kTripUnrollDefault, true>, block_threads, 0);
     return e;
 }
 

@@ -99,6 +99,17 @@ def test_chain_three_kib_trips(noise, stages, M, C, offsets):
     assert info["trip_bytes"] == 3072 and info["slice_bytes"] % 3072 == 0
 
 
+@pytest.mark.parametrize("block", [64, 128, 256])
+@pytest.mark.parametrize("P,stages,lanes,M,C", [(2, 1, 1, 5, 16), (5, 4, 3, 70001, 8192), (9, 3, 7, MiB + 3, 64 * KiB),
+                                                (64, 2, 0, 3 * MiB + 5, 384 * KiB), (64, 63, 5, 100000, 4096)])
+def test_chain_workgroup_sizes(noise, block, P, stages, lanes, M, C):
+    """Workgroups of 1, 2 and 4 wavefronts, also where the last one is only
+    partly used (odd stage x lane products)."""
+    info = run_and_check(P, P - 1, M, C, B.BCAST_ALGO_CHAIN, noise, stages=stages, lanes=lanes, block=block)
+    assert info["block_threads"] == block
+    assert info["grid_blocks"] == -(-info["stages"] * info["lanes"] // (block // 64))
+
+
 @pytest.mark.parametrize("P,radix", [(2, 2), (5, 3), (9, 3), (10, 3), (16, 4), (17, 4), (64, 4), (64, 8), (64, 64), (33, 2), (7, 9)])
 @pytest.mark.parametrize("M", [9, 4096, MiB + 3])
 def test_knomial_radices(noise, P, radix, M):
@@ -315,8 +326,9 @@ def test_random_configurations(noise):
                    [int(x) for x in rng.integers(0, 33, P)]][kind]
         radix = int(rng.integers(2, 10)) if algo == B.BCAST_ALGO_KNOMIAL else 0
         trip = int(rng.choice([0, 3072, 4096])) if algo == B.BCAST_ALGO_CHAIN else 0
+        block = int(rng.choice([0, 64, 128, 256])) if algo == B.BCAST_ALGO_CHAIN else 0
         try:
-            run_and_check(P, root, M, C, algo, noise, offsets=offsets, lanes=lanes, stages=stages, radix=radix, trip=trip)
+            run_and_check(P, root, M, C, algo, noise, offsets=offsets, lanes=lanes, stages=stages, radix=radix, trip=trip, block=block)
         except Exception as e:
             raise AssertionError("case %d: P=%d root=%d M=%d C=%d algo=%d stages=%d lanes=%d offsets=%s radix=%d trip=%d: %s"
                                  % (case, P, root, M, C, algo, stages, lanes, kind, radix, trip, e))

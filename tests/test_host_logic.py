@@ -72,6 +72,14 @@ def test_chain_geometry_matches_eq5_chunking():
     assert (g["lanes"], g["slice_bytes"]) == (512, 8192)  # 768 trips: the next power of two below
     with pytest.raises(B.BcastError):
         B.bcast_chain_geometry(8, 1 << 20, 4096, 64, trip_request=2048)
+    # workgroups of 1, 2 or 4 wavefronts: same waves, more blocks
+    for block, blocks in ((64, 2048), (128, 1024), (256, 512), (0, 512)):
+        g = B.bcast_chain_geometry(64, 1 << 30, 3 << 20, 8192, stages_request=2, trip_request=3072, block_request=block)
+        assert (g["lanes"], g["grid_blocks"], g["block_threads"]) == (1024, blocks, block or 256)
+    g = B.bcast_chain_geometry(4, 100, 16, 64, lanes_request=1, block_request=128)
+    assert g["grid_blocks"] == 2  # 3 stages x 1 lane in 2-wave workgroups
+    with pytest.raises(B.BcastError):
+        B.bcast_chain_geometry(8, 1 << 20, 4096, 64, block_request=32)
     # no-ops
     assert B.bcast_chain_geometry(1, 1 << 20, 4096, 64)["nchunks"] == 0
     assert B.bcast_chain_geometry(4, 0, 4096, 64)["nchunks"] == 0
