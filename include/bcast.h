@@ -158,6 +158,12 @@ int bcast_plan_set_block_threads(bcast_plan_t *plan, int block_threads);
  * in round j every position q < k^j sends to q + i k^j, i = 1..k-1. */
 int bcast_plan_set_radix(bcast_plan_t *plan, int radix);
 int bcast_plan_set_debug(bcast_plan_t *plan, uint64_t spin_limit_ticks, int mute_hop);
+/* Test hook: make the plan behave as if it had already run `epoch` times
+ * (never fewer than it has).  Runs are told apart by a 32-bit count in the
+ * flag words; bcast_run drains the device and clears the flags before the count
+ * would wrap, and this lets a test reach that point without 2^32 runs.
+ * BCAST_ERR_ARG if epoch is below the plan's count or above 2^32 - 2. */
+int bcast_plan_debug_set_epoch(bcast_plan_t *plan, uint64_t epoch);
 
 /* Chain kernel modes (bit mask).  BCAST_MODE_COUNT: count the hand-offs whose
  * producer and consumer waves ran on the same XCD (one L2) and on different

@@ -99,6 +99,8 @@ def _bind(path):
     lib.oracle_binomial_bcast.restype = ctypes.c_long
     lib.oracle_knomial_bcast.argtypes = [pp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_int, tp]
     lib.oracle_knomial_bcast.restype = ctypes.c_long
+    lib.oracle_knomial_pipeline_bcast.argtypes = [pp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, tp]
+    lib.oracle_knomial_pipeline_bcast.restype = ctypes.c_long
     lp = ctypes.POINTER(ctypes.c_long)
     lib.oracle_scatter_allgather_bcast.argtypes = [pp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, lp, lp, tp]
     lib.oracle_scatter_allgather_bcast.restype = ctypes.c_long
@@ -108,7 +110,8 @@ def _bind(path):
     lib.oracle_model_knomial.argtypes = [ctypes.c_int, ctypes.c_int, d, d, d]
     lib.oracle_model_scatter_allgather.argtypes = [ctypes.c_int, d, d, d]
     lib.oracle_model_chain_pipeline.argtypes = [ctypes.c_int, d, d, d, d]
-    for n in ("direct", "chain", "knomial", "scatter_allgather", "chain_pipeline"):
+    lib.oracle_model_knomial_pipeline.argtypes = [ctypes.c_int, ctypes.c_int, d, d, d, d]
+    for n in ("direct", "chain", "knomial", "scatter_allgather", "chain_pipeline", "knomial_pipeline"):
         getattr(lib, "oracle_model_" + n).restype = d
     return lib
 
@@ -209,6 +212,15 @@ def knomial_bcast(bufs: Optional[np.ndarray], P: int, root: int, M: int, k: int,
     return tb.result(n)
 
 
+def knomial_pipeline_bcast(bufs: Optional[np.ndarray], P: int, root: int, M: int, C: int, k: int, trace: bool = False) -> Result:
+    """Pipelined k-nomial tree: the levels of Eq. 3, chunk by chunk (Sec. IV-B)."""
+    nchunks = -(-M // C) if C > 0 else 0
+    tb = _TraceBuf(P, trace, nchunks * max(0, P - 1), 1)
+    n = _check(_load().oracle_knomial_pipeline_bcast(_row_pointers(bufs, P, M), P, root, M, C, k, ctypes.byref(tb.c)),
+               "knomial_pipeline_bcast")
+    return tb.result(n)
+
+
 def scatter_allgather_bcast(bufs: Optional[np.ndarray], P: int, root: int, M: int, trace: bool = False) -> Result:
     """Binomial scatter + ring allgather (Sec. III-A, Eq. 4)."""
     tb = _TraceBuf(P, trace, P * P + P, 1)
@@ -236,6 +248,10 @@ def model_chain(n, M, ts, B):
 
 def model_knomial(n, k, M, ts, B):
     return _load().oracle_model_knomial(n, k, M, ts, B)
+
+
+def model_knomial_pipeline(n, k, M, C, ts, B):
+    return _load().oracle_model_knomial_pipeline(n, k, M, C, ts, B)
 
 
 def model_scatter_allgather(n, M, ts, B):

@@ -143,6 +143,34 @@ long oracle_knomial_bcast(unsigned char **bufs, int P, int root, size_t M, int k
     return rounds;
 }
 
+long oracle_knomial_pipeline_bcast(unsigned char **bufs, int P, int root, size_t M, size_t C, int k,
+                                   oracle_trace_t *tr)
+{
+    if (bad_common(P, root) || k < 2 || C == 0) return -1;
+    trace_reset(tr);
+    if (P < 2 || M == 0) return 0;
+    long pieces = (long)(M / C);
+    if (M % C) pieces++; /* a short last chunk is a chunk */
+    long steps = 0;
+    /* level by level as in the k-nomial tree; inside a level the message goes
+     * out one chunk per step, to all children of the level at once */
+    for (long span = 1; span < P; span *= k) {
+        for (long ch = 0; ch < pieces; ch++) {
+            size_t from = (size_t)ch * C;
+            size_t to = from + C < M ? from + C : M;
+            for (long holder = 0; holder < span; holder++)
+                for (long d = 1; d < k; d++) {
+                    long target = holder + d * span;
+                    if (target < P)
+                        transfer(bufs, tr, steps, rank_at(root, (int)holder, P),
+                                 rank_at(root, (int)target, P), ch, from, to);
+                }
+            steps++;
+        }
+    }
+    return steps;
+}
+
 long oracle_scatter_allgather_bcast(unsigned char **bufs, int P, int root, size_t M,
                                     long *scatter_rounds, long *ring_steps, oracle_trace_t *tr)
 {
@@ -207,6 +235,11 @@ double oracle_model_chain(int n, double M, double ts, double B) { return (n - 1)
 double oracle_model_knomial(int n, int k, double M, double ts, double B)
 {
     return ceil_log(n, k) * (ts + M / B);
+}
+
+double oracle_model_knomial_pipeline(int n, int k, double M, double C, double ts, double B)
+{
+    return (M / C * ceil_log(n, k)) * (ts + C / B);
 }
 
 double oracle_model_scatter_allgather(int n, double M, double ts, double B)

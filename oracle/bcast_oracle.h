@@ -83,6 +83,19 @@ long oracle_binomial_bcast(unsigned char **bufs, int P, int root, size_t M,
 long oracle_knomial_bcast(unsigned char **bufs, int P, int root, size_t M, int k,
                           oracle_trace_t *tr);
 
+/* Pipelined k-nomial tree: the k-nomial levels of Eq. 3 with the message cut
+ * into chunks of C bytes as in Sec. IV-B.  The paper's source carries, after
+ * Eq. 5, a remark (not typeset) that the tree can be pipelined too: a sender
+ * needs M/C steps to push the message to the children of one level and there
+ * are ceil(log_k n) levels, (M/C * ceil(log_k n)) steps of (t_s + C/B) each.
+ * This function walks exactly that: level after level, and inside a level one
+ * step per chunk in which every holder sends that chunk to each of its k - 1
+ * children of the level.  C >= M is oracle_knomial_bcast.  Returns the number
+ * of steps, ceil(M/C) * ceil(log_k P), 0 when P < 2 or M == 0, or -1 on bad
+ * arguments. */
+long oracle_knomial_pipeline_bcast(unsigned char **bufs, int P, int root, size_t M, size_t C, int k,
+                                   oracle_trace_t *tr);
+
 /* Scatter + ring allgather (Sec. III-A, Eq. 4): the message is cut into P
  * pieces of ceil(M/P) bytes (piece q may be short or empty); a binomial
  * scatter leaves position q holding piece q, then P - 1 ring steps pass
@@ -101,6 +114,8 @@ double oracle_model_direct(int n, double M, double ts, double B);
 double oracle_model_chain(int n, double M, double ts, double B);
 double oracle_model_knomial(int n, int k, double M, double ts, double B);
 double oracle_model_scatter_allgather(int n, double M, double ts, double B);
+/* the pipelined k-nomial remark after Eq. 5: (M/C * ceil(log_k n)) (t_s + C/B) */
+double oracle_model_knomial_pipeline(int n, int k, double M, double C, double ts, double B);
 double oracle_model_chain_pipeline(int n, double M, double C, double ts, double B);
 
 #ifdef __cplusplus

@@ -38,7 +38,7 @@ BCAST_ERR_UNTUNED = -5
 # every symbol include/bcast.h declares
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
     "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
@@ -119,6 +119,7 @@ def _load():
         "bcast_plan_set_stages": ([vp, i], i),
         "bcast_plan_set_radix": ([vp, i], i),
         "bcast_plan_set_trip": ([vp, i], i),
+        "bcast_plan_debug_set_epoch": ([vp, ctypes.c_uint64], i),
         "bcast_plan_set_block_threads": ([vp, i], i),
         "bcast_plan_set_debug": ([vp, u64, i], i),
         "bcast_plan_set_mode": ([vp, ctypes.c_uint], i),
@@ -250,6 +251,10 @@ def bcast_plan_set_trip(plan: Plan, trip_bytes: int) -> None:
 
 def bcast_plan_set_block_threads(plan: Plan, block_threads: int) -> None:
     _check(_lib.bcast_plan_set_block_threads(plan.handle, block_threads), "bcast_plan_set_block_threads")
+
+
+def bcast_plan_debug_set_epoch(plan: Plan, epoch: int) -> None:
+    _check(_lib.bcast_plan_debug_set_epoch(plan.handle, epoch), "bcast_plan_debug_set_epoch")
 
 
 def bcast_plan_set_radix(plan: Plan, radix: int) -> None:

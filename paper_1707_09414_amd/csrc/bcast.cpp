@@ -91,6 +91,9 @@ static u64 default_chunk(int nranks, int max_waves, int stages_request, u64 trip
     return p * trip;
 }
 
+// Runs of one plan are told apart by a 32-bit epoch in the flag words.
+constexpr u64 kEpochLimit = 0xFFFFFFFEull;
+
 static int block_index(int block_threads) { return block_threads == 64 ? 0 : block_threads == 128 ? 1 : 2; }
 
 extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
@@ -267,6 +270,15 @@ extern "C" int bcast_plan_set_debug(bcast_plan_t *p, uint64_t spin_limit_ticks, 
     if (!p || mute_hop < 0 || mute_hop >= BCAST_MAX_RANKS) return BCAST_ERR_ARG;
     p->spin_ticks = spin_limit_ticks ? spin_limit_ticks : kDefaultSpinTicks;
     p->mute_hop = mute_hop;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_debug_set_epoch(bcast_plan_t *p, uint64_t epoch)
+{
+    if (!p || epoch > kEpochLimit) return BCAST_ERR_ARG;
+    // flags left by earlier runs must stay below every later run's base
+    if (epoch < p->epoch) return BCAST_ERR_ARG;
+    p->epoch = epoch;
     return BCAST_OK;
 }
 
@@ -577,6 +589,15 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         if (bytes <= kStageWriteBackMaxBytes) a.mode |= kModeStageWriteBack;
         if (p->d_trace) a.mode |= kModeTrace;
         a.status = p->d_status;
+        // the flag word keeps the epoch in its upper 32 bits: before that would
+        // wrap (after 2^32 - 2 runs of this plan), let the device drain, clear
+        // the flags and the abort word, and count from one again
+        if (p->epoch >= kEpochLimit) {
+            HIP_TRY(hipDeviceSynchronize());
+            HIP_TRY(hipMemset(p->d_flags, 0, ((size_t)p->max_flags + 2) * kFlagStrideWords * sizeof(u64)));
+            HIP_TRY(hipDeviceSynchronize());
+            p->epoch = 0;
+        }
         a.base = (++p->epoch) << 32;
         a.bytes = bytes;
         a.chunk_bytes = info.chunk_bytes;
@@ -591,7 +612,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         // the launch must match what the kernel indexes: stages*lanes waves, each with its own flag,
         // and the stages together cover exactly the P-1 hops
         if ((u64)a.stages * a.lanes > (u64)waves_for(p, bytes)) return BCAST_ERR_ARG;
-        if ((u64)info.grid_blocks * kWavesPerBlock < (u64)a.stages * a.lanes) return BCAST_ERR_ARG;
+        if ((u64)info.grid_blocks * (u64)(info.block_threads / kWaveSize) < (u64)a.stages * a.lanes) return BCAST_ERR_ARG;
         if (a.stages == 0 || a.hops_per_stage == 0) return BCAST_ERR_ARG;
         if ((u64)a.stages * a.hops_per_stage < (u64)(P - 1) || (u64)(a.stages - 1) * a.hops_per_stage >= (u64)(P - 1))
             return BCAST_ERR_ARG;

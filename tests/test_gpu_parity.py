@@ -181,6 +181,26 @@ def test_burst_of_small_broadcasts_reuses_flags(noise):
     plan.destroy()
 
 
+def test_epoch_count_wraps_without_stale_flags(noise):
+    """The flag words hold a 32-bit run count.  A plan pushed to the end of that
+    range must clear its flags and start over: 12 runs across the wrap, each
+    with its own message, two lanes' worth of chunks, all checked."""
+    P, root, M = 9, 4, 40 * KiB + 8
+    plan = B.bcast_plan_create(P, M, 8 * KiB, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_stages(plan, 4)
+    run_and_check(P, root, M, 8 * KiB, B.BCAST_ALGO_CHAIN, noise, plan=plan)
+    B.bcast_plan_debug_set_epoch(plan, (1 << 32) - 8)
+    with pytest.raises(B.BcastError):
+        B.bcast_plan_debug_set_epoch(plan, 5)        # never backwards
+    with pytest.raises(B.BcastError):
+        B.bcast_plan_debug_set_epoch(plan, 1 << 32)  # beyond the range
+    for i in range(12):
+        run_and_check(P, (root + i) % P, M - 16 * i, 8 * KiB, B.BCAST_ALGO_CHAIN, noise[1000 * i:], plan=plan)
+    # and the wait limit still works after the wrap
+    assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+    plan.destroy()
+
+
 def test_two_plans_alternating_and_moving_root(noise):
     P, M = 8, 512 * KiB + 48
     rb = RankBuffers(P, M)

@@ -118,7 +118,7 @@ def pin_chain_forwarding_is_from_neighbour_payload():
 def pin_golden_counts():
     with open(os.path.join(GOLDEN, "schedule_counts.txt")) as f:
         rows = [l.split() for l in f if l.strip() and not l.startswith("#")]
-    assert len(rows) >= 20
+    assert len(rows) >= 24
     for kind, n, M, C, want in rows:
         n, M, C, want = int(n), int(M), int(C), int(want)
         if kind == "chain":
@@ -129,6 +129,8 @@ def pin_golden_counts():
             got = oracle.direct_bcast(None, n, 0, M).steps
         elif kind == "scatter_allgather":
             got = oracle.scatter_allgather_bcast(None, n, 0, M).steps
+        elif kind.startswith("knomialpipe"):
+            got = oracle.knomial_pipeline_bcast(None, n, 0, M, C, int(kind[len("knomialpipe"):])).steps
         elif kind.startswith("knomial"):
             got = oracle.knomial_bcast(None, n, 0, M, int(kind[len("knomial"):])).steps
         else:
@@ -186,6 +188,35 @@ def pin_variants_end_state_and_counts(maxP=9):
                         # the parent is q without its leading base-k digit; reached in round j
                         assert got_from[q] == (q % top, j), (P, k, q, got_from[q])
 
+                for k, C in ((2, 1), (3, 4), (4, 5), (3, M + 3)):
+                    b = before.copy()
+                    r = oracle.knomial_pipeline_bcast(b, P, root, M, C, k, trace=True)
+                    assert np.array_equal(b, exp), (P, root, M, k, C)
+                    levels, reach = 0, 1
+                    while reach < P:
+                        reach *= k
+                        levels += 1
+                    nchunks = -(-M // C)
+                    assert r.steps == (nchunks * levels if P > 1 else 0), (P, M, C, k, r.steps)
+                    assert r.bytes_copied == (P - 1) * M
+                    seen = {}
+                    for t in r.transfers:
+                        q = (t.dst_rank - root) % P
+                        assert (q, t.chunk) not in seen and q != 0
+                        assert (t.lo, t.hi) == (t.chunk * C, min(M, (t.chunk + 1) * C))
+                        seen[(q, t.chunk)] = ((t.src_rank - root) % P, t.step)
+                    for q in range(1, P):
+                        j, top = 0, 1
+                        while top * k <= q:
+                            top *= k
+                            j += 1
+                        for c in range(nchunks):
+                            # parent as in the k-nomial tree; level j starts after j whole messages
+                            assert seen[(q, c)] == (q % top, j * nchunks + c), (P, k, q, c, seen[(q, c)])
+                    if C >= M and P > 1 and M > 0:
+                        plain = oracle.knomial_bcast(before.copy(), P, root, M, k, trace=True)
+                        assert [(t.src_rank, t.dst_rank) for t in plain.transfers] == [(t.src_rank, t.dst_rank) for t in r.transfers]
+
                 b = before.copy()
                 r = oracle.scatter_allgather_bcast(b, P, root, M, trace=True)
                 assert np.array_equal(b, exp), (P, root, M)
@@ -214,7 +245,7 @@ def pin_variants_end_state_and_counts(maxP=9):
 def pin_cost_models():
     with open(os.path.join(GOLDEN, "cost_models.txt")) as f:
         rows = [l.split() for l in f if l.strip() and not l.startswith("#")]
-    assert len(rows) == 6
+    assert len(rows) == 7
     for kind, n, k, M, C, ts, B, want in rows:
         n, k = int(n), int(k)
         M, C, ts, B, want = float(M), float(C), float(ts), float(B), float(want)
@@ -224,6 +255,7 @@ def pin_cost_models():
             "knomial": lambda: oracle.model_knomial(n, k, M, ts, B),
             "scatter_allgather": lambda: oracle.model_scatter_allgather(n, M, ts, B),
             "chain_pipeline": lambda: oracle.model_chain_pipeline(n, M, C, ts, B),
+            "knomial_pipeline": lambda: oracle.model_knomial_pipeline(n, k, M, C, ts, B),
         }[kind]()
         assert got == pytest.approx(want, rel=1e-12), (kind, got, want)
     # identities between the printed formulas
@@ -233,6 +265,11 @@ def pin_cost_models():
         assert oracle.model_chain_pipeline(n, M, M, ts, B) == pytest.approx(oracle.model_chain(n, M, ts, B), rel=1e-14)
         assert oracle.model_direct(n, M, ts, B) - oracle.model_chain(n, M, ts, B) == pytest.approx(unit, rel=1e-12)
         assert oracle.model_knomial(n, n, M, ts, B) == pytest.approx(unit, rel=1e-14)
+        for k in (2, 4):
+            # one chunk: the unpipelined tree; chunking only adds start-ups
+            assert oracle.model_knomial_pipeline(n, k, M, M, ts, B) == pytest.approx(oracle.model_knomial(n, k, M, ts, B), rel=1e-14)
+            extra = oracle.model_knomial_pipeline(n, k, M, M / 8, ts, B) - oracle.model_knomial(n, k, M, ts, B)
+            assert extra == pytest.approx(7 * ts * oracle.model_knomial(n, k, M, ts, B) / unit, rel=1e-9)
     assert oracle.model_scatter_allgather(2, 1e6, 1e-6, 1e9) == pytest.approx(2e-6 + 1e-3, rel=1e-14)
 
 
@@ -300,6 +337,12 @@ MUTANTS = [
     ("knomial_skips_last_child", "for (long i = 1; i < k; i++) {", "for (long i = 1; i < k - 1; i++) {"),
     ("knomial_wrong_stride", "long child = q + i * reach;", "long child = q + i * (reach + 1);"),
     ("knomial_reach_doubles", "for (long reach = 1; reach < P; reach *= k) {", "for (long reach = 1; reach < P; reach *= 2) {"),
+    ("pipe_wrong_target", "long target = holder + d * span;", "long target = holder + d * span + 1;"),
+    ("pipe_levels_double", "for (long span = 1; span < P; span *= k) {", "for (long span = 1; span < P; span *= 2) {"),
+    ("pipe_drops_tail_chunk", "if (M % C) pieces++;", "if (M % C > 1) pieces++;"),
+    ("pipe_chunk_overrun", "size_t to = from + C < M ? from + C : M;", "size_t to = from + C;"),
+    ("pipe_step_per_level", "            steps++;\n        }\n    }\n    return steps;", "        }\n        steps++;\n    }\n    return steps;"),
+    ("model_pipe_levels", "return (M / C * ceil_log(n, k)) * (ts + C / B);", "return (M / C + ceil_log(n, k)) * (ts + C / B);"),
     ("direct_skips_last", "for (int k = 1; k < P; k++) {\n        transfer(bufs, tr, sends, root,",
      "for (int k = 1; k < P - 1; k++) {\n        transfer(bufs, tr, sends, root,"),
     ("ring_wrong_piece", "long pc = ((q - t) % P + P) % P;", "long pc = ((q + t) % P + P) % P;"),
