@@ -46,7 +46,10 @@ typedef enum {
     BCAST_ALGO_BINOMIAL = 3, /* binomial tree, Sec. III-A Eq. 3 with k = 2 */
     BCAST_ALGO_FANOUT = 4,   /* one-die shortcut: read root once, store to all ranks (no paper equivalent) */
     BCAST_ALGO_SCATTER_ALLGATHER = 5, /* binomial scatter + ring allgather, Sec. III-A Eq. 4 */
-    BCAST_ALGO_KNOMIAL = 6   /* k-nomial tree, Sec. III-A Eq. 3, radix from bcast_plan_set_radix (default 4) */
+    BCAST_ALGO_KNOMIAL = 6,  /* k-nomial tree, Sec. III-A Eq. 3, radix from bcast_plan_set_radix (default 4) */
+    BCAST_ALGO_KNOMIAL_PIPELINED = 7 /* the same tree in ONE launch, chunked and flag-driven like the chain
+                                        (Sec. IV-B's pipelining applied to Eq. 3's tree): every position copies
+                                        chunk c out of its parent's buffer as soon as the parent holds it */
 } bcast_algo_t;
 
 typedef enum {
@@ -208,8 +211,9 @@ int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_w
  *
  * bcast_tune measures, on the current device and `stream`, every candidate
  * (chain over chunk sizes 8 KiB..64 MiB and stage counts, direct, binomial, and
- * -- only if `algo_mask` has their bits -- the fan-out, scatter + allgather and
- * the k-nomial tree at radix 4 and 8) for message sizes that are
+ * -- only if `algo_mask` has their bits -- the fan-out, scatter + allgather,
+ * the k-nomial tree at radix 4 and 8 and the one-launch pipelined k-nomial
+ * tree at radix 2, 4 and 8) for message sizes that are
  * powers of two in [min_bytes, max_bytes], keeps the fastest per size, installs
  * the entries, and, if table_path (HOST, nullable) is given, appends them there
  * as text.  It allocates nranks scratch buffers of max_bytes itself.
@@ -227,7 +231,7 @@ int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsigned algo_mas
 typedef struct {
     int algo;                   /* winner: bcast_algo_t */
     uint64_t chunk_bytes;       /* winner's chunk size (chain only) */
-    int stages;                 /* winner's stage count (chain) or radix (k-nomial) */
+    int stages;                 /* winner's stage count (chain) or radix (k-nomial trees) */
     int trip_bytes;             /* winner's trip size (chain only; 0 = default) */
     double usec;                /* winner's measured time */
     uint64_t chain_chunk_bytes; /* chain: best chunk size (0 = not measured) */

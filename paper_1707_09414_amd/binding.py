@@ -26,7 +26,8 @@ BCAST_ALGO_BINOMIAL = 3
 BCAST_ALGO_FANOUT = 4
 BCAST_ALGO_SCATTER_ALLGATHER = 5
 BCAST_ALGO_KNOMIAL = 6
-ALGO_NAMES = {0: "auto", 1: "chain", 2: "direct", 3: "binomial", 4: "fanout", 5: "scatter_allgather", 6: "knomial"}
+BCAST_ALGO_KNOMIAL_PIPELINED = 7
+ALGO_NAMES = {0: "auto", 1: "chain", 2: "direct", 3: "binomial", 4: "fanout", 5: "scatter_allgather", 6: "knomial", 7: "knomial_pipelined"}
 
 BCAST_OK = 0
 BCAST_ERR_ARG = -1

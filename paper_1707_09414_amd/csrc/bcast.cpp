@@ -160,7 +160,7 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
     if (!out) return BCAST_ERR_ARG;
     *out = nullptr;
     if (nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
-    if (algo < BCAST_ALGO_AUTO || algo > BCAST_ALGO_KNOMIAL) return BCAST_ERR_ARG;
+    if (algo < BCAST_ALGO_AUTO || algo > BCAST_ALGO_KNOMIAL_PIPELINED) return BCAST_ERR_ARG;
     if (chunk_bytes % 16 != 0) return BCAST_ERR_ARG;
 
     bcast_plan *p = new (std::nothrow) bcast_plan;
@@ -377,6 +377,16 @@ static int waves_for(const bcast_plan *p, size_t bytes)
     return bytes <= kStageWriteBackMaxBytes ? p->max_waves_cached[b] : p->max_waves[b];
 }
 
+// Wavefronts per position of the pipelined tree: every position but the root has
+// its own, all resident at once; a power of two like the chain's lanes.
+static u64 tree_lanes_max(const bcast_plan *p)
+{
+    const u64 per_pos = (u64)p->max_waves[block_index(kBlockThreads)] / (u64)std::max(1, p->nranks - 1);
+    u64 l = 1;
+    while (l * 2 <= per_pos) l *= 2;
+    return l;
+}
+
 static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
 {
     r->algo = p->algo;
@@ -399,12 +409,17 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
         if (r->trip == 0) r->trip = e.chain_trip_bytes;
     }
     r->radix = p->radix_request;
-    if (r->algo == BCAST_ALGO_KNOMIAL) {
+    if (r->algo == BCAST_ALGO_KNOMIAL || r->algo == BCAST_ALGO_KNOMIAL_PIPELINED) {
         // an AUTO plan takes the radix the table recorded (in the stages column)
-        if (r->radix == 0 && p->algo == BCAST_ALGO_AUTO && tuned && e.algo == BCAST_ALGO_KNOMIAL) r->radix = e.stages;
+        if (r->radix == 0 && p->algo == BCAST_ALGO_AUTO && tuned && e.algo == r->algo) r->radix = e.stages;
         if (r->radix < 2) r->radix = 4;
         r->radix = std::min(r->radix, std::max(2, p->nranks));
         r->stages = 0;
+    }
+    if (r->algo == BCAST_ALGO_KNOMIAL_PIPELINED) {
+        // default chunk: one 4 KiB trip for each of a position's wavefronts
+        if (r->chunk == 0) r->chunk = tree_lanes_max(p) * trip_bytes_of(kTripUnrollDefault);
+        r->chunk = round_up(r->chunk, 16);
     }
     if (r->algo == BCAST_ALGO_CHAIN) {
         if (r->stages == 0) r->stages = default_stages(p->nranks);
@@ -520,6 +535,31 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
         info->algorithmic_bytes = 2ull * (P - 1) * bytes;
         break;
     }
+    case BCAST_ALGO_KNOMIAL_PIPELINED: {
+        const u64 trip = trip_bytes_of(kTripUnrollDefault);
+        const u64 C = std::min<u64>(r.chunk, round_up(bytes, 16));
+        const u64 nchunks = ceil_div(bytes, C);
+        if (nchunks >= (1ull << 27)) return BCAST_ERR_ARG;  // the flag word keeps the count in 28 bits
+        u64 lanes = std::max<u64>(1, std::min(tree_lanes_max(p), ceil_div(C, trip)));
+        if (p->lanes_request > 0) lanes = std::min<u64>((u64)p->lanes_request, (u64)p->max_waves[block_index(kBlockThreads)] / (u64)(P - 1));
+        else {
+            u64 l = 1;
+            while (l * 2 <= lanes) l *= 2;
+            lanes = l;
+        }
+        if (lanes < 1) return BCAST_ERR_ARG;
+        info->chunk_bytes = C;
+        info->nchunks = nchunks;
+        info->lanes = (int)lanes;
+        info->trip_bytes = (int)trip;
+        info->slice_bytes = ceil_div(C, lanes * trip) * trip;
+        info->stages = r.radix;  // reported here: the tree's radix
+        info->hops_per_stage = 1;
+        info->launches = 1;
+        info->grid_blocks = (int)ceil_div((u64)(P - 1) * lanes, kWavesPerBlock);
+        info->algorithmic_bytes = 2ull * (P - 1) * bytes;
+        break;
+    }
     case BCAST_ALGO_FANOUT:
         info->launches = 1;
         info->grid_blocks = copy_grid(p, bytes, 1);
@@ -551,6 +591,37 @@ extern "C" int bcast_plan_info(bcast_plan_t *p, void *const *rank_bufs, size_t b
     return describe(p, rank_bufs, bytes, info);
 }
 
+// What the chain and the pipelined tree share: buffers by position, the plan's
+// flags, status words and wait limit, the chunking, and a fresh epoch.
+static int begin_flag_run(bcast_plan *p, ChainArgs *a, char *const *by_pos, size_t bytes, const bcast_plan_info_t &info)
+{
+    memset(a, 0, sizeof *a);
+    memcpy(a->buf, by_pos, sizeof(char *) * p->nranks);
+    a->flags = p->d_flags;
+    a->abort_word = p->d_abort;
+    a->status = p->d_status;
+    a->bytes = bytes;
+    a->chunk_bytes = info.chunk_bytes;
+    a->spin_ticks = p->spin_ticks;
+    a->nchunks = (unsigned)info.nchunks;
+    a->lanes = (unsigned)info.lanes;
+    a->nranks = (unsigned)p->nranks;
+    a->mute_hop = (unsigned)p->mute_hop;
+    if (a->nchunks == 0 || a->lanes == 0 || a->chunk_bytes == 0) return BCAST_ERR_ARG;
+    if ((u64)a->nchunks * a->chunk_bytes < a->bytes) return BCAST_ERR_ARG;
+    // the flag word keeps the epoch in its upper 32 bits: before that would
+    // wrap (after 2^32 - 2 runs of this plan), let the device drain, clear
+    // the flags and the abort word, and count from one again
+    if (p->epoch >= kEpochLimit) {
+        HIP_TRY(hipDeviceSynchronize());
+        HIP_TRY(hipMemset(p->d_flags, 0, ((size_t)p->max_flags + 2) * kFlagStrideWords * sizeof(u64)));
+        HIP_TRY(hipDeviceSynchronize());
+        p->epoch = 0;
+    }
+    a->base = (++p->epoch) << 32;
+    return BCAST_OK;
+}
+
 extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size_t bytes, bcast_stream_t stream)
 {
     if (!p || !rank_bufs) return BCAST_ERR_ARG;
@@ -578,37 +649,17 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
 
     if (info.algo == BCAST_ALGO_CHAIN) {
         ChainArgs a;
-        memset(&a, 0, sizeof a);
-        memcpy(a.buf, by_pos, sizeof(char *) * P);
-        a.flags = p->d_flags;
-        a.abort_word = p->d_abort;
+        rc = begin_flag_run(p, &a, by_pos, bytes, info);
+        if (rc != BCAST_OK) return rc;
         a.counters = p->d_counters;
         a.trace = p->d_trace;
         a.trace_entries = p->trace_entries;
         a.mode = p->mode;
         if (bytes <= kStageWriteBackMaxBytes) a.mode |= kModeStageWriteBack;
         if (p->d_trace) a.mode |= kModeTrace;
-        a.status = p->d_status;
-        // the flag word keeps the epoch in its upper 32 bits: before that would
-        // wrap (after 2^32 - 2 runs of this plan), let the device drain, clear
-        // the flags and the abort word, and count from one again
-        if (p->epoch >= kEpochLimit) {
-            HIP_TRY(hipDeviceSynchronize());
-            HIP_TRY(hipMemset(p->d_flags, 0, ((size_t)p->max_flags + 2) * kFlagStrideWords * sizeof(u64)));
-            HIP_TRY(hipDeviceSynchronize());
-            p->epoch = 0;
-        }
-        a.base = (++p->epoch) << 32;
-        a.bytes = bytes;
-        a.chunk_bytes = info.chunk_bytes;
-        a.spin_ticks = p->spin_ticks;
-        a.nchunks = (unsigned)info.nchunks;
-        a.lanes = (unsigned)info.lanes;
         a.stages = (unsigned)info.stages;
         a.hops_per_stage = (unsigned)info.hops_per_stage;
         a.unroll = (unsigned)(info.trip_bytes / (kWaveSize * 16));
-        a.nranks = (unsigned)P;
-        a.mute_hop = (unsigned)p->mute_hop;
         // the launch must match what the kernel indexes: stages*lanes waves, each with its own flag,
         // and the stages together cover exactly the P-1 hops
         if ((u64)a.stages * a.lanes > (u64)waves_for(p, bytes)) return BCAST_ERR_ARG;
@@ -655,6 +706,27 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
     }
     if (info.algo == BCAST_ALGO_FANOUT) {
         HIP_TRY(launch_fanout(c, info.vec_bytes, info.grid_blocks, stream));
+        return BCAST_OK;
+    }
+    if (info.algo == BCAST_ALGO_KNOMIAL_PIPELINED) {
+        ChainArgs a;
+        rc = begin_flag_run(p, &a, by_pos, bytes, info);
+        if (rc != BCAST_OK) return rc;
+        const int k = info.stages;
+        if (k < 2) return BCAST_ERR_ARG;
+        if ((u64)(P - 1) * a.lanes > (u64)p->max_waves[block_index(kBlockThreads)]) return BCAST_ERR_ARG;
+        // the k-nomial tree of Eq. 3: position q = holder + i k^j (holder < k^j,
+        // 1 <= i < k) receives from holder, i.e. from q without its leading
+        // base-k digit
+        for (long reach = 1; reach < P; reach *= k)
+            for (long holder = 0; holder < reach; ++holder)
+                for (long i = 1; i < k; ++i) {
+                    const long child = holder + i * reach;
+                    if (child >= P) continue;
+                    a.parent[child] = (unsigned char)holder;
+                    a.forward_mask |= 1ull << holder;
+                }
+        HIP_TRY(launch_tree(a, info.vec_bytes, info.grid_blocks, stream));
         return BCAST_OK;
     }
     if (info.algo == BCAST_ALGO_KNOMIAL) {

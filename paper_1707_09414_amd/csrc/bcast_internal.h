@@ -59,6 +59,10 @@ struct ChainArgs {
     unsigned nranks;
     unsigned mute_hop; // debug: this position never publishes (0 = off)
     unsigned mode;     // kMode* bits
+    // pipelined k-nomial tree only (tree_kernel): the position each position
+    // receives from, and the positions that have children (bit = position)
+    unsigned char parent[BCAST_MAX_RANKS];
+    u64 forward_mask;
 };
 
 // ChainArgs::mode
@@ -103,6 +107,7 @@ struct RangedCopyArgs {
 // buffer address in the call is congruent modulo vec_bytes.
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream);
 bool valid_chain_block(int block_threads);  // 64, 128 or 256
+hipError_t launch_tree(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);

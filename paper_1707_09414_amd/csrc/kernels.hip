@@ -362,6 +362,60 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// Pipelined k-nomial tree in one launch: the tree of Eq. 3 with the chunking and
+// the ready flags of the pipelined chain (the paper's source notes after Eq. 5
+// that the tree can be pipelined in the same way).  Every receiving position
+// has `lanes` wavefronts of its own; wavefront (position, lane) waits until its
+// PARENT position has published lane's share of chunk c, copies it out of the
+// parent's buffer into its own, and publishes it for its children.  A chunk
+// therefore moves down all levels of the tree while later chunks follow, and a
+// small message needs one launch and ceil(log_k P) flag hand-offs instead of
+// one launch per level.  The protocol, the flag layout (flag(position, lane))
+// and the wait limit are the chain kernel's.  Every buffer is read by other
+// wavefronts (the children's), so every access is agent-scope.  Wavefronts are
+// numbered position-major and a parent's position is below its children's, so
+// a wave only waits for a wave with a lower workgroup index.
+template <int V>
+__global__ void __launch_bounds__(kBlockThreads) tree_kernel(const ChainArgs a)
+{
+    const unsigned lane = threadIdx.x & (kWaveSize - 1);
+    const unsigned gw = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    if (gw >= (a.nranks - 1) * a.lanes) return;
+    const unsigned pos = gw / a.lanes + 1;  // the position this wave receives for
+    const unsigned s = gw - (pos - 1) * a.lanes;
+    const unsigned par = a.parent[pos];
+    const u64 *in_flag = par > 0 ? a.flags + ((u64)(par - 1) * a.lanes + s) * kFlagStrideWords : nullptr;
+    const bool forwards = ((a.forward_mask >> pos) & 1) != 0 && a.mute_hop != pos;
+    u64 *out_flag = forwards ? a.flags + ((u64)(pos - 1) * a.lanes + s) * kFlagStrideWords : nullptr;
+    const char *src = a.buf[par];
+    char *dst = a.buf[pos];
+
+    const u64 trip = (u64)kTripUnrollDefault * kWaveSize * V;
+    const u64 stride = trip * a.lanes;
+    u64 seen = 0;
+    u64 chunk_lo = 0;
+    for (unsigned c = 0; c < a.nchunks; ++c, chunk_lo += a.chunk_bytes) {
+        u64 chunk_hi = chunk_lo + a.chunk_bytes;
+        if (chunk_hi > a.bytes) chunk_hi = a.bytes;
+        if (in_flag) {
+            const u64 want = a.base + ((u64)(c + 1) << 4);
+            if (seen < want && !wait_ready(in_flag, want, a, pos, c, lane, &seen)) return;
+        }
+        for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
+            const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
+            copy_span_agent<V, kTripUnrollDefault>(dst, src, lo, hi, lane);
+        }
+        if (in_flag && c + 1 < a.nchunks) seen = read_flag(in_flag, lane);
+        if (out_flag) {
+            // all payload stores of this wave are complete and, being
+            // write-through, visible device-wide before the flag is raised
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0) __hip_atomic_store(out_flag, a.base + ((u64)(c + 1) << 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Whole-message copies src -> dst for up to 32 pairs at once (blockIdx.y picks
 // the pair): one round of the binomial tree (Sec. III-A, Eq. 3) or one send of
 // the direct algorithm (Eq. 1).  Waves stride over 4 KiB tiles.
@@ -451,6 +505,16 @@ hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int 
     } else {
         return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_tree(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream)
+{
+    if (grid_blocks < 1 || a.nranks < 2 || a.nranks > BCAST_MAX_RANKS) return hipErrorInvalidValue;
+    if ((u64)grid_blocks * kWavesPerBlock < (u64)(a.nranks - 1) * a.lanes) return hipErrorInvalidValue;
+    for (unsigned q = 1; q < a.nranks; ++q)
+        if (a.parent[q] >= q) return hipErrorInvalidValue;  // a parent lies below its child
+    BCAST_LAUNCH_V(tree_kernel, vec_bytes, dim3(grid_blocks), stream, a);
     return hipGetLastError();
 }
 

@@ -30,12 +30,14 @@ static std::string g_log_path;  // if set, bcast_tune appends every candidate it
 
 using namespace bcast;
 
-static bool valid_algo(int algo) { return algo >= BCAST_ALGO_CHAIN && algo <= BCAST_ALGO_KNOMIAL; }
+static bool valid_algo(int algo) { return algo >= BCAST_ALGO_CHAIN && algo <= BCAST_ALGO_KNOMIAL_PIPELINED; }
+static bool has_radix(int algo) { return algo == BCAST_ALGO_KNOMIAL || algo == BCAST_ALGO_KNOMIAL_PIPELINED; }
 
 static bool valid_entry(int nranks, const bcast_tune_entry_t &e)
 {
     if (nranks < 1 || nranks > BCAST_MAX_RANKS || !valid_algo(e.algo)) return false;
-    if (e.algo == BCAST_ALGO_CHAIN && (e.chunk_bytes == 0 || e.chunk_bytes % 16 != 0)) return false;
+    const bool chunked = e.algo == BCAST_ALGO_CHAIN || e.algo == BCAST_ALGO_KNOMIAL_PIPELINED;
+    if (chunked && (e.chunk_bytes == 0 || e.chunk_bytes % 16 != 0)) return false;
     if (e.chain_chunk_bytes % 16 != 0) return false;
     if (e.stages < 0 || e.stages > BCAST_MAX_RANKS || e.chain_stages < 0 || e.chain_stages > BCAST_MAX_RANKS) return false;
     for (int t : {e.trip_bytes, e.chain_trip_bytes})
@@ -213,7 +215,7 @@ int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages,
     bcast_plan_t *plan = nullptr;
     int rc = bcast_plan_create(&plan, nranks, bytes, chunk, algo);
     if (rc != BCAST_OK) return rc;
-    rc = algo == BCAST_ALGO_KNOMIAL ? bcast_plan_set_radix(plan, stages) : bcast_plan_set_stages(plan, stages);
+    rc = has_radix(algo) ? bcast_plan_set_radix(plan, stages) : bcast_plan_set_stages(plan, stages);
     if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN) rc = bcast_plan_set_trip(plan, trip);
     int reps = 1;
     double best = 1e30;
@@ -307,7 +309,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
             if (us < best.usec) {
                 best.algo = algo;
                 best.chunk_bytes = chunk;
-                best.stages = (algo == BCAST_ALGO_CHAIN || algo == BCAST_ALGO_KNOMIAL) ? stages : 0;
+                best.stages = (algo == BCAST_ALGO_CHAIN || has_radix(algo)) ? stages : 0;
                 best.trip_bytes = algo == BCAST_ALGO_CHAIN ? trip : 0;
                 best.usec = us;
             }
@@ -339,6 +341,14 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         consider(BCAST_ALGO_SCATTER_ALLGATHER, 0, 0);
         for (int k : {4, 8})
             if (k < nranks) consider(BCAST_ALGO_KNOMIAL, 0, k);  // radix travels in the stages column
+        // the same trees in one launch, chunked: the whole message as one chunk,
+        // and 64 KiB and 512 KiB chunks where the message is longer
+        for (int k : {2, 4, 8}) {
+            if (k >= nranks && k != 2) continue;
+            consider(BCAST_ALGO_KNOMIAL_PIPELINED, std::max<size_t>(16, (M + 15) / 16 * 16), k);
+            for (size_t C : {(size_t)64 << 10, (size_t)512 << 10})
+                if (C < M && M / C <= 4096) consider(BCAST_ALGO_KNOMIAL_PIPELINED, C, k);
+        }
         if (rc != BCAST_OK) break;
         if (best.chain_chunk_bytes == 0) best.chain_usec = 0.0;
         rc = bcast_tune_put(nranks, M, &best);

@@ -1,7 +1,7 @@
 """Measure the tuning table on the GPU in this machine and write it as text.
 
     python -m paper_1707_09414_amd.tuned.make_table [--out PATH] [--ranks 2,4,8,...]
-                                                    [--min-bytes N] [--max-bytes N] [--with-fanout] [--with-knomial]
+                                                    [--min-bytes N] [--max-bytes N] [--with-fanout] [--with-knomial] [--with-knomial-pipelined]
                                                     [--with-scatter-allgather] [--folded]
 
 For every rank count it runs ``bcast_tune`` (chain over chunk sizes and stage counts,
@@ -25,6 +25,8 @@ def main() -> int:
     ap.add_argument("--max-bytes", type=int, default=1 << 30)
     ap.add_argument("--with-fanout", action="store_true")
     ap.add_argument("--with-knomial", action="store_true", help="also try the k-nomial tree at radix 4 and 8")
+    ap.add_argument("--with-knomial-pipelined", action="store_true",
+                    help="also try the one-launch pipelined k-nomial tree at radix 2, 4 and 8")
     ap.add_argument("--with-scatter-allgather", action="store_true")
     ap.add_argument("--log", default=None, help="also append every timed candidate to this file")
     ap.add_argument("--folded", action="store_true", help="also try the chain with a single stage (no flag hand-off)")
@@ -40,6 +42,8 @@ def main() -> int:
         mask |= 1 << B.BCAST_ALGO_FANOUT
     if args.with_knomial:
         mask |= 1 << B.BCAST_ALGO_KNOMIAL
+    if args.with_knomial_pipelined:
+        mask |= 1 << B.BCAST_ALGO_KNOMIAL_PIPELINED
     if args.with_scatter_allgather:
         mask |= 1 << B.BCAST_ALGO_SCATTER_ALLGATHER
     if args.folded:

@@ -112,6 +112,8 @@ def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0,
     starts = [rb.start(r) for r in range(P)]
     if info["algo"] == B.BCAST_ALGO_KNOMIAL:
         schedule = lambda a: oracle.knomial_bcast(a, P, root, M, max(2, info["stages"]))
+    elif info["algo"] == B.BCAST_ALGO_KNOMIAL_PIPELINED:
+        schedule = lambda a: oracle.knomial_pipeline_bcast(a, P, root, M, max(16, info["chunk_bytes"]), max(2, info["stages"]))
     else:
         schedule = oracle_schedule(info["algo"], P, root, M, info["chunk_bytes"])
     exp, res = expected_with_oracle(before, starts, root, M, schedule)

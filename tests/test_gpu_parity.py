@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 KiB, MiB = inputs.KiB, inputs.MiB
 ALGOS = [B.BCAST_ALGO_CHAIN, B.BCAST_ALGO_DIRECT, B.BCAST_ALGO_BINOMIAL, B.BCAST_ALGO_FANOUT,
-         B.BCAST_ALGO_SCATTER_ALLGATHER, B.BCAST_ALGO_KNOMIAL]
+         B.BCAST_ALGO_SCATTER_ALLGATHER, B.BCAST_ALGO_KNOMIAL, B.BCAST_ALGO_KNOMIAL_PIPELINED]
 
 
 @pytest.fixture(scope="module")
@@ -115,6 +115,18 @@ def test_chain_workgroup_sizes(noise, block, P, stages, lanes, M, C):
 def test_knomial_radices(noise, P, radix, M):
     info = run_and_check(P, P // 2, M, 0, B.BCAST_ALGO_KNOMIAL, noise, radix=radix)
     assert info["stages"] == min(radix, max(2, P))
+
+
+@pytest.mark.parametrize("P,radix", [(2, 2), (3, 2), (5, 3), (9, 3), (10, 3), (17, 4), (64, 2), (64, 4), (64, 8), (64, 64), (33, 5), (7, 9)])
+@pytest.mark.parametrize("M,C,lanes", [(9, 16, 0), (4096, 1024, 0), (70001, 8192, 3), (MiB + 3, 64 * KiB, 0), (2 * MiB + 77, 0, 0)])
+def test_pipelined_knomial_tree(noise, P, radix, M, C, lanes):
+    """One launch: every position pulls each chunk from its tree parent as soon
+    as the parent has published it.  Several chunks, ragged tails, odd lane
+    counts, trees of depth 1 to 6."""
+    info = run_and_check(P, P // 3, M, C, B.BCAST_ALGO_KNOMIAL_PIPELINED, noise, radix=radix, lanes=lanes)
+    assert info["launches"] == 1 and info["stages"] == min(radix, P)
+    assert info["nchunks"] == -(-M // info["chunk_bytes"])
+    assert info["grid_blocks"] * 4 >= (P - 1) * info["lanes"]
 
 
 def test_degenerate_cases(noise):
@@ -344,7 +356,7 @@ def test_random_configurations(noise):
         kind = int(rng.integers(0, 4))
         offsets = [[0] * P, [int(rng.integers(0, 16))] * P, [int(x) for x in rng.integers(0, 4, P) * 4],
                    [int(x) for x in rng.integers(0, 33, P)]][kind]
-        radix = int(rng.integers(2, 10)) if algo == B.BCAST_ALGO_KNOMIAL else 0
+        radix = int(rng.integers(2, 10)) if algo in (B.BCAST_ALGO_KNOMIAL, B.BCAST_ALGO_KNOMIAL_PIPELINED) else 0
         trip = int(rng.choice([0, 3072, 4096])) if algo == B.BCAST_ALGO_CHAIN else 0
         block = int(rng.choice([0, 64, 128, 256])) if algo == B.BCAST_ALGO_CHAIN else 0
         try:
