@@ -167,7 +167,23 @@ def _stream(s) -> Optional[int]:
     return int(s.cuda_stream) if hasattr(s, "cuda_stream") else int(s)
 
 
-def _ptr_array(rank_bufs: Sequence):
+class RankPointers:
+    """The rank buffers' device addresses in the C array ``bcast_run`` takes.
+    Building it costs more than a small broadcast takes, so a caller that
+    broadcasts into the same buffers many times builds it once and passes it in
+    place of the buffer list.  It keeps the buffers alive."""
+
+    def __init__(self, rank_bufs: Sequence):
+        self.bufs = list(rank_bufs)
+        self.array = (ctypes.c_void_p * len(self.bufs))(*[_ptr(b) for b in self.bufs])
+
+    def __len__(self) -> int:
+        return len(self.bufs)
+
+
+def _ptr_array(rank_bufs):
+    if isinstance(rank_bufs, RankPointers):
+        return rank_bufs.array
     return (ctypes.c_void_p * len(rank_bufs))(*[_ptr(b) for b in rank_bufs])
 
 

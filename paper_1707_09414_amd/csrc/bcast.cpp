@@ -629,14 +629,15 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
     if (root < 0 || root >= P || bytes > p->bytes) return BCAST_ERR_ARG;
     for (int i = 0; i < P; ++i)
         if (!rank_bufs[i]) return BCAST_ERR_ARG;
-    // buffers must not overlap over the message (duplicates included)
-    for (int i = 0; i < P; ++i)
-        for (int j = i + 1; j < P; ++j) {
-            uintptr_t a = (uintptr_t)rank_bufs[i], b = (uintptr_t)rank_bufs[j];
-            if (a == b) return BCAST_ERR_ARG;
-            uintptr_t lo = std::min(a, b), hi = std::max(a, b);
-            if (hi - lo < bytes) return BCAST_ERR_ARG;
-        }
+    // buffers must not overlap over the message (duplicates included): sorted by
+    // address, every buffer must end before the next one begins
+    {
+        uintptr_t at[BCAST_MAX_RANKS];
+        for (int i = 0; i < P; ++i) at[i] = (uintptr_t)rank_bufs[i];
+        std::sort(at, at + P);
+        for (int i = 0; i + 1 < P; ++i)
+            if (at[i + 1] == at[i] || at[i + 1] - at[i] < bytes) return BCAST_ERR_ARG;
+    }
     if (P < 2 || bytes == 0) return BCAST_OK;
 
     bcast_plan_info_t info;

@@ -127,7 +127,7 @@ extern "C" int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *ch
 }
 
 static const char kHeaderLine[] =
-    "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout 5=scatter-allgather 6=knomial) chunk_bytes usec "
+    "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout 5=scatter-allgather 6=knomial 7=pipelined-knomial) chunk_bytes usec "
     "chain_chunk_bytes chain_usec stages chain_stages trip_bytes chain_trip_bytes\n";
 
 // Text format, one entry per line (columns after usec are optional; for a

@@ -265,6 +265,37 @@ def test_wait_limit_reports_timeout_and_plan_recovers(noise):
     plan.destroy()
 
 
+def test_wait_limit_in_the_pipelined_tree(noise):
+    """Radix-3 tree over 9 positions; position 1 never publishes, so its
+    children 4 and 7 give up after the (tiny) wait limit while every other
+    position is served.  All waves exit; the plan reports it and recovers."""
+    P, M = 9, 200 * KiB
+    rb = RankBuffers(P, M)
+    rb.reset(0, noise[:M])
+    plan = B.bcast_plan_create(P, M, 16 * KiB, B.BCAST_ALGO_KNOMIAL_PIPELINED)
+    B.bcast_plan_set_radix(plan, 3)
+    B.bcast_plan_set_debug(plan, 200000, 1)  # 2 ms of the 100 MHz clock
+    B.bcast_run(plan, rb.ptrs(), 0, M)
+    torch.cuda.synchronize()
+    st, detail = B.bcast_plan_status(plan)
+    assert st == B.BCAST_ERR_TIMEOUT
+    assert detail >> 32 in (4, 7) and (detail & 0xFFFFFFFF) == 0, hex(detail)
+    got = rb.to_host()
+    for r in (1, 2, 3, 5, 6, 8):
+        assert np.array_equal(got[r][rb.start(r): rb.start(r) + M], noise[:M]), r
+    for r in (4, 7):
+        assert (got[r] == FILL).all(), r
+    B.bcast_plan_clear_status(plan)
+    B.bcast_plan_set_debug(plan, 0, 0)
+    rb.reset(0, noise[7: 7 + M])
+    B.bcast_run(plan, rb.ptrs(), 0, M)
+    got = rb.to_host()
+    assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+    for r in range(P):
+        assert np.array_equal(got[r][rb.start(r): rb.start(r) + M], noise[7: 7 + M]), r
+    plan.destroy()
+
+
 def test_tune_then_auto(noise, tmp_path):
     P = 4
     B.bcast_tune_clear()
