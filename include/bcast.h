@@ -67,8 +67,10 @@ typedef struct {
     uint64_t chunk_bytes;  /* chunk size C in use (== bytes when unchunked) */
     uint64_t nchunks;      /* ceil(bytes / C) */
     int stages;            /* chain: groups of consecutive hops; each stage has its own wavefronts and flags */
-    int hops_per_stage;    /* chain: hops a stage's wavefront plays one after the other (1 = a stage per rank) */
+    int hops_per_stage;    /* chain: hops a stage's wavefront plays one after the other (1 = a stage per rank);
+                              where nranks-1 is no multiple of stages this is the larger of the two counts */
     int lanes;             /* chain: wavefronts per stage, each streaming its own share of every chunk */
+    int rotating_spans;    /* chain: 1 if the stages that play one hop more change from chunk to chunk */
     int trip_bytes;        /* chain: bytes a wavefront moves per trip at 16-byte accesses (3072 or 4096) */
     uint64_t slice_bytes;  /* chain: bytes of every chunk owned by one lane, in trips dealt round-robin over the lanes */
     int grid_blocks;       /* workgroups of the (first) launch */
@@ -144,8 +146,10 @@ int bcast_plan_destroy(bcast_plan_t *plan);
  * automatic).  stages: how many groups of consecutive hops get wavefronts of
  * their own (0 = automatic; nranks-1 = one stage per receiving rank; fewer =
  * a wavefront plays several consecutive ranks in turn, re-reading from each
- * rank's buffer what it stored there, and flags are only used between stages).  spin_limit_ticks: wait limit in 100 MHz ticks (0 = default,
- * about 10 s).  mute_hop: chain position (1..P-2) that stores its chunks but
+ * rank's buffer what it stored there, and flags are only used between stages;
+ * where nranks-1 is no multiple of stages, the stages that play one hop more
+ * rotate from chunk to chunk, so the stage boundaries differ between chunks).
+ * spin_limit_ticks: wait limit in 100 MHz ticks (0 = default, about 10 s).  mute_hop: chain position (1..P-2) that stores its chunks but
  * never publishes them, so that its right neighbour runs into the wait limit;
  * 0 = off.  Kernels always run to completion under these settings. */
 int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
@@ -171,8 +175,15 @@ int bcast_plan_debug_set_epoch(bcast_plan_t *plan, uint64_t epoch);
 /* Chain kernel modes (bit mask).  BCAST_MODE_COUNT: count the hand-offs whose
  * producer and consumer waves ran on the same XCD (one L2) and on different
  * XCDs; read back (after a device synchronise) by bcast_plan_handoff_counts.
- * The counts accumulate over runs.  Diagnostic: it slows the kernel down. */
+ * The counts accumulate over runs.  Diagnostic: it slows the kernel down.
+ * BCAST_MODE_FIXED_SPANS / BCAST_MODE_ROTATE_SPANS (not both): where nranks-1 is
+ * no multiple of the stage count, the first stages keep the extra hop for every
+ * chunk (every chunk has chunk 0's spans of bcast_chain_stage_span), or the
+ * extra hop is passed round as that function describes.  With neither bit the
+ * library rotates where a stage plays fewer than four hops. */
 #define BCAST_MODE_COUNT 2u
+#define BCAST_MODE_FIXED_SPANS 16u
+#define BCAST_MODE_ROTATE_SPANS 32u
 int bcast_plan_set_mode(bcast_plan_t *plan, unsigned mode);
 
 /* Pipeline trace (diagnostic).  After bcast_plan_enable_trace(plan, entries),
@@ -203,6 +214,17 @@ typedef struct {
  */
 int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
                          const bcast_chain_request_t *request, bcast_plan_info_t *info);
+
+/* Pure host arithmetic: the chain positions that `stage` (0-based, of `stages`)
+ * plays for chunk number `chunk`: hops *first_hop .. *last_hop, hop h being the
+ * copy from position h-1 to position h.  With nranks-1 = q stages + r, every
+ * stage plays q hops and r of them one more; stage j has the extra hop for
+ * chunk c iff (j + c) mod stages < r, so the longer stages rotate and over any
+ * `stages` consecutive chunks all stages play the same number of hops.  This is
+ * the function the kernel itself evaluates when spans rotate (plan info's
+ * rotating_spans); when they do not, every chunk has the spans of chunk 0.  BCAST_ERR_ARG unless
+ * 2 <= nranks <= BCAST_MAX_RANKS, 1 <= stages <= nranks-1, 0 <= stage < stages. */
+int bcast_chain_stage_span(int nranks, int stages, int stage, uint64_t chunk, int *first_hop, int *last_hop);
 
 /*
  * Tuning table (Sec. III-B "Discussion" and IV-B last paragraph: algorithm and

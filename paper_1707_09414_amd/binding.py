@@ -39,7 +39,7 @@ BCAST_ERR_UNTUNED = -5
 # every symbol include/bcast.h declares
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
     "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
@@ -67,6 +67,7 @@ class PlanInfo(ctypes.Structure):
         ("stages", ctypes.c_int),
         ("hops_per_stage", ctypes.c_int),
         ("lanes", ctypes.c_int),
+        ("rotating_spans", ctypes.c_int),
         ("trip_bytes", ctypes.c_int),
         ("slice_bytes", ctypes.c_uint64),
         ("grid_blocks", ctypes.c_int),
@@ -120,6 +121,7 @@ def _load():
         "bcast_plan_set_stages": ([vp, i], i),
         "bcast_plan_set_radix": ([vp, i], i),
         "bcast_plan_set_trip": ([vp, i], i),
+        "bcast_chain_stage_span": ([i, i, i, ctypes.c_uint64, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)], i),
         "bcast_plan_debug_set_epoch": ([vp, ctypes.c_uint64], i),
         "bcast_plan_set_block_threads": ([vp, i], i),
         "bcast_plan_set_debug": ([vp, u64, i], i),
@@ -270,6 +272,14 @@ def bcast_plan_set_block_threads(plan: Plan, block_threads: int) -> None:
     _check(_lib.bcast_plan_set_block_threads(plan.handle, block_threads), "bcast_plan_set_block_threads")
 
 
+def bcast_chain_stage_span(nranks: int, stages: int, stage: int, chunk: int) -> Tuple[int, int]:
+    """(first_hop, last_hop) that `stage` plays for chunk number `chunk`."""
+    first, last = ctypes.c_int(0), ctypes.c_int(0)
+    _check(_lib.bcast_chain_stage_span(nranks, stages, stage, chunk, ctypes.byref(first), ctypes.byref(last)),
+           "bcast_chain_stage_span")
+    return first.value, last.value
+
+
 def bcast_plan_debug_set_epoch(plan: Plan, epoch: int) -> None:
     _check(_lib.bcast_plan_debug_set_epoch(plan.handle, epoch), "bcast_plan_debug_set_epoch")
 
@@ -283,6 +293,8 @@ def bcast_plan_set_debug(plan: Plan, spin_limit_ticks: int, mute_hop: int) -> No
 
 
 BCAST_MODE_COUNT = 2
+BCAST_MODE_FIXED_SPANS = 16
+BCAST_MODE_ROTATE_SPANS = 32
 
 
 def bcast_plan_set_mode(plan: Plan, mode: int) -> None:

@@ -60,12 +60,13 @@ static u64 ceil_div(u64 a, u64 b) { return (a + b - 1) / b; }
 static u64 round_up(u64 a, u64 b) { return ceil_div(a, b) * b; }
 
 
-// Stages for `hops` chain hops when the caller asks for `request` (0 = one per hop).
+// Stages for `hops` chain hops when the caller asks for `request` (0 = one per
+// hop): that many, and each plays floor or ceil(hops / stages) consecutive hops
+// (the kernel rotates the longer ones from chunk to chunk).
 static void stage_shape(int hops, int request, int *stages, int *hops_per_stage)
 {
-    int want = request > 0 ? std::min(request, hops) : hops;
-    *hops_per_stage = (hops + want - 1) / want;
-    *stages = (hops + *hops_per_stage - 1) / *hops_per_stage;
+    *stages = request > 0 ? std::min(request, hops) : hops;
+    *hops_per_stage = (hops + *stages - 1) / *stages;
 }
 
 // Bytes of one trip of the copy loop at 16-byte vectors: the least worth a lane.
@@ -152,6 +153,31 @@ extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes
     info->grid_blocks = (int)ceil_div((u64)stages * lanes, (u64)(block / kWaveSize));
     info->launches = 1;
     info->algorithmic_bytes = 2ull * hops * bytes;
+    return BCAST_OK;
+}
+
+// Whether the longer stages rotate from chunk to chunk.  Measured on MI355X
+// (same buffers, same process): rotation gains 3-20 % where a stage plays fewer
+// than four hops (P = 8 in two stages: 4|3 hops, 8.27 vs 8.03 TB/s; in three:
+// 6.5 vs 5.4), where the idle time of the shorter stages is large; with long
+// stages (P >= 16 in two stages) it loses 5 % at 3 KiB trips -- there the short
+// idle time of one stage relieves the CUs' L1, which those trips fill to the brim.
+static bool rotate_spans(unsigned mode, int hops, int stages)
+{
+    if (mode & kModeRotateSpans) return true;
+    if (mode & kModeFixedSpans) return false;
+    return hops % stages != 0 && hops / stages < 4;
+}
+
+extern "C" int bcast_chain_stage_span(int nranks, int stages, int stage, uint64_t chunk, int *first_hop, int *last_hop)
+{
+    if (nranks < 2 || nranks > BCAST_MAX_RANKS || stages < 1 || stages > nranks - 1 || stage < 0 || stage >= stages ||
+        !first_hop || !last_hop)
+        return BCAST_ERR_ARG;
+    const unsigned hops = (unsigned)(nranks - 1), S = (unsigned)stages;
+    const unsigned c = (unsigned)(chunk % S);  // the pattern repeats every `stages` chunks
+    *first_hop = (int)stage_begin((unsigned)stage, c, S, hops / S, hops % S) + 1;
+    *last_hop = (int)stage_begin((unsigned)stage + 1, c, S, hops / S, hops % S);
     return BCAST_OK;
 }
 
@@ -284,7 +310,8 @@ extern "C" int bcast_plan_debug_set_epoch(bcast_plan_t *p, uint64_t epoch)
 
 extern "C" int bcast_plan_set_mode(bcast_plan_t *p, unsigned mode)
 {
-    if (!p || (mode & ~kModeCount)) return BCAST_ERR_ARG;
+    if (!p || (mode & ~(kModeCount | kModeFixedSpans | kModeRotateSpans))) return BCAST_ERR_ARG;
+    if ((mode & kModeFixedSpans) && (mode & kModeRotateSpans)) return BCAST_ERR_ARG;
     p->mode = mode;
     return BCAST_OK;
 }
@@ -503,6 +530,7 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
         rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, waves_for(p, bytes), &req, info);
         if (rc != BCAST_OK) return rc;
         info->vec_bytes = vec;
+        info->rotating_spans = info->stages > 0 && rotate_spans(p->mode, P - 1, info->stages) ? 1 : 0;
         return BCAST_OK;
     }
     memset(info, 0, sizeof *info);
@@ -655,19 +683,18 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         a.counters = p->d_counters;
         a.trace = p->d_trace;
         a.trace_entries = p->trace_entries;
-        a.mode = p->mode;
+        a.mode = p->mode & ~(kModeFixedSpans | kModeRotateSpans);
+        if (!info.rotating_spans) a.mode |= kModeFixedSpans;
         if (bytes <= kStageWriteBackMaxBytes) a.mode |= kModeStageWriteBack;
         if (p->d_trace) a.mode |= kModeTrace;
         a.stages = (unsigned)info.stages;
         a.hops_per_stage = (unsigned)info.hops_per_stage;
         a.unroll = (unsigned)(info.trip_bytes / (kWaveSize * 16));
         // the launch must match what the kernel indexes: stages*lanes waves, each with its own flag,
-        // and the stages together cover exactly the P-1 hops
+        // and no more stages than hops
         if ((u64)a.stages * a.lanes > (u64)waves_for(p, bytes)) return BCAST_ERR_ARG;
         if ((u64)info.grid_blocks * (u64)(info.block_threads / kWaveSize) < (u64)a.stages * a.lanes) return BCAST_ERR_ARG;
-        if (a.stages == 0 || a.hops_per_stage == 0) return BCAST_ERR_ARG;
-        if ((u64)a.stages * a.hops_per_stage < (u64)(P - 1) || (u64)(a.stages - 1) * a.hops_per_stage >= (u64)(P - 1))
-            return BCAST_ERR_ARG;
+        if (a.stages == 0 || a.stages > (unsigned)(P - 1)) return BCAST_ERR_ARG;
         if (a.nchunks == 0 || a.lanes == 0 || a.chunk_bytes == 0) return BCAST_ERR_ARG;
         if ((u64)a.nchunks * a.chunk_bytes < a.bytes) return BCAST_ERR_ARG;
         HIP_TRY(launch_chain(a, info.vec_bytes, info.grid_blocks, info.block_threads, stream));

@@ -54,7 +54,7 @@ struct ChainArgs {
     unsigned nchunks;
     unsigned lanes;    // wavefronts per stage
     unsigned stages;   // groups of consecutive chain positions, each served by its own waves
-    unsigned hops_per_stage;
+    unsigned hops_per_stage; // the most hops a stage plays for one chunk (informational)
     unsigned unroll;   // vector instructions per lane and trip: kTripUnrollDefault or kTripUnrollSmall
     unsigned nranks;
     unsigned mute_hop; // debug: this position never publishes (0 = off)
@@ -65,6 +65,23 @@ struct ChainArgs {
     u64 forward_mask;
 };
 
+// Number of chain hops that lie before stage g for chunk c, so that stage g plays
+// hops stage_begin(g) + 1 .. stage_begin(g + 1) of that chunk.  Every stage plays
+// hops_min = hops / stages hops and hops_extra = hops % stages of the stages one
+// more; which ones rotates with the chunk: stage j has the extra hop for chunk c
+// iff (j + c) mod stages < hops_extra.  Over any `stages` consecutive chunks
+// every stage plays exactly `hops` hops.
+__host__ __device__ inline unsigned stage_begin(unsigned g, unsigned c, unsigned stages, unsigned hops_min, unsigned hops_extra)
+{
+    // extras among stages 0..g-1 = the residues (c mod stages) .. (c mod stages) + g - 1
+    // that are below hops_extra; below(x) counts them in [0, x)
+    const unsigned start = c % stages;
+    const unsigned x1 = start + g, x0 = start;
+    const unsigned below1 = (x1 / stages) * hops_extra + (x1 % stages < hops_extra ? x1 % stages : hops_extra);
+    const unsigned below0 = (x0 / stages) * hops_extra + (x0 % stages < hops_extra ? x0 % stages : hops_extra);
+    return g * hops_min + below1 - below0;
+}
+
 // ChainArgs::mode
 // Count hand-offs whose two waves ran on the same XCD / on different XCDs.
 // Diagnostic only: every wave ends with two atomics on one cache line, which
@@ -72,6 +89,12 @@ struct ChainArgs {
 constexpr unsigned kModeCount = 2;
 // Lane 0's wave of every stage records when it begins and ends each chunk.
 constexpr unsigned kModeTrace = 8;
+// The stages that play one hop more do not rotate from chunk to chunk: the
+// first hops % stages stages always have it.  The host sets it per run unless
+// rotation pays (see rotate_spans in bcast.cpp); kModeRotateSpans is the
+// caller's request to rotate regardless and never reaches the kernel.
+constexpr unsigned kModeFixedSpans = 16;
+constexpr unsigned kModeRotateSpans = 32;
 // Chosen by the host per run (small messages): write-back stores inside a stage.
 constexpr unsigned kModeStageWriteBack = 4;
 // Largest message that uses it (measured crossover on MI355X: 2-4 MiB).

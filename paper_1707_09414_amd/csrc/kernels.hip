@@ -277,22 +277,24 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
     // the workgroup is only the unit the dispatcher places on a CU
     const unsigned gw = __builtin_amdgcn_readfirstlane(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
     if (gw >= a.stages * a.lanes) return;
-    // Stage g serves the consecutive chain positions first_hop .. last_hop: its
-    // waves play those ranks one after the other for every chunk (hops_per_stage
-    // == 1 is one stage per rank).  Hand-offs between stages go through flags;
-    // inside a stage the same wave stored what it reads next, so its own
-    // s_waitcnt orders the two.
+    // Stage g serves consecutive chain positions first_hop .. last_hop: its waves
+    // play those ranks one after the other (one hop per stage is one stage per
+    // rank).  Hand-offs between stages go through flags; inside a stage the
+    // same wave stored what it reads next, so its own s_waitcnt orders the two.
+    // Where the P-1 hops do not divide evenly over the stages, the stages that
+    // take one hop more rotate from chunk to chunk (see stage_begin), so that
+    // over the message every stage plays the same number of hops and none
+    // idles while a longer one finishes.
     const unsigned g = gw / a.lanes;
     const unsigned s = gw - g * a.lanes;
-    const unsigned first_hop = g * a.hops_per_stage + 1;
-    unsigned last_hop = first_hop + a.hops_per_stage - 1;
-    if (last_hop > a.nranks - 1) last_hop = a.nranks - 1;
+    const unsigned hops = a.nranks - 1;
+    const unsigned hops_min = hops / a.stages;            // every stage plays at least this many
+    const unsigned hops_extra = hops - hops_min * a.stages;  // this many stages play one more
     // which XCD (L2 domain) this wave runs on: HW_REG_XCC_ID, bits 3:0
     const unsigned xcd = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 15u;
 
     const u64 *in_flag = g > 0 ? a.flags + ((u64)(g - 1) * a.lanes + s) * kFlagStrideWords : nullptr;
-    const bool muted = a.mute_hop >= first_hop && a.mute_hop <= last_hop;
-    u64 *out_flag = (g + 1 < a.stages && !muted) ? a.flags + ((u64)g * a.lanes + s) * kFlagStrideWords : nullptr;
+    u64 *const my_flag = g + 1 < a.stages ? a.flags + ((u64)g * a.lanes + s) * kFlagStrideWords : nullptr;
     unsigned near = 0, far = 0;  // hand-offs received from the same / another XCD
 
     // A lane's share of a chunk is every lanes-th trip (one trip = U vector
@@ -307,6 +309,13 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
     for (unsigned c = 0; c < a.nchunks; ++c, chunk_lo += a.chunk_bytes) {
         u64 chunk_hi = chunk_lo + a.chunk_bytes;
         if (chunk_hi > a.bytes) chunk_hi = a.bytes;
+        // this chunk's positions for this stage: the producer stage computes
+        // the same boundary, so it publishes exactly the buffer read here
+        const unsigned turn = (a.mode & kModeFixedSpans) ? 0u : c;
+        const unsigned first_hop = stage_begin(g, turn, a.stages, hops_min, hops_extra) + 1;
+        const unsigned last_hop = stage_begin(g + 1, turn, a.stages, hops_min, hops_extra);
+        const bool muted = a.mute_hop >= first_hop && a.mute_hop <= last_hop;
+        u64 *const out_flag = muted ? nullptr : my_flag;
 
         // flag value: base + (chunks stored << 4) + producer's XCD
         if (in_flag) {

@@ -67,15 +67,34 @@ def test_chain_lane_counts(noise, lanes):
     assert info["lanes"] == lanes
 
 
-@pytest.mark.parametrize("P,stages", [(2, 1), (5, 1), (5, 2), (5, 3), (9, 3), (17, 4), (33, 5), (64, 1), (64, 8), (64, 9), (64, 63), (64, 100)])
+@pytest.mark.parametrize("P,stages", [(2, 1), (5, 1), (5, 2), (5, 3), (8, 2), (9, 3), (10, 4), (17, 4), (33, 5), (64, 1), (64, 2), (64, 8), (64, 9),
+                                      (64, 10), (64, 62), (64, 63), (64, 100)])
 @pytest.mark.parametrize("M,C", [(7, 16), (70000, 8192), (3 * MiB + 5, 256 * KiB)])
 def test_chain_stages(noise, P, stages, M, C):
     """A stage's wavefront plays several consecutive ranks in turn; every rank's
     buffer must still end up with the root's bytes, whatever the grouping."""
     info = run_and_check(P, P // 3, M, C, B.BCAST_ALGO_CHAIN, noise, stages=stages)
     want = min(stages, P - 1)
-    hps = -(-(P - 1) // want)
-    assert info["hops_per_stage"] == hps and info["stages"] == -(-(P - 1) // hps)
+    assert info["stages"] == want and info["hops_per_stage"] == -(-(P - 1) // want)
+
+
+@pytest.mark.parametrize("mode", [0, B.BCAST_MODE_FIXED_SPANS, B.BCAST_MODE_ROTATE_SPANS])
+@pytest.mark.parametrize("P,stages", [(4, 2), (6, 2), (8, 2), (8, 3), (10, 4), (17, 3), (33, 2), (64, 2), (64, 5), (64, 40)])
+def test_chain_rotating_and_fixed_spans(noise, P, stages, mode):
+    """Stages of unequal length: the longer ones either stay where they are or
+    move on by one stage per chunk.  Enough chunks for several full turns, a
+    ragged last chunk, several trips per lane."""
+    M, C = 40 * 24 * KiB + 4100, 24 * KiB
+    plan = B.bcast_plan_create(P, M, C, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_mode(plan, mode)
+    info = run_and_check(P, 1, M, C, B.BCAST_ALGO_CHAIN, noise, stages=stages, lanes=2, plan=plan)
+    hops = P - 1
+    auto = hops % stages != 0 and hops // stages < 4
+    want = {0: auto, B.BCAST_MODE_FIXED_SPANS: False, B.BCAST_MODE_ROTATE_SPANS: True}[mode]
+    assert info["rotating_spans"] == int(want) and info["nchunks"] == 41
+    with pytest.raises(B.BcastError):
+        B.bcast_plan_set_mode(plan, B.BCAST_MODE_FIXED_SPANS | B.BCAST_MODE_ROTATE_SPANS)
+    plan.destroy()
 
 
 @pytest.mark.parametrize("P", [2, 3, 5, 8, 13, 64])

@@ -60,6 +60,9 @@ def test_chain_geometry_matches_eq5_chunking():
     assert (g["stages"], g["hops_per_stage"], g["lanes"]) == (8, 8, 1024)  # 4 MiB = 1024 trips of 4 KiB
     g = B.bcast_chain_geometry(64, 1 << 30, 4 << 20, 8192, stages_request=5)
     assert (g["stages"], g["hops_per_stage"]) == (5, 13)
+    # exactly the stages asked for (up to one per hop), also where they cannot be equal
+    g = B.bcast_chain_geometry(10, 1 << 20, 64 << 10, 8192, stages_request=4)
+    assert (g["stages"], g["hops_per_stage"]) == (4, 3)  # 9 hops as 3+2+2+2, rotating
     g = B.bcast_chain_geometry(8, 1 << 26, 8 << 20, 8192, stages_request=100)
     assert (g["stages"], g["hops_per_stage"], g["lanes"]) == (7, 1, 1024)
     g = B.bcast_chain_geometry(8, 1 << 26, 8 << 20, 8192, stages_request=1)
@@ -86,6 +89,34 @@ def test_chain_geometry_matches_eq5_chunking():
     for bad in [(4, 100, 0, 64), (4, 100, 8, 64), (65, 100, 16, 64), (4, 100, 16, 2)]:
         with pytest.raises(B.BcastError):
             B.bcast_chain_geometry(*bad)
+
+
+def test_stage_spans_cover_the_chain_and_rotate_evenly():
+    """For every chunk the stages' spans tile hops 1..P-1 in order, each span has
+    floor or ceil((P-1)/stages) hops, the stage with an extra hop is the one the
+    rule names, and over `stages` consecutive chunks all stages play equally."""
+    for P in list(range(2, 20)) + [31, 32, 33, 63, 64]:
+        H = P - 1
+        for S in range(1, H + 1):
+            q, r = divmod(H, S)
+            played = [0] * S
+            for c in list(range(2 * S + 1)) + [10 ** 9 + 7]:
+                nxt = 1
+                for g in range(S):
+                    first, last = B.bcast_chain_stage_span(P, S, g, c)
+                    assert first == nxt, (P, S, c, g)
+                    n = last - first + 1
+                    assert n == q + (1 if (g + c) % S < r else 0), (P, S, c, g, n)
+                    nxt = last + 1
+                    if c < S:
+                        played[g] += n
+                assert nxt == H + 1
+            assert played == [H] * S, (P, S, played)
+    assert B.bcast_chain_stage_span(8, 2, 0, 0) == (1, 4) and B.bcast_chain_stage_span(8, 2, 1, 0) == (5, 7)
+    assert B.bcast_chain_stage_span(8, 2, 0, 1) == (1, 3) and B.bcast_chain_stage_span(8, 2, 1, 1) == (4, 7)
+    for bad in [(1, 1, 0, 0), (8, 8, 0, 0), (8, 0, 0, 0), (8, 2, 2, 0), (8, 2, -1, 0), (65, 2, 0, 0)]:
+        with pytest.raises(B.BcastError):
+            B.bcast_chain_stage_span(*bad)
 
 
 def test_tuning_table_lookup_rules(tmp_path):
