@@ -270,8 +270,11 @@ int bcast_tune_load(const char *table_path);  /* HOST path; adds the file's entr
 int bcast_tune_save(const char *table_path);  /* HOST path; writes all entries */
 int bcast_tune_clear(void);
 int bcast_tune_put(int nranks, size_t bytes, const bcast_tune_entry_t *entry);
-/* Nearest entry for nranks at or below log2(bytes), else the nearest above;
- * BCAST_ERR_UNTUNED if the table has none for nranks. */
+/* Nearest entry for nranks at or below log2(bytes), else the nearest above.  If
+ * the table has no entry for nranks at all, the rank count in the table that is
+ * closest to it in ratio stands in (the larger on a tie); stage counts and
+ * radices beyond what nranks allows are cut down when a plan uses them.
+ * BCAST_ERR_UNTUNED if the table is empty. */
 int bcast_tune_get(int nranks, size_t bytes, bcast_tune_entry_t *entry);
 /* Shorthands: set / look up the winner only. */
 int bcast_tune_set(int nranks, size_t bytes, int algo, size_t chunk_bytes, double usec);

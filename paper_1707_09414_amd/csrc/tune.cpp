@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <climits>
 #include <map>
 #include <mutex>
 #include <string>
@@ -80,9 +81,9 @@ extern "C" int bcast_tune_put(int nranks, size_t bytes, const bcast_tune_entry_t
     return BCAST_OK;
 }
 
-// nearest bucket at or below, else the nearest above, among this nranks' entries
+// nearest bucket at or below, else the nearest above, among one rank count's entries
 // (caller holds g_mu)
-static const bcast_tune_entry_t *nearest(int nranks, size_t bytes)
+static const bcast_tune_entry_t *nearest_size(int nranks, size_t bytes)
 {
     const int want = log2_bucket(bytes);
     auto it = g_table.upper_bound({nranks, want});
@@ -92,6 +93,27 @@ static const bcast_tune_entry_t *nearest(int nranks, size_t bytes)
     }
     if (it != g_table.end() && it->first.first == nranks) return &it->second;
     return nullptr;
+}
+
+// The entry for (nranks, bytes): this rank count's if it has any, else that of
+// the measured rank count closest to it in ratio (the larger one on a tie) --
+// tables are measured for a few process counts and serve the ranges between
+// them (Sec. III-B).  (caller holds g_mu)
+static const bcast_tune_entry_t *nearest(int nranks, size_t bytes)
+{
+    if (const bcast_tune_entry_t *e = nearest_size(nranks, bytes)) return e;
+    int best = 0;
+    for (auto it = g_table.begin(); it != g_table.end(); it = g_table.upper_bound({it->first.first, INT_MAX})) {
+        const int n = it->first.first;
+        // n is closer than best if max(n, nranks) / min(n, nranks) is smaller
+        auto closer = [&](int a, int b) {
+            const long long ra_num = std::max(a, nranks), ra_den = std::min(a, nranks);
+            const long long rb_num = std::max(b, nranks), rb_den = std::min(b, nranks);
+            return ra_num * rb_den < rb_num * ra_den || (ra_num * rb_den == rb_num * ra_den && a > b);
+        };
+        if (best == 0 || closer(n, best)) best = n;
+    }
+    return best ? nearest_size(best, bytes) : nullptr;
 }
 
 extern "C" int bcast_tune_get(int nranks, size_t bytes, bcast_tune_entry_t *entry)

@@ -162,3 +162,19 @@ def test_config5_1gib_p64_root17():
         full = {(root + 1) % P, (root + 32) % P, (root + P - 1) % P}
         check_against_message(bufs, msg, M, root, full_ranks=full, seed=6)
     oracle_prefix_check(P, root, msg, int(info["chunk_bytes"]) if info["algo"] == B.BCAST_ALGO_CHAIN else 4 * MiB, 4 * MiB)
+
+
+@pytest.mark.parametrize("P", [3, 6, 12, 24, 48, 63])
+def test_auto_for_rank_counts_the_table_does_not_hold(P):
+    """The shipped table is measured for P in {2, 4, 8, 16, 32, 64}; any other
+    rank count borrows the closest one's entries, with stage counts and radices
+    cut down to what P allows.  Small, medium and large messages, bit-exact."""
+    from gpu_harness import run_and_check
+
+    noise = inputs.random_bytes(11, 24 * MiB + 64)
+    for M in (24, 4 * KiB, 300 * KiB + 8, 24 * MiB + 16):
+        info = run_and_check(P, P // 2, M, 0, B.BCAST_ALGO_AUTO, noise)
+        assert info["algo"] in (B.BCAST_ALGO_CHAIN, B.BCAST_ALGO_KNOMIAL_PIPELINED, B.BCAST_ALGO_KNOMIAL,
+                                B.BCAST_ALGO_BINOMIAL, B.BCAST_ALGO_DIRECT)
+        if info["algo"] == B.BCAST_ALGO_CHAIN:
+            assert 1 <= info["stages"] <= P - 1

@@ -135,10 +135,15 @@ def test_tuning_table_lookup_rules(tmp_path):
     assert B.bcast_tune_lookup(8, 1 << 26) == (B.BCAST_ALGO_CHAIN, 64 << 10, 50.0)
     # below the smallest entry: nearest above
     assert B.bcast_tune_lookup(8, 16)[0] == B.BCAST_ALGO_BINOMIAL
-    # other rank counts are separate
+    # rank counts have their own entries ...
     assert B.bcast_tune_lookup(16, 4)[0] == B.BCAST_ALGO_DIRECT
-    with pytest.raises(B.BcastError):
-        B.bcast_tune_lookup(4, 4096)
+    # ... and a rank count without any borrows those of the closest one in ratio
+    assert B.bcast_tune_lookup(4, 4096)[0] == B.BCAST_ALGO_BINOMIAL    # 8 (x2) is closer than 16 (x4)
+    assert B.bcast_tune_lookup(12, 4096)[0] == B.BCAST_ALGO_DIRECT     # 16 (x1.33) is closer than 8 (x1.5)
+    assert B.bcast_tune_lookup(11, 4096)[0] == B.BCAST_ALGO_BINOMIAL   # 8 (x1.375) is closer than 16 (x1.45)
+    assert B.bcast_tune_lookup(64, 1 << 20)[0] == B.BCAST_ALGO_DIRECT
+    B.bcast_tune_set(32, 1 << 12, B.BCAST_ALGO_CHAIN, 4096, 9.0)
+    assert B.bcast_tune_lookup(23, 4096)[0] == B.BCAST_ALGO_CHAIN     # 16 and 32 are equally close: the larger
     # chain entries need a valid chunk
     with pytest.raises(B.BcastError):
         B.bcast_tune_set(8, 1 << 20, B.BCAST_ALGO_CHAIN, 0)
@@ -164,7 +169,7 @@ def test_tuning_table_lookup_rules(tmp_path):
     B.bcast_tune_save(str(path))
     B.bcast_tune_clear()
     B.bcast_tune_load(str(path))
-    assert B.bcast_tune_count() == 4
+    assert B.bcast_tune_count() == 5
     e = B.bcast_tune_get(16, 1 << 24)
     assert (e["trip_bytes"], e["chain_trip_bytes"], e["chain_chunk_bytes"], e["stages"]) == (3072, 3072, 3 << 20, 2)
     assert B.bcast_tune_lookup(8, 1 << 20) == (B.BCAST_ALGO_CHAIN, 64 << 10, 50.0)
