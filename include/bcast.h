@@ -86,11 +86,12 @@ typedef struct {
  *   out         HOST pointer; receives the plan on success, NULL otherwise.
  *   nranks      number of ranks P, 1..BCAST_MAX_RANKS (the paper's n).
  *   bytes       largest message M this plan will carry (0 allowed).
- *   chunk_bytes chunk size C for CHAIN: a positive multiple of 16; values
- *               >= bytes give the unpipelined chain (Eq. 2).  0 = choose: the
- *               tuning table's entry if one is loaded, else a built-in rule.
- *               Ignored by DIRECT, BINOMIAL, KNOMIAL, FANOUT and SCATTER_ALLGATHER
- *               (whose piece size is ceil(bytes / nranks)).
+ *   chunk_bytes chunk size C for CHAIN and KNOMIAL_PIPELINED: a positive multiple
+ *               of 16; values >= bytes give the unpipelined chain (Eq. 2) or
+ *               tree (Eq. 3).  0 = choose: the tuning table's entry if one is
+ *               loaded, else a built-in rule.  Ignored by DIRECT, BINOMIAL,
+ *               KNOMIAL, FANOUT and SCATTER_ALLGATHER (whose piece size is
+ *               ceil(bytes / nranks)).
  *   algo        a bcast_algo_t.  AUTO resolves per run from the tuning table and
  *               fails with BCAST_ERR_UNTUNED if no table covers nranks.
  * Allocates device memory for ready flags (zeroed once; they are never reset,
@@ -104,6 +105,8 @@ int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, size_t chunk
  * problem, Sec. I and III-A; chain order per Sec. III-A "Chain and Ring").
  *   plan       from bcast_plan_create.  One plan must not run on two streams
  *              at once (not detected); back-to-back runs on one stream are fine.
+ *              Calls on one plan must come from one thread at a time; different
+ *              plans are independent.
  *   rank_bufs  HOST array of plan.nranks DEVICE pointers, one per rank, on the
  *              current device, pairwise non-overlapping over `bytes`.  Read
  *              during the call only; the buffers must stay valid until the
@@ -117,7 +120,9 @@ int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, size_t chunk
  * rank root+1, which forwards to root+2, ... and rank root-1 only receives.
  * Returns after enqueueing; completion follows stream order.  Every run gets a
  * fresh epoch from the host as a kernel argument, so a bcast_run recorded into
- * a HIP graph must not be replayed: call it directly.
+ * a HIP graph must not be replayed: call it directly.  The epoch is a 32-bit
+ * count: once in 2^32 - 2 runs of a plan, bcast_run waits for the device and
+ * clears the plan's flags before it goes on.
  * bytes == 0 or nranks == 1 succeed without launching.
  * Errors: ERR_ARG (NULL/duplicate/overlapping pointers, root or bytes out of
  * range), ERR_UNTUNED, ERR_HIP.  A wave that waits longer than the plan's

@@ -17,7 +17,10 @@
  *
  * Parity status: every function here is pinned by tests that do not use this
  * file's own arithmetic (numpy row replication for the end state, the paper's
- * closed-form step counts for the schedules).
+ * closed-form step counts for the schedules, hand-worked values of the cost
+ * models, parent and step of every transfer derived independently in the test,
+ * and a set of planted mistakes that the pins must reject).  Nothing is
+ * "parity unpinned".
  */
 #ifndef BCAST_ORACLE_H
 #define BCAST_ORACLE_H
