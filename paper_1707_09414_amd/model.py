@@ -24,6 +24,7 @@ from typing import Dict, Iterable, List, Tuple
 import numpy as np
 
 ALGO_CHAIN, ALGO_DIRECT, ALGO_BINOMIAL, ALGO_FANOUT = 1, 2, 3, 4
+ALGO_KNOMIAL, ALGO_KNOMIAL_PIPELINED = 6, 7
 
 
 def ceil_log(n: int, k: int) -> int:
@@ -60,6 +61,12 @@ def t_scatter_allgather(n, M, ts, B):
 def t_chain_pipeline(n, M, C, ts, B):
     """Eq. 5: (M/C + n - 2)(t_s + C/B)."""
     return (M / C + (n - 2)) * (ts + C / B)
+
+
+def t_knomial_pipeline(n, k, M, C, ts, B):
+    """The pipelined k-nomial remark after Eq. 5 in the paper's source:
+    (M/C ceil(log_k n))(t_s + C/B)."""
+    return (M / C * ceil_log(n, k)) * (ts + C / B)
 
 
 def best_chunk(n, M, ts, B):

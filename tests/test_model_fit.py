@@ -22,6 +22,7 @@ def test_models_match_the_oracle(n):
         assert model.t_chain(n, M, ts, Bw) == pytest.approx(oracle.model_chain(n, M, ts, Bw), rel=1e-13)
         for k in (2, 3, 4, 8):
             assert model.t_knomial(n, k, M, ts, Bw) == pytest.approx(oracle.model_knomial(n, k, M, ts, Bw), rel=1e-13)
+            assert model.t_knomial_pipeline(n, k, M, C, ts, Bw) == pytest.approx(oracle.model_knomial_pipeline(n, k, M, C, ts, Bw), rel=1e-13)
         assert model.t_scatter_allgather(n, M, ts, Bw) == pytest.approx(oracle.model_scatter_allgather(n, M, ts, Bw), rel=1e-13)
         assert model.t_chain_pipeline(n, M, C, ts, Bw) == pytest.approx(oracle.model_chain_pipeline(n, M, C, ts, Bw), rel=1e-13)
 
