@@ -231,6 +231,9 @@ def main() -> int:
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
             "traffic": traffic,
+            # the same counters as a rate: fabric bytes per launch / launch duration, and against the HBM peak
+            "traffic_GBps": round(traffic / (avg_launch_ms * 1e-3) / 1e9, 2) if traffic else None,
+            "traffic_frac": round(traffic / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
             "kernel": ("bcast::chain_kernel<%d, %d, %s>" % (info["vec_bytes"], info["trip_bytes"] // 1024, "true" if M <= (2 << 20) else "false"))
             if info["algo"] == B.BCAST_ALGO_CHAIN else B.ALGO_NAMES[info["algo"]],
             "algorithmic_bytes_per_launch": algorithmic,
