@@ -404,10 +404,27 @@ def test_chunks_overlap_across_stages_on_the_device(noise, stages):
     assert end[stages - 1][0] < end[0][nchunks - 1]
 
 
-def test_random_configurations(noise):
+@pytest.mark.parametrize("P,stages,lanes,M,C,trip", [
+    (64, 63, 4, 8 * MiB + 48, 16 * KiB, 4096),      # 513 chunks through 63 flag hand-offs
+    (64, 8, 32, 24 * MiB, 96 * KiB, 3072),          # 256 chunks, one 3 KiB trip per lane
+    (64, 5, 0, 32 * MiB + 3, 1 * MiB, 4096),        # unequal stages (13, 13, 13, 12, 12 hops), fixed
+    (7, 4, 0, 48 * MiB, 64 * KiB, 4096),            # 768 chunks, rotating spans (2, 2, 1, 1)
+    (33, 32, 64, 16 * MiB, 256 * KiB, 4096),        # every position its own stage, full grid
+    (16, 2, 0, 100 * MiB + 5, 3 * MiB, 3072),       # the tuned shape for large messages
+])
+def test_chain_many_chunks(noise, P, stages, lanes, M, C, trip):
+    """Long pipelines: hundreds of chunks through many flag hand-offs with the
+    device full of waiting and copying waves; every rank checked in full."""
+    big = inputs.random_bytes(12, M)
+    info = run_and_check(P, P - 2, M, C, B.BCAST_ALGO_CHAIN, big, stages=stages, lanes=lanes, trip=trip)
+    assert info["nchunks"] == -(-M // C)
+
+
+@pytest.mark.parametrize("seed", [20240607, 7, 8])
+def test_random_configurations(noise, seed):
     """Seeded sweep over the whole parameter space at small sizes: ranks, root,
     message and chunk size, stage and lane counts, pointer offsets, algorithm."""
-    rng = np.random.default_rng(20240607)
+    rng = np.random.default_rng(seed)
     algos = ALGOS
     for case in range(150):
         P = int(rng.integers(1, 65)) if case % 3 else int(rng.integers(1, 9))
