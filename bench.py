@@ -45,11 +45,11 @@ WORKLOADS = {
 # The chain's traffic is BELOW its algorithmic bytes: part of what a wave reads
 # back inside a stage is served by the CU's vector L1 and never reaches the fabric.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg2", "chain"): int((138266.8 * (65536.0 / 32786.4) + 459264.0) * 1024),
-    ("cfg2", "direct"): int((32784.5 * (65536.0 / 32786.9) + 65536.0) * 1024),
-    ("cfg3", "chain"): int((993754.3 * (540459.2 / 270255.1) + 8112519.3) * 1024),
-    ("cfg4", "chain"): int((1542330.8 * (524288.0 / 262167.2) + 16258400.0) * 1024),
-    ("cfg5", "chain"): int((5636280.7 * (1048576.0 / 524313.2) + 66071232.0) * 1024),
+    ("cfg2", "chain"): int((138361.4 * (65536.0 / 32787.3) + 459264.0) * 1024),
+    ("cfg2", "direct"): int((32785.0 * (65536.0 / 32786.9) + 65536.0) * 1024),
+    ("cfg3", "chain"): int((1022961.4 * (540459.2 / 270254.7) + 8112519.3) * 1024),
+    ("cfg4", "chain"): int((1598370.7 * (524288.0 / 262166.7) + 16258400.0) * 1024),
+    ("cfg5", "chain"): int((5878015.7 * (1048576.0 / 524315.7) + 66071232.0) * 1024),
 }
 
 
