@@ -82,3 +82,21 @@ def test_fit_of_the_committed_mi355x_sweep():
             # one die: binomial's rounds do not run on separate links, so its
             # fitted per-round bandwidth falls as rounds get more crowded
             assert fits["binomial"]["B"] < fits["direct"]["B"]
+
+
+def test_latency_report_of_the_committed_sweep():
+    """The per-size latency table is derived from the shipped log and agrees
+    with the committed text copy of it."""
+    import os
+
+    from paper_1707_09414_amd.tuned import report
+
+    here = os.path.dirname(report.__file__)
+    text = report.report(os.path.join(here, "sweep_mi355x.txt"))
+    assert text.strip() == open(os.path.join(here, "latency_mi355x.txt")).read().strip()
+    best = report.read(os.path.join(here, "sweep_mi355x.txt"))
+    assert len(best) == 6 * 29
+    # the landscape the tuning table encodes: a tree for small messages, the chain for large ones
+    assert min(best[(64, 4096)], key=lambda a: best[(64, 4096)][a][0]) == 7
+    assert min(best[(64, 1 << 30)], key=lambda a: best[(64, 1 << 30)][a][0]) == 1
+    assert best[(64, 4096)][1][0] < best[(64, 4096)][2][0]  # the chain beats direct at P = 64
