@@ -101,6 +101,8 @@ def _bind(path):
     lib.oracle_knomial_bcast.restype = ctypes.c_long
     lib.oracle_knomial_pipeline_bcast.argtypes = [pp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, tp]
     lib.oracle_knomial_pipeline_bcast.restype = ctypes.c_long
+    lib.oracle_chain_reduce_f32.argtypes = [pp, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, ctypes.c_size_t, tp]
+    lib.oracle_chain_reduce_f32.restype = ctypes.c_long
     lp = ctypes.POINTER(ctypes.c_long)
     lib.oracle_scatter_allgather_bcast.argtypes = [pp, ctypes.c_int, ctypes.c_int, ctypes.c_size_t, lp, lp, tp]
     lib.oracle_scatter_allgather_bcast.restype = ctypes.c_long
@@ -219,6 +221,23 @@ def knomial_pipeline_bcast(bufs: Optional[np.ndarray], P: int, root: int, M: int
     n = _check(_load().oracle_knomial_pipeline_bcast(_row_pointers(bufs, P, M), P, root, M, C, k, ctypes.byref(tb.c)),
                "knomial_pipeline_bcast")
     return tb.result(n)
+
+
+def chain_reduce_f32(send: Optional[np.ndarray], P: int, root: int, count: int, chunk_elems: int, trace: bool = False):
+    """Pipelined chain reduction (fp32 sum) in chain order; ``send`` is a
+    C-contiguous float32 array [P, count] (row r = rank r's contribution) or
+    None for the schedule only.  Returns (recv, Result)."""
+    nchunks = -(-count // chunk_elems) if chunk_elems > 0 else 0
+    tb = _TraceBuf(P, trace, nchunks * max(0, P - 1), 1)
+    recv = None
+    if send is not None:
+        assert send.dtype == np.float32 and send.flags["C_CONTIGUOUS"] and send.shape == (P, count)
+        rows = (ctypes.c_void_p * P)(*[send.ctypes.data + r * send.strides[0] for r in range(P)])
+        recv = np.empty(count, dtype=np.float32)
+        n = _load().oracle_chain_reduce_f32(rows, recv.ctypes.data, P, root, count, chunk_elems, ctypes.byref(tb.c))
+    else:
+        n = _load().oracle_chain_reduce_f32(None, None, P, root, count, chunk_elems, ctypes.byref(tb.c))
+    return recv, tb.result(_check(n, "chain_reduce_f32"))
 
 
 def scatter_allgather_bcast(bufs: Optional[np.ndarray], P: int, root: int, M: int, trace: bool = False) -> Result:

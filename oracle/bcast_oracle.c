@@ -219,6 +219,59 @@ long oracle_scatter_allgather_bcast(unsigned char **bufs, int P, int root, size_
     return rounds + steps;
 }
 
+long oracle_chain_reduce_f32(const float *const *send, float *recv, int P, int root, size_t count,
+                             size_t chunk_elems, oracle_trace_t *tr)
+{
+    if (bad_common(P, root) || chunk_elems == 0) return -1;
+    if (count && (!send || !recv) && (send || recv)) return -1; /* both or neither */
+    trace_reset(tr);
+    if (count == 0) return 0;
+    const int payload = send != NULL;
+    if (P == 1) {
+        if (payload) memmove(recv, send[root], count * sizeof(float));
+        return 0;
+    }
+    long nchunks = (long)(count / chunk_elems) + (count % chunk_elems ? 1 : 0);
+
+    /* partial[k] = running sum held by chain position k: position P-1 starts
+     * with its own contribution, every other position adds its own to what its
+     * RIGHT neighbour (k + 1) hands over, and position 0 is the root */
+    float *partial = payload ? malloc((size_t)P * count * sizeof(float)) : NULL;
+    long *got = calloc((size_t)P, sizeof *got);   /* chunks of its partial that position k holds */
+    long *before = calloc((size_t)P, sizeof *before);
+    if ((payload && !partial) || !got || !before) { free(partial); free(got); free(before); return -1; }
+    if (payload) memcpy(partial + (size_t)(P - 1) * count, send[rank_at(root, P - 1, P)], count * sizeof(float));
+    got[P - 1] = nchunks;
+
+    long steps = 0;
+    while (got[0] < nchunks) {
+        memcpy(before, got, (size_t)P * sizeof *got); /* all links decide from the start of the step */
+        for (int k = P - 2; k >= 0; k--) {
+            long c = before[k];
+            if (c < nchunks && before[k + 1] > c) {
+                size_t e0 = (size_t)c * chunk_elems;
+                size_t e1 = e0 + chunk_elems < count ? e0 + chunk_elems : count;
+                if (payload) {
+                    const float *mine = send[rank_at(root, k, P)];
+                    const float *in = partial + (size_t)(k + 1) * count;
+                    float *out = partial + (size_t)k * count;
+                    for (size_t i = e0; i < e1; i++) out[i] = mine[i] + in[i]; /* one fp32 addition */
+                }
+                /* account for the hand-over as a transfer of the partial's bytes */
+                transfer(NULL, tr, steps, rank_at(root, k + 1, P), rank_at(root, k, P), c,
+                         e0 * sizeof(float), e1 * sizeof(float));
+                got[k] = c + 1;
+            }
+        }
+        steps++;
+    }
+    if (payload) memcpy(recv, partial, count * sizeof(float));
+    free(partial);
+    free(got);
+    free(before);
+    return steps;
+}
+
 /* smallest r with k^r >= n */
 static int ceil_log(int n, int k)
 {

@@ -109,6 +109,24 @@ long oracle_scatter_allgather_bcast(unsigned char **bufs, int P, int root, size_
                                     long *scatter_rounds, long *ring_steps,
                                     oracle_trace_t *tr);
 
+/* Pipelined chain REDUCTION (sum, fp32): the collective the paper names as the
+ * next one to receive the pipelined chain (Sec. VII); the paper gives no
+ * schedule, so this is the broadcast chain of Sec. IV-B run backwards.  Chain
+ * position k is rank (root + k) mod P as before.  Position P-1 starts the
+ * running sum with its own contribution; every position k < P-1 receives the
+ * running sum of a chunk from its right neighbour k+1, adds its own
+ * contribution with ONE fp32 addition per element (own + incoming) and hands the
+ * result to k-1; position 0, the root, stores it in recv.  Hence
+ *   recv[i] = x_0[i] + (x_1[i] + ( ... + (x_{P-2}[i] + x_{P-1}[i]))),
+ * every addition rounded to fp32 (round to nearest even), x_k = send[(root+k)%P].
+ * One step moves at most one chunk (chunk_elems elements, the last one short)
+ * per link, all links deciding from the state at the start of the step, so the
+ * step count is chunks + P - 2 as in Eq. 5.  send == recv == NULL walks the
+ * schedule only.  recv may be send[root].  Returns the steps, 0 when P == 1
+ * (recv = send[root]) or count == 0, -1 on bad arguments. */
+long oracle_chain_reduce_f32(const float *const *send, float *recv, int P, int root, size_t count,
+                             size_t chunk_elems, oracle_trace_t *tr);
+
 /* Cost models of Sec. III-A and IV-B, evaluated literally as printed
  * (Eq. 1: direct, Eq. 2: chain, Eq. 3: k-nomial, Eq. 4: scatter-allgather,
  * Eq. 5: pipelined chain).  n ranks, M message bytes, C chunk bytes,

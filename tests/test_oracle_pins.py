@@ -242,6 +242,76 @@ def pin_variants_end_state_and_counts(maxP=9):
                 assert np.array_equal(b, exp)
 
 
+def pin_reduce_golden():
+    with open(os.path.join(GOLDEN, "reduce_order.txt")) as f:
+        rows = [l.split() for l in f if l.strip() and not l.startswith("#")]
+    assert len(rows) == 9
+    for row in rows:
+        P, root = int(row[0]), int(row[1])
+        vals = np.array([[float(v)] for v in row[2:2 + P]], dtype=np.float32)
+        want = np.float32(float(row[2 + P]))
+        got, _ = oracle.chain_reduce_f32(vals, P, root, 1, 1)
+        assert got[0] == want, (row, got)
+        # the same values in every element of a longer, chunked message
+        wide = np.repeat(vals, 11, axis=1).copy()
+        got, _ = oracle.chain_reduce_f32(wide, P, root, 11, 4)
+        assert (got == want).all(), (row, got)
+
+
+def pin_reduce_exact_integers_and_schedule(maxP=7, maxN=13):
+    """Small integers sum exactly in fp32 whatever the order, so the result is
+    fixed by integer arithmetic; the schedule is the chain's, run backwards."""
+    rng = np.random.default_rng(5)
+    for P in range(1, maxP + 1):
+        for root in range(P):
+            for count in range(0, maxN + 1):
+                ints = rng.integers(-1000, 1001, size=(P, count))
+                send = ints.astype(np.float32)
+                for C in sorted({1, 2, 5, max(1, count), count + 2}):
+                    keep = send.copy()
+                    got, res = oracle.chain_reduce_f32(send, P, root, count, C, trace=True)
+                    assert np.array_equal(send, keep), "contributions are inputs only"
+                    assert np.array_equal(got.astype(np.int64), ints.sum(axis=0)), (P, root, count, C)
+                    nchunks = -(-count // C)
+                    if P < 2 or count == 0:
+                        assert res.steps == 0 and not res.transfers
+                        continue
+                    assert res.steps == nchunks + P - 2
+                    assert res.bytes_copied == (P - 1) * count * 4
+                    seen = {}
+                    for t in res.transfers:
+                        k = (t.dst_rank - root) % P
+                        assert (t.src_rank - root) % P == k + 1, "a partial comes from the right neighbour"
+                        assert (k, t.chunk) not in seen
+                        assert (t.lo, t.hi) == (4 * t.chunk * C, 4 * min(count, (t.chunk + 1) * C))
+                        seen[(k, t.chunk)] = t.step
+                    for k in range(P - 1):
+                        for c in range(nchunks):
+                            assert seen[(k, c)] == (P - 2 - k) + c, (P, k, c, seen[(k, c)])
+    with pytest.raises(ValueError):
+        oracle.chain_reduce_f32(np.zeros((2, 4), np.float32), 2, 2, 4, 2)
+    with pytest.raises(ValueError):
+        oracle.chain_reduce_f32(np.zeros((2, 4), np.float32), 2, 0, 4, 0)
+    assert oracle.chain_reduce_f32(None, 64, 17, 1 << 28, 1 << 20)[1].steps == 256 + 62
+
+
+def pin_reduce_rounding_bound():
+    """Against the exact sum (float64 is exact enough here): the error of P - 1
+    fp32 additions is at most (P - 1) u sum|x| with u = 2^-24, and it is not zero
+    -- a sum carried in higher precision and rounded once would be closer."""
+    rng = np.random.default_rng(6)
+    for P in (2, 3, 8, 16, 64):
+        send = rng.normal(0.0, 0.01, size=(P, 5000)).astype(np.float32)
+        got, _ = oracle.chain_reduce_f32(send, P, P // 2, 5000, 777)
+        exact = send.astype(np.float64).sum(axis=0)
+        bound = (P - 1) * 2.0 ** -24 * np.abs(send.astype(np.float64)).sum(axis=0)
+        err = np.abs(got.astype(np.float64) - exact)
+        assert (err <= bound).all()
+        if P >= 8:
+            once = exact.astype(np.float32)
+            assert (got != once).mean() > 0.05, "P - 1 roundings must show"
+
+
 def pin_cost_models():
     with open(os.path.join(GOLDEN, "cost_models.txt")) as f:
         rows = [l.split() for l in f if l.strip() and not l.startswith("#")]
@@ -280,6 +350,9 @@ BATTERY = [
     pin_golden_counts,
     pin_variants_end_state_and_counts,
     pin_cost_models,
+    pin_reduce_golden,
+    pin_reduce_exact_integers_and_schedule,
+    pin_reduce_rounding_bound,
 ]
 
 
@@ -343,6 +416,12 @@ MUTANTS = [
     ("pipe_chunk_overrun", "size_t to = from + C < M ? from + C : M;", "size_t to = from + C;"),
     ("pipe_step_per_level", "            steps++;\n        }\n    }\n    return steps;", "        }\n        steps++;\n    }\n    return steps;"),
     ("model_pipe_levels", "return (M / C * ceil_log(n, k)) * (ts + C / B);", "return (M / C + ceil_log(n, k)) * (ts + C / B);"),
+    ("reduce_drops_own_term", "out[i] = mine[i] + in[i];", "out[i] = in[i];"),
+    ("reduce_from_the_roots_end", "const float *mine = send[rank_at(root, k, P)];", "const float *mine = send[rank_at(root, P - 2 - k, P)];"),
+    ("reduce_seed_from_root", "send[rank_at(root, P - 1, P)], count * sizeof(float));", "send[rank_at(root, 0, P)], count * sizeof(float));"),
+    ("reduce_chunk_gap", "size_t e0 = (size_t)c * chunk_elems;\n                size_t e1 = e0 + chunk_elems < count ? e0 + chunk_elems : count;\n                if (payload) {",
+     "size_t e0 = (size_t)c * chunk_elems;\n                size_t e1 = e0 + chunk_elems < count ? e0 + chunk_elems - (c == 1) : count;\n                if (payload) {"),
+    ("reduce_two_hops_a_step", "if (c < nchunks && before[k + 1] > c) {", "if (c < nchunks && got[k + 1] > c) {"),
     ("direct_skips_last", "for (int k = 1; k < P; k++) {\n        transfer(bufs, tr, sends, root,",
      "for (int k = 1; k < P - 1; k++) {\n        transfer(bufs, tr, sends, root,"),
     ("ring_wrong_piece", "long pc = ((q - t) % P + P) % P;", "long pc = ((q + t) % P + P) % P;"),
@@ -360,6 +439,8 @@ def _battery_passes():
         pin_golden_counts()
         pin_variants_end_state_and_counts(maxP=6)
         pin_cost_models()
+        pin_reduce_golden()
+        pin_reduce_exact_integers_and_schedule(maxP=5, maxN=7)
     except (AssertionError, ValueError, KeyError, IndexError):
         return False
     return True
