@@ -220,6 +220,37 @@ typedef struct {
 int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
                          const bcast_chain_request_t *request, bcast_plan_info_t *info);
 
+/*
+ * bcast_reduce_sum_f32 -- enqueue one rooted reduction (MPI_Reduce with MPI_SUM
+ * on MPI_FLOAT) as a pipelined chain: the collective the paper names as the
+ * next one to receive its chain design (Sec. VII), built here as the chain of
+ * Sec. IV-B run backwards.  With x_k the contribution of chain position
+ * k = (rank - root) mod P,
+ *     recv[i] = x_0[i] + (x_1[i] + ( ... + (x_{P-2}[i] + x_{P-1}[i]))),
+ * every addition rounded to fp32 (round to nearest even, denormals kept): the
+ * result is defined bit for bit.
+ *   plan       from bcast_plan_create (its algo is not used; chunk_bytes is the
+ *              chunk size, 0 = built-in rule; bcast_plan_set_stages / _lanes apply).
+ *   send_bufs  HOST array of plan.nranks DEVICE pointers to `count` floats each,
+ *              16-byte aligned, pairwise non-overlapping; only read.
+ *   recv_buf   DEVICE pointer to `count` floats, 16-byte aligned: either
+ *              send_bufs[root] itself (in place) or memory that overlaps no
+ *              contribution.  Only these count floats are written.
+ *   count      elements, count * 4 <= plan bytes.
+ * The first call (and any call that needs more stages than an earlier one)
+ * allocates scratch memory of (stages - 1) x plan bytes for the running sums
+ * that cross a stage boundary, after waiting for the device.  Flags, epoch,
+ * wait limit and status word are the plan's, as for bcast_run.
+ * Errors: ERR_ARG (NULL, misaligned or overlapping pointers, root or count out
+ * of range), ERR_NOMEM, ERR_HIP; ERR_TIMEOUT through the status word.
+ */
+int bcast_reduce_sum_f32(bcast_plan_t *plan, const void *const *send_bufs, void *recv_buf, int root, size_t count,
+                         bcast_stream_t stream);
+/* The launch shape bcast_reduce_sum_f32 would use for `count` elements (fields as
+ * for the chain; algorithmic_bytes = (nranks + 1) * count * 4: every input read
+ * once, the result written once). */
+int bcast_reduce_info(bcast_plan_t *plan, size_t count, bcast_plan_info_t *info);
+
 /* Pure host arithmetic: the chain positions that `stage` (0-based, of `stages`)
  * plays for chunk number `chunk`: hops *first_hop .. *last_hop, hop h being the
  * copy from position h-1 to position h.  With nranks-1 = q stages + r, every

@@ -23,6 +23,9 @@ struct bcast_plan {
     int max_waves[3] = {0, 0, 0};
     int max_waves_cached[3] = {0, 0, 0};  // the same for its small-message (write-back) variant
     int max_flags = 0;                    // flags allocated: the largest of the above
+    int max_waves_reduce = 0;             // the same limit for the reduction kernel (256-thread workgroups)
+    char *d_scratch = nullptr;            // reduction: running sums handed from stage to stage
+    size_t scratch_bytes = 0;
     u64 *d_flags = nullptr;  // max_waves flags, kFlagStrideWords apart, plus the abort word
     u64 *d_abort = nullptr;
     u64 *d_counters = nullptr; // two words after the abort word
@@ -218,6 +221,12 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
         }
     }
     if (e == hipSuccess) {
+        int per_cu = 0;
+        e = reduce_max_blocks_per_cu(&per_cu);
+        per_cu = std::max(1, std::min(per_cu, 8));
+        p->max_waves_reduce = std::min(p->max_flags, std::max(nranks, p->cu_count * per_cu * kWavesPerBlock));
+    }
+    if (e == hipSuccess) {
         size_t flag_bytes = ((size_t)p->max_flags + 2) * kFlagStrideWords * sizeof(u64);
         e = hipMalloc((void **)&p->d_flags, flag_bytes);
         if (e == hipSuccess) e = hipMemset(p->d_flags, 0, flag_bytes);
@@ -251,6 +260,7 @@ extern "C" int bcast_plan_destroy(bcast_plan_t *p)
     if (e != hipSuccess) rc = hip_fail(e);
     if (p->d_flags && (e = hipFree(p->d_flags)) != hipSuccess) rc = hip_fail(e);
     if (p->d_trace && (e = hipFree(p->d_trace)) != hipSuccess) rc = hip_fail(e);
+    if (p->d_scratch && (e = hipFree(p->d_scratch)) != hipSuccess) rc = hip_fail(e);
     if (p->h_status && (e = hipHostFree(p->h_status)) != hipSuccess) rc = hip_fail(e);
     delete p;
     return rc;
@@ -795,6 +805,88 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         return BCAST_OK;
     }
     return BCAST_ERR_ARG;
+}
+
+// Launch shape of a reduction of `bytes` bytes: the chain's geometry (stages of
+// consecutive hops, lanes, chunks) with 4 KiB trips and fixed spans.
+static int reduce_shape(const bcast_plan *p, size_t bytes, bcast_plan_info_t *info)
+{
+    const int stages = p->stages_request > 0 ? p->stages_request : default_stages(p->nranks);
+    size_t chunk = p->chunk_bytes;
+    if (chunk == 0) chunk = (size_t)default_chunk(p->nranks, p->max_waves_reduce, stages, trip_bytes_of(kTripUnrollDefault));
+    const bcast_chain_request_t req = {p->lanes_request, stages, (int)trip_bytes_of(kTripUnrollDefault), 0};
+    int rc = bcast_chain_geometry(p->nranks, bytes, chunk, p->max_waves_reduce, &req, info);
+    if (rc != BCAST_OK) return rc;
+    // every input byte is read once and every result byte written once
+    info->algorithmic_bytes = ((u64)p->nranks + 1) * bytes;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_reduce_info(bcast_plan_t *p, size_t count, bcast_plan_info_t *info)
+{
+    if (!p || !info || count > p->bytes / sizeof(float)) return BCAST_ERR_ARG;
+    return reduce_shape(p, count * sizeof(float), info);
+}
+
+extern "C" int bcast_reduce_sum_f32(bcast_plan_t *p, const void *const *send_bufs, void *recv_buf, int root, size_t count,
+                                    bcast_stream_t stream)
+{
+    if (!p || !send_bufs || !recv_buf) return BCAST_ERR_ARG;
+    const int P = p->nranks;
+    if (root < 0 || root >= P || count > p->bytes / sizeof(float)) return BCAST_ERR_ARG;
+    const size_t bytes = count * sizeof(float);
+    // whole 16-byte vectors are moved: every buffer must start on a 16-byte boundary
+    if ((uintptr_t)recv_buf & 15u) return BCAST_ERR_ARG;
+    for (int i = 0; i < P; ++i)
+        if (!send_bufs[i] || ((uintptr_t)send_bufs[i] & 15u)) return BCAST_ERR_ARG;
+    // contributions must not overlap each other; the result may be the root's own
+    // contribution (in place) but must not touch any other buffer
+    {
+        uintptr_t at[BCAST_MAX_RANKS + 1];
+        int n = 0;
+        for (int i = 0; i < P; ++i) at[n++] = (uintptr_t)send_bufs[i];
+        if (recv_buf != send_bufs[root]) at[n++] = (uintptr_t)recv_buf;
+        std::sort(at, at + n);
+        for (int i = 0; i + 1 < n; ++i)
+            if (at[i + 1] == at[i] || at[i + 1] - at[i] < bytes) return BCAST_ERR_ARG;
+    }
+    if (bytes == 0) return BCAST_OK;
+    if (P == 1) {
+        if (recv_buf != send_bufs[0]) HIP_TRY(hipMemcpyAsync(recv_buf, send_bufs[0], bytes, hipMemcpyDeviceToDevice, stream));
+        return BCAST_OK;
+    }
+    bcast_plan_info_t info;
+    int rc = reduce_shape(p, bytes, &info);
+    if (rc != BCAST_OK) return rc;
+
+    // one region of the plan's size per stage boundary; (re)allocated when the
+    // stage count grows, which waits for the device
+    const size_t region = round_up(p->bytes, 256);
+    const size_t need = (size_t)(info.stages - 1) * region;
+    if (need > p->scratch_bytes) {
+        HIP_TRY(hipDeviceSynchronize());
+        if (p->d_scratch) {
+            HIP_TRY(hipFree(p->d_scratch));
+            p->d_scratch = nullptr;
+            p->scratch_bytes = 0;
+        }
+        HIP_TRY(hipMalloc((void **)&p->d_scratch, need));
+        p->scratch_bytes = need;
+    }
+
+    char *by_pos[BCAST_MAX_RANKS];
+    for (int k = 0; k < P; ++k) by_pos[k] = (char *)const_cast<void *>(send_bufs[(root + k) % P]);
+    ChainArgs a;
+    rc = begin_flag_run(p, &a, by_pos, bytes, info);
+    if (rc != BCAST_OK) return rc;
+    a.stages = (unsigned)info.stages;
+    a.hops_per_stage = (unsigned)info.hops_per_stage;
+    a.recv = (char *)recv_buf;
+    a.scratch = p->d_scratch;
+    a.scratch_stride = region;
+    if ((u64)a.stages * a.lanes > (u64)p->max_waves_reduce) return BCAST_ERR_ARG;
+    HIP_TRY(launch_reduce(a, info.grid_blocks, stream));
+    return BCAST_OK;
 }
 
 extern "C" const char *bcast_strerror(int status)

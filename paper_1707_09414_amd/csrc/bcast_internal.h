@@ -63,6 +63,12 @@ struct ChainArgs {
     // receives from, and the positions that have children (bit = position)
     unsigned char parent[BCAST_MAX_RANKS];
     u64 forward_mask;
+    // chain reduction only (reduce_kernel): buf[] holds the contributions by
+    // chain position (read only); recv is the root's result buffer; stage g < last
+    // hands its running sum to stage g + 1 through scratch + g * scratch_stride
+    char *recv;
+    char *scratch;
+    u64 scratch_stride;
 };
 
 // Number of chain hops that lie before stage g for chunk c, so that stage g plays
@@ -131,6 +137,8 @@ struct RangedCopyArgs {
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream);
 bool valid_chain_block(int block_threads);  // 64, 128 or 256
 hipError_t launch_tree(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
+hipError_t launch_reduce(const ChainArgs &a, int grid_blocks, hipStream_t stream);
+hipError_t reduce_max_blocks_per_cu(int *blocks);
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);

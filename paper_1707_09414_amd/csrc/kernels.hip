@@ -425,6 +425,138 @@ __global__ void __launch_bounds__(kBlockThreads) tree_kernel(const ChainArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// Pipelined chain reduction (fp32 sum): the collective the paper names as next
+// in line for the pipelined chain (Sec. VII), built as the broadcast chain of
+// Sec. IV-B run backwards.  Chain position P-1 starts the running sum of a chunk
+// with its own contribution, every position below adds its own with one fp32
+// addition per element and hands the sum on, position 0 (the root) stores it:
+//     recv = x_0 + (x_1 + ( ... + (x_{P-2} + x_{P-1})))
+// with every addition rounded to fp32, the order the CPU reference fixes, so the
+// two agree bit for bit.
+//
+// Stages, lanes, chunks, flags and the wait limit are the chain kernel's: "hop"
+// j = 1..P-1 is position P-1-j adding its contribution; stage g plays the
+// consecutive hops stage_begin(g)+1 .. stage_begin(g+1).  Inside a stage the
+// running sum of a trip stays in registers (it is a new value at every hop and
+// nobody but the next position needs it); between stages it goes through a
+// scratch buffer in memory -- written through at agent scope, flag raised, read
+// at agent scope by the same lane of the next stage.  The contributions are
+// read exactly once, kRedBatch positions at a time so that their loads are in
+// flight together; the additions then run in chain order.
+constexpr int kRedBatch = 4;
+constexpr int kRedUnroll = 4;  // 16-byte vectors per lane and trip: 4 KiB per wave and position
+
+__device__ __forceinline__ void add_f32x4(VecOf<16>::type &acc, const VecOf<16>::type &x)
+{
+    // own + incoming, element by element; no contraction is possible (no multiply)
+    acc.x = __float_as_uint(__uint_as_float(x.x) + __uint_as_float(acc.x));
+    acc.y = __float_as_uint(__uint_as_float(x.y) + __uint_as_float(acc.y));
+    acc.z = __float_as_uint(__uint_as_float(x.z) + __uint_as_float(acc.z));
+    acc.w = __float_as_uint(__uint_as_float(x.w) + __uint_as_float(acc.w));
+}
+
+// One span [lo, hi) (at most one trip; a multiple of sizeof(T) bytes) through the
+// hops first_hop .. last_hop: T is a 16-byte vector of four floats or one float.
+template <int V, int U, int LD_IN, int ST_OUT>
+__device__ __forceinline__ void reduce_span(const ChainArgs &a, const char *in, char *out, unsigned first_hop, unsigned last_hop,
+                                            u64 lo, unsigned n, unsigned lane)
+{
+    typedef AgentIO<V, LD_IN, ST_OUT> EDGE;            // the running sum coming in and going out
+    typedef AgentIO<V, kAuxCached, kAuxCached> OWN;    // contributions: read once, never written
+    typedef typename EDGE::T T;
+    const unsigned top = a.nranks - 1;
+    const unsigned off = lane * V;
+    T acc[U];
+    const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(in + lo), 0, n, kRsrcWord3);
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc[u] = EDGE::ld(rin, off + u * kWaveSize * V);
+    for (unsigned hop = first_hop; hop <= last_hop; hop += kRedBatch) {
+        T x[kRedBatch][U];
+#pragma unroll
+        for (int b = 0; b < kRedBatch; ++b) {
+            if (hop + b <= last_hop) {  // wave-uniform
+                const __amdgpu_buffer_rsrc_t rx =
+                    __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(a.buf[top - (hop + b)] + lo), 0, n, kRsrcWord3);
+#pragma unroll
+                for (int u = 0; u < U; ++u) x[b][u] = OWN::ld(rx, off + u * kWaveSize * V);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < kRedBatch; ++b) {
+            if (hop + b <= last_hop) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if constexpr (V == 16) add_f32x4(acc[u], x[b][u]);
+                    else acc[u] = __float_as_uint(__uint_as_float(x[b][u]) + __uint_as_float(acc[u]));
+                }
+            }
+        }
+    }
+    const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(out + lo, 0, n, kRsrcWord3);
+#pragma unroll
+    for (int u = 0; u < U; ++u) EDGE::st(acc[u], rout, off + u * kWaveSize * V);
+}
+
+__global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a)
+{
+    constexpr int U = kRedUnroll;
+    const unsigned lane = threadIdx.x & (kWaveSize - 1);
+    const unsigned gw = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
+    if (gw >= a.stages * a.lanes) return;
+    const unsigned g = gw / a.lanes;
+    const unsigned s = gw - g * a.lanes;
+    const unsigned hops = a.nranks - 1;
+    const unsigned hops_min = hops / a.stages, hops_extra = hops - hops_min * a.stages;
+    const unsigned first_hop = stage_begin(g, 0, a.stages, hops_min, hops_extra) + 1;
+    const unsigned last_hop = stage_begin(g + 1, 0, a.stages, hops_min, hops_extra);
+    const bool last_stage = g + 1 == a.stages;
+
+    const u64 *in_flag = g > 0 ? a.flags + ((u64)(g - 1) * a.lanes + s) * kFlagStrideWords : nullptr;
+    const bool muted = a.mute_hop >= first_hop && a.mute_hop <= last_hop;
+    u64 *out_flag = (!last_stage && !muted) ? a.flags + ((u64)g * a.lanes + s) * kFlagStrideWords : nullptr;
+    // stage 0 starts from position P-1's contribution, later stages from the previous stage's sum
+    const char *in = g > 0 ? a.scratch + (u64)(g - 1) * a.scratch_stride : a.buf[hops];
+    char *out = last_stage ? a.recv : a.scratch + (u64)g * a.scratch_stride;
+
+    const u64 trip = (u64)U * kWaveSize * 16;
+    const u64 stride = trip * a.lanes;
+    u64 seen = 0;
+    u64 chunk_lo = 0;
+    for (unsigned c = 0; c < a.nchunks; ++c, chunk_lo += a.chunk_bytes) {
+        u64 chunk_hi = chunk_lo + a.chunk_bytes;
+        if (chunk_hi > a.bytes) chunk_hi = a.bytes;
+        if (in_flag) {
+            const u64 want = a.base + ((u64)(c + 1) << 4);
+            if (seen < want && !wait_ready(in_flag, want, a, first_hop, c, lane, &seen)) return;
+        }
+        for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
+            const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
+            const unsigned n = (unsigned)(hi - lo);
+            const unsigned body = n & ~15u;  // whole vectors of four floats; the rest (at the message's end) float by float
+            if (g > 0 && !last_stage) {
+                if (body) reduce_span<16, U, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+            } else if (g > 0) {
+                if (body) reduce_span<16, U, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+            } else if (!last_stage) {
+                if (body) reduce_span<16, U, kAuxCached, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, kAuxCached, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+            } else {
+                if (body) reduce_span<16, U, kAuxCached, kAuxCached>(a, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, kAuxCached, kAuxCached>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+            }
+        }
+        if (in_flag && c + 1 < a.nchunks) seen = read_flag(in_flag, lane);
+        if (out_flag) {
+            // the running sums of this chunk are written through and complete before the flag is raised
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0) __hip_atomic_store(out_flag, a.base + ((u64)(c + 1) << 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Whole-message copies src -> dst for up to 32 pairs at once (blockIdx.y picks
 // the pair): one round of the binomial tree (Sec. III-A, Eq. 3) or one send of
 // the direct algorithm (Eq. 1).  Waves stride over 4 KiB tiles.
@@ -525,6 +657,20 @@ hipError_t launch_tree(const ChainArgs &a, int vec_bytes, int grid_blocks, hipSt
         if (a.parent[q] >= q) return hipErrorInvalidValue;  // a parent lies below its child
     BCAST_LAUNCH_V(tree_kernel, vec_bytes, dim3(grid_blocks), stream, a);
     return hipGetLastError();
+}
+
+hipError_t launch_reduce(const ChainArgs &a, int grid_blocks, hipStream_t stream)
+{
+    if (grid_blocks < 1 || a.nranks < 2 || a.nranks > BCAST_MAX_RANKS || a.stages < 1 || a.stages > a.nranks - 1) return hipErrorInvalidValue;
+    if ((u64)grid_blocks * kWavesPerBlock < (u64)a.stages * a.lanes) return hipErrorInvalidValue;
+    if (!a.recv || (a.stages > 1 && !a.scratch) || (a.bytes & 3u)) return hipErrorInvalidValue;
+    reduce_kernel<<<dim3(grid_blocks), dim3(kBlockThreads), 0, stream>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t reduce_max_blocks_per_cu(int *blocks)
+{
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, reduce_kernel, kBlockThreads, 0);
 }
 
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream)
