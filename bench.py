@@ -75,6 +75,8 @@ def main() -> int:
     ap.add_argument("--chunk", type=int, default=0, help="chain chunk bytes (0 = tuned table / built-in rule)")
     ap.add_argument("--lanes", type=int, default=0, help="wavefronts per chain hop (0 = automatic)")
     ap.add_argument("--stages", type=int, default=0, help="chain stages (0 = tuned table / built-in rule)")
+    ap.add_argument("--op", choices=["bcast", "reduce"], default="bcast",
+                    help="reduce: the chain reduction (fp32 sum to the root) at the workload's P and size instead of the broadcast")
     ap.add_argument("--rank-stride", type=int, default=0,
                     help="place the rank buffers in one allocation this many bytes apart (>= message bytes, multiple of 256; "
                          "0 = one allocation per rank)")
@@ -113,6 +115,8 @@ def main() -> int:
             "fanout": B.BCAST_ALGO_FANOUT, "auto": B.BCAST_ALGO_AUTO}[args.algo]
 
     table = tuned.load_default_table()  # installs the shipped MI355X table if present
+    if args.op == "reduce":
+        return bench_reduce(args, B, torch, P, root, M, seed, what)
 
     msg = make_message(args.workload, seed, M, custom=bool(args.ranks or args.bytes))
     assert msg.nbytes == M
@@ -242,6 +246,86 @@ def main() -> int:
         "cpu_baseline": cpu,
         "sweep": sweep,
         "per_tensor": per_tensor,
+    }
+    print(json.dumps(out))
+    plan.destroy()
+    return 0
+
+
+def bench_reduce(args, B, torch, P, root, M, seed, what):
+    """The pipelined chain reduction (fp32 sum to the root) at the workload's rank
+    count and message size: every rank contributes M bytes of N(0, 0.01) values
+    (one seeded draw, shifted and rescaled per rank).  Algorithmic bytes: every
+    input read once, the result written once, (P + 1) M."""
+    import numpy as np
+
+    import oracle
+
+    count = M // 4
+    rng = np.random.default_rng(seed)
+    base = rng.normal(0.0, 0.01, size=count).astype(np.float32)
+    d_base = torch.from_numpy(base).cuda()
+    send = [torch.roll(d_base, 4099 * r) * (1.0 + r / 64.0) for r in range(P)]
+    recv = torch.empty(count, dtype=torch.float32, device="cuda")
+    plan = B.bcast_plan_create(P, count * 4, args.chunk, B.BCAST_ALGO_CHAIN)
+    if args.lanes:
+        B.bcast_plan_set_lanes(plan, args.lanes)
+    if args.stages:
+        B.bcast_plan_set_stages(plan, args.stages)
+    info = B.bcast_reduce_info(plan, count)
+    stream = torch.cuda.current_stream()
+    ptrs = B.RankPointers(send)
+    for _ in range(max(1, args.warmup)):
+        B.bcast_reduce_sum_f32(plan, ptrs, recv, root, count, stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        B.bcast_reduce_sum_f32(plan, ptrs, recv, root, count, stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    avg_launch_ms = e0.elapsed_time(e1) / args.steps
+    st, detail = B.bcast_plan_status(plan)
+    if st != B.BCAST_OK:
+        print("bench.py: plan status %d (detail %#x)" % (st, detail), file=sys.stderr)
+        return 1
+
+    # bit-exact against the oracle on a prefix (a sum is element-wise, so a prefix stands alone)
+    sample = min(count, 4 << 20)
+    host = np.stack([s[:sample].cpu().numpy() for s in send])
+    verified = None
+    if not args.no_verify:
+        want, _ = oracle.chain_reduce_f32(host, P, root, sample, max(1, int(info["chunk_bytes"]) // 4))
+        verified = bool(np.array_equal(recv[:sample].cpu().numpy().view(np.uint32), want.view(np.uint32)))
+        if not verified:
+            print("bench.py: the reduction differs from the oracle", file=sys.stderr)
+            return 1
+    cpu = None
+    if not args.no_cpu_baseline:
+        reps, t = 0, 0.0
+        while t < 2.0 or reps < 3:
+            c0 = time.perf_counter()
+            oracle.chain_reduce_f32(host, P, root, sample, max(1, int(info["chunk_bytes"]) // 4))
+            t += time.perf_counter() - c0
+            reps += 1
+        cpu = {"value": round((P + 1) * sample * 4 / (t / reps) / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "oracle.chain_reduce_f32, P=%d, first %d elements, %d reps, %.1f ms each" % (P, sample, reps, 1e3 * t / reps)}
+    algorithmic = (P + 1) * count * 4
+    out = {
+        "metric": "chain reduction (fp32 sum to the root) effective HBM bandwidth (P+1)M/t (GB/s); latency in ms_per_step",
+        "value": round(algorithmic / (wall_ms * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5), "latency_us": round(wall_ms * 1e3, 2), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s as a reduction: P=%d contributions of %d fp32 values N(0, 0.01), root %d" % (args.workload, P, count, root),
+                   "P": P, "message_bytes": count * 4, "algo": "chain_reduce", "chunk_bytes": int(info["chunk_bytes"]),
+                   "nchunks": int(info["nchunks"]), "stages": info["stages"], "lanes": info["lanes"], "grid_blocks": info["grid_blocks"]},
+        "verified_bit_exact": verified,
+        "roofline": {"bound": "hbm", "achieved": round(algorithmic / (avg_launch_ms * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(algorithmic / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "bcast::reduce_kernel", "algorithmic_bytes_per_launch": algorithmic, "avg_launch_ms": round(avg_launch_ms, 5)},
+        "cpu_baseline": cpu,
     }
     print(json.dumps(out))
     plan.destroy()
