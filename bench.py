@@ -50,6 +50,10 @@ MEASURED_TRAFFIC_BYTES = {
     ("cfg3", "chain"): int((1022961.4 * (540459.2 / 270254.7) + 8112519.3) * 1024),
     ("cfg4", "chain"): int((1598370.7 * (524288.0 / 262166.7) + 16258400.0) * 1024),
     ("cfg5", "chain"): int((5878015.7 * (1048576.0 / 524315.7) + 66071232.0) * 1024),
+    # the chain reduction (--op reduce): (P + 3) M with two stages -- every contribution read once, the running
+    # sum written to and read from the scratch buffer once, the result written once
+    ("cfg2", "reduce"): int((295938.8 * (65536.0 / 32787.3) + 131584.0) * 1024),
+    ("cfg4", "reduce"): int((8656715.8 * (524288.0 / 262166.7) + 1052672.0) * 1024),
 }
 
 
@@ -313,6 +317,8 @@ def bench_reduce(args, B, torch, P, root, M, seed, what):
         cpu = {"value": round((P + 1) * sample * 4 / (t / reps) / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
                "sample": "oracle.chain_reduce_f32, P=%d, first %d elements, %d reps, %.1f ms each" % (P, sample, reps, 1e3 * t / reps)}
     algorithmic = (P + 1) * count * 4
+    custom = bool(args.ranks or args.bytes or args.chunk or args.lanes or args.stages)
+    traffic = None if custom else MEASURED_TRAFFIC_BYTES.get((args.workload, "reduce"))
     out = {
         "metric": "chain reduction (fp32 sum to the root) effective HBM bandwidth (P+1)M/t (GB/s); latency in ms_per_step",
         "value": round(algorithmic / (wall_ms * 1e-3) / 1e9, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -323,7 +329,9 @@ def bench_reduce(args, B, torch, P, root, M, seed, what):
                    "nchunks": int(info["nchunks"]), "stages": info["stages"], "lanes": info["lanes"], "grid_blocks": info["grid_blocks"]},
         "verified_bit_exact": verified,
         "roofline": {"bound": "hbm", "achieved": round(algorithmic / (avg_launch_ms * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(algorithmic / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(algorithmic / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "traffic_GBps": round(traffic / (avg_launch_ms * 1e-3) / 1e9, 2) if traffic else None,
+                     "traffic_frac": round(traffic / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
                      "kernel": "bcast::reduce_kernel", "algorithmic_bytes_per_launch": algorithmic, "avg_launch_ms": round(avg_launch_ms, 5)},
         "cpu_baseline": cpu,
     }
