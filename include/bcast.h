@@ -246,6 +246,15 @@ int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_w
  */
 int bcast_reduce_sum_f32(bcast_plan_t *plan, const void *const *send_bufs, void *recv_buf, int root, size_t count,
                          bcast_stream_t stream);
+/* MPI_Allreduce (sum of fp32) as the two chains one after the other on `stream`:
+ * bcast_reduce_sum_f32 into recv_bufs[root], then bcast_run of that result to
+ * every recv_bufs[r] with the plan's broadcast algorithm (an AUTO plan needs a
+ * tuning table).  recv_bufs: HOST array of nranks DEVICE pointers, 16-byte
+ * aligned; recv_bufs[r] may be send_bufs[r] (in place) and must otherwise
+ * overlap nothing.  Every rank ends with the same bits, those
+ * bcast_reduce_sum_f32 defines.  Errors as for the two calls. */
+int bcast_allreduce_sum_f32(bcast_plan_t *plan, const void *const *send_bufs, void *const *recv_bufs, int root, size_t count,
+                            bcast_stream_t stream);
 /* The launch shape bcast_reduce_sum_f32 would use for `count` elements (fields as
  * for the chain; algorithmic_bytes = (nranks + 1) * count * 4: every input read
  * once, the result written once). */

@@ -39,7 +39,7 @@ BCAST_ERR_UNTUNED = -5
 # every symbol include/bcast.h declares
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_allreduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
     "bcast_plan_handoff_counts", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
@@ -123,6 +123,7 @@ def _load():
         "bcast_plan_set_trip": ([vp, i], i),
         "bcast_reduce_sum_f32": ([vp, ctypes.POINTER(ctypes.c_void_p), vp, i, sz, vp], i),
         "bcast_reduce_info": ([vp, sz, ctypes.POINTER(PlanInfo)], i),
+        "bcast_allreduce_sum_f32": ([vp, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p), i, sz, vp], i),
         "bcast_chain_stage_span": ([i, i, i, ctypes.c_uint64, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)], i),
         "bcast_plan_debug_set_epoch": ([vp, ctypes.c_uint64], i),
         "bcast_plan_set_block_threads": ([vp, i], i),
@@ -279,6 +280,13 @@ def bcast_reduce_sum_f32(plan: Plan, send_bufs, recv_buf, root: int, count: int,
         raise BcastError(BCAST_ERR_ARG, "bcast_reduce_sum_f32: need %d buffers, got %d" % (plan.nranks, len(send_bufs)))
     _check(_lib.bcast_reduce_sum_f32(plan.handle, _ptr_array(send_bufs), _ptr(recv_buf), root, count, _stream(stream)),
            "bcast_reduce_sum_f32")
+
+
+def bcast_allreduce_sum_f32(plan: Plan, send_bufs, recv_bufs, root: int, count: int, stream=None) -> None:
+    if len(send_bufs) != plan.nranks or len(recv_bufs) != plan.nranks:
+        raise BcastError(BCAST_ERR_ARG, "bcast_allreduce_sum_f32: need %d buffers each" % plan.nranks)
+    _check(_lib.bcast_allreduce_sum_f32(plan.handle, _ptr_array(send_bufs), _ptr_array(recv_bufs), root, count, _stream(stream)),
+           "bcast_allreduce_sum_f32")
 
 
 def bcast_reduce_status(plan: Plan, send_bufs, recv_buf, root: int, count: int, stream=None) -> int:

@@ -889,6 +889,34 @@ extern "C" int bcast_reduce_sum_f32(bcast_plan_t *p, const void *const *send_buf
     return BCAST_OK;
 }
 
+extern "C" int bcast_allreduce_sum_f32(bcast_plan_t *p, const void *const *send_bufs, void *const *recv_bufs, int root,
+                                       size_t count, bcast_stream_t stream)
+{
+    if (!p || !send_bufs || !recv_bufs) return BCAST_ERR_ARG;
+    const int P = p->nranks;
+    if (root < 0 || root >= P || count > p->bytes / sizeof(float)) return BCAST_ERR_ARG;
+    const size_t bytes = count * sizeof(float);
+    // every rank's result is either its own contribution (in place) or memory that
+    // touches no contribution and no other result
+    {
+        uintptr_t at[2 * BCAST_MAX_RANKS];
+        int n = 0;
+        for (int i = 0; i < P; ++i) {
+            if (!send_bufs[i] || !recv_bufs[i]) return BCAST_ERR_ARG;
+            at[n++] = (uintptr_t)send_bufs[i];
+            if (recv_bufs[i] != send_bufs[i]) at[n++] = (uintptr_t)recv_bufs[i];
+        }
+        std::sort(at, at + n);
+        for (int i = 0; i + 1 < n; ++i)
+            if (at[i + 1] == at[i] || at[i + 1] - at[i] < bytes) return BCAST_ERR_ARG;
+    }
+    // the chain reduction to the root, then the root's result down the broadcast
+    // chain: stream order makes the second wait for the first
+    int rc = bcast_reduce_sum_f32(p, send_bufs, recv_bufs[root], root, count, stream);
+    if (rc != BCAST_OK) return rc;
+    return bcast_run(p, recv_bufs, root, bytes, stream);
+}
+
 extern "C" const char *bcast_strerror(int status)
 {
     switch (status) {

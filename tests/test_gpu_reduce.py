@@ -196,3 +196,25 @@ def test_vgg16_gradient_sized_reduction_p16():
     want, res = oracle.chain_reduce_f32(host, P, root, count, info["chunk_bytes"] // 4)
     assert res.steps == info["nchunks"] + P - 2
     assert np.array_equal(recv.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+@pytest.mark.parametrize("P,root,count,in_place", [(2, 1, 5, False), (4, 0, 70001, True), (8, 5, 1 << 20, False), (16, 3, 300000, True), (64, 17, 65536, False)])
+def test_allreduce_is_reduce_then_broadcast(P, root, count, in_place):
+    """Every rank ends with the bits the chain reduction defines."""
+    send = contributions(P + count, P, count)
+    dev = [torch.from_numpy(send[r]).cuda() for r in range(P)]
+    recv = dev if in_place else [torch.full((count,), float(CANARY), dtype=torch.float32, device="cuda") for _ in range(P)]
+    plan = B.bcast_plan_create(P, count * 4, 64 * KiB, B.BCAST_ALGO_CHAIN)
+    B.bcast_allreduce_sum_f32(plan, dev, recv, root, count, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+    want, _ = oracle.chain_reduce_f32(send, P, root, count, 16 * KiB)
+    for r in range(P):
+        assert np.array_equal(recv[r].cpu().numpy().view(np.uint32), want.view(np.uint32)), r
+        if not in_place:
+            assert np.array_equal(dev[r].cpu().numpy().view(np.uint32), send[r].view(np.uint32)), r
+    # a result placed on another rank's contribution is refused
+    if not in_place:
+        with pytest.raises(B.BcastError):
+            B.bcast_allreduce_sum_f32(plan, dev, [dev[(r + 1) % P] for r in range(P)], root, count)
+    plan.destroy()
