@@ -6,10 +6,12 @@
  * every buffer holds the root's bytes) for P "virtual ranks" that are P
  * distinct device buffers in one GPU's HBM.  The flagship algorithm is the
  * pipelined chain of Sec. IV-B (Eq. 5); the direct algorithm (Eq. 1), the
- * binomial tree (Eq. 3, k = 2), scatter + ring allgather (Eq. 4), a one-die
- * fan-out and a tuning table that picks
- * algorithm and chunk size per (message bytes, ranks) (Sec. III-B, IV-B) sit
- * beside it.
+ * binomial and k-nomial trees (Eq. 3; per level, and pipelined in one launch),
+ * scatter + ring allgather (Eq. 4), a one-die fan-out and a tuning table that
+ * picks algorithm and chunk size per (message bytes, ranks) (Sec. III-B, IV-B)
+ * sit beside it, and so does the chain run backwards as a rooted fp32 sum
+ * (MPI_Reduce, the collective Sec. VII names next), alone or followed by the
+ * broadcast (MPI_Allreduce).
  *
  * Conventions for every call
  *   - Plain C linkage, no C++ or torch types.  Every pointer argument says
@@ -18,8 +20,8 @@
  *     aborts or throws.  After BCAST_ERR_HIP, bcast_last_hip_error() gives the
  *     hipError_t value of the failing runtime call on this thread.
  *   - The caller owns all rank buffers and the rank_bufs array; the library
- *     owns what a plan allocates (ready flags, status word) until
- *     bcast_plan_destroy.
+ *     owns what a plan allocates (ready flags, status word, the reduction's
+ *     scratch buffer) until bcast_plan_destroy.
  *   - Streams are passed as HIP's own handle type.  To keep this header free
  *     of HIP includes it is spelled bcast_stream_t, which is the same type as
  *     hipStream_t (struct ihipStream_t *); NULL is the default stream.
