@@ -218,3 +218,23 @@ def test_allreduce_is_reduce_then_broadcast(P, root, count, in_place):
         with pytest.raises(B.BcastError):
             B.bcast_allreduce_sum_f32(plan, dev, [dev[(r + 1) % P] for r in range(P)], root, count)
     plan.destroy()
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_random_reduction_configurations(seed):
+    """Seeded sweep: ranks, root, count, chunk size, stage and lane counts, in
+    place or not."""
+    rng = np.random.default_rng(seed)
+    for case in range(60):
+        P = int(rng.integers(1, 65)) if case % 3 else int(rng.integers(1, 9))
+        root = int(rng.integers(0, P))
+        count = int(rng.choice([0, 1, 2, 3, 4, 7, 1024, 4097, 100003, int(rng.integers(1, 400000))]))
+        C = int(rng.choice([0, 16, 112, 4096, 65536, 1 << 20])) if rng.random() < 0.8 else 16 * int(rng.integers(1, 20000))
+        stages = int(rng.integers(0, 70))
+        lanes = int(rng.choice([0, 0, 1, 3, 32, 100]))
+        in_place = bool(rng.integers(0, 2))
+        try:
+            reduce_and_check(P, root, count, C, seed=1000 * seed + case, stages=stages, lanes=lanes, in_place=in_place)
+        except Exception as e:
+            raise AssertionError("case %d: P=%d root=%d count=%d C=%d stages=%d lanes=%d in_place=%s: %s"
+                                 % (case, P, root, count, C, stages, lanes, in_place, e))
