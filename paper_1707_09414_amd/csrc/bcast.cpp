@@ -65,7 +65,8 @@ static u64 round_up(u64 a, u64 b) { return ceil_div(a, b) * b; }
 
 // Stages for `hops` chain hops when the caller asks for `request` (0 = one per
 // hop): that many, and each plays floor or ceil(hops / stages) consecutive hops
-// (the kernel rotates the longer ones from chunk to chunk).
+// (where stages are short the kernel passes the extra hop round from chunk to
+// chunk, see rotate_spans).
 static void stage_shape(int hops, int request, int *stages, int *hops_per_stage)
 {
     *stages = request > 0 ? std::min(request, hops) : hops;
@@ -817,6 +818,23 @@ static int reduce_shape(const bcast_plan *p, size_t bytes, bcast_plan_info_t *in
     const bcast_chain_request_t req = {p->lanes_request, stages, (int)trip_bytes_of(kTripUnrollDefault), 0};
     int rc = bcast_chain_geometry(p->nranks, bytes, chunk, p->max_waves_reduce, &req, info);
     if (rc != BCAST_OK) return rc;
+    if (p->nranks >= 2 && bytes > 0 && bytes <= kRedSmallMaxBytes) {
+        // small messages: 1 KiB trips (and 16 positions loaded at a time), so more lanes share the work
+        const u64 trip = trip_bytes_of(kRedUnrollSmall);
+        const u64 most = (u64)(p->max_waves_reduce / info->stages);
+        u64 lanes = p->lanes_request > 0 ? std::min<u64>((u64)p->lanes_request, most)
+                                         : std::min<u64>(ceil_div(info->chunk_bytes, trip), most);
+        if (p->lanes_request == 0) {
+            u64 l = 1;
+            while (l * 2 <= lanes) l *= 2;
+            lanes = l;
+        }
+        lanes = std::max<u64>(1, lanes);
+        info->lanes = (int)lanes;
+        info->trip_bytes = (int)trip;
+        info->slice_bytes = ceil_div(info->chunk_bytes, lanes * trip) * trip;
+        info->grid_blocks = (int)ceil_div((u64)info->stages * lanes, kWavesPerBlock);
+    }
     // every input byte is read once and every result byte written once
     info->algorithmic_bytes = ((u64)p->nranks + 1) * bytes;
     return BCAST_OK;
@@ -881,6 +899,7 @@ extern "C" int bcast_reduce_sum_f32(bcast_plan_t *p, const void *const *send_buf
     if (rc != BCAST_OK) return rc;
     a.stages = (unsigned)info.stages;
     a.hops_per_stage = (unsigned)info.hops_per_stage;
+    a.unroll = (unsigned)(info.trip_bytes / (kWaveSize * 16));
     a.recv = (char *)recv_buf;
     a.scratch = p->d_scratch;
     a.scratch_stride = region;

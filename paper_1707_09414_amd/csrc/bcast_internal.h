@@ -34,6 +34,12 @@ constexpr u64 kTileBytes = (u64)kWaveSize * 16 * kUnroll;
 constexpr int kTripUnrollDefault = 4;
 constexpr int kTripUnrollSmall = 3;
 
+// The reduction kernel's trips: 16-byte vectors per lane, trip and position
+// (4 KiB per wave) for streaming messages, one (1 KiB) for small ones.
+constexpr int kRedUnroll = 4;
+constexpr int kRedUnrollSmall = 1;
+constexpr u64 kRedSmallMaxBytes = 2u << 20;  // measured crossover on MI355X: 2-4 MiB
+
 // Wait limit default: 10 s of the 100 MHz constant clock.
 constexpr u64 kDefaultSpinTicks = 1000000000ull;
 

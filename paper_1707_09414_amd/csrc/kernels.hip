@@ -442,10 +442,12 @@ __global__ void __launch_bounds__(kBlockThreads) tree_kernel(const ChainArgs a)
 // nobody but the next position needs it); between stages it goes through a
 // scratch buffer in memory -- written through at agent scope, flag raised, read
 // at agent scope by the same lane of the next stage.  The contributions are
-// read exactly once, kRedBatch positions at a time so that their loads are in
-// flight together; the additions then run in chain order.
-constexpr int kRedBatch = 4;
-constexpr int kRedUnroll = 4;  // 16-byte vectors per lane and trip: 4 KiB per wave and position
+// read exactly once, B positions at a time so that their loads are in flight
+// together; the additions then run in chain order.  Two shapes are built: trips
+// of 4 KiB per position, 4 positions at a time, for messages that stream, and
+// trips of 1 KiB, 16 positions at a time, for small ones, where the number of
+// dependent memory round trips per stage is what a reduction takes
+// (P = 64, 4 KiB: 2 instead of 8 per stage).
 
 __device__ __forceinline__ void add_f32x4(VecOf<16>::type &acc, const VecOf<16>::type &x)
 {
@@ -458,7 +460,7 @@ __device__ __forceinline__ void add_f32x4(VecOf<16>::type &acc, const VecOf<16>:
 
 // One span [lo, hi) (at most one trip; a multiple of sizeof(T) bytes) through the
 // hops first_hop .. last_hop: T is a 16-byte vector of four floats or one float.
-template <int V, int U, int LD_IN, int ST_OUT>
+template <int V, int U, int B, int LD_IN, int ST_OUT>
 __device__ __forceinline__ void reduce_span(const ChainArgs &a, const char *in, char *out, unsigned first_hop, unsigned last_hop,
                                             u64 lo, unsigned n, unsigned lane)
 {
@@ -471,10 +473,10 @@ __device__ __forceinline__ void reduce_span(const ChainArgs &a, const char *in, 
     const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(in + lo), 0, n, kRsrcWord3);
 #pragma unroll
     for (int u = 0; u < U; ++u) acc[u] = EDGE::ld(rin, off + u * kWaveSize * V);
-    for (unsigned hop = first_hop; hop <= last_hop; hop += kRedBatch) {
-        T x[kRedBatch][U];
+    for (unsigned hop = first_hop; hop <= last_hop; hop += B) {
+        T x[B][U];
 #pragma unroll
-        for (int b = 0; b < kRedBatch; ++b) {
+        for (int b = 0; b < B; ++b) {
             if (hop + b <= last_hop) {  // wave-uniform
                 const __amdgpu_buffer_rsrc_t rx =
                     __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(a.buf[top - (hop + b)] + lo), 0, n, kRsrcWord3);
@@ -483,7 +485,7 @@ __device__ __forceinline__ void reduce_span(const ChainArgs &a, const char *in, 
             }
         }
 #pragma unroll
-        for (int b = 0; b < kRedBatch; ++b) {
+        for (int b = 0; b < B; ++b) {
             if (hop + b <= last_hop) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -498,9 +500,9 @@ __device__ __forceinline__ void reduce_span(const ChainArgs &a, const char *in, 
     for (int u = 0; u < U; ++u) EDGE::st(acc[u], rout, off + u * kWaveSize * V);
 }
 
+template <int U, int B>
 __global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a)
 {
-    constexpr int U = kRedUnroll;
     const unsigned lane = threadIdx.x & (kWaveSize - 1);
     const unsigned gw = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     if (gw >= a.stages * a.lanes) return;
@@ -535,17 +537,17 @@ __global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a
             const unsigned n = (unsigned)(hi - lo);
             const unsigned body = n & ~15u;  // whole vectors of four floats; the rest (at the message's end) float by float
             if (g > 0 && !last_stage) {
-                if (body) reduce_span<16, U, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
-                if (n != body) reduce_span<4, 1, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                if (body) reduce_span<16, U, B, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
             } else if (g > 0) {
-                if (body) reduce_span<16, U, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo, body, lane);
-                if (n != body) reduce_span<4, 1, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                if (body) reduce_span<16, U, B, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
             } else if (!last_stage) {
-                if (body) reduce_span<16, U, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
-                if (n != body) reduce_span<4, 1, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                if (body) reduce_span<16, U, B, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, B, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
             } else {
-                if (body) reduce_span<16, U, kAuxStream, kAuxCached>(a, in, out, first_hop, last_hop, lo, body, lane);
-                if (n != body) reduce_span<4, 1, kAuxStream, kAuxCached>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                if (body) reduce_span<16, U, B, kAuxStream, kAuxCached>(a, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, B, kAuxStream, kAuxCached>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
             }
         }
         if (in_flag && c + 1 < a.nchunks) seen = read_flag(in_flag, lane);
@@ -665,13 +667,19 @@ hipError_t launch_reduce(const ChainArgs &a, int grid_blocks, hipStream_t stream
     if (grid_blocks < 1 || a.nranks < 2 || a.nranks > BCAST_MAX_RANKS || a.stages < 1 || a.stages > a.nranks - 1) return hipErrorInvalidValue;
     if ((u64)grid_blocks * kWavesPerBlock < (u64)a.stages * a.lanes) return hipErrorInvalidValue;
     if (!a.recv || (a.stages > 1 && !a.scratch) || (a.bytes & 3u)) return hipErrorInvalidValue;
-    reduce_kernel<<<dim3(grid_blocks), dim3(kBlockThreads), 0, stream>>>(a);
+    if (a.unroll == (unsigned)kRedUnrollSmall) reduce_kernel<kRedUnrollSmall, 16><<<dim3(grid_blocks), dim3(kBlockThreads), 0, stream>>>(a);
+    else if (a.unroll == (unsigned)kRedUnroll) reduce_kernel<kRedUnroll, 4><<<dim3(grid_blocks), dim3(kBlockThreads), 0, stream>>>(a);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
 hipError_t reduce_max_blocks_per_cu(int *blocks)
 {
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, reduce_kernel, kBlockThreads, 0);
+    int small = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, reduce_kernel<kRedUnroll, 4>, kBlockThreads, 0);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&small, reduce_kernel<kRedUnrollSmall, 16>, kBlockThreads, 0);
+    if (e == hipSuccess && small < *blocks) *blocks = small;
+    return e;
 }
 
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream)
