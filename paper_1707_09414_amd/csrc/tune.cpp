@@ -304,9 +304,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
     std::vector<int> stage_counts;
     for (int s : {hops, 16, 8, 4, 2, 1}) {
         if (s > hops || (s == 1 && hops > 1 && !(algo_mask & BCAST_TUNE_FOLDED))) continue;
-        const int hps = (hops + s - 1) / s;
-        const int eff = (hops + hps - 1) / hps;
-        if (std::find(stage_counts.begin(), stage_counts.end(), eff) == stage_counts.end()) stage_counts.push_back(eff);
+        if (std::find(stage_counts.begin(), stage_counts.end(), s) == stage_counts.end()) stage_counts.push_back(s);
     }
 
     int rc = BCAST_OK;
