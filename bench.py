@@ -332,7 +332,7 @@ def bench_reduce(args, B, torch, P, root, M, seed, what):
                      "frac": round(algorithmic / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "traffic_GBps": round(traffic / (avg_launch_ms * 1e-3) / 1e9, 2) if traffic else None,
                      "traffic_frac": round(traffic / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
-                     "kernel": "bcast::reduce_kernel", "algorithmic_bytes_per_launch": algorithmic, "avg_launch_ms": round(avg_launch_ms, 5)},
+                     "kernel": "bcast::reduce_kernel<1, 16>" if count * 4 <= (2 << 20) else "bcast::reduce_kernel<4, 4>", "algorithmic_bytes_per_launch": algorithmic, "avg_launch_ms": round(avg_launch_ms, 5)},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
