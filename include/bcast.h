@@ -269,8 +269,8 @@ int bcast_reduce_info(bcast_plan_t *plan, size_t count, bcast_plan_info_t *info)
  * chunk c iff (j + c) mod stages < r, so the longer stages rotate and over any
  * `stages` consecutive chunks all stages play the same number of hops.  This is
  * the function the kernel itself evaluates when spans rotate (plan info's
- * rotating_spans); when they do not, every chunk has the spans of chunk 0.  BCAST_ERR_ARG unless
- * 2 <= nranks <= BCAST_MAX_RANKS, 1 <= stages <= nranks-1, 0 <= stage < stages. */
+ * rotating_spans); when they do not, every chunk has the spans of chunk 0.
+ * BCAST_ERR_ARG unless 2 <= nranks <= BCAST_MAX_RANKS, 1 <= stages <= nranks-1, 0 <= stage < stages. */
 int bcast_chain_stage_span(int nranks, int stages, int stage, uint64_t chunk, int *first_hop, int *last_hop);
 
 /*
@@ -279,7 +279,8 @@ int bcast_chain_stage_span(int nranks, int stages, int stage, uint64_t chunk, in
  * measurements).  Process-wide; entries are keyed by (nranks, floor(log2 bytes)).
  *
  * bcast_tune measures, on the current device and `stream`, every candidate
- * (chain over chunk sizes 8 KiB..64 MiB and stage counts, direct, binomial, and
+ * (chain over chunk sizes 8 KiB..64 MiB, stage counts and both trip sizes,
+ * direct, binomial, and
  * -- only if `algo_mask` has their bits -- the fan-out, scatter + allgather,
  * the k-nomial tree at radix 4 and 8 and the one-launch pipelined k-nomial
  * tree at radix 2, 4 and 8) for message sizes that are
@@ -299,7 +300,7 @@ int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsigned algo_mas
  * chunk_bytes == 0 uses.  stages: 0 = automatic. */
 typedef struct {
     int algo;                   /* winner: bcast_algo_t */
-    uint64_t chunk_bytes;       /* winner's chunk size (chain only) */
+    uint64_t chunk_bytes;       /* winner's chunk size (chain and pipelined k-nomial tree) */
     int stages;                 /* winner's stage count (chain) or radix (k-nomial trees) */
     int trip_bytes;             /* winner's trip size (chain only; 0 = default) */
     double usec;                /* winner's measured time */
@@ -310,7 +311,8 @@ typedef struct {
 } bcast_tune_entry_t;
 
 /* While a log path (HOST, NULL = off) is set, bcast_tune appends one line per
- * candidate it times: "nranks bytes algo chunk_bytes stages usec" -- the raw
+ * candidate it times: "nranks bytes algo chunk_bytes stages usec trip_bytes"
+ * (stages holds the radix for the k-nomial trees) -- the raw
  * material for fitting the cost models of Sec. III-A / IV-B. */
 int bcast_tune_set_log(const char *log_path);
 int bcast_tune_load(const char *table_path);  /* HOST path; adds the file's entries */
