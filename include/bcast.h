@@ -60,7 +60,9 @@ typedef enum {
     BCAST_ERR_NOMEM = -2,   /* host or device allocation failed */
     BCAST_ERR_HIP = -3,     /* a HIP runtime call failed; see bcast_last_hip_error() */
     BCAST_ERR_TIMEOUT = -4, /* a chain wave gave up waiting for its left neighbour */
-    BCAST_ERR_UNTUNED = -5  /* BCAST_ALGO_AUTO but the table has no entry for this nranks */
+    BCAST_ERR_UNTUNED = -5, /* BCAST_ALGO_AUTO but the table has no entry for this nranks */
+    BCAST_ERR_CAPACITY = -6 /* the staging memory reserved for the plan cannot carry this size at
+                               this stage count; nothing was enqueued */
 } bcast_status_t;
 
 /* What a plan will launch for a given message size (host-side bookkeeping). */
@@ -149,16 +151,14 @@ int bcast_plan_info(bcast_plan_t *plan, void *const *rank_bufs, size_t bytes, bc
 /* bcast_plan_destroy -- waits for the device, then frees the plan's memory. */
 int bcast_plan_destroy(bcast_plan_t *plan);
 
-/* Knobs for experiments and tests.  lanes: wavefronts per chain stage (0 =
- * automatic).  stages: how many groups of consecutive hops get wavefronts of
- * their own (0 = automatic; nranks-1 = one stage per receiving rank; fewer =
- * a wavefront plays several consecutive ranks in turn, re-reading from each
- * rank's buffer what it stored there, and flags are only used between stages;
- * where nranks-1 is no multiple of stages, the stages that play one hop more
- * rotate from chunk to chunk, so the stage boundaries differ between chunks).
- * spin_limit_ticks: wait limit in 100 MHz ticks (0 = default, about 10 s).  mute_hop: chain position (1..P-2) that stores its chunks but
- * never publishes them, so that its right neighbour runs into the wait limit;
- * 0 = off.  Kernels always run to completion under these settings. */
+/* Launch-shape knobs.  lanes: wavefronts per chain stage (0 = automatic).
+ * stages: how many groups of consecutive hops get wavefronts of their own (0 =
+ * automatic; nranks-1 = one stage per receiving rank, the literal picture of
+ * Sec. IV-B; fewer = a wavefront plays several consecutive ranks in turn,
+ * re-reading from each rank's buffer what it stored there, and flags are only
+ * used between stages; where nranks-1 is no multiple of stages, the stages that
+ * play one hop more rotate from chunk to chunk, so the stage boundaries differ
+ * between chunks).  Test and diagnostic hooks are declared in bcast_debug.h. */
 int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
 int bcast_plan_set_stages(bcast_plan_t *plan, int stages);
 /* Bytes a chain wavefront moves per trip (16-byte accesses): 4096 or 3072,
@@ -171,40 +171,6 @@ int bcast_plan_set_block_threads(bcast_plan_t *plan, int block_threads);
 /* Radix k of BCAST_ALGO_KNOMIAL, 2..nranks (0 = the tuning table's, else 4):
  * in round j every position q < k^j sends to q + i k^j, i = 1..k-1. */
 int bcast_plan_set_radix(bcast_plan_t *plan, int radix);
-int bcast_plan_set_debug(bcast_plan_t *plan, uint64_t spin_limit_ticks, int mute_hop);
-/* Test hook: make the plan behave as if it had already run `epoch` times
- * (never fewer than it has).  Runs are told apart by a 32-bit count in the
- * flag words; bcast_run drains the device and clears the flags before the count
- * would wrap, and this lets a test reach that point without 2^32 runs.
- * BCAST_ERR_ARG if epoch is below the plan's count or above 2^32 - 2. */
-int bcast_plan_debug_set_epoch(bcast_plan_t *plan, uint64_t epoch);
-
-/* Chain kernel modes (bit mask).  BCAST_MODE_COUNT: count the hand-offs whose
- * producer and consumer waves ran on the same XCD (one L2) and on different
- * XCDs; read back (after a device synchronise) by bcast_plan_handoff_counts.
- * The counts accumulate over runs.  Diagnostic: it slows the kernel down.
- * BCAST_MODE_FIXED_SPANS / BCAST_MODE_ROTATE_SPANS (not both): where nranks-1 is
- * no multiple of the stage count, the first stages keep the extra hop for every
- * chunk (every chunk has chunk 0's spans of bcast_chain_stage_span), or the
- * extra hop is passed round as that function describes.  With neither bit the
- * library rotates where a stage plays fewer than four hops. */
-#define BCAST_MODE_COUNT 2u
-#define BCAST_MODE_FIXED_SPANS 16u
-#define BCAST_MODE_ROTATE_SPANS 32u
-int bcast_plan_set_mode(bcast_plan_t *plan, unsigned mode);
-
-/* Pipeline trace (diagnostic).  After bcast_plan_enable_trace(plan, entries),
- * every chain run records, for the first `entries` (stage, chunk) pairs in
- * stage-major order (index = stage * nchunks + chunk), the 100 MHz device
- * clock at which lane 0's wavefront of the stage began copying the chunk (after
- * its wait) and at which all its stores for the chunk had completed.
- * bcast_plan_read_trace synchronises the device and copies `entries` pairs
- * [begin, end] into `out` (HOST, 2 * entries words).  entries == 0 turns the
- * trace off.  Each run overwrites the previous one's record. */
-int bcast_plan_enable_trace(bcast_plan_t *plan, size_t entries);
-int bcast_plan_read_trace(bcast_plan_t *plan, uint64_t *out, size_t entries);
-int bcast_plan_handoff_counts(bcast_plan_t *plan, uint64_t *same_xcd, uint64_t *cross_xcd);
-
 /* Launch-shape requests for the chain kernel; 0 = automatic in every field. */
 typedef struct {
     int lanes;         /* wavefronts per stage */
@@ -239,15 +205,25 @@ int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_w
  *              send_bufs[root] itself (in place) or memory that overlaps no
  *              contribution.  Only these count floats are written.
  *   count      elements, count * 4 <= plan bytes.
- * The first call (and any call that needs more stages than an earlier one)
- * allocates scratch memory of (stages - 1) x plan bytes for the running sums
- * that cross a stage boundary, after waiting for the device.  Flags, epoch,
- * wait limit and status word are the plan's, as for bcast_run.
+ * The running sums that cross a stage boundary go through staging memory the
+ * plan owns: one region of round_up(count * 4, 256) bytes per boundary, reserved
+ * beforehand with bcast_plan_reserve_reduce.  This call itself never allocates
+ * and never waits for the device.  A stage count set with bcast_plan_set_stages
+ * that the reserved memory cannot carry fails with BCAST_ERR_CAPACITY; the
+ * library's own choice of stages shrinks to what fits (one stage needs none, so
+ * a plan without any reservation reduces in one stage).  Flags, epoch, wait
+ * limit and status word are the plan's, as for bcast_run.
  * Errors: ERR_ARG (NULL, misaligned or overlapping pointers, root or count out
- * of range), ERR_NOMEM, ERR_HIP; ERR_TIMEOUT through the status word.
+ * of range), ERR_CAPACITY, ERR_HIP; ERR_TIMEOUT through the status word.
  */
 int bcast_reduce_sum_f32(bcast_plan_t *plan, const void *const *send_bufs, void *recv_buf, int root, size_t count,
                          bcast_stream_t stream);
+/* bcast_plan_reserve_reduce -- make sure the plan owns staging memory for
+ * reductions of up to `count` floats in up to `stages` stages (stages >= 1;
+ * cut down to nranks - 1).  Grows only; growing waits for the device, frees the
+ * old memory and allocates (stages - 1) * round_up(count * 4, 256) bytes.
+ * Errors: ERR_ARG (count * 4 beyond the plan's bytes), ERR_NOMEM, ERR_HIP. */
+int bcast_plan_reserve_reduce(bcast_plan_t *plan, size_t count, int stages);
 /* MPI_Allreduce (sum of fp32) as the two chains one after the other on `stream`:
  * bcast_reduce_sum_f32 into recv_bufs[root], then bcast_run of that result to
  * every recv_bufs[r] with the plan's broadcast algorithm (an AUTO plan needs a

@@ -1,7 +1,8 @@
 """ctypes binding for the gfx950 broadcast library (``lib/libbcast.so``).
 
 Argument marshalling only: every byte is moved by the library's HIP kernels.
-Function names and argument order follow ``include/bcast.h``.  Buffers may be
+Function names and argument order follow ``include/bcast.h`` and
+``include/bcast_debug.h``.  Buffers may be
 given as integers (device addresses) or as objects with ``data_ptr()`` (torch
 tensors); streams as integers (``torch.cuda.current_stream().cuda_stream``),
 objects with ``cuda_stream``, or None for the default stream.
@@ -35,12 +36,13 @@ BCAST_ERR_NOMEM = -2
 BCAST_ERR_HIP = -3
 BCAST_ERR_TIMEOUT = -4
 BCAST_ERR_UNTUNED = -5
+BCAST_ERR_CAPACITY = -6
 
-# every symbol include/bcast.h declares
+# every symbol include/bcast.h and include/bcast_debug.h declare
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_allreduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
-    "bcast_plan_handoff_counts", "bcast_chain_geometry",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_plan_reserve_reduce", "bcast_allreduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
+    "bcast_plan_handoff_counts", "bcast_plan_set_cache_policy", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
 ]
@@ -123,12 +125,14 @@ def _load():
         "bcast_plan_set_trip": ([vp, i], i),
         "bcast_reduce_sum_f32": ([vp, ctypes.POINTER(ctypes.c_void_p), vp, i, sz, vp], i),
         "bcast_reduce_info": ([vp, sz, ctypes.POINTER(PlanInfo)], i),
+        "bcast_plan_reserve_reduce": ([vp, sz, i], i),
         "bcast_allreduce_sum_f32": ([vp, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p), i, sz, vp], i),
         "bcast_chain_stage_span": ([i, i, i, ctypes.c_uint64, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)], i),
         "bcast_plan_debug_set_epoch": ([vp, ctypes.c_uint64], i),
         "bcast_plan_set_block_threads": ([vp, i], i),
         "bcast_plan_set_debug": ([vp, u64, i], i),
         "bcast_plan_set_mode": ([vp, ctypes.c_uint], i),
+        "bcast_plan_set_cache_policy": ([vp, i, i, i, i], i),
         "bcast_plan_enable_trace": ([vp, sz], i),
         "bcast_plan_read_trace": ([vp, ctypes.POINTER(u64), sz], i),
         "bcast_plan_handoff_counts": ([vp, ctypes.POINTER(u64), ctypes.POINTER(u64)], i),
@@ -282,6 +286,10 @@ def bcast_reduce_sum_f32(plan: Plan, send_bufs, recv_buf, root: int, count: int,
            "bcast_reduce_sum_f32")
 
 
+def bcast_plan_reserve_reduce(plan: Plan, count: int, stages: int) -> None:
+    _check(_lib.bcast_plan_reserve_reduce(plan.handle, count, stages), "bcast_plan_reserve_reduce")
+
+
 def bcast_allreduce_sum_f32(plan: Plan, send_bufs, recv_bufs, root: int, count: int, stream=None) -> None:
     if len(send_bufs) != plan.nranks or len(recv_bufs) != plan.nranks:
         raise BcastError(BCAST_ERR_ARG, "bcast_allreduce_sum_f32: need %d buffers each" % plan.nranks)
@@ -328,6 +336,14 @@ BCAST_MODE_ROTATE_SPANS = 32
 
 def bcast_plan_set_mode(plan: Plan, mode: int) -> None:
     _check(_lib.bcast_plan_set_mode(plan.handle, mode), "bcast_plan_set_mode")
+
+
+BCAST_CACHE_STREAM = 2
+BCAST_CACHE_AGENT = 16
+
+
+def bcast_plan_set_cache_policy(plan: Plan, ld_root: int = -1, ld_edge: int = -1, ld_back: int = -1, st_mid: int = -1) -> None:
+    _check(_lib.bcast_plan_set_cache_policy(plan.handle, ld_root, ld_edge, ld_back, st_mid), "bcast_plan_set_cache_policy")
 
 
 def bcast_plan_enable_trace(plan: Plan, entries: int) -> None:

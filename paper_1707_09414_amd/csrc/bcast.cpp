@@ -21,11 +21,10 @@ struct bcast_plan {
     // wavefronts of the chain kernel the device holds at once, per workgroup
     // size (index: 0 = 64, 1 = 128, 2 = 256 threads)
     int max_waves[3] = {0, 0, 0};
-    int max_waves_cached[3] = {0, 0, 0};  // the same for its small-message (write-back) variant
     int max_flags = 0;                    // flags allocated: the largest of the above
     int max_waves_reduce = 0;             // the same limit for the reduction kernel (256-thread workgroups)
     char *d_scratch = nullptr;            // reduction: running sums handed from stage to stage
-    size_t scratch_bytes = 0;
+    size_t scratch_bytes = 0;             // (bcast_plan_reserve_reduce; the run path never allocates)
     u64 *d_flags = nullptr;  // max_waves flags, kFlagStrideWords apart, plus the abort word
     u64 *d_abort = nullptr;
     u64 *d_counters = nullptr; // two words after the abort word
@@ -42,6 +41,7 @@ struct bcast_plan {
     int block_request = 0; // chain workgroup size: 0 = choose, else 64, 128 or 256
     u64 spin_ticks = kDefaultSpinTicks;
     int mute_hop = 0;
+    int policy_request[4] = {-1, -1, -1, -1};  // ld_root, ld_edge, ld_back, st_mid; -1 = choose
 };
 
 static thread_local int g_last_hip_error = 0;
@@ -75,7 +75,7 @@ static void stage_shape(int hops, int request, int *stages, int *hops_per_stage)
 
 // Bytes of one trip of the copy loop at 16-byte vectors: the least worth a lane.
 static u64 trip_bytes_of(int unroll) { return (u64)unroll * kWaveSize * 16; }
-static bool valid_trip(u64 t) { return t == trip_bytes_of(kTripUnrollDefault) || t == trip_bytes_of(kTripUnrollSmall); }
+static bool valid_trip(u64 t) { return t != 0 && t % (kWaveSize * 16) == 0 && valid_chain_unroll((int)(t / (kWaveSize * 16))); }
 
 // Chunk size when the caller gives none and no tuning entry applies.  On one
 // die every hop shares the same HBM, so Eq. 5's fill term (n - 2 idle links)
@@ -212,12 +212,10 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
         // 32 waves per CU are counted on
         for (int b = 0; b < 3 && e == hipSuccess; ++b) {
             const int threads = kWaveSize << b, waves = 1 << b;
-            int per_cu = 0, per_cu_cached = 0;
-            e = chain_max_blocks_per_cu(threads, &per_cu, &per_cu_cached);
+            int per_cu = 0;
+            e = chain_max_blocks_per_cu(threads, &per_cu);
             per_cu = std::max(1, std::min(per_cu * waves, 32) / waves);
-            per_cu_cached = std::max(1, std::min(per_cu_cached, per_cu));
             p->max_waves[b] = std::max(nranks, p->cu_count * per_cu * waves);
-            p->max_waves_cached[b] = std::max(nranks, p->cu_count * per_cu_cached * waves);
             p->max_flags = std::max(p->max_flags, p->max_waves[b]);
         }
     }
@@ -307,6 +305,21 @@ extern "C" int bcast_plan_set_debug(bcast_plan_t *p, uint64_t spin_limit_ticks, 
     if (!p || mute_hop < 0 || mute_hop >= BCAST_MAX_RANKS) return BCAST_ERR_ARG;
     p->spin_ticks = spin_limit_ticks ? spin_limit_ticks : kDefaultSpinTicks;
     p->mute_hop = mute_hop;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_set_cache_policy(bcast_plan_t *p, int ld_root, int ld_edge, int ld_back, int st_mid)
+{
+    if (!p) return BCAST_ERR_ARG;
+    const int v[4] = {ld_root, ld_edge, ld_back, st_mid};
+    for (int x : v)
+        if (x != -1 && (x & ~(kAuxAgent | kAuxStream))) return BCAST_ERR_ARG;
+    // what another stage stored must be loaded at agent scope, and a wave's own
+    // write-back stores are not read back at agent scope
+    if (ld_edge != -1 && !(ld_edge & kAuxAgent)) return BCAST_ERR_ARG;
+    if (st_mid != -1 && !(st_mid & kAuxAgent) && ld_back != -1 && (ld_back & kAuxAgent)) return BCAST_ERR_ARG;
+    if (st_mid == -1 && ld_back != -1 && (ld_back & kAuxAgent)) return BCAST_ERR_ARG;  // the default store may be write-back
+    for (int i = 0; i < 4; ++i) p->policy_request[i] = v[i];
     return BCAST_OK;
 }
 
@@ -408,11 +421,10 @@ struct Resolved {
 // hands every chunk over through a flag.
 static int default_stages(int nranks) { return std::min(std::max(1, nranks - 1), 2); }
 
-// Co-residency limit of the kernel variant a message of `bytes` bytes will use.
-static int waves_for(const bcast_plan *p, size_t bytes)
+// Co-residency limit of the chain kernel at the plan's workgroup size.
+static int waves_for(const bcast_plan *p, size_t)
 {
-    const int b = block_index(p->block_request ? p->block_request : kBlockThreads);
-    return bytes <= kStageWriteBackMaxBytes ? p->max_waves_cached[b] : p->max_waves[b];
+    return p->max_waves[block_index(p->block_request ? p->block_request : kBlockThreads)];
 }
 
 // Wavefronts per position of the pipelined tree: every position but the root has
@@ -634,14 +646,24 @@ extern "C" int bcast_plan_info(bcast_plan_t *p, void *const *rank_bufs, size_t b
     return describe(p, rank_bufs, bytes, info);
 }
 
-// What the chain and the pipelined tree share: buffers by position, the plan's
-// flags, status words and wait limit, the chunking, and a fresh epoch.
-static int begin_flag_run(bcast_plan *p, ChainArgs *a, char *const *by_pos, size_t bytes, const bcast_plan_info_t &info)
+// Where a run's ready flags live and which run counter tells its runs apart:
+// the plan's own.
+struct FlagHome {
+    u64 *flags;
+    u64 *abort_word;
+    u64 *epoch;      // host counter of runs that used these flags
+    u64 clear_words; // 64-bit words from `flags` on to clear before the counter wraps
+};
+
+// What the chain, the pipelined tree and the reduction share: buffers by
+// position, ready flags, status words and wait limit, the chunking, and a fresh epoch.
+static int begin_flag_run(bcast_plan *p, ChainArgs *a, char *const *by_pos, size_t bytes, const bcast_plan_info_t &info,
+                          const FlagHome &home, hipStream_t)
 {
     memset(a, 0, sizeof *a);
     memcpy(a->buf, by_pos, sizeof(char *) * p->nranks);
-    a->flags = p->d_flags;
-    a->abort_word = p->d_abort;
+    a->flags = home.flags;
+    a->abort_word = home.abort_word;
     a->status = p->d_status;
     a->bytes = bytes;
     a->chunk_bytes = info.chunk_bytes;
@@ -653,16 +675,21 @@ static int begin_flag_run(bcast_plan *p, ChainArgs *a, char *const *by_pos, size
     if (a->nchunks == 0 || a->lanes == 0 || a->chunk_bytes == 0) return BCAST_ERR_ARG;
     if ((u64)a->nchunks * a->chunk_bytes < a->bytes) return BCAST_ERR_ARG;
     // the flag word keeps the epoch in its upper 32 bits: before that would
-    // wrap (after 2^32 - 2 runs of this plan), let the device drain, clear
+    // wrap (after 2^32 - 2 runs on these flags), let the device drain, clear
     // the flags and the abort word, and count from one again
-    if (p->epoch >= kEpochLimit) {
+    if (*home.epoch >= kEpochLimit) {
         HIP_TRY(hipDeviceSynchronize());
-        HIP_TRY(hipMemset(p->d_flags, 0, ((size_t)p->max_flags + 2) * kFlagStrideWords * sizeof(u64)));
+        HIP_TRY(hipMemset(home.flags, 0, home.clear_words * sizeof(u64)));
         HIP_TRY(hipDeviceSynchronize());
-        p->epoch = 0;
+        *home.epoch = 0;
     }
-    a->base = (++p->epoch) << 32;
+    a->base = (++*home.epoch) << 32;
     return BCAST_OK;
+}
+
+static FlagHome plan_flags(bcast_plan *p)
+{
+    return FlagHome{p->d_flags, p->d_abort, &p->epoch, ((u64)p->max_flags + 2) * kFlagStrideWords};
 }
 
 extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size_t bytes, bcast_stream_t stream)
@@ -693,14 +720,23 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
 
     if (info.algo == BCAST_ALGO_CHAIN) {
         ChainArgs a;
-        rc = begin_flag_run(p, &a, by_pos, bytes, info);
+        rc = begin_flag_run(p, &a, by_pos, bytes, info, plan_flags(p), stream);
         if (rc != BCAST_OK) return rc;
         a.counters = p->d_counters;
         a.trace = p->d_trace;
         a.trace_entries = p->trace_entries;
         a.mode = p->mode & ~(kModeFixedSpans | kModeRotateSpans);
         if (!info.rotating_spans) a.mode |= kModeFixedSpans;
-        if (bytes <= kStageWriteBackMaxBytes) a.mode |= kModeStageWriteBack;
+        // cache policies: everything another wave reads or wrote at agent scope;
+        // the wave's own read-back cached; its in-stage stores write-through, or
+        // write-back for small messages
+        const int chosen[4] = {kAuxAgent, kAuxAgent, kAuxCached, bytes <= kStageWriteBackMaxBytes ? kAuxCached : kAuxAgent};
+        unsigned char pol[4];
+        for (int i = 0; i < 4; ++i) pol[i] = (unsigned char)(p->policy_request[i] >= 0 ? p->policy_request[i] : chosen[i]);
+        a.ld_root = pol[0];
+        a.ld_edge = pol[1];
+        a.ld_back = pol[2];
+        a.st_mid = pol[3];
         if (p->d_trace) a.mode |= kModeTrace;
         a.stages = (unsigned)info.stages;
         a.hops_per_stage = (unsigned)info.hops_per_stage;
@@ -753,7 +789,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
     }
     if (info.algo == BCAST_ALGO_KNOMIAL_PIPELINED) {
         ChainArgs a;
-        rc = begin_flag_run(p, &a, by_pos, bytes, info);
+        rc = begin_flag_run(p, &a, by_pos, bytes, info, plan_flags(p), stream);
         if (rc != BCAST_OK) return rc;
         const int k = info.stages;
         if (k < 2) return BCAST_ERR_ARG;
@@ -809,19 +845,33 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
 }
 
 // Launch shape of a reduction of `bytes` bytes: the chain's geometry (stages of
-// consecutive hops, lanes, chunks) with 4 KiB trips and fixed spans.
-static int reduce_shape(const bcast_plan *p, size_t bytes, bcast_plan_info_t *info)
+// consecutive hops, lanes, chunks) with 4 KiB trips and fixed spans, inside what
+// the staging memory (`staging_bytes`, for the running sums that cross a stage
+// boundary: one region of round_up(bytes, 256) per boundary) and the flags
+// (`max_waves`) allow.  A stage count the caller asked for is an error if the
+// staging memory cannot carry it (BCAST_ERR_CAPACITY); the library's own choice
+// shrinks to what fits (one stage needs none).
+static int reduce_shape(const bcast_plan *p, size_t bytes, size_t staging_bytes, int max_waves, bcast_plan_info_t *info)
 {
-    const int stages = p->stages_request > 0 ? p->stages_request : default_stages(p->nranks);
+    const int hops = std::max(1, p->nranks - 1);
+    int stages = p->stages_request > 0 ? std::min(p->stages_request, hops) : default_stages(p->nranks);
+    if (p->nranks >= 2 && bytes > 0) {
+        const u64 region = round_up(bytes, 256);
+        const u64 fit = 1 + staging_bytes / region;  // stages the staging memory carries
+        if ((u64)stages > fit) {
+            if (p->stages_request > 0) return BCAST_ERR_CAPACITY;
+            stages = (int)fit;
+        }
+    }
     size_t chunk = p->chunk_bytes;
-    if (chunk == 0) chunk = (size_t)default_chunk(p->nranks, p->max_waves_reduce, stages, trip_bytes_of(kTripUnrollDefault));
+    if (chunk == 0) chunk = (size_t)default_chunk(p->nranks, max_waves, stages, trip_bytes_of(kTripUnrollDefault));
     const bcast_chain_request_t req = {p->lanes_request, stages, (int)trip_bytes_of(kTripUnrollDefault), 0};
-    int rc = bcast_chain_geometry(p->nranks, bytes, chunk, p->max_waves_reduce, &req, info);
+    int rc = bcast_chain_geometry(p->nranks, bytes, chunk, max_waves, &req, info);
     if (rc != BCAST_OK) return rc;
     if (p->nranks >= 2 && bytes > 0 && bytes <= kRedSmallMaxBytes) {
         // small messages: 1 KiB trips (and 16 positions loaded at a time), so more lanes share the work
         const u64 trip = trip_bytes_of(kRedUnrollSmall);
-        const u64 most = (u64)(p->max_waves_reduce / info->stages);
+        const u64 most = (u64)(max_waves / info->stages);
         u64 lanes = p->lanes_request > 0 ? std::min<u64>((u64)p->lanes_request, most)
                                          : std::min<u64>(ceil_div(info->chunk_bytes, trip), most);
         if (p->lanes_request == 0) {
@@ -843,11 +893,29 @@ static int reduce_shape(const bcast_plan *p, size_t bytes, bcast_plan_info_t *in
 extern "C" int bcast_reduce_info(bcast_plan_t *p, size_t count, bcast_plan_info_t *info)
 {
     if (!p || !info || count > p->bytes / sizeof(float)) return BCAST_ERR_ARG;
-    return reduce_shape(p, count * sizeof(float), info);
+    return reduce_shape(p, count * sizeof(float), p->scratch_bytes, p->max_waves_reduce, info);
 }
 
-extern "C" int bcast_reduce_sum_f32(bcast_plan_t *p, const void *const *send_bufs, void *recv_buf, int root, size_t count,
-                                    bcast_stream_t stream)
+extern "C" int bcast_plan_reserve_reduce(bcast_plan_t *p, size_t count, int stages)
+{
+    if (!p || stages < 1 || count > p->bytes / sizeof(float)) return BCAST_ERR_ARG;
+    stages = std::min(stages, std::max(1, p->nranks - 1));
+    const size_t need = (size_t)(stages - 1) * round_up(count * sizeof(float), 256);
+    if (need <= p->scratch_bytes) return BCAST_OK;
+    // earlier runs may still read the old staging memory
+    HIP_TRY(hipDeviceSynchronize());
+    if (p->d_scratch) {
+        HIP_TRY(hipFree(p->d_scratch));
+        p->d_scratch = nullptr;
+        p->scratch_bytes = 0;
+    }
+    HIP_TRY(hipMalloc((void **)&p->d_scratch, need));
+    p->scratch_bytes = need;
+    return BCAST_OK;
+}
+
+// Argument checks shared by the two reduction entry points.
+static int reduce_check(const bcast_plan *p, const void *const *send_bufs, const void *recv_buf, int root, size_t count)
 {
     if (!p || !send_bufs || !recv_buf) return BCAST_ERR_ARG;
     const int P = p->nranks;
@@ -859,53 +927,58 @@ extern "C" int bcast_reduce_sum_f32(bcast_plan_t *p, const void *const *send_buf
         if (!send_bufs[i] || ((uintptr_t)send_bufs[i] & 15u)) return BCAST_ERR_ARG;
     // contributions must not overlap each other; the result may be the root's own
     // contribution (in place) but must not touch any other buffer
-    {
-        uintptr_t at[BCAST_MAX_RANKS + 1];
-        int n = 0;
-        for (int i = 0; i < P; ++i) at[n++] = (uintptr_t)send_bufs[i];
-        if (recv_buf != send_bufs[root]) at[n++] = (uintptr_t)recv_buf;
-        std::sort(at, at + n);
-        for (int i = 0; i + 1 < n; ++i)
-            if (at[i + 1] == at[i] || at[i + 1] - at[i] < bytes) return BCAST_ERR_ARG;
-    }
-    if (bytes == 0) return BCAST_OK;
-    if (P == 1) {
-        if (recv_buf != send_bufs[0]) HIP_TRY(hipMemcpyAsync(recv_buf, send_bufs[0], bytes, hipMemcpyDeviceToDevice, stream));
-        return BCAST_OK;
-    }
-    bcast_plan_info_t info;
-    int rc = reduce_shape(p, bytes, &info);
-    if (rc != BCAST_OK) return rc;
+    uintptr_t at[BCAST_MAX_RANKS + 1];
+    int n = 0;
+    for (int i = 0; i < P; ++i) at[n++] = (uintptr_t)send_bufs[i];
+    if (recv_buf != send_bufs[root]) at[n++] = (uintptr_t)recv_buf;
+    std::sort(at, at + n);
+    for (int i = 0; i + 1 < n; ++i)
+        if (at[i + 1] == at[i] || at[i + 1] - at[i] < bytes) return BCAST_ERR_ARG;
+    return BCAST_OK;
+}
 
-    // one region of the plan's size per stage boundary; (re)allocated when the
-    // stage count grows, which waits for the device
-    const size_t region = round_up(p->bytes, 256);
-    const size_t need = (size_t)(info.stages - 1) * region;
-    if (need > p->scratch_bytes) {
-        HIP_TRY(hipDeviceSynchronize());
-        if (p->d_scratch) {
-            HIP_TRY(hipFree(p->d_scratch));
-            p->d_scratch = nullptr;
-            p->scratch_bytes = 0;
-        }
-        HIP_TRY(hipMalloc((void **)&p->d_scratch, need));
-        p->scratch_bytes = need;
-    }
-
+// Enqueue the reduction kernel with the given flags and staging memory.  Calls
+// nothing that allocates or waits for the device (the flags' once-in-2^32-runs
+// clearing aside, see begin_flag_run).
+static int reduce_enqueue(bcast_plan *p, const void *const *send_bufs, void *recv_buf, int root, size_t bytes,
+                          const bcast_plan_info_t &info, const FlagHome &home, char *staging, size_t staging_bytes, int max_waves,
+                          hipStream_t stream)
+{
+    const int P = p->nranks;
+    const size_t region = round_up(bytes, 256);
+    if ((size_t)(info.stages - 1) * region > staging_bytes) return BCAST_ERR_CAPACITY;
     char *by_pos[BCAST_MAX_RANKS];
     for (int k = 0; k < P; ++k) by_pos[k] = (char *)const_cast<void *>(send_bufs[(root + k) % P]);
     ChainArgs a;
-    rc = begin_flag_run(p, &a, by_pos, bytes, info);
+    int rc = begin_flag_run(p, &a, by_pos, bytes, info, home, stream);
     if (rc != BCAST_OK) return rc;
     a.stages = (unsigned)info.stages;
     a.hops_per_stage = (unsigned)info.hops_per_stage;
     a.unroll = (unsigned)(info.trip_bytes / (kWaveSize * 16));
     a.recv = (char *)recv_buf;
-    a.scratch = p->d_scratch;
+    a.scratch = staging;
     a.scratch_stride = region;
-    if ((u64)a.stages * a.lanes > (u64)p->max_waves_reduce) return BCAST_ERR_ARG;
+    if ((u64)a.stages * a.lanes > (u64)max_waves) return BCAST_ERR_ARG;
     HIP_TRY(launch_reduce(a, info.grid_blocks, stream));
     return BCAST_OK;
+}
+
+extern "C" int bcast_reduce_sum_f32(bcast_plan_t *p, const void *const *send_bufs, void *recv_buf, int root, size_t count,
+                                    bcast_stream_t stream)
+{
+    int rc = reduce_check(p, send_bufs, recv_buf, root, count);
+    if (rc != BCAST_OK) return rc;
+    const size_t bytes = count * sizeof(float);
+    if (bytes == 0) return BCAST_OK;
+    if (p->nranks == 1) {
+        if (recv_buf != send_bufs[0]) HIP_TRY(hipMemcpyAsync(recv_buf, send_bufs[0], bytes, hipMemcpyDeviceToDevice, stream));
+        return BCAST_OK;
+    }
+    bcast_plan_info_t info;
+    rc = reduce_shape(p, bytes, p->scratch_bytes, p->max_waves_reduce, &info);
+    if (rc != BCAST_OK) return rc;
+    return reduce_enqueue(p, send_bufs, recv_buf, root, bytes, info, plan_flags(p), p->d_scratch, p->scratch_bytes,
+                          p->max_waves_reduce, stream);
 }
 
 extern "C" int bcast_allreduce_sum_f32(bcast_plan_t *p, const void *const *send_bufs, void *const *recv_bufs, int root,
@@ -945,6 +1018,7 @@ extern "C" const char *bcast_strerror(int status)
     case BCAST_ERR_HIP: return "HIP runtime call failed";
     case BCAST_ERR_TIMEOUT: return "chain wave gave up waiting for its left neighbour";
     case BCAST_ERR_UNTUNED: return "no tuning table entry for this number of ranks";
+    case BCAST_ERR_CAPACITY: return "staging memory too small for this size and stage count";
     default: return "unknown status";
     }
 }

@@ -7,6 +7,7 @@
 #include <stdint.h>
 
 #include "bcast.h"
+#include "bcast_debug.h"
 
 namespace bcast {
 
@@ -40,6 +41,14 @@ constexpr int kRedUnroll = 4;
 constexpr int kRedUnrollSmall = 1;
 constexpr u64 kRedSmallMaxBytes = 2u << 20;  // measured crossover on MI355X: 2-4 MiB
 
+// Cache-policy bits of the raw-buffer accesses (gfx940-class encoding): sc1
+// marks an access as agent-scope (a load is not served from a line that may be
+// stale in this CU's L1 or this XCD's L2, a store is written through), nt marks
+// it as streaming (not expected to be reused).
+constexpr int kAuxAgent = 16;
+constexpr int kAuxCached = 0;
+constexpr int kAuxStream = 2;
+
 // Wait limit default: 10 s of the 100 MHz constant clock.
 constexpr u64 kDefaultSpinTicks = 1000000000ull;
 
@@ -65,6 +74,11 @@ struct ChainArgs {
     unsigned nranks;
     unsigned mute_hop; // debug: this position never publishes (0 = off)
     unsigned mode;     // kMode* bits
+    // chain kernel: cache-policy bits (kAux*) of its four kinds of access
+    unsigned char ld_root;  // loads of the root's buffer, which nobody writes during the run
+    unsigned char ld_edge;  // loads of what another stage's waves stored: agent scope
+    unsigned char ld_back;  // a wave's read-back of its own stores inside a stage
+    unsigned char st_mid;   // stores the wave itself reads back, and the last position's
     // pipelined k-nomial tree only (tree_kernel): the position each position
     // receives from, and the positions that have children (bit = position)
     unsigned char parent[BCAST_MAX_RANKS];
@@ -107,9 +121,8 @@ constexpr unsigned kModeTrace = 8;
 // caller's request to rotate regardless and never reaches the kernel.
 constexpr unsigned kModeFixedSpans = 16;
 constexpr unsigned kModeRotateSpans = 32;
-// Chosen by the host per run (small messages): write-back stores inside a stage.
-constexpr unsigned kModeStageWriteBack = 4;
-// Largest message that uses it (measured crossover on MI355X: 2-4 MiB).
+// Largest message whose in-stage stores are write-back by default (measured
+// crossover on MI355X: 2-4 MiB).
 constexpr u64 kStageWriteBackMaxBytes = 2u << 20;
 
 // Arguments of the plain copy kernels: up to 32 simultaneous (src -> dst)
@@ -142,12 +155,13 @@ struct RangedCopyArgs {
 // buffer address in the call is congruent modulo vec_bytes.
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream);
 bool valid_chain_block(int block_threads);  // 64, 128 or 256
+bool valid_chain_unroll(int unroll);        // vector instructions per lane and trip the chain kernel is built for
 hipError_t launch_tree(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
 hipError_t launch_reduce(const ChainArgs &a, int grid_blocks, hipStream_t stream);
 hipError_t reduce_max_blocks_per_cu(int *blocks);
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
-hipError_t chain_max_blocks_per_cu(int block_threads, int *blocks, int *blocks_write_back);
+hipError_t chain_max_blocks_per_cu(int block_threads, int *blocks);
 
 }  // namespace bcast

@@ -65,9 +65,6 @@ __device__ __forceinline__ void copy_span(char *__restrict__ dst, const char *__
 // the hand-off needs no L2 write-back / invalidate (which cost microseconds
 // per wave and serialise on the L2).
 // ---------------------------------------------------------------------------
-constexpr int kAuxAgent = 16;               // sc1: agent scope
-constexpr int kAuxCached = 0;               // ordinary cached access
-constexpr int kAuxStream = 2;               // nt: read once, do not keep (measured +6-21 % on the reduction's inputs)
 constexpr int kRsrcWord3 = 0x00020000;      // raw buffer, 32-bit data format
 
 // LD / ST: cache-policy bits of the loads / stores (kAuxAgent or kAuxCached).
@@ -132,6 +129,36 @@ __device__ __forceinline__ void copy_span_agent(char *dst, const char *src, u64 
 #pragma unroll
         for (int u = 0; u < U; ++u) IO::st(r[u], rd, off + u * kWaveSize * V);
     }
+}
+
+// copy_span_agent with the cache policies as run-time (wave-uniform) values: the
+// host picks them per run.  ld and st are each one of kAuxCached, kAuxStream,
+// kAuxAgent, kAuxAgent | kAuxStream.
+template <int V, int U>
+__device__ __forceinline__ void copy_span_policy(char *dst, const char *src, u64 lo, u64 hi, unsigned lane, unsigned ld, unsigned st)
+{
+#define BCAST_POLICY_CASE(LD, ST) \
+    case ((LD) | ((ST) << 8)): copy_span_agent<V, U, (LD), (ST)>(dst, src, lo, hi, lane); break;
+    switch (ld | (st << 8)) {
+        BCAST_POLICY_CASE(kAuxCached, kAuxCached)
+        BCAST_POLICY_CASE(kAuxCached, kAuxStream)
+        BCAST_POLICY_CASE(kAuxCached, kAuxAgent)
+        BCAST_POLICY_CASE(kAuxCached, kAuxAgent | kAuxStream)
+        BCAST_POLICY_CASE(kAuxStream, kAuxCached)
+        BCAST_POLICY_CASE(kAuxStream, kAuxStream)
+        BCAST_POLICY_CASE(kAuxStream, kAuxAgent)
+        BCAST_POLICY_CASE(kAuxStream, kAuxAgent | kAuxStream)
+        BCAST_POLICY_CASE(kAuxAgent, kAuxCached)
+        BCAST_POLICY_CASE(kAuxAgent, kAuxStream)
+        BCAST_POLICY_CASE(kAuxAgent, kAuxAgent)
+        BCAST_POLICY_CASE(kAuxAgent, kAuxAgent | kAuxStream)
+        BCAST_POLICY_CASE(kAuxAgent | kAuxStream, kAuxCached)
+        BCAST_POLICY_CASE(kAuxAgent | kAuxStream, kAuxStream)
+        BCAST_POLICY_CASE(kAuxAgent | kAuxStream, kAuxAgent)
+        BCAST_POLICY_CASE(kAuxAgent | kAuxStream, kAuxAgent | kAuxStream)
+    default: break;  // the host admits no other value
+    }
+#undef BCAST_POLICY_CASE
 }
 
 // Same span, one source, many destinations: each vector is read once and
@@ -258,19 +285,22 @@ __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const Chai
 // Cache policy inside a stage.  A buffer that a wave stores as position h and
 // reads back for position h+1 is touched by no other wave during the kernel, and
 // a wave always sees its own earlier stores once s_waitcnt has passed, whatever
-// cache they sit in.  So the read-back is an ordinary cached load: the
+// cache they sit in.  So the read-back may be an ordinary cached load: the
 // write-through store left the line in this CU's 32 KiB vector L1, and while the
 // trips of the CU's resident waves fit there (8 waves of 3 KiB, 4-8 of 4 KiB)
 // all or most of it is still there -- measured 8-10 TB/s instead of 7.3 TB/s
-// when every load goes to memory.  U (3 or 4 KiB trips) is the host's choice.
-// STAGE_WRITE_BACK (small messages): these buffers, and the chain's last
-// position, are also *stored* with ordinary cached stores; the end of the
-// kernel writes the dirty lines back like for any kernel.  The L2 round trip is
-// about half the memory one, which is what a small broadcast over many hops
-// consists of; for large messages write-back is slower than write-through, so
-// the host only selects it up to a couple of MiB.  Buffers handed from stage to
-// stage are always loaded and stored at agent scope.
-template <int V, int U, bool STAGE_WRITE_BACK>
+// when every load goes to memory.  U (3 or 4 KiB trips) is the host's choice,
+// and so are four cache policies (ChainArgs::ld_root, ld_edge, ld_back, st_mid):
+//   ld_root  loads of the root's buffer (never written during the run: any policy);
+//   ld_edge  loads of a buffer another stage's wave stored (always agent scope);
+//   ld_back  the read-back of the wave's own stores inside a stage;
+//   st_mid   stores a wave reads back itself, and the chain's last position
+//            (write-through at agent scope, or ordinary write-back stores whose
+//            dirty lines the end of the kernel writes back like for any kernel:
+//            the L2 round trip is about half the memory one, which is what a
+//            small broadcast over many hops consists of).
+// Buffers handed from stage to stage are always stored at agent scope.
+template <int V, int U>
 __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 {
     const unsigned lane = threadIdx.x & (kWaveSize - 1);
@@ -343,12 +373,9 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
                 // measured it is 10-25 % slower with 3 KiB trips: loads issued
                 // behind stores still in flight miss the L1.)
                 if (hop != first_hop) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                const bool ld_cached = hop != first_hop;
-                const bool st_cached = STAGE_WRITE_BACK && (hop != last_hop || g + 1 == a.stages);
-                if (ld_cached && st_cached) copy_span_agent<V, U, kAuxCached, kAuxCached>(dst, src, lo, hi, lane);
-                else if (ld_cached) copy_span_agent<V, U, kAuxCached, kAuxAgent>(dst, src, lo, hi, lane);
-                else if (st_cached) copy_span_agent<V, U, kAuxAgent, kAuxCached>(dst, src, lo, hi, lane);
-                else copy_span_agent<V, U>(dst, src, lo, hi, lane);
+                const unsigned ld = hop != first_hop ? a.ld_back : (g == 0 ? a.ld_root : a.ld_edge);
+                const unsigned st = (hop != last_hop || g + 1 == a.stages) ? a.st_mid : (unsigned)kAuxAgent;
+                copy_span_policy<V, U>(dst, src, lo, hi, lane, ld, st);
             }
         }
         // Look at the next chunk's flag while this chunk's stores drain: in
@@ -628,26 +655,24 @@ __global__ void __launch_bounds__(kBlockThreads) fanout_kernel(const CopyArgs a)
 
 bool valid_chain_block(int block_threads) { return block_threads == 64 || block_threads == 128 || block_threads == 256; }
 
+static bool valid_policy(unsigned aux) { return (aux & ~(unsigned)(kAuxAgent | kAuxStream)) == 0; }
+
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream)
 {
     if (grid_blocks < 1 || !valid_chain_block(block_threads)) return hipErrorInvalidValue;
     if ((u64)grid_blocks * (unsigned)(block_threads / kWaveSize) < (u64)a.stages * a.lanes) return hipErrorInvalidValue;
+    // what another stage's wave stored is loaded at agent scope; a wave's own
+    // write-back stores are not read back at agent scope
+    if (!valid_policy(a.ld_root) || !valid_policy(a.ld_edge) || !valid_policy(a.ld_back) || !valid_policy(a.st_mid)) return hipErrorInvalidValue;
+    if (!(a.ld_edge & kAuxAgent)) return hipErrorInvalidValue;
+    if (!(a.st_mid & kAuxAgent) && (a.ld_back & kAuxAgent)) return hipErrorInvalidValue;
     const dim3 grid(grid_blocks), block(block_threads);
-    const bool wb = (a.mode & kModeStageWriteBack) != 0;
-    if (a.unroll == (unsigned)kTripUnrollSmall) {
-        if (wb) {
-            BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, kTripUnrollSmall, true);
-        } else {
-            BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, kTripUnrollSmall, false);
-        }
-    } else if (a.unroll == (unsigned)kTripUnrollDefault) {
-        if (wb) {
-            BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, kTripUnrollDefault, true);
-        } else {
-            BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, kTripUnrollDefault, false);
-        }
-    } else {
-        return hipErrorInvalidValue;
+    switch (a.unroll) {
+    case 2: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, 2); break;
+    case 3: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, 3); break;
+    case 4: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, 4); break;
+    case 6: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, 6); break;
+    default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
@@ -703,11 +728,19 @@ hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x
     return hipGetLastError();
 }
 
-hipError_t chain_max_blocks_per_cu(int block_threads, int *blocks, int *blocks_write_back)
+bool valid_chain_unroll(int unroll) { return unroll == 2 || unroll == 3 || unroll == 4 || unroll == 6; }
+
+hipError_t chain_max_blocks_per_cu(int block_threads, int *blocks)
 {
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, chain_kernel<16, kTripUnrollDefault, false>, block_threads, 0);
-    if (e == hipSuccess)
-        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_write_back, chain_kernel<16, kTripUnrollDefault, true>, block_threads, 0);
+    // the smallest over the trip sizes the kernel is built for
+    int n[4] = {0, 0, 0, 0};
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[0], chain_kernel<16, 2>, block_threads, 0);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[1], chain_kernel<16, 3>, block_threads, 0);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[2], chain_kernel<16, 4>, block_threads, 0);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[3], chain_kernel<16, 6>, block_threads, 0);
+    *blocks = n[0];
+    for (int x : n)
+        if (x < *blocks) *blocks = x;
     return e;
 }
 

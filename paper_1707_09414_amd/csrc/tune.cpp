@@ -42,7 +42,7 @@ static bool valid_entry(int nranks, const bcast_tune_entry_t &e)
     if (e.chain_chunk_bytes % 16 != 0) return false;
     if (e.stages < 0 || e.stages > BCAST_MAX_RANKS || e.chain_stages < 0 || e.chain_stages > BCAST_MAX_RANKS) return false;
     for (int t : {e.trip_bytes, e.chain_trip_bytes})
-        if (t != 0 && t != 3072 && t != 4096) return false;
+        if (t != 0 && (t % 1024 != 0 || !valid_chain_unroll(t / 1024))) return false;
     return true;
 }
 

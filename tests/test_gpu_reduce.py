@@ -53,6 +53,8 @@ def reduce_and_check(P, root, count, C, seed=0, stages=0, lanes=0, in_place=Fals
             B.bcast_plan_set_stages(plan, stages)
         if lanes:
             B.bcast_plan_set_lanes(plan, lanes)
+        # staging memory for the running sums between stages: reserved up front, the run path never allocates
+        B.bcast_plan_reserve_reduce(plan, cap, max(2, stages))
         info = B.bcast_reduce_info(plan, count)
         B.bcast_reduce_sum_f32(plan, ptrs, recv_t.data_ptr() + 4 * GUARD, root, count, torch.cuda.current_stream())
         torch.cuda.synchronize()
@@ -115,7 +117,7 @@ def test_degenerate_and_repeated_runs():
     reduce_and_check(4, 2, 0, 4096, cap=1024)
     reduce_and_check(1, 0, 1000, 4096)
     reduce_and_check(1, 0, 1000, 4096, in_place=True)
-    # one plan, many runs: growing stage counts re-allocate the scratch memory, sizes change, flags are reused
+    # one plan, many runs: growing stage counts re-reserve the staging memory, sizes change, flags are reused
     P, cap = 9, 200000
     plan = B.bcast_plan_create(P, cap * 4, 16 * KiB, B.BCAST_ALGO_CHAIN)
     for i, (stages, count) in enumerate([(1, 1000), (2, cap), (5, 77777), (8, 12345), (2, cap), (3, 4)]):
@@ -159,6 +161,7 @@ def test_wait_limit_in_the_reduction():
     recv = torch.zeros(count, dtype=torch.float32, device="cuda")
     plan = B.bcast_plan_create(P, count * 4, 16 * KiB, B.BCAST_ALGO_CHAIN)
     B.bcast_plan_set_stages(plan, 3)       # hops 1-2, 3-4, 5-6
+    B.bcast_plan_reserve_reduce(plan, count, 3)
     B.bcast_plan_set_debug(plan, 200000, 3)  # the stage that plays hop 3 stays silent; 2 ms limit
     B.bcast_reduce_sum_f32(plan, dev, recv, 0, count)
     torch.cuda.synchronize()
@@ -188,6 +191,7 @@ def test_vgg16_gradient_sized_reduction_p16():
         dev.append(torch.from_numpy(host[r]).cuda())
     recv = torch.empty(count, dtype=torch.float32, device="cuda")
     plan = B.bcast_plan_create(P, count * 4, 0, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_reserve_reduce(plan, count, 2)
     info = B.bcast_reduce_info(plan, count)
     B.bcast_reduce_sum_f32(plan, dev, recv, root, count, torch.cuda.current_stream())
     torch.cuda.synchronize()
@@ -205,6 +209,8 @@ def test_allreduce_is_reduce_then_broadcast(P, root, count, in_place):
     dev = [torch.from_numpy(send[r]).cuda() for r in range(P)]
     recv = dev if in_place else [torch.full((count,), float(CANARY), dtype=torch.float32, device="cuda") for _ in range(P)]
     plan = B.bcast_plan_create(P, count * 4, 64 * KiB, B.BCAST_ALGO_CHAIN)
+    if P % 2 == 0 and count > 5:
+        B.bcast_plan_reserve_reduce(plan, count, 2)   # else: no staging memory, the reduction runs in one stage
     B.bcast_allreduce_sum_f32(plan, dev, recv, root, count, torch.cuda.current_stream())
     torch.cuda.synchronize()
     assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
@@ -217,6 +223,43 @@ def test_allreduce_is_reduce_then_broadcast(P, root, count, in_place):
     if not in_place:
         with pytest.raises(B.BcastError):
             B.bcast_allreduce_sum_f32(plan, dev, [dev[(r + 1) % P] for r in range(P)], root, count)
+    plan.destroy()
+
+
+def test_staging_memory_is_reserved_never_allocated_by_a_run():
+    """Without a reservation the library's own choice is one stage (no staging
+    memory needed); a stage count the caller asks for beyond the reservation is
+    refused and launches nothing; the reservation grows on request."""
+    P, count = 6, 50000
+    send = contributions(5, P, count)
+    dev = [torch.from_numpy(send[r]).cuda() for r in range(P)]
+    recv = torch.full((count,), 7.0, dtype=torch.float32, device="cuda")
+    want, _ = oracle.chain_reduce_f32(send, P, 2, count, 4 * KiB)
+    plan = B.bcast_plan_create(P, count * 4, 16 * KiB, B.BCAST_ALGO_CHAIN)
+    assert B.bcast_reduce_info(plan, count)["stages"] == 1
+    B.bcast_reduce_sum_f32(plan, dev, recv, 2, count)
+    torch.cuda.synchronize()
+    assert np.array_equal(recv.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    recv.fill_(7.0)
+    B.bcast_plan_set_stages(plan, 3)
+    assert B.bcast_reduce_status(plan, dev, recv, 2, count) == B.BCAST_ERR_CAPACITY
+    B.bcast_plan_reserve_reduce(plan, count // 2, 3)          # enough for half the size only
+    assert B.bcast_reduce_status(plan, dev, recv, 2, count) == B.BCAST_ERR_CAPACITY
+    torch.cuda.synchronize()
+    assert bool((recv == 7.0).all())
+    B.bcast_reduce_sum_f32(plan, dev, recv, 2, count // 2)
+    torch.cuda.synchronize()
+    assert np.array_equal(recv[: count // 2].cpu().numpy().view(np.uint32), want[: count // 2].view(np.uint32))
+    assert bool((recv[count // 2:] == 7.0).all())
+    B.bcast_plan_reserve_reduce(plan, count, 3)
+    assert B.bcast_reduce_info(plan, count)["stages"] == 3
+    B.bcast_reduce_sum_f32(plan, dev, recv, 2, count)
+    torch.cuda.synchronize()
+    assert np.array_equal(recv.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    with pytest.raises(B.BcastError):
+        B.bcast_plan_reserve_reduce(plan, count + 1, 2)       # beyond the plan's size
+    with pytest.raises(B.BcastError):
+        B.bcast_plan_reserve_reduce(plan, count, 0)
     plan.destroy()
 
 

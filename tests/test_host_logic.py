@@ -13,7 +13,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "bcast.h")).read()
+    headers = sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
+    assert "bcast.h" in headers and "bcast_debug.h" in headers
+    header = "".join(open(os.path.join(ROOT, "include", f)).read() for f in headers)
     # strip comments, then collect identifiers followed by '(' at declaration level
     code = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(bcast_[a-z_0-9]+)\s*\(", code))
@@ -73,8 +75,10 @@ def test_chain_geometry_matches_eq5_chunking():
     assert (g["trip_bytes"], g["lanes"], g["slice_bytes"], g["nchunks"]) == (3072, 1024, 3072, 342)
     g = B.bcast_chain_geometry(64, 1 << 30, 3 << 20, 8192, stages_request=2, trip_request=4096)
     assert (g["lanes"], g["slice_bytes"]) == (512, 8192)  # 768 trips: the next power of two below
-    with pytest.raises(B.BcastError):
-        B.bcast_chain_geometry(8, 1 << 20, 4096, 64, trip_request=2048)
+    for bad_trip in (1024, 5120, 3000, 8192):  # built for 2, 3, 4 and 6 KiB
+        with pytest.raises(B.BcastError):
+            B.bcast_chain_geometry(8, 1 << 20, 4096, 64, trip_request=bad_trip)
+    assert B.bcast_chain_geometry(8, 1 << 20, 64 << 10, 64, trip_request=2048)["trip_bytes"] == 2048
     # workgroups of 1, 2 or 4 wavefronts: same waves, more blocks
     for block, blocks in ((64, 2048), (128, 1024), (256, 512), (0, 512)):
         g = B.bcast_chain_geometry(64, 1 << 30, 3 << 20, 8192, stages_request=2, trip_request=3072, block_request=block)
@@ -162,7 +166,7 @@ def test_tuning_table_lookup_rules(tmp_path):
     with pytest.raises(B.BcastError):
         B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_DIRECT, chain_stages=65)
     with pytest.raises(B.BcastError):
-        B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=4096, trip_bytes=2048)
+        B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=4096, trip_bytes=5120)
     B.bcast_tune_put(16, 1 << 24, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=3 << 20, stages=2, trip_bytes=3072, usec=80.0)
 
     path = tmp_path / "table.txt"
