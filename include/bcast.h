@@ -61,8 +61,8 @@ typedef enum {
     BCAST_ERR_HIP = -3,     /* a HIP runtime call failed; see bcast_last_hip_error() */
     BCAST_ERR_TIMEOUT = -4, /* a chain wave gave up waiting for its left neighbour */
     BCAST_ERR_UNTUNED = -5, /* BCAST_ALGO_AUTO but the table has no entry for this nranks */
-    BCAST_ERR_CAPACITY = -6 /* the staging memory reserved for the plan cannot carry this size at
-                               this stage count; nothing was enqueued */
+    BCAST_ERR_CAPACITY = -6 /* the staging memory at hand (reserved for the plan, or the library's static
+                               array) cannot carry this size at this stage count; nothing was enqueued */
 } bcast_status_t;
 
 /* What a plan will launch for a given message size (host-side bookkeeping). */
@@ -224,6 +224,28 @@ int bcast_reduce_sum_f32(bcast_plan_t *plan, const void *const *send_bufs, void 
  * old memory and allocates (stages - 1) * round_up(count * 4, 256) bytes.
  * Errors: ERR_ARG (count * 4 beyond the plan's bytes), ERR_NOMEM, ERR_HIP. */
 int bcast_plan_reserve_reduce(bcast_plan_t *plan, size_t count, int stages);
+/*
+ * bcast_reduce_sum_f32_static -- bcast_reduce_sum_f32 for callers that cannot
+ * allocate device memory at all: code running under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result
+ * bits, same argument checks.  It allocates nothing and needs no reservation:
+ * ready flags and staging memory come out of one array in the library's own
+ * data segment (about 33 MiB per GPU the library runs on, held until the
+ * process ends), whose address on the plan's device was looked up when the plan
+ * was created.  Limits: (stages - 1) * round_up(count * 4, 256) <= 32 MiB of
+ * staging (so 8 Mi floats in two stages, any size in one stage) and at most
+ * 8192 wavefronts; a stage count set with bcast_plan_set_stages beyond that
+ * fails with BCAST_ERR_CAPACITY and enqueues nothing, the library's own choice
+ * shrinks to what fits.  The plan's device must be the current device.
+ * Every call on a GPU shares that GPU's array: calls that overlap in time on
+ * one GPU (two streams, two threads, two plans) race and give undefined
+ * results; calls that follow one another in stream order are fine -- runs are
+ * told apart by a per-device run count in the flag words, nothing needs to be
+ * cleared between them (once in 2^32 - 2 runs a fill kernel on `stream` clears
+ * the flags).  Timeouts surface through the plan's status word as usual.
+ */
+int bcast_reduce_sum_f32_static(bcast_plan_t *plan, const void *const *send_bufs, void *recv_buf, int root, size_t count,
+                                bcast_stream_t stream);
 /* MPI_Allreduce (sum of fp32) as the two chains one after the other on `stream`:
  * bcast_reduce_sum_f32 into recv_bufs[root], then bcast_run of that result to
  * every recv_bufs[r] with the plan's broadcast algorithm (an AUTO plan needs a

@@ -41,7 +41,7 @@ BCAST_ERR_CAPACITY = -6
 # every symbol include/bcast.h and include/bcast_debug.h declare
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
-    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_plan_reserve_reduce", "bcast_allreduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
+    "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_reduce_sum_f32_static", "bcast_plan_reserve_reduce", "bcast_allreduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
     "bcast_plan_handoff_counts", "bcast_plan_set_cache_policy", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
@@ -125,6 +125,7 @@ def _load():
         "bcast_plan_set_trip": ([vp, i], i),
         "bcast_reduce_sum_f32": ([vp, ctypes.POINTER(ctypes.c_void_p), vp, i, sz, vp], i),
         "bcast_reduce_info": ([vp, sz, ctypes.POINTER(PlanInfo)], i),
+        "bcast_reduce_sum_f32_static": ([vp, ctypes.POINTER(ctypes.c_void_p), vp, i, sz, vp], i),
         "bcast_plan_reserve_reduce": ([vp, sz, i], i),
         "bcast_allreduce_sum_f32": ([vp, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p), i, sz, vp], i),
         "bcast_chain_stage_span": ([i, i, i, ctypes.c_uint64, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)], i),
@@ -284,6 +285,18 @@ def bcast_reduce_sum_f32(plan: Plan, send_bufs, recv_buf, root: int, count: int,
         raise BcastError(BCAST_ERR_ARG, "bcast_reduce_sum_f32: need %d buffers, got %d" % (plan.nranks, len(send_bufs)))
     _check(_lib.bcast_reduce_sum_f32(plan.handle, _ptr_array(send_bufs), _ptr(recv_buf), root, count, _stream(stream)),
            "bcast_reduce_sum_f32")
+
+
+def bcast_reduce_sum_f32_static(plan: Plan, send_bufs, recv_buf, root: int, count: int, stream=None) -> None:
+    if len(send_bufs) != plan.nranks:
+        raise BcastError(BCAST_ERR_ARG, "bcast_reduce_sum_f32_static: need %d buffers, got %d" % (plan.nranks, len(send_bufs)))
+    _check(_lib.bcast_reduce_sum_f32_static(plan.handle, _ptr_array(send_bufs), _ptr(recv_buf), root, count, _stream(stream)),
+           "bcast_reduce_sum_f32_static")
+
+
+def bcast_reduce_static_status(plan: Plan, send_bufs, recv_buf, root: int, count: int, stream=None) -> int:
+    """Like bcast_reduce_sum_f32_static but returns the status code instead of raising."""
+    return _lib.bcast_reduce_sum_f32_static(plan.handle, _ptr_array(send_bufs), _ptr(recv_buf), root, count, _stream(stream))
 
 
 def bcast_plan_reserve_reduce(plan: Plan, count: int, stages: int) -> None:

@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "bcast_internal.h"
@@ -25,6 +26,7 @@ struct bcast_plan {
     int max_waves_reduce = 0;             // the same limit for the reduction kernel (256-thread workgroups)
     char *d_scratch = nullptr;            // reduction: running sums handed from stage to stage
     size_t scratch_bytes = 0;             // (bcast_plan_reserve_reduce; the run path never allocates)
+    char *static_scratch = nullptr;       // this device's copy of the library's static scratch array
     u64 *d_flags = nullptr;  // max_waves flags, kFlagStrideWords apart, plus the abort word
     u64 *d_abort = nullptr;
     u64 *d_counters = nullptr; // two words after the abort word
@@ -234,6 +236,9 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
             p->d_counters = p->d_abort + kFlagStrideWords;
         }
     }
+    // set-up for bcast_reduce_sum_f32_static: the address of this device's copy of
+    // the static scratch array, looked up while the device is current
+    if (e == hipSuccess) e = static_scratch_address(p->device, &p->static_scratch);
     if (e == hipSuccess) e = hipHostMalloc((void **)&p->h_status, 2 * sizeof(u64), hipHostMallocMapped);
     if (e == hipSuccess) {
         p->h_status[0] = p->h_status[1] = 0;
@@ -647,18 +652,23 @@ extern "C" int bcast_plan_info(bcast_plan_t *p, void *const *rank_bufs, size_t b
 }
 
 // Where a run's ready flags live and which run counter tells its runs apart:
-// the plan's own.
+// the plan's own, or (bcast_reduce_sum_f32_static) the static scratch array's,
+// whose counter is per device because every plan on the device shares the array.
 struct FlagHome {
     u64 *flags;
     u64 *abort_word;
     u64 *epoch;      // host counter of runs that used these flags
     u64 clear_words; // 64-bit words from `flags` on to clear before the counter wraps
+    bool own_memory; // plan-owned: may wait for the device and memset; else a fill kernel on the run's stream
 };
+
+static std::mutex g_static_mu;
+static u64 g_static_epoch[kStaticMaxDevices];
 
 // What the chain, the pipelined tree and the reduction share: buffers by
 // position, ready flags, status words and wait limit, the chunking, and a fresh epoch.
 static int begin_flag_run(bcast_plan *p, ChainArgs *a, char *const *by_pos, size_t bytes, const bcast_plan_info_t &info,
-                          const FlagHome &home, hipStream_t)
+                          const FlagHome &home, hipStream_t stream)
 {
     memset(a, 0, sizeof *a);
     memcpy(a->buf, by_pos, sizeof(char *) * p->nranks);
@@ -675,12 +685,19 @@ static int begin_flag_run(bcast_plan *p, ChainArgs *a, char *const *by_pos, size
     if (a->nchunks == 0 || a->lanes == 0 || a->chunk_bytes == 0) return BCAST_ERR_ARG;
     if ((u64)a->nchunks * a->chunk_bytes < a->bytes) return BCAST_ERR_ARG;
     // the flag word keeps the epoch in its upper 32 bits: before that would
-    // wrap (after 2^32 - 2 runs on these flags), let the device drain, clear
-    // the flags and the abort word, and count from one again
+    // wrap (after 2^32 - 2 runs on these flags), clear the flags and the abort
+    // word and count from one again.  Plan-owned flags: let the device drain
+    // first.  The static array: a fill kernel on this run's stream, which is in
+    // order with every earlier run on it (runs that overlap are the caller's
+    // responsibility there), allocates nothing and may be captured.
     if (*home.epoch >= kEpochLimit) {
-        HIP_TRY(hipDeviceSynchronize());
-        HIP_TRY(hipMemset(home.flags, 0, home.clear_words * sizeof(u64)));
-        HIP_TRY(hipDeviceSynchronize());
+        if (home.own_memory) {
+            HIP_TRY(hipDeviceSynchronize());
+            HIP_TRY(hipMemset(home.flags, 0, home.clear_words * sizeof(u64)));
+            HIP_TRY(hipDeviceSynchronize());
+        } else {
+            HIP_TRY(launch_zero_words(home.flags, home.clear_words, stream));
+        }
         *home.epoch = 0;
     }
     a->base = (++*home.epoch) << 32;
@@ -689,7 +706,7 @@ static int begin_flag_run(bcast_plan *p, ChainArgs *a, char *const *by_pos, size
 
 static FlagHome plan_flags(bcast_plan *p)
 {
-    return FlagHome{p->d_flags, p->d_abort, &p->epoch, ((u64)p->max_flags + 2) * kFlagStrideWords};
+    return FlagHome{p->d_flags, p->d_abort, &p->epoch, ((u64)p->max_flags + 2) * kFlagStrideWords, true};
 }
 
 extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size_t bytes, bcast_stream_t stream)
@@ -981,6 +998,34 @@ extern "C" int bcast_reduce_sum_f32(bcast_plan_t *p, const void *const *send_buf
                           p->max_waves_reduce, stream);
 }
 
+extern "C" int bcast_reduce_sum_f32_static(bcast_plan_t *p, const void *const *send_bufs, void *recv_buf, int root, size_t count,
+                                           bcast_stream_t stream)
+{
+    int rc = reduce_check(p, send_bufs, recv_buf, root, count);
+    if (rc != BCAST_OK) return rc;
+    const size_t bytes = count * sizeof(float);
+    if (bytes == 0) return BCAST_OK;
+    if (p->nranks == 1) {
+        if (recv_buf != send_bufs[0]) HIP_TRY(hipMemcpyAsync(recv_buf, send_bufs[0], bytes, hipMemcpyDeviceToDevice, stream));
+        return BCAST_OK;
+    }
+    // the static array of the device the plan was made on (its address was looked
+    // up at plan creation): flags first, staging after them
+    int device = -1;
+    HIP_TRY(hipGetDevice(&device));
+    if (device != p->device || !p->static_scratch || device < 0 || device >= kStaticMaxDevices) return BCAST_ERR_ARG;
+    const int max_waves = std::min(p->max_waves_reduce, kStaticFlagWaves);
+    bcast_plan_info_t info;
+    rc = reduce_shape(p, bytes, (size_t)kStaticStagingBytes, max_waves, &info);
+    if (rc != BCAST_OK) return rc;
+    u64 *flags = reinterpret_cast<u64 *>(p->static_scratch);
+    std::lock_guard<std::mutex> g(g_static_mu);
+    const FlagHome home{flags, flags + (u64)kStaticFlagWaves * kFlagStrideWords, &g_static_epoch[device],
+                        kStaticFlagBytes / sizeof(u64), false};
+    return reduce_enqueue(p, send_bufs, recv_buf, root, bytes, info, home, p->static_scratch + kStaticFlagBytes,
+                          (size_t)kStaticStagingBytes, max_waves, stream);
+}
+
 extern "C" int bcast_allreduce_sum_f32(bcast_plan_t *p, const void *const *send_bufs, void *const *recv_bufs, int root,
                                        size_t count, bcast_stream_t stream)
 {
@@ -1018,7 +1063,7 @@ extern "C" const char *bcast_strerror(int status)
     case BCAST_ERR_HIP: return "HIP runtime call failed";
     case BCAST_ERR_TIMEOUT: return "chain wave gave up waiting for its left neighbour";
     case BCAST_ERR_UNTUNED: return "no tuning table entry for this number of ranks";
-    case BCAST_ERR_CAPACITY: return "staging memory too small for this size and stage count";
+    case BCAST_ERR_CAPACITY: return "staging memory too small for this size and stage count (reserve more, or beyond the static array's limit)";
     default: return "unknown status";
     }
 }

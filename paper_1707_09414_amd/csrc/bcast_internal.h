@@ -151,6 +151,18 @@ struct RangedCopyArgs {
     unsigned npairs;
 };
 
+// The statically allocated scratch array (kernels.hip): flag lines, then staging.
+constexpr int kStaticFlagWaves = 8192;                                  // ready flags it holds
+constexpr u64 kStaticFlagLines = (u64)kStaticFlagWaves + 2;             // + abort word + one spare line
+constexpr u64 kStaticFlagBytes = kStaticFlagLines * kFlagStrideWords * sizeof(u64);
+constexpr u64 kStaticStagingBytes = 32ull << 20;                        // running sums between stages
+constexpr u64 kStaticScratchBytes = kStaticFlagBytes + kStaticStagingBytes;
+constexpr int kStaticMaxDevices = 64;
+// Device address of the current device's copy of the array (looked up once per
+// device; `device` must be the current device on that first call).
+hipError_t static_scratch_address(int device, char **ptr);
+hipError_t launch_zero_words(u64 *dst, u64 words, hipStream_t stream);
+
 // Launchers implemented in kernels.hip.  vec_bytes is 16, 8, 4 or 1: every
 // buffer address in the call is congruent modulo vec_bytes.
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream);

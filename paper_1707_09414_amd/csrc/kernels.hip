@@ -5,6 +5,9 @@
 // accesses per lane (1 KiB per wave instruction, kUnroll of them in flight),
 // and byte accesses for a head/tail that is not 16-byte aligned.  There are no
 // workgroup barriers and no LDS: the path is bound by HBM, not by arithmetic.
+#include <algorithm>
+#include <mutex>
+
 #include "bcast_internal.h"
 
 namespace bcast {
@@ -725,6 +728,65 @@ hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x
 {
     if (grid_x < 1 || a.npairs < 1 || a.npairs > BCAST_MAX_RANKS) return hipErrorInvalidValue;
     BCAST_LAUNCH_V(ranged_copy_kernel, vec_bytes, dim3(grid_x, a.npairs), stream, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Scratch memory that exists without any allocation call: one array in the
+// code object's data segment, for the entry point that callers use who cannot
+// allocate (bcast_reduce_sum_f32_static).  Layout: the ready flags and the
+// abort word first (kStaticFlagLines lines of 128 bytes), then the staging area
+// for the running sums that cross a stage boundary (kStaticStagingBytes).  Every
+// GPU the library runs on holds its own copy, zero-filled when the code object
+// is loaded, until the process ends.  In host code the array's name is only a
+// handle for hipGetSymbolAddress: the address of a device's copy is looked up
+// once per device, with that device current, and that pointer is what every
+// launch, fill and copy uses.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+struct StaticScratchSlot {
+    char *ptr = nullptr;
+    bool looked_up = false;
+};
+StaticScratchSlot g_static_slot[kStaticMaxDevices];
+std::mutex g_static_mu;
+}  // namespace
+
+hipError_t static_scratch_address(int device, char **ptr)
+{
+    if (!ptr || device < 0 || device >= kStaticMaxDevices) return hipErrorInvalidValue;
+    std::lock_guard<std::mutex> g(g_static_mu);
+    StaticScratchSlot &slot = g_static_slot[device];
+    if (!slot.looked_up) {
+        int current = -1;
+        hipError_t e = hipGetDevice(&current);
+        if (e != hipSuccess) return e;
+        if (current != device) return hipErrorInvalidDevice;  // the look-up answers for the current device
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p || ((uintptr_t)p & 255u)) return hipErrorInvalidSymbol;
+        slot.ptr = (char *)p;
+        slot.looked_up = true;
+    }
+    *ptr = slot.ptr;
+    return hipSuccess;
+}
+
+// Clears `words` 64-bit words at `dst` on `stream` with a kernel (a fill that a
+// captured graph replays correctly, and no allocation).
+__global__ void __launch_bounds__(kBlockThreads) zero_words_kernel(u64 *dst, u64 words)
+{
+    for (u64 i = (u64)blockIdx.x * kBlockThreads + threadIdx.x; i < words; i += (u64)gridDim.x * kBlockThreads) dst[i] = 0;
+}
+
+hipError_t launch_zero_words(u64 *dst, u64 words, hipStream_t stream)
+{
+    if (!dst || words == 0) return hipErrorInvalidValue;
+    const unsigned blocks = (unsigned)std::min<u64>(1024, (words + kBlockThreads - 1) / kBlockThreads);
+    zero_words_kernel<<<dim3(blocks), dim3(kBlockThreads), 0, stream>>>(dst, words);
     return hipGetLastError();
 }
 
