@@ -82,6 +82,8 @@ typedef struct {
     int vec_bytes;         /* widest access usable for these pointers: 16, 8, 4 or 1 */
     int launches;          /* kernel launches per bcast_run */
     uint64_t algorithmic_bytes; /* HBM bytes the schedule must move: reads + writes */
+    int rank_waves;        /* chain: 1 if every rank has wavefronts of its own (a stage is a workgroup of
+                              hops_per_stage wavefronts), 0 if one wavefront plays its stage's ranks in turn */
 } bcast_plan_info_t;
 
 /*
@@ -160,9 +162,29 @@ int bcast_plan_destroy(bcast_plan_t *plan);
  * play one hop more rotate from chunk to chunk, so the stage boundaries differ
  * between chunks).  Test and diagnostic hooks are declared in bcast_debug.h. */
 int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
+/* How a stage of the chain is executed (Sec. IV-B).
+ * BCAST_CHAIN_WAVE_PER_RANK: every receiving rank has wavefronts of its own --
+ * the literal picture of the section: receive a piece from the left neighbour,
+ * store it, tell the right neighbour.  A stage is a workgroup of up to 16
+ * wavefronts, one per consecutive rank, on one compute unit; neighbours inside
+ * it hand a trip (the pipelining unit there, bcast_plan_set_trip) over with a
+ * workgroup-scope release/acquire on a counter in LDS and the payload moves
+ * through the compute unit's cache; between stages whole chunks are handed over
+ * through the ready flags in memory.  stages = 0 then means: as few stages as
+ * 8 ranks per workgroup allow (at least ceil((nranks-1)/16) are needed).
+ * BCAST_CHAIN_WAVE_PER_STAGE: one wavefront plays all ranks of its stage in
+ * turn, reading back from each rank's buffer what it stored there.
+ * BCAST_CHAIN_AUTO (default): the tuning table's choice, else WAVE_PER_STAGE.
+ * The bytes every rank ends up with are the same in all modes. */
+#define BCAST_CHAIN_AUTO 0
+#define BCAST_CHAIN_WAVE_PER_STAGE 1
+#define BCAST_CHAIN_WAVE_PER_RANK 2
+int bcast_plan_set_chain_waves(bcast_plan_t *plan, int mode);
 int bcast_plan_set_stages(bcast_plan_t *plan, int stages);
-/* Bytes a chain wavefront moves per trip (16-byte accesses): 4096 or 3072,
- * 0 = the tuning table's choice, else 4096. */
+/* Bytes a chain wavefront moves per trip (16-byte accesses): a multiple of
+ * 1024 the run's kernel is built for (2048, 3072, 4096 or 6144 with a wavefront
+ * per stage; 1024, 2048, 3072, 4096, 6144 or 8192 with a wavefront per rank),
+ * 0 = the tuning table's choice, else 4096 (8192 with a wavefront per rank). */
 int bcast_plan_set_trip(bcast_plan_t *plan, int trip_bytes);
 /* Threads per workgroup of the chain kernel: 64, 128 or 256 (1, 2 or 4
  * wavefronts; they never synchronise, the workgroup is only the unit placed on
@@ -277,8 +299,8 @@ int bcast_chain_stage_span(int nranks, int stages, int stage, uint64_t chunk, in
  * measurements).  Process-wide; entries are keyed by (nranks, floor(log2 bytes)).
  *
  * bcast_tune measures, on the current device and `stream`, every candidate
- * (chain over chunk sizes 8 KiB..64 MiB, stage counts and both trip sizes,
- * direct, binomial, and
+ * (chain over chunk sizes 8 KiB..64 MiB, stage counts and trip sizes, with a
+ * wavefront per stage and with a wavefront per rank, direct, binomial, and
  * -- only if `algo_mask` has their bits -- the fan-out, scatter + allgather,
  * the k-nomial tree at radix 4 and 8 and the one-launch pipelined k-nomial
  * tree at radix 2, 4 and 8) for message sizes that are
@@ -292,6 +314,8 @@ int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsigned algo_mas
 /* algo_mask flag: also try the chain with a single stage (one wavefront plays
  * every rank of its share in turn; no flag hand-off is left). */
 #define BCAST_TUNE_FOLDED (1u << 16)
+/* algo_mask flag: leave out the chain with a wavefront per rank. */
+#define BCAST_TUNE_NO_RANK_WAVES (1u << 17)
 
 /* One table entry: the fastest candidate for the bucket and, beside it, the
  * chain's own best setting (whoever won), which a CHAIN plan with
@@ -306,10 +330,12 @@ typedef struct {
     int chain_stages;           /* chain: best stage count */
     int chain_trip_bytes;       /* chain: best trip size (0 = default) */
     double chain_usec;          /* chain: time at that setting */
+    int rank_waves;             /* winner is the chain with a wavefront per rank (1) or per stage (0) */
+    int chain_rank_waves;       /* the same for the chain's own best setting */
 } bcast_tune_entry_t;
 
 /* While a log path (HOST, NULL = off) is set, bcast_tune appends one line per
- * candidate it times: "nranks bytes algo chunk_bytes stages usec trip_bytes"
+ * candidate it times: "nranks bytes algo chunk_bytes stages usec trip_bytes rank_waves"
  * (stages holds the radix for the k-nomial trees) -- the raw
  * material for fitting the cost models of Sec. III-A / IV-B. */
 int bcast_tune_set_log(const char *log_path);

@@ -42,7 +42,7 @@ BCAST_ERR_CAPACITY = -6
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
     "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_reduce_sum_f32_static", "bcast_plan_reserve_reduce", "bcast_allreduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
-    "bcast_plan_handoff_counts", "bcast_plan_set_cache_policy", "bcast_chain_geometry",
+    "bcast_plan_handoff_counts", "bcast_plan_set_cache_policy", "bcast_plan_set_chain_waves", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
 ]
@@ -77,6 +77,7 @@ class PlanInfo(ctypes.Structure):
         ("vec_bytes", ctypes.c_int),
         ("launches", ctypes.c_int),
         ("algorithmic_bytes", ctypes.c_uint64),
+        ("rank_waves", ctypes.c_int),
     ]
 
     def as_dict(self):
@@ -94,6 +95,8 @@ class TuneEntry(ctypes.Structure):
         ("chain_stages", ctypes.c_int),
         ("chain_trip_bytes", ctypes.c_int),
         ("chain_usec", ctypes.c_double),
+        ("rank_waves", ctypes.c_int),
+        ("chain_rank_waves", ctypes.c_int),
     ]
 
     def as_dict(self):
@@ -101,6 +104,7 @@ class TuneEntry(ctypes.Structure):
 
 
 BCAST_TUNE_FOLDED = 1 << 16
+BCAST_TUNE_NO_RANK_WAVES = 1 << 17
 
 
 def _load():
@@ -134,6 +138,7 @@ def _load():
         "bcast_plan_set_debug": ([vp, u64, i], i),
         "bcast_plan_set_mode": ([vp, ctypes.c_uint], i),
         "bcast_plan_set_cache_policy": ([vp, i, i, i, i], i),
+        "bcast_plan_set_chain_waves": ([vp, i], i),
         "bcast_plan_enable_trace": ([vp, sz], i),
         "bcast_plan_read_trace": ([vp, ctypes.POINTER(u64), sz], i),
         "bcast_plan_handoff_counts": ([vp, ctypes.POINTER(u64), ctypes.POINTER(u64)], i),
@@ -357,6 +362,15 @@ BCAST_CACHE_AGENT = 16
 
 def bcast_plan_set_cache_policy(plan: Plan, ld_root: int = -1, ld_edge: int = -1, ld_back: int = -1, st_mid: int = -1) -> None:
     _check(_lib.bcast_plan_set_cache_policy(plan.handle, ld_root, ld_edge, ld_back, st_mid), "bcast_plan_set_cache_policy")
+
+
+BCAST_CHAIN_AUTO = 0
+BCAST_CHAIN_WAVE_PER_STAGE = 1
+BCAST_CHAIN_WAVE_PER_RANK = 2
+
+
+def bcast_plan_set_chain_waves(plan: Plan, mode: int) -> None:
+    _check(_lib.bcast_plan_set_chain_waves(plan.handle, mode), "bcast_plan_set_chain_waves")
 
 
 def bcast_plan_enable_trace(plan: Plan, entries: int) -> None:

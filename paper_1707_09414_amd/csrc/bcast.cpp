@@ -44,6 +44,8 @@ struct bcast_plan {
     u64 spin_ticks = kDefaultSpinTicks;
     int mute_hop = 0;
     int policy_request[4] = {-1, -1, -1, -1};  // ld_root, ld_edge, ld_back, st_mid; -1 = choose
+    int chain_waves = BCAST_CHAIN_AUTO;        // chain: a wavefront per stage (chain_kernel) or per rank (rank_chain_kernel)
+    int rank_blocks_per_cu[kRankWavesMax + 1] = {0};  // workgroups of w waves a CU holds (0 = not asked yet)
 };
 
 static thread_local int g_last_hip_error = 0;
@@ -78,6 +80,8 @@ static void stage_shape(int hops, int request, int *stages, int *hops_per_stage)
 // Bytes of one trip of the copy loop at 16-byte vectors: the least worth a lane.
 static u64 trip_bytes_of(int unroll) { return (u64)unroll * kWaveSize * 16; }
 static bool valid_trip(u64 t) { return t != 0 && t % (kWaveSize * 16) == 0 && valid_chain_unroll((int)(t / (kWaveSize * 16))); }
+// ... and of the chain kernel with one wavefront per rank
+static bool valid_rank_trip(u64 t) { return t == 1024 || t == 2048 || t == 3072 || t == 4096 || t == 6144 || t == 8192; }
 
 // Chunk size when the caller gives none and no tuning entry applies.  On one
 // die every hop shares the same HBM, so Eq. 5's fill term (n - 2 idle links)
@@ -286,7 +290,9 @@ extern "C" int bcast_plan_set_stages(bcast_plan_t *p, int stages)
 
 extern "C" int bcast_plan_set_trip(bcast_plan_t *p, int trip_bytes)
 {
-    if (!p || (trip_bytes != 0 && !valid_trip((u64)trip_bytes))) return BCAST_ERR_ARG;
+    // the two chain kernels are built for different sets of sizes; which one a run
+    // uses is known when the run is described, and checked again there
+    if (!p || (trip_bytes != 0 && !valid_trip((u64)trip_bytes) && !valid_rank_trip((u64)trip_bytes))) return BCAST_ERR_ARG;
     p->trip_request = trip_bytes;
     return BCAST_OK;
 }
@@ -325,6 +331,13 @@ extern "C" int bcast_plan_set_cache_policy(bcast_plan_t *p, int ld_root, int ld_
     if (st_mid != -1 && !(st_mid & kAuxAgent) && ld_back != -1 && (ld_back & kAuxAgent)) return BCAST_ERR_ARG;
     if (st_mid == -1 && ld_back != -1 && (ld_back & kAuxAgent)) return BCAST_ERR_ARG;  // the default store may be write-back
     for (int i = 0; i < 4; ++i) p->policy_request[i] = v[i];
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_set_chain_waves(bcast_plan_t *p, int mode)
+{
+    if (!p || mode < BCAST_CHAIN_AUTO || mode > BCAST_CHAIN_WAVE_PER_RANK) return BCAST_ERR_ARG;
+    p->chain_waves = mode;
     return BCAST_OK;
 }
 
@@ -418,6 +431,7 @@ struct Resolved {
     int stages;  // 0 = built-in rule
     int radix;   // k-nomial only
     int trip;    // chain: bytes per trip
+    bool rank_waves;  // chain: a wavefront per rank
 };
 
 // Without a measurement: two stages (hops 1..h | h+1..P-1).  On one die the
@@ -448,20 +462,30 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
     r->chunk = p->chunk_bytes;
     r->stages = p->stages_request;
     r->trip = p->trip_request;
+    r->rank_waves = p->chain_waves == BCAST_CHAIN_WAVE_PER_RANK;
     bcast_tune_entry_t e;
     const bool tuned = bcast_tune_get(p->nranks, bytes, &e) == BCAST_OK;
+    // a table entry's chunk, stages and trip belong to the wave mode it was
+    // measured in: they apply if the plan leaves the mode open or asks for that one
+    auto mode_fits = [&](int entry_rank_waves) {
+        return p->chain_waves == BCAST_CHAIN_AUTO || (p->chain_waves == BCAST_CHAIN_WAVE_PER_RANK) == (entry_rank_waves != 0);
+    };
     if (p->algo == BCAST_ALGO_AUTO) {
         if (!tuned) return BCAST_ERR_UNTUNED;
         r->algo = e.algo;
-        if (r->chunk == 0) {
+        if (r->chunk == 0 && (e.algo != BCAST_ALGO_CHAIN || mode_fits(e.rank_waves))) {
             r->chunk = e.chunk_bytes;
             if (r->stages == 0) r->stages = e.stages;
-            if (r->trip == 0 && e.algo == BCAST_ALGO_CHAIN) r->trip = e.trip_bytes;
+            if (e.algo == BCAST_ALGO_CHAIN) {
+                if (r->trip == 0) r->trip = e.trip_bytes;
+                r->rank_waves = e.rank_waves != 0;
+            }
         }
-    } else if (p->algo == BCAST_ALGO_CHAIN && r->chunk == 0 && tuned && e.chain_chunk_bytes != 0) {
+    } else if (p->algo == BCAST_ALGO_CHAIN && r->chunk == 0 && tuned && e.chain_chunk_bytes != 0 && mode_fits(e.chain_rank_waves)) {
         r->chunk = e.chain_chunk_bytes;
         if (r->stages == 0) r->stages = e.chain_stages;
         if (r->trip == 0) r->trip = e.chain_trip_bytes;
+        r->rank_waves = e.chain_rank_waves != 0;
     }
     r->radix = p->radix_request;
     if (r->algo == BCAST_ALGO_KNOMIAL || r->algo == BCAST_ALGO_KNOMIAL_PIPELINED) {
@@ -475,6 +499,10 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
         // default chunk: one 4 KiB trip for each of a position's wavefronts
         if (r->chunk == 0) r->chunk = tree_lanes_max(p) * trip_bytes_of(kTripUnrollDefault);
         r->chunk = round_up(r->chunk, 16);
+    }
+    if (r->algo == BCAST_ALGO_CHAIN && r->rank_waves) {
+        r->chunk = round_up(r->chunk, 16);  // 0 = one trip per lane and chunk (rank_chain_geometry)
+        return BCAST_OK;
     }
     if (r->algo == BCAST_ALGO_CHAIN) {
         if (r->stages == 0) r->stages = default_stages(p->nranks);
@@ -550,6 +578,73 @@ static void walk_scatter_allgather(int P, u64 M, F &&emit)
     }
 }
 
+// Launch shape of the chain with one wavefront per rank: a stage is a workgroup
+// of (hops of the stage) waves, `lanes` workgroups per stage, all resident at
+// once.  Rules without a measurement (from the sweeps on MI355X): stages so that
+// a workgroup holds at most 8 ranks; 8 KiB trips; lanes so that the waves of a
+// compute unit have about 64 KiB of trips in flight (a power of two, like the
+// staged chain's lanes); one trip per lane and chunk.
+constexpr int kRankWavesPreferred = 8;
+constexpr u64 kRankTripDefault = 8192;
+constexpr u64 kRankBytesPerCu = 64u << 10;
+
+static int rank_chain_geometry(bcast_plan *p, size_t bytes, u64 chunk, int stages_request, int trip_request, bcast_plan_info_t *info)
+{
+    const int P = p->nranks;
+    memset(info, 0, sizeof *info);
+    info->algo = BCAST_ALGO_CHAIN;
+    info->vec_bytes = 16;
+    info->rank_waves = 1;
+    info->chunk_bytes = chunk;
+    if (P < 2 || bytes == 0) return BCAST_OK;
+    const int hops = P - 1;
+    // as many stages as asked for, but no stage longer than a workgroup can hold waves
+    int stages = stages_request > 0 ? std::min(stages_request, hops) : (hops + kRankWavesPreferred - 1) / kRankWavesPreferred;
+    stages = std::max(stages, (hops + kRankWavesMax - 1) / kRankWavesMax);
+    const int waves = (hops + stages - 1) / stages;  // of the longest stage = of every workgroup
+    if (p->rank_blocks_per_cu[waves] == 0) {
+        int n = 0;
+        HIP_TRY(rank_chain_max_blocks_per_cu(waves * kWaveSize, &n));
+        p->rank_blocks_per_cu[waves] = std::max(1, std::min(n, 32 / waves));
+    }
+    // every workgroup resident at once, and a flag for every (stage, lane)
+    const u64 lanes_most = std::min<u64>((u64)p->rank_blocks_per_cu[waves] * p->cu_count, (u64)p->max_flags) / stages;
+    if (lanes_most < 1) return BCAST_ERR_ARG;
+    const u64 trip = trip_request ? (u64)trip_request : kRankTripDefault;
+    if (!valid_rank_trip(trip)) return BCAST_ERR_ARG;
+    auto pow2_floor = [](u64 x) {
+        u64 l = 1;
+        while (l * 2 <= x) l *= 2;
+        return l;
+    };
+    const u64 lanes_rule = pow2_floor(std::max<u64>(1, kRankBytesPerCu * p->cu_count / (trip * waves * stages)));
+    u64 lanes;
+    if (p->lanes_request > 0) {
+        lanes = std::min<u64>((u64)p->lanes_request, lanes_most);
+    } else if (chunk == 0) {
+        lanes = std::min(lanes_rule, pow2_floor(std::min<u64>(lanes_most, std::max<u64>(1, ceil_div(bytes, trip)))));
+    } else {
+        // a given chunk: a lane should own at least one trip of it
+        lanes = pow2_floor(std::min<u64>(std::min(lanes_rule, lanes_most), std::max<u64>(1, ceil_div(std::min<u64>(chunk, bytes), trip))));
+    }
+    if (chunk == 0) chunk = lanes * trip;
+    const u64 C = std::min<u64>(chunk, round_up(bytes, 16));
+    const u64 nchunks = ceil_div(bytes, C);
+    if (C == 0 || C % 16 != 0 || nchunks >= (1ull << 27)) return BCAST_ERR_ARG;
+    info->chunk_bytes = C;
+    info->nchunks = nchunks;
+    info->stages = stages;
+    info->hops_per_stage = waves;
+    info->lanes = (int)lanes;
+    info->trip_bytes = (int)trip;
+    info->slice_bytes = ceil_div(C, lanes * trip) * trip;
+    info->grid_blocks = (int)((u64)stages * lanes);
+    info->block_threads = waves * kWaveSize;
+    info->launches = 1;
+    info->algorithmic_bytes = 2ull * hops * bytes;
+    return BCAST_OK;
+}
+
 static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_plan_info_t *info)
 {
     Resolved r;
@@ -557,6 +652,12 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
     if (rc != BCAST_OK) return rc;
     const int P = p->nranks;
     const int vec = common_vec_bytes(rank_bufs, P);
+    if (r.algo == BCAST_ALGO_CHAIN && r.rank_waves) {
+        rc = rank_chain_geometry(p, bytes, r.chunk, r.stages, r.trip, info);
+        if (rc != BCAST_OK) return rc;
+        info->vec_bytes = vec;
+        return BCAST_OK;
+    }
     if (r.algo == BCAST_ALGO_CHAIN) {
         const bcast_chain_request_t req = {p->lanes_request, r.stages, r.trip, p->block_request};
         rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, waves_for(p, bytes), &req, info);
@@ -758,6 +859,12 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         a.stages = (unsigned)info.stages;
         a.hops_per_stage = (unsigned)info.hops_per_stage;
         a.unroll = (unsigned)(info.trip_bytes / (kWaveSize * 16));
+        if (info.rank_waves) {
+            a.mode |= kModeFixedSpans;
+            if ((u64)a.stages * a.lanes > (u64)p->max_flags) return BCAST_ERR_ARG;
+            HIP_TRY(launch_rank_chain(a, info.vec_bytes, info.grid_blocks, info.block_threads, stream));
+            return BCAST_OK;
+        }
         // the launch must match what the kernel indexes: stages*lanes waves, each with its own flag,
         // and no more stages than hops
         if ((u64)a.stages * a.lanes > (u64)waves_for(p, bytes)) return BCAST_ERR_ARG;

@@ -20,6 +20,16 @@ constexpr int kBlockThreads = 256;
 constexpr int kWaveSize = 64;
 constexpr int kWavesPerBlock = kBlockThreads / kWaveSize;
 
+// The chain with one wavefront per rank: a workgroup holds at most this many
+// waves, one per consecutive chain position.
+constexpr int kRankWavesMax = 16;
+constexpr int kRankBlockThreadsMax = kRankWavesMax * kWaveSize;
+// Trips a rank may be ahead of its right neighbour's reading: what it stored
+// should be read out of the compute unit's cache before later trips push it out
+// (measured on MI355X: without a limit 19-21 ms at 64 ranks x 1 GiB, with 1, 2
+// or 4 trips 15.0 ms).
+constexpr unsigned kRankLead = 2;
+
 // One ready flag per (hop, lane), each alone in a 128-byte line so that a
 // producer's store and other lanes' polls never share a line.
 constexpr int kFlagStrideWords = 16;
@@ -168,6 +178,8 @@ hipError_t launch_zero_words(u64 *dst, u64 words, hipStream_t stream);
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream);
 bool valid_chain_block(int block_threads);  // 64, 128 or 256
 bool valid_chain_unroll(int unroll);        // vector instructions per lane and trip the chain kernel is built for
+hipError_t launch_rank_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream);
+hipError_t rank_chain_max_blocks_per_cu(int block_threads, int *blocks);
 hipError_t launch_tree(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
 hipError_t launch_reduce(const ChainArgs &a, int grid_blocks, hipStream_t stream);
 hipError_t reduce_max_blocks_per_cu(int *blocks);

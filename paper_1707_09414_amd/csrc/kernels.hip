@@ -402,6 +402,123 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// The pipelined chain with one wavefront per rank (Sec. IV-B read literally:
+// every non-root process receives a chunk from its left neighbour, stores it and
+// forwards it to its right neighbour).  Stage g, lane s is a WORKGROUP; its
+// wave j plays chain position first_hop(g) + j and nothing else.  The waves of
+// a workgroup run on one compute unit and share its vector L1 and its LDS, so a
+// hand-off between two ranks of the same workgroup stays on the CU:
+//   producer (rank h):   stores of a trip complete (s_waitcnt vmcnt(0)), then a
+//                        workgroup-scope release store of its trip count to LDS;
+//   consumer (rank h+1): workgroup-scope acquire load of that count from LDS,
+//                        then ordinary loads of the trip out of rank h's buffer,
+//                        which the CU's L1 (written through by the producer a
+//                        moment ago) or its XCD's L2 serves.
+// At workgroup scope (and without threadgroup-split mode) the CU's L1 is the
+// point of coherence for the workgroup's waves, so this is the plain
+// release/acquire protocol with nothing to write back or invalidate.  The
+// pipelining unit inside a workgroup is the trip (U KiB); between workgroups
+// (stage g's last rank to stage g+1's first) it is the chunk, handed over
+// through the flags in memory exactly as in chain_kernel.  Every rank's bytes
+// come out of its left neighbour's buffer, every hop is a flag hand-off, and
+// every rank has wavefronts of its own: lanes workgroups per stage, each
+// sweeping its share (every lanes-th trip) of every chunk.
+// Forward progress: a wave waits either for the wave before it in its own
+// workgroup (resident with it) or for a workgroup with a lower index; waits are
+// bounded by the clock limit like everywhere else.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ bool wait_trip(const unsigned *count, unsigned want, const ChainArgs &a, unsigned hop, unsigned chunk,
+                                          unsigned lane)
+{
+    unsigned v = __builtin_amdgcn_readfirstlane(__hip_atomic_load(count, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+    if (v < want) {
+        const u64 t0 = wall_clock64();
+        const u64 epoch = a.base >> 32;
+        unsigned spins = 0;
+        for (;;) {
+            __builtin_amdgcn_s_sleep(1);
+            v = __builtin_amdgcn_readfirstlane(__hip_atomic_load(count, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
+            if (v >= want) break;
+            if ((++spins & 63u) == 0) {
+                if (read_flag(a.abort_word, lane) >= epoch) return false;
+                if (wall_clock64() - t0 > a.spin_ticks) {
+                    if (lane == 0) report_timeout(a, hop, chunk);
+                    return false;
+                }
+            }
+        }
+    }
+    asm volatile("" ::: "memory");  // payload loads stay behind the acquire
+    return true;
+}
+
+template <int V, int U>
+__global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const ChainArgs a)
+{
+    __shared__ unsigned trips_done[kRankWavesMax];  // per wave of this workgroup: trips stored so far
+    __shared__ unsigned trips_read[kRankWavesMax];  // per wave: trips whose loads have returned
+    const unsigned lane = threadIdx.x & (kWaveSize - 1);
+    const unsigned j = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const unsigned g = blockIdx.x / a.lanes;
+    const unsigned s = blockIdx.x - g * a.lanes;
+    if (threadIdx.x < kRankWavesMax) trips_done[threadIdx.x] = trips_read[threadIdx.x] = 0;
+    __syncthreads();  // the only barrier: every wave of the workgroup is still here
+    if (g >= a.stages) return;
+    const unsigned hops = a.nranks - 1;
+    const unsigned hops_min = hops / a.stages, hops_extra = hops - hops_min * a.stages;
+    const unsigned first_hop = stage_begin(g, 0, a.stages, hops_min, hops_extra) + 1;
+    const unsigned last_hop = stage_begin(g + 1, 0, a.stages, hops_min, hops_extra);
+    const unsigned hop = first_hop + j;  // the one chain position this wave plays
+    if (hop > last_hop) return;
+    const bool first = j == 0, last = hop == last_hop;
+    const bool muted = a.mute_hop == hop;
+    const u64 *in_flag = (first && g > 0) ? a.flags + ((u64)(g - 1) * a.lanes + s) * kFlagStrideWords : nullptr;
+    u64 *const out_flag = (last && g + 1 < a.stages && !muted) ? a.flags + ((u64)g * a.lanes + s) * kFlagStrideWords : nullptr;
+    const char *src = a.buf[hop - 1];
+    char *dst = a.buf[hop];
+    const unsigned ld = first ? (g == 0 ? a.ld_root : a.ld_edge) : a.ld_back;
+    const unsigned st = (last && g + 1 < a.stages) ? (unsigned)kAuxAgent : a.st_mid;
+
+    const u64 trip = (u64)U * kWaveSize * V;
+    const u64 stride = trip * a.lanes;
+    unsigned seq = 0;  // trips this wave has stored
+    u64 seen = 0;
+    u64 chunk_lo = 0;
+    for (unsigned c = 0; c < a.nchunks; ++c, chunk_lo += a.chunk_bytes) {
+        u64 chunk_hi = chunk_lo + a.chunk_bytes;
+        if (chunk_hi > a.bytes) chunk_hi = a.bytes;
+        if (in_flag) {
+            const u64 want = a.base + ((u64)(c + 1) << 4);
+            if (seen < want && !wait_ready(in_flag, want, a, hop, c, lane, &seen)) return;
+        }
+        for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
+            const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
+            if (!first && !wait_trip(&trips_done[j - 1], seq + 1, a, hop, c, lane)) return;
+            // Back-pressure: a rank stays at most kRankLead trips ahead of its
+            // right neighbour's reading, so that what it stores is read out of
+            // the CU's cache before later trips push it out.
+            if (!last && seq >= kRankLead && !wait_trip(&trips_read[j + 1], seq + 1 - kRankLead, a, hop + 1, c, lane)) return;
+            copy_span_policy<V, U>(dst, src, lo, hi, lane, ld, st);
+            ++seq;
+            // the stores above were issued with the loaded data, so the loads of this trip have returned
+            if (!first && lane == 0)
+                __hip_atomic_store(&trips_read[j], seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (!last && !muted) {
+                // forward: the trip is stored (complete and written through) before the right neighbour is told
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                if (lane == 0) __hip_atomic_store(&trips_done[j], seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
+        if (in_flag && c + 1 < a.nchunks) seen = read_flag(in_flag, lane);
+        if (out_flag) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0)
+                __hip_atomic_store(out_flag, a.base + ((u64)(c + 1) << 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Pipelined k-nomial tree in one launch: the tree of Eq. 3 with the chunking and
 // the ready flags of the pipelined chain (the paper's source notes after Eq. 5
 // that the tree can be pipelined in the same way).  Every receiving position
@@ -656,9 +773,9 @@ __global__ void __launch_bounds__(kBlockThreads) fanout_kernel(const CopyArgs a)
 #define BCAST_LAUNCH_V(KERNEL, vec_bytes, grid, stream, args, ...) \
     BCAST_LAUNCH_VB(KERNEL, vec_bytes, grid, dim3(kBlockThreads), stream, args __VA_OPT__(,) __VA_ARGS__)
 
-bool valid_chain_block(int block_threads) { return block_threads == 64 || block_threads == 128 || block_threads == 256; }
-
 static bool valid_policy(unsigned aux) { return (aux & ~(unsigned)(kAuxAgent | kAuxStream)) == 0; }
+
+bool valid_chain_block(int block_threads) { return block_threads == 64 || block_threads == 128 || block_threads == 256; }
 
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream)
 {
@@ -678,6 +795,42 @@ hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int 
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+hipError_t launch_rank_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream)
+{
+    if (a.nranks < 2 || a.stages < 1 || a.stages > a.nranks - 1 || a.lanes < 1) return hipErrorInvalidValue;
+    // one wave per hop of the longest stage, one workgroup per (stage, lane)
+    const unsigned longest = (a.nranks - 1 + a.stages - 1) / a.stages;
+    if (longest > (unsigned)kRankWavesMax || block_threads != (int)(longest * kWaveSize)) return hipErrorInvalidValue;
+    if ((u64)grid_blocks != (u64)a.stages * a.lanes) return hipErrorInvalidValue;
+    if (!(a.mode & kModeFixedSpans)) return hipErrorInvalidValue;  // a wave keeps its position for every chunk
+    if (!valid_policy(a.ld_root) || !valid_policy(a.ld_edge) || !valid_policy(a.ld_back) || !valid_policy(a.st_mid)) return hipErrorInvalidValue;
+    if (!(a.ld_edge & kAuxAgent)) return hipErrorInvalidValue;
+    const dim3 grid(grid_blocks), block(block_threads);
+    switch (a.unroll) {
+    case 1: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 1); break;
+    case 2: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 2); break;
+    case 3: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 3); break;
+    case 4: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 4); break;
+    case 6: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 6); break;
+    case 8: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 8); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t rank_chain_max_blocks_per_cu(int block_threads, int *blocks)
+{
+    int n[4] = {0, 0, 0, 0};
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[0], rank_chain_kernel<16, 1>, block_threads, 0);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[1], rank_chain_kernel<16, 2>, block_threads, 0);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[2], rank_chain_kernel<16, 3>, block_threads, 0);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[3], rank_chain_kernel<16, 4>, block_threads, 0);
+    *blocks = n[0];
+    for (int x : n)
+        if (x < *blocks) *blocks = x;
+    return e;
 }
 
 hipError_t launch_tree(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream)

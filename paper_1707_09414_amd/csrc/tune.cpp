@@ -41,8 +41,16 @@ static bool valid_entry(int nranks, const bcast_tune_entry_t &e)
     if (chunked && (e.chunk_bytes == 0 || e.chunk_bytes % 16 != 0)) return false;
     if (e.chain_chunk_bytes % 16 != 0) return false;
     if (e.stages < 0 || e.stages > BCAST_MAX_RANKS || e.chain_stages < 0 || e.chain_stages > BCAST_MAX_RANKS) return false;
-    for (int t : {e.trip_bytes, e.chain_trip_bytes})
-        if (t != 0 && (t % 1024 != 0 || !valid_chain_unroll(t / 1024))) return false;
+    if ((e.rank_waves != 0 && e.rank_waves != 1) || (e.chain_rank_waves != 0 && e.chain_rank_waves != 1)) return false;
+    // trip sizes: those the chain kernel of the entry's wave mode is built for
+    auto trip_ok = [](int t, int rank_waves) {
+        if (t == 0) return true;
+        if (t % 1024 != 0) return false;
+        const int u = t / 1024;
+        return rank_waves ? (u == 1 || u == 2 || u == 3 || u == 4 || u == 6 || u == 8) : valid_chain_unroll(u);
+    };
+    if (!trip_ok(e.trip_bytes, e.rank_waves) || !trip_ok(e.chain_trip_bytes, e.chain_rank_waves)) return false;
+    if (e.rank_waves && e.algo != BCAST_ALGO_CHAIN) return false;
     return true;
 }
 
@@ -75,6 +83,7 @@ extern "C" int bcast_tune_put(int nranks, size_t bytes, const bcast_tune_entry_t
         e.chain_stages = e.stages;
         e.chain_trip_bytes = e.trip_bytes;
         e.chain_usec = e.usec;
+        e.chain_rank_waves = e.rank_waves;
     }
     std::lock_guard<std::mutex> g(g_mu);
     g_table[{nranks, log2_bucket(bytes)}] = e;
@@ -150,18 +159,18 @@ extern "C" int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *ch
 
 static const char kHeaderLine[] =
     "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout 5=scatter-allgather 6=knomial 7=pipelined-knomial) chunk_bytes usec "
-    "chain_chunk_bytes chain_usec stages chain_stages trip_bytes chain_trip_bytes\n";
+    "chain_chunk_bytes chain_usec stages chain_stages trip_bytes chain_trip_bytes rank_waves chain_rank_waves\n";
 
 // Text format, one entry per line (columns after usec are optional; for a
 // k-nomial winner the stages column holds the radix):
 //   nranks log2_bytes algo chunk_bytes usec [chain_chunk_bytes chain_usec [stages chain_stages
-//   [trip_bytes chain_trip_bytes]]]
+//   [trip_bytes chain_trip_bytes [rank_waves chain_rank_waves]]]]
 // Lines starting with '#' are comments.
 static void print_entry(FILE *f, int nranks, int bucket, const bcast_tune_entry_t &e)
 {
-    fprintf(f, "%d %d %d %llu %.3f %llu %.3f %d %d %d %d\n", nranks, bucket, e.algo, (unsigned long long)e.chunk_bytes,
+    fprintf(f, "%d %d %d %llu %.3f %llu %.3f %d %d %d %d %d %d\n", nranks, bucket, e.algo, (unsigned long long)e.chunk_bytes,
             e.usec, (unsigned long long)e.chain_chunk_bytes, e.chain_usec, e.stages, e.chain_stages, e.trip_bytes,
-            e.chain_trip_bytes);
+            e.chain_trip_bytes, e.rank_waves, e.chain_rank_waves);
 }
 
 extern "C" int bcast_tune_save(const char *path)
@@ -192,8 +201,9 @@ extern "C" int bcast_tune_load(const char *path)
         unsigned long long chunk = 0, cchunk = 0;
         bcast_tune_entry_t e;
         memset(&e, 0, sizeof e);
-        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf %d %d %d %d", &nranks, &bucket, &e.algo, &chunk, &e.usec, &cchunk,
-                         &e.chain_usec, &e.stages, &e.chain_stages, &e.trip_bytes, &e.chain_trip_bytes);
+        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf %d %d %d %d %d %d", &nranks, &bucket, &e.algo, &chunk, &e.usec, &cchunk,
+                         &e.chain_usec, &e.stages, &e.chain_stages, &e.trip_bytes, &e.chain_trip_bytes, &e.rank_waves,
+                         &e.chain_rank_waves);
         e.chunk_bytes = chunk;
         e.chain_chunk_bytes = cchunk;
         if (got < 4 || bucket < 0 || bucket > 62 || !valid_entry(nranks, e)) {
@@ -205,6 +215,7 @@ extern "C" int bcast_tune_load(const char *path)
             e.chain_stages = e.stages;
             e.chain_trip_bytes = e.trip_bytes;
             e.chain_usec = e.usec;
+            e.chain_rank_waves = e.rank_waves;
         }
         rows.push_back({{nranks, bucket}, e});
     }
@@ -231,7 +242,7 @@ struct Scratch {
 
 // Microseconds per run of one candidate.  One timed run warms up and sizes
 // the batches (about 20 ms each, 2..40 runs); the best of three batches counts.
-int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages, int trip, Scratch &sc,
+int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages, int trip, int rank_waves, Scratch &sc,
                    hipStream_t stream, double *usec)
 {
     bcast_plan_t *plan = nullptr;
@@ -239,6 +250,8 @@ int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages,
     if (rc != BCAST_OK) return rc;
     rc = has_radix(algo) ? bcast_plan_set_radix(plan, stages) : bcast_plan_set_stages(plan, stages);
     if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN) rc = bcast_plan_set_trip(plan, trip);
+    if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN)
+        rc = bcast_plan_set_chain_waves(plan, rank_waves ? BCAST_CHAIN_WAVE_PER_RANK : BCAST_CHAIN_WAVE_PER_STAGE);
     int reps = 1;
     double best = 1e30;
     for (int batch = 0; batch < 4 && rc == BCAST_OK; ++batch) {
@@ -267,7 +280,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
                           bcast_stream_t stream, const char *table_path)
 {
     if (nranks < 2 || nranks > BCAST_MAX_RANKS || min_bytes == 0 || max_bytes < min_bytes) return BCAST_ERR_ARG;
-    if ((algo_mask & ~BCAST_TUNE_FOLDED) == 0)
+    if ((algo_mask & ~(BCAST_TUNE_FOLDED | BCAST_TUNE_NO_RANK_WAVES)) == 0)
         algo_mask |= (1u << BCAST_ALGO_CHAIN) | (1u << BCAST_ALGO_DIRECT) | (1u << BCAST_ALGO_BINOMIAL);
 
     Scratch sc;
@@ -284,7 +297,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         std::lock_guard<std::mutex> g(g_mu);
         if (!g_log_path.empty()) log = fopen(g_log_path.c_str(), "a");
     }
-    if (log) fprintf(log, "# nranks bytes algo chunk_bytes stages usec trip_bytes\n");
+    if (log) fprintf(log, "# nranks bytes algo chunk_bytes stages usec trip_bytes rank_waves\n");
     struct LogCloser {
         FILE *f;
         ~LogCloser() { if (f) fclose(f); }
@@ -314,16 +327,17 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         bcast_tune_entry_t best;
         memset(&best, 0, sizeof best);
         best.usec = best.chain_usec = 1e30;
-        auto consider = [&](int algo, size_t chunk, int stages, int trip = 0) {
+        auto consider = [&](int algo, size_t chunk, int stages, int trip = 0, int rank_waves = 0) {
             if (rc != BCAST_OK || !(algo_mask & (1u << algo))) return;
             double us = 0.0;
-            rc = time_candidate(nranks, M, algo, chunk, stages, trip, sc, stream, &us);
+            rc = time_candidate(nranks, M, algo, chunk, stages, trip, rank_waves, sc, stream, &us);
             if (rc != BCAST_OK) return;
-            if (log) fprintf(log, "%d %zu %d %zu %d %.3f %d\n", nranks, M, algo, chunk, stages, us, trip);
+            if (log) fprintf(log, "%d %zu %d %zu %d %.3f %d %d\n", nranks, M, algo, chunk, stages, us, trip, rank_waves);
             if (algo == BCAST_ALGO_CHAIN && us < best.chain_usec) {
                 best.chain_chunk_bytes = chunk;
                 best.chain_stages = stages;
                 best.chain_trip_bytes = trip;
+                best.chain_rank_waves = rank_waves;
                 best.chain_usec = us;
             }
             if (us < best.usec) {
@@ -331,6 +345,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
                 best.chunk_bytes = chunk;
                 best.stages = (algo == BCAST_ALGO_CHAIN || has_radix(algo)) ? stages : 0;
                 best.trip_bytes = algo == BCAST_ALGO_CHAIN ? trip : 0;
+                best.rank_waves = algo == BCAST_ALGO_CHAIN ? rank_waves : 0;
                 best.usec = us;
             }
         };
@@ -352,6 +367,30 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
                     if (C >= M || M / C > 4096 || C > (64u << 20)) continue;
                     if (trip == 3072 && lanes * (size_t)stages < 512) continue;
                     consider(BCAST_ALGO_CHAIN, C, stages, trip);
+                }
+            }
+        }
+        // The chain with a wavefront per rank: as few stages as 8 and as 16 ranks
+        // per workgroup allow; 4 and 8 KiB trips; chunks of one trip per lane for
+        // lane counts around 64 KiB of trips in flight per compute unit (the
+        // library's rule), half and twice that; and the whole message as one chunk.
+        if (!(algo_mask & BCAST_TUNE_NO_RANK_WAVES)) {
+            std::vector<int> rank_stages;
+            for (int per : {8, 16}) {
+                const int st = (hops + per - 1) / per;
+                if (std::find(rank_stages.begin(), rank_stages.end(), st) == rank_stages.end()) rank_stages.push_back(st);
+            }
+            for (int stages : rank_stages) {
+                const int waves = (hops + stages - 1) / stages;
+                for (int trip : {4096, 8192}) {
+                    consider(BCAST_ALGO_CHAIN, std::max<size_t>(16, (M + 15) / 16 * 16), stages, trip, 1);
+                    size_t rule = 1;
+                    while (rule * 2 * (size_t)trip * waves * stages <= ((size_t)64 << 10) * 256) rule *= 2;
+                    for (size_t lanes : {rule / 2, rule, rule * 2}) {
+                        const size_t C = lanes * (size_t)trip;
+                        if (lanes < 1 || C >= M || M / C > 4096) continue;
+                        consider(BCAST_ALGO_CHAIN, C, stages, trip, 1);
+                    }
                 }
             }
         }

@@ -80,7 +80,8 @@ def assert_same(got, exp, what):
                                  % (what, r, bad.size, bad[0], g[bad[0]], e[bad[0]]))
 
 
-def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0, stream=None, plan=None, stages=0, radix=0, trip=0, block=0):
+def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0, stream=None, plan=None, stages=0, radix=0, trip=0, block=0,
+                  waves=0):
     """One broadcast on the GPU, compared byte for byte (guards included) with
     the oracle's end state.  Returns the plan info used."""
     cap = M if cap is None else cap
@@ -101,6 +102,8 @@ def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0,
             B.bcast_plan_set_trip(plan, trip)
         if block:
             B.bcast_plan_set_block_threads(plan, block)
+        if waves:
+            B.bcast_plan_set_chain_waves(plan, waves)
         info = B.bcast_plan_info(plan, M, rb.ptrs())
         B.bcast_run(plan, rb.ptrs(), root, M, stream)
         got = rb.to_host()
