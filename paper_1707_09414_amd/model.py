@@ -121,7 +121,12 @@ def read_log(path: str) -> Dict[int, List[Tuple[int, int, int, int, float]]]:
         for line in f:
             if not line.strip() or line.startswith("#"):
                 continue
-            n, M, algo, C, stages, us = line.split()[:6]
+            cols = line.split()
+            n, M, algo, C, stages, us = cols[:6]
+            # column 8 (newer logs): 1 = the chain ran with a wavefront per rank, whose hand-offs inside a
+            # workgroup are per trip, not per chunk: Eq. 5 with chunk C models the other kernel, so those rows are left out
+            if len(cols) > 7 and int(cols[7]) != 0:
+                continue
             out[int(n)].append((int(M), int(algo), int(C), int(stages), float(us) * 1e-6))
     return out
 

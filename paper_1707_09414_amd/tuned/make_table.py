@@ -2,10 +2,11 @@
 
     python -m paper_1707_09414_amd.tuned.make_table [--out PATH] [--ranks 2,4,8,...]
                                                     [--min-bytes N] [--max-bytes N] [--with-fanout] [--with-knomial] [--with-knomial-pipelined]
-                                                    [--with-scatter-allgather] [--folded]
+                                                    [--with-scatter-allgather] [--folded] [--no-rank-waves] [--append]
 
-For every rank count it runs ``bcast_tune`` (chain over chunk sizes and stage counts,
-direct, binomial; the one-die fan-out and the single-stage chain only on request) over power-of-two message sizes
+For every rank count it runs ``bcast_tune`` (chain over chunk sizes, stage counts and
+trip sizes, with a wavefront per stage and with a wavefront per rank, direct, binomial;
+the one-die fan-out and the single-stage chain only on request) over power-of-two message sizes
 and writes the winners.  The file it produces is what ``load_default_table``
 installs.
 """
@@ -30,6 +31,8 @@ def main() -> int:
     ap.add_argument("--with-scatter-allgather", action="store_true")
     ap.add_argument("--log", default=None, help="also append every timed candidate to this file")
     ap.add_argument("--folded", action="store_true", help="also try the chain with a single stage (no flag hand-off)")
+    ap.add_argument("--no-rank-waves", action="store_true", help="leave out the chain with a wavefront per rank")
+    ap.add_argument("--append", action="store_true", help="keep the entries --out already holds (other rank counts)")
     args = ap.parse_args()
 
     import torch  # device context and stream only
@@ -48,7 +51,11 @@ def main() -> int:
         mask |= 1 << B.BCAST_ALGO_SCATTER_ALLGATHER
     if args.folded:
         mask |= B.BCAST_TUNE_FOLDED
+    if args.no_rank_waves:
+        mask |= B.BCAST_TUNE_NO_RANK_WAVES
     B.bcast_tune_clear()
+    if args.append and os.path.exists(args.out):
+        B.bcast_tune_load(args.out)
     B.bcast_tune_set_log(args.log)
     stream = torch.cuda.current_stream()
     for P in [int(x) for x in args.ranks.split(",")]:
