@@ -220,7 +220,8 @@ int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_w
  * every addition rounded to fp32 (round to nearest even, denormals kept): the
  * result is defined bit for bit.
  *   plan       from bcast_plan_create (its algo is not used; chunk_bytes is the
- *              chunk size, 0 = built-in rule; bcast_plan_set_stages / _lanes apply).
+ *              chunk size, 0 = the reduction table's entry, else a built-in rule;
+ *              bcast_plan_set_stages / _lanes apply).
  *   send_bufs  HOST array of plan.nranks DEVICE pointers to `count` floats each,
  *              16-byte aligned, pairwise non-overlapping; only read.
  *   recv_buf   DEVICE pointer to `count` floats, 16-byte aligned: either
@@ -241,8 +242,9 @@ int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_w
 int bcast_reduce_sum_f32(bcast_plan_t *plan, const void *const *send_bufs, void *recv_buf, int root, size_t count,
                          bcast_stream_t stream);
 /* bcast_plan_reserve_reduce -- make sure the plan owns staging memory for
- * reductions of up to `count` floats in up to `stages` stages (stages >= 1;
- * cut down to nranks - 1).  Grows only; growing waits for the device, frees the
+ * reductions of up to `count` floats in up to `stages` stages (cut down to
+ * nranks - 1; 0 = what the library would choose for `count` floats: the
+ * reduction table's entry, else two).  Grows only; growing waits for the device, frees the
  * old memory and allocates (stages - 1) * round_up(count * 4, 256) bytes.
  * Errors: ERR_ARG (count * 4 beyond the plan's bytes), ERR_NOMEM, ERR_HIP. */
 int bcast_plan_reserve_reduce(bcast_plan_t *plan, size_t count, int stages);
@@ -353,6 +355,34 @@ int bcast_tune_get(int nranks, size_t bytes, bcast_tune_entry_t *entry);
 int bcast_tune_set(int nranks, size_t bytes, int algo, size_t chunk_bytes, double usec);
 int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *chunk_bytes, double *usec);
 int bcast_tune_count(void);
+
+/*
+ * The reduction's own tuning table (Sec. III-B applied to the collective
+ * Sec. VII names next): per (nranks, floor(log2 bytes)) the stage count, chunk
+ * size and trip size bcast_reduce_sum_f32 uses when the plan leaves them open
+ * (chunk_bytes == 0 and no bcast_plan_set_stages).  Process-wide, saved to and
+ * loaded from the same text file as the broadcast's entries (lines
+ * "reduce nranks log2_bytes chunk_bytes stages trip_bytes usec").
+ * trip_bytes: 4096 (contributions loaded 4 positions at a time) or 1024 (16 at
+ * a time, for small messages).
+ */
+typedef struct {
+    uint64_t chunk_bytes; /* multiple of 16 */
+    int stages;           /* 1..nranks-1; 1 = no hand-off at all, no staging memory */
+    int trip_bytes;       /* 4096 or 1024 */
+    double usec;          /* measured time at that setting */
+} bcast_reduce_entry_t;
+/* bcast_tune_reduce -- measure, on the current device and `stream`, the chain
+ * reduction of `nranks` contributions over stage counts 1, 2 and 4, both trip
+ * sizes and chunk sizes lanes * trip for power-of-two lane counts (and the whole
+ * message as one chunk), for message sizes that are powers of two in
+ * [min_bytes, max_bytes]; keeps the fastest per size, installs the entries and,
+ * if table_path (HOST, nullable) is given, appends them there.  Allocates
+ * nranks + 1 buffers of max_bytes and the staging memory itself. */
+int bcast_tune_reduce(int nranks, size_t min_bytes, size_t max_bytes, bcast_stream_t stream, const char *table_path);
+int bcast_tune_reduce_put(int nranks, size_t bytes, const bcast_reduce_entry_t *entry);
+/* Nearest entry as for bcast_tune_get; BCAST_ERR_UNTUNED if there is none. */
+int bcast_tune_reduce_get(int nranks, size_t bytes, bcast_reduce_entry_t *entry);
 
 const char *bcast_strerror(int status);
 int bcast_last_hip_error(void);

@@ -69,6 +69,10 @@ int bcast_plan_read_trace(bcast_plan_t *plan, uint64_t *out, size_t entries);
 #define BCAST_CACHE_AGENT 16
 int bcast_plan_set_cache_policy(bcast_plan_t *plan, int ld_root, int ld_edge, int ld_back, int st_mid);
 
+/* Trip size of the chain reduction for measurements: 4096 (contributions loaded
+ * 4 positions at a time) or 1024 (16 at a time), 0 = the library's choice. */
+int bcast_plan_set_reduce_trip(bcast_plan_t *plan, int trip_bytes);
+
 #ifdef __cplusplus
 }
 #endif

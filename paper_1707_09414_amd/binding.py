@@ -44,7 +44,7 @@ EXPORTS = [
     "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_reduce_sum_f32_static", "bcast_plan_reserve_reduce", "bcast_allreduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
     "bcast_plan_handoff_counts", "bcast_plan_set_cache_policy", "bcast_plan_set_chain_waves", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
-    "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
+    "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_tune_reduce", "bcast_tune_reduce_put", "bcast_tune_reduce_get", "bcast_plan_set_reduce_trip", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
 ]
 
 
@@ -103,6 +103,13 @@ class TuneEntry(ctypes.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_}
 
 
+class ReduceEntry(ctypes.Structure):
+    _fields_ = [("chunk_bytes", ctypes.c_uint64), ("stages", ctypes.c_int), ("trip_bytes", ctypes.c_int), ("usec", ctypes.c_double)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
 BCAST_TUNE_FOLDED = 1 << 16
 BCAST_TUNE_NO_RANK_WAVES = 1 << 17
 
@@ -153,6 +160,10 @@ def _load():
         "bcast_tune_put": ([i, sz, ctypes.POINTER(TuneEntry)], i),
         "bcast_tune_get": ([i, sz, ctypes.POINTER(TuneEntry)], i),
         "bcast_tune_count": ([], i),
+        "bcast_tune_reduce": ([i, sz, sz, vp, ctypes.c_char_p], i),
+        "bcast_tune_reduce_put": ([i, sz, ctypes.POINTER(ReduceEntry)], i),
+        "bcast_tune_reduce_get": ([i, sz, ctypes.POINTER(ReduceEntry)], i),
+        "bcast_plan_set_reduce_trip": ([vp, i], i),
         "bcast_strerror": ([i], ctypes.c_char_p),
         "bcast_last_hip_error": ([], i),
         "bcast_version": ([], ctypes.c_char_p),
@@ -444,6 +455,26 @@ def bcast_tune_get(nranks: int, bytes: int) -> dict:
     e = TuneEntry()
     _check(_lib.bcast_tune_get(nranks, bytes, ctypes.byref(e)), "bcast_tune_get")
     return e.as_dict()
+
+
+def bcast_tune_reduce(nranks: int, min_bytes: int, max_bytes: int, stream=None, table_path: Optional[str] = None) -> None:
+    path = table_path.encode() if table_path else None
+    _check(_lib.bcast_tune_reduce(nranks, min_bytes, max_bytes, _stream(stream), path), "bcast_tune_reduce")
+
+
+def bcast_tune_reduce_put(nranks: int, bytes: int, **fields) -> None:
+    e = ReduceEntry(**fields)
+    _check(_lib.bcast_tune_reduce_put(nranks, bytes, ctypes.byref(e)), "bcast_tune_reduce_put")
+
+
+def bcast_tune_reduce_get(nranks: int, bytes: int) -> dict:
+    e = ReduceEntry()
+    _check(_lib.bcast_tune_reduce_get(nranks, bytes, ctypes.byref(e)), "bcast_tune_reduce_get")
+    return e.as_dict()
+
+
+def bcast_plan_set_reduce_trip(plan: Plan, trip_bytes: int) -> None:
+    _check(_lib.bcast_plan_set_reduce_trip(plan.handle, trip_bytes), "bcast_plan_set_reduce_trip")
 
 
 def bcast_tune_count() -> int:

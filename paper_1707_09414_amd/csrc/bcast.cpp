@@ -44,6 +44,7 @@ struct bcast_plan {
     u64 spin_ticks = kDefaultSpinTicks;
     int mute_hop = 0;
     int policy_request[4] = {-1, -1, -1, -1};  // ld_root, ld_edge, ld_back, st_mid; -1 = choose
+    int reduce_trip_request = 0;               // reduction: 0 = choose, 4096 or 1024
     int chain_waves = BCAST_CHAIN_AUTO;        // chain: a wavefront per stage (chain_kernel) or per rank (rank_chain_kernel)
     int rank_blocks_per_cu[kRankWavesMax + 1] = {0};  // workgroups of w waves a CU holds (0 = not asked yet)
 };
@@ -331,6 +332,13 @@ extern "C" int bcast_plan_set_cache_policy(bcast_plan_t *p, int ld_root, int ld_
     if (st_mid != -1 && !(st_mid & kAuxAgent) && ld_back != -1 && (ld_back & kAuxAgent)) return BCAST_ERR_ARG;
     if (st_mid == -1 && ld_back != -1 && (ld_back & kAuxAgent)) return BCAST_ERR_ARG;  // the default store may be write-back
     for (int i = 0; i < 4; ++i) p->policy_request[i] = v[i];
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_set_reduce_trip(bcast_plan_t *p, int trip_bytes)
+{
+    if (!p || (trip_bytes != 0 && trip_bytes != 4096 && trip_bytes != 1024)) return BCAST_ERR_ARG;
+    p->reduce_trip_request = trip_bytes;
     return BCAST_OK;
 }
 
@@ -978,7 +986,12 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
 static int reduce_shape(const bcast_plan *p, size_t bytes, size_t staging_bytes, int max_waves, bcast_plan_info_t *info)
 {
     const int hops = std::max(1, p->nranks - 1);
-    int stages = p->stages_request > 0 ? std::min(p->stages_request, hops) : default_stages(p->nranks);
+    // what the plan leaves open comes from the reduction's tuning table, if it has an entry
+    bcast_reduce_entry_t e;
+    const bool tuned = p->nranks >= 2 && bytes > 0 && bcast_tune_reduce_get(p->nranks, bytes, &e) == BCAST_OK;
+    const bool open_shape = p->chunk_bytes == 0 && p->stages_request == 0;
+    int stages = p->stages_request > 0 ? std::min(p->stages_request, hops)
+                                       : (tuned && open_shape ? std::min(e.stages, hops) : default_stages(p->nranks));
     if (p->nranks >= 2 && bytes > 0) {
         const u64 region = round_up(bytes, 256);
         const u64 fit = 1 + staging_bytes / region;  // stages the staging memory carries
@@ -987,14 +1000,19 @@ static int reduce_shape(const bcast_plan *p, size_t bytes, size_t staging_bytes,
             stages = (int)fit;
         }
     }
+    const bool use_entry = tuned && open_shape && stages == std::min(e.stages, hops);
+    // trips: 4 KiB and 4 positions loaded at a time for messages that stream, 1 KiB
+    // and 16 positions for small ones (more lanes share the work, fewer dependent
+    // memory round trips per stage)
+    u64 trip = p->reduce_trip_request ? (u64)p->reduce_trip_request
+                                      : (use_entry ? (u64)e.trip_bytes
+                                                   : trip_bytes_of(bytes <= kRedSmallMaxBytes ? kRedUnrollSmall : kRedUnroll));
     size_t chunk = p->chunk_bytes;
-    if (chunk == 0) chunk = (size_t)default_chunk(p->nranks, max_waves, stages, trip_bytes_of(kTripUnrollDefault));
-    const bcast_chain_request_t req = {p->lanes_request, stages, (int)trip_bytes_of(kTripUnrollDefault), 0};
+    if (chunk == 0) chunk = use_entry ? (size_t)e.chunk_bytes : (size_t)default_chunk(p->nranks, max_waves, stages, trip_bytes_of(kRedUnroll));
+    const bcast_chain_request_t req = {p->lanes_request, stages, (int)trip_bytes_of(kRedUnroll), 0};
     int rc = bcast_chain_geometry(p->nranks, bytes, chunk, max_waves, &req, info);
     if (rc != BCAST_OK) return rc;
-    if (p->nranks >= 2 && bytes > 0 && bytes <= kRedSmallMaxBytes) {
-        // small messages: 1 KiB trips (and 16 positions loaded at a time), so more lanes share the work
-        const u64 trip = trip_bytes_of(kRedUnrollSmall);
+    if (p->nranks >= 2 && bytes > 0 && trip != trip_bytes_of(kRedUnroll)) {
         const u64 most = (u64)(max_waves / info->stages);
         u64 lanes = p->lanes_request > 0 ? std::min<u64>((u64)p->lanes_request, most)
                                          : std::min<u64>(ceil_div(info->chunk_bytes, trip), most);
@@ -1022,7 +1040,13 @@ extern "C" int bcast_reduce_info(bcast_plan_t *p, size_t count, bcast_plan_info_
 
 extern "C" int bcast_plan_reserve_reduce(bcast_plan_t *p, size_t count, int stages)
 {
-    if (!p || stages < 1 || count > p->bytes / sizeof(float)) return BCAST_ERR_ARG;
+    if (!p || stages < 0 || count > p->bytes / sizeof(float)) return BCAST_ERR_ARG;
+    if (stages == 0) {
+        bcast_reduce_entry_t e;
+        stages = p->nranks >= 2 && count > 0 && bcast_tune_reduce_get(p->nranks, count * sizeof(float), &e) == BCAST_OK
+                     ? e.stages
+                     : default_stages(p->nranks);
+    }
     stages = std::min(stages, std::max(1, p->nranks - 1));
     const size_t need = (size_t)(stages - 1) * round_up(count * sizeof(float), 256);
     if (need <= p->scratch_bytes) return BCAST_OK;
@@ -1080,6 +1104,7 @@ static int reduce_enqueue(bcast_plan *p, const void *const *send_bufs, void *rec
     a.hops_per_stage = (unsigned)info.hops_per_stage;
     a.unroll = (unsigned)(info.trip_bytes / (kWaveSize * 16));
     a.recv = (char *)recv_buf;
+    a.st_mid = (unsigned char)(p->policy_request[3] >= 0 ? p->policy_request[3] : kRedResultStore);
     a.scratch = staging;
     a.scratch_stride = region;
     if ((u64)a.stages * a.lanes > (u64)max_waves) return BCAST_ERR_ARG;

@@ -660,6 +660,9 @@ __global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a
     const unsigned first_hop = stage_begin(g, 0, a.stages, hops_min, hops_extra) + 1;
     const unsigned last_hop = stage_begin(g + 1, 0, a.stages, hops_min, hops_extra);
     const bool last_stage = g + 1 == a.stages;
+    // the result: written through (a store that does not linger in the L2 among
+    // the streaming reads) or with ordinary write-back stores; the host's choice
+    const bool result_through = (a.st_mid & kAuxAgent) != 0;
 
     const u64 *in_flag = g > 0 ? a.flags + ((u64)(g - 1) * a.lanes + s) * kFlagStrideWords : nullptr;
     const bool muted = a.mute_hop >= first_hop && a.mute_hop <= last_hop;
@@ -687,9 +690,17 @@ __global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a
                 if (body) reduce_span<16, U, B, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
                 if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
             } else if (g > 0) {
-                if (body) reduce_span<16, U, B, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo, body, lane);
-                if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                if (result_through) {
+                    if (body) reduce_span<16, U, B, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
+                    if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                } else {
+                    if (body) reduce_span<16, U, B, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo, body, lane);
+                    if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                }
             } else if (!last_stage) {
+                if (body) reduce_span<16, U, B, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, B, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+            } else if (result_through) {
                 if (body) reduce_span<16, U, B, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
                 if (n != body) reduce_span<4, 1, B, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
             } else {

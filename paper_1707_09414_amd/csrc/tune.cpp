@@ -25,6 +25,7 @@ int log2_bucket(size_t bytes)
 
 static std::mutex g_mu;
 static std::map<std::pair<int, int>, bcast_tune_entry_t> g_table;  // (nranks, bucket)
+static std::map<std::pair<int, int>, bcast_reduce_entry_t> g_reduce_table;  // the reduction's own entries
 static std::string g_log_path;  // if set, bcast_tune appends every candidate it times
 
 }  // namespace bcast
@@ -58,6 +59,7 @@ extern "C" int bcast_tune_clear(void)
 {
     std::lock_guard<std::mutex> g(g_mu);
     g_table.clear();
+    g_reduce_table.clear();
     return BCAST_OK;
 }
 
@@ -125,6 +127,44 @@ static const bcast_tune_entry_t *nearest(int nranks, size_t bytes)
     return best ? nearest_size(best, bytes) : nullptr;
 }
 
+static bool valid_reduce_entry(int nranks, const bcast_reduce_entry_t &e)
+{
+    if (nranks < 2 || nranks > BCAST_MAX_RANKS) return false;
+    if (e.chunk_bytes == 0 || e.chunk_bytes % 16 != 0) return false;
+    if (e.stages < 1 || e.stages > BCAST_MAX_RANKS) return false;
+    return e.trip_bytes == 4096 || e.trip_bytes == 1024;
+}
+
+extern "C" int bcast_tune_reduce_put(int nranks, size_t bytes, const bcast_reduce_entry_t *entry)
+{
+    if (!entry || bytes == 0 || !valid_reduce_entry(nranks, *entry)) return BCAST_ERR_ARG;
+    std::lock_guard<std::mutex> g(g_mu);
+    g_reduce_table[{nranks, log2_bucket(bytes)}] = *entry;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_tune_reduce_get(int nranks, size_t bytes, bcast_reduce_entry_t *entry)
+{
+    if (!entry || nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
+    std::lock_guard<std::mutex> g(g_mu);
+    // this rank count's nearest bucket at or below, else the nearest above; no
+    // borrowing from other rank counts (a reduction's best stage count depends on it)
+    const int want = log2_bucket(bytes);
+    auto it = g_reduce_table.upper_bound({nranks, want});
+    if (it != g_reduce_table.begin()) {
+        auto below = std::prev(it);
+        if (below->first.first == nranks) {
+            *entry = below->second;
+            return BCAST_OK;
+        }
+    }
+    if (it != g_reduce_table.end() && it->first.first == nranks) {
+        *entry = it->second;
+        return BCAST_OK;
+    }
+    return BCAST_ERR_UNTUNED;
+}
+
 extern "C" int bcast_tune_get(int nranks, size_t bytes, bcast_tune_entry_t *entry)
 {
     if (!entry || nranks < 1 || nranks > BCAST_MAX_RANKS) return BCAST_ERR_ARG;
@@ -173,6 +213,13 @@ static void print_entry(FILE *f, int nranks, int bucket, const bcast_tune_entry_
             e.chain_trip_bytes, e.rank_waves, e.chain_rank_waves);
 }
 
+static const char kReduceHeaderLine[] = "# reduce nranks log2_bytes chunk_bytes stages trip_bytes usec   (the chain reduction's own entries)\n";
+
+static void print_reduce_entry(FILE *f, int nranks, int bucket, const bcast_reduce_entry_t &e)
+{
+    fprintf(f, "reduce %d %d %llu %d %d %.3f\n", nranks, bucket, (unsigned long long)e.chunk_bytes, e.stages, e.trip_bytes, e.usec);
+}
+
 extern "C" int bcast_tune_save(const char *path)
 {
     if (!path) return BCAST_ERR_ARG;
@@ -181,6 +228,8 @@ extern "C" int bcast_tune_save(const char *path)
     fprintf(f, "%s", kHeaderLine);
     std::lock_guard<std::mutex> g(g_mu);
     for (const auto &kv : g_table) print_entry(f, kv.first.first, kv.first.second, kv.second);
+    if (!g_reduce_table.empty()) fprintf(f, "%s", kReduceHeaderLine);
+    for (const auto &kv : g_reduce_table) print_reduce_entry(f, kv.first.first, kv.first.second, kv.second);
     fclose(f);
     return BCAST_OK;
 }
@@ -193,10 +242,25 @@ extern "C" int bcast_tune_load(const char *path)
     char line[256];
     int rc = BCAST_OK;
     std::vector<std::pair<std::pair<int, int>, bcast_tune_entry_t>> rows;
+    std::vector<std::pair<std::pair<int, int>, bcast_reduce_entry_t>> reduce_rows;
     while (fgets(line, sizeof line, f)) {
         const char *s = line;
         while (*s == ' ' || *s == '\t') ++s;
         if (*s == '#' || *s == '\n' || *s == '\0') continue;
+        if (strncmp(s, "reduce ", 7) == 0) {
+            int nranks, bucket;
+            unsigned long long chunk = 0;
+            bcast_reduce_entry_t e;
+            memset(&e, 0, sizeof e);
+            int got = sscanf(s + 7, "%d %d %llu %d %d %lf", &nranks, &bucket, &chunk, &e.stages, &e.trip_bytes, &e.usec);
+            e.chunk_bytes = chunk;
+            if (got < 5 || bucket < 0 || bucket > 62 || !valid_reduce_entry(nranks, e)) {
+                rc = BCAST_ERR_ARG;
+                break;
+            }
+            reduce_rows.push_back({{nranks, bucket}, e});
+            continue;
+        }
         int nranks, bucket;
         unsigned long long chunk = 0, cchunk = 0;
         bcast_tune_entry_t e;
@@ -223,6 +287,7 @@ extern "C" int bcast_tune_load(const char *path)
     if (rc != BCAST_OK) return rc;  // a malformed file installs nothing
     std::lock_guard<std::mutex> g(g_mu);
     for (const auto &r : rows) g_table[r.first] = r.second;
+    for (const auto &r : reduce_rows) g_reduce_table[r.first] = r.second;
     return BCAST_OK;
 }
 
@@ -415,5 +480,99 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         if (M > (max_bytes >> 1)) break;  // next doubling would overflow or pass max
     }
     if (f) fclose(f);
+    return rc;
+}
+
+// The reduction's sweep: stage counts 1, 2, 4; trips of 4 KiB and (up to a few
+// MiB) 1 KiB; chunks of one trip per lane for power-of-two lane counts, and the
+// whole message as one chunk.  Timed like the broadcast's candidates.
+extern "C" int bcast_tune_reduce(int nranks, size_t min_bytes, size_t max_bytes, bcast_stream_t stream, const char *table_path)
+{
+    if (nranks < 2 || nranks > BCAST_MAX_RANKS || min_bytes < 4 || max_bytes < min_bytes) return BCAST_ERR_ARG;
+    Scratch sc;
+    sc.bufs.assign(nranks + 1, nullptr);
+    for (int r = 0; r <= nranks; ++r) {
+        hipError_t e = hipMalloc(&sc.bufs[r], max_bytes);
+        if (e == hipSuccess) e = hipMemset(sc.bufs[r], 0, max_bytes);  // fp32 zeros: sums stay finite
+        if (e != hipSuccess) return e == hipErrorOutOfMemory ? BCAST_ERR_NOMEM : BCAST_ERR_HIP;
+    }
+    if (hipEventCreate(&sc.e0) != hipSuccess || hipEventCreate(&sc.e1) != hipSuccess) return BCAST_ERR_HIP;
+    FILE *log = nullptr;
+    {
+        std::lock_guard<std::mutex> g(g_mu);
+        if (!g_log_path.empty()) log = fopen(g_log_path.c_str(), "a");
+    }
+    if (log) fprintf(log, "# reduce nranks bytes chunk_bytes stages trip_bytes usec\n");
+    struct Closer {
+        FILE *f;
+        ~Closer() { if (f) fclose(f); }
+    } log_closer{log};
+    FILE *f = nullptr;
+    if (table_path) {
+        f = fopen(table_path, "a");
+        if (!f) return BCAST_ERR_ARG;
+        fprintf(f, "%s", kReduceHeaderLine);
+    }
+    Closer table_closer{f};
+    const int hops = nranks - 1;
+    int rc = BCAST_OK;
+    size_t M = (size_t)1 << log2_bucket(min_bytes);
+    if (M < min_bytes) M <<= 1;
+    for (; M <= max_bytes && rc == BCAST_OK; M <<= 1) {
+        bcast_reduce_entry_t best;
+        memset(&best, 0, sizeof best);
+        best.usec = 1e30;
+        auto consider = [&](size_t chunk, int stages, int trip) {
+            if (rc != BCAST_OK) return;
+            bcast_plan_t *plan = nullptr;
+            rc = bcast_plan_create(&plan, nranks, M, chunk, BCAST_ALGO_CHAIN);
+            if (rc != BCAST_OK) return;
+            rc = bcast_plan_set_stages(plan, stages);
+            if (rc == BCAST_OK) rc = bcast_plan_set_reduce_trip(plan, trip);
+            if (rc == BCAST_OK) rc = bcast_plan_reserve_reduce(plan, M / sizeof(float), stages);
+            int reps = 1;
+            double fastest = 1e30;
+            for (int batch = 0; batch < 4 && rc == BCAST_OK; ++batch) {
+                if (hipEventRecord(sc.e0, stream) != hipSuccess) { rc = BCAST_ERR_HIP; break; }
+                for (int i = 0; i < reps && rc == BCAST_OK; ++i)
+                    rc = bcast_reduce_sum_f32(plan, sc.bufs.data(), sc.bufs[nranks], 0, M / sizeof(float), stream);
+                if (rc != BCAST_OK) break;
+                if (hipEventRecord(sc.e1, stream) != hipSuccess || hipEventSynchronize(sc.e1) != hipSuccess) { rc = BCAST_ERR_HIP; break; }
+                float ms = 0.f;
+                if (hipEventElapsedTime(&ms, sc.e0, sc.e1) != hipSuccess) { rc = BCAST_ERR_HIP; break; }
+                const double us = (double)ms * 1000.0 / reps;
+                if (batch == 0) reps = (int)std::min(40.0, std::max(2.0, 20000.0 / std::max(us, 1.0)));
+                else fastest = std::min(fastest, us);
+            }
+            if (rc == BCAST_OK && bcast_plan_status(plan, nullptr) != BCAST_OK) rc = BCAST_ERR_TIMEOUT;
+            int rd = bcast_plan_destroy(plan);
+            if (rc == BCAST_OK) rc = rd;
+            if (rc != BCAST_OK) return;
+            if (log) fprintf(log, "reduce %d %zu %zu %d %d %.3f\n", nranks, M, chunk, stages, trip, fastest);
+            if (fastest < best.usec) {
+                best.chunk_bytes = chunk;
+                best.stages = stages;
+                best.trip_bytes = trip;
+                best.usec = fastest;
+            }
+        };
+        const size_t whole = std::max<size_t>(16, (M + 15) / 16 * 16);
+        for (int stages : {1, 2, 4}) {
+            if (stages > hops) continue;
+            for (int trip : {4096, 1024}) {
+                if (trip == 1024 && M > ((size_t)8 << 20)) continue;
+                consider(whole, stages, trip);
+                for (size_t lanes = 64; lanes * (size_t)stages <= 8192; lanes <<= 1) {
+                    const size_t C = lanes * (size_t)trip;
+                    if (C >= M || M / C > 4096) continue;
+                    consider(C, stages, trip);
+                }
+            }
+        }
+        if (rc != BCAST_OK) break;
+        rc = bcast_tune_reduce_put(nranks, M, &best);
+        if (f) print_reduce_entry(f, nranks, log2_bucket(M), best);
+        if (M > (max_bytes >> 1)) break;
+    }
     return rc;
 }

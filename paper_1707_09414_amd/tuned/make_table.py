@@ -3,6 +3,7 @@
     python -m paper_1707_09414_amd.tuned.make_table [--out PATH] [--ranks 2,4,8,...]
                                                     [--min-bytes N] [--max-bytes N] [--with-fanout] [--with-knomial] [--with-knomial-pipelined]
                                                     [--with-scatter-allgather] [--folded] [--no-rank-waves] [--append]
+                                                    [--reduce] [--reduce-only]
 
 For every rank count it runs ``bcast_tune`` (chain over chunk sizes, stage counts and
 trip sizes, with a wavefront per stage and with a wavefront per rank, direct, binomial;
@@ -32,6 +33,8 @@ def main() -> int:
     ap.add_argument("--log", default=None, help="also append every timed candidate to this file")
     ap.add_argument("--folded", action="store_true", help="also try the chain with a single stage (no flag hand-off)")
     ap.add_argument("--no-rank-waves", action="store_true", help="leave out the chain with a wavefront per rank")
+    ap.add_argument("--reduce", action="store_true", help="also measure the chain reduction's table (bcast_tune_reduce)")
+    ap.add_argument("--reduce-only", action="store_true", help="measure only the chain reduction's table")
     ap.add_argument("--append", action="store_true", help="keep the entries --out already holds (other rank counts)")
     args = ap.parse_args()
 
@@ -60,8 +63,13 @@ def main() -> int:
     stream = torch.cuda.current_stream()
     for P in [int(x) for x in args.ranks.split(",")]:
         t0 = time.time()
-        B.bcast_tune(P, args.min_bytes, args.max_bytes, mask, stream, None)
-        print("tuned P=%d in %.1f s (%d entries so far)" % (P, time.time() - t0, B.bcast_tune_count()), flush=True)
+        if not args.reduce_only:
+            B.bcast_tune(P, args.min_bytes, args.max_bytes, mask, stream, None)
+            print("tuned P=%d in %.1f s (%d entries so far)" % (P, time.time() - t0, B.bcast_tune_count()), flush=True)
+        if args.reduce or args.reduce_only:
+            t0 = time.time()
+            B.bcast_tune_reduce(P, max(4, args.min_bytes), args.max_bytes, stream, None)
+            print("tuned the reduction for P=%d in %.1f s" % (P, time.time() - t0), flush=True)
     B.bcast_tune_set_log(None)
     B.bcast_tune_save(args.out)
     print("wrote", args.out)

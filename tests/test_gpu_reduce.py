@@ -259,8 +259,75 @@ def test_staging_memory_is_reserved_never_allocated_by_a_run():
     with pytest.raises(B.BcastError):
         B.bcast_plan_reserve_reduce(plan, count + 1, 2)       # beyond the plan's size
     with pytest.raises(B.BcastError):
-        B.bcast_plan_reserve_reduce(plan, count, 0)
+        B.bcast_plan_reserve_reduce(plan, count, -1)
+    B.bcast_plan_reserve_reduce(plan, count, 0)               # 0 = the library's own choice for this size
     plan.destroy()
+
+
+def test_reduction_table_entries_shape_the_run():
+    """What a plan leaves open (chunk 0, no stage request) comes from the
+    reduction's tuning table: stage count, chunk and trip size; the reservation
+    with stages = 0 follows it; a plan that fixes its chunk ignores it."""
+    P, count = 6, 300000
+    send = contributions(8, P, count)
+    dev = [torch.from_numpy(send[r]).cuda() for r in range(P)]
+    recv = torch.zeros(count, dtype=torch.float32, device="cuda")
+    want, _ = oracle.chain_reduce_f32(send, P, 1, count, 4 * KiB)
+    B.bcast_tune_clear()
+    try:
+        with pytest.raises(B.BcastError):
+            B.bcast_tune_reduce_get(P, count * 4)
+        B.bcast_tune_reduce_put(P, 1 << 20, chunk_bytes=96 * KiB, stages=3, trip_bytes=1024, usec=5.0)
+        for bad in (dict(chunk_bytes=0, stages=1, trip_bytes=4096), dict(chunk_bytes=24, stages=1, trip_bytes=4096),
+                    dict(chunk_bytes=4096, stages=0, trip_bytes=4096), dict(chunk_bytes=4096, stages=1, trip_bytes=2048)):
+            with pytest.raises(B.BcastError):
+                B.bcast_tune_reduce_put(P, 1 << 20, **bad)
+        assert B.bcast_tune_reduce_get(P, count * 4)["stages"] == 3
+        plan = B.bcast_plan_create(P, count * 4, 0, B.BCAST_ALGO_CHAIN)
+        # nothing reserved yet: the entry's three stages do not fit, the choice shrinks to one and the entry's chunk is not used
+        assert B.bcast_reduce_info(plan, count)["stages"] == 1
+        B.bcast_plan_reserve_reduce(plan, count, 0)
+        info = B.bcast_reduce_info(plan, count)
+        assert (info["stages"], info["chunk_bytes"], info["trip_bytes"]) == (3, 96 * KiB, 1024)
+        B.bcast_reduce_sum_f32(plan, dev, recv, 1, count)
+        torch.cuda.synchronize()
+        assert np.array_equal(recv.cpu().numpy().view(np.uint32), want.view(np.uint32))
+        plan.destroy()
+        fixed = B.bcast_plan_create(P, count * 4, 64 * KiB, B.BCAST_ALGO_CHAIN)
+        B.bcast_plan_reserve_reduce(fixed, count, 2)
+        info = B.bcast_reduce_info(fixed, count)
+        assert (info["stages"], info["chunk_bytes"]) == (2, 64 * KiB)
+        fixed.destroy()
+    finally:
+        B.bcast_tune_clear()
+
+
+def test_tune_reduce_installs_measured_entries(tmp_path):
+    """The sweep itself, small: entries for every size, saved and loaded with the
+    broadcast's in one file; the tuned shape gives the oracle's bits."""
+    P = 5
+    B.bcast_tune_clear()
+    try:
+        path = str(tmp_path / "table.txt")
+        B.bcast_tune_set(P, 1 << 16, B.BCAST_ALGO_DIRECT, 0, 3.0)
+        B.bcast_tune_reduce(P, 1 << 14, 1 << 18, torch.cuda.current_stream(), None)
+        entries = {b: B.bcast_tune_reduce_get(P, 1 << b) for b in range(14, 19)}
+        assert all(1 <= e["stages"] <= 4 and e["usec"] > 0 and e["trip_bytes"] in (1024, 4096) for e in entries.values())
+        B.bcast_tune_save(path)
+        B.bcast_tune_clear()
+        B.bcast_tune_load(path)
+        assert B.bcast_tune_lookup(P, 1 << 16)[0] == B.BCAST_ALGO_DIRECT
+        for b, e in entries.items():
+            got = B.bcast_tune_reduce_get(P, 1 << b)
+            assert (got["stages"], got["chunk_bytes"], got["trip_bytes"]) == (e["stages"], e["chunk_bytes"], e["trip_bytes"])
+        count = (1 << 16) + 5
+        plan = B.bcast_plan_create(P, count * 4, 0, B.BCAST_ALGO_CHAIN)
+        B.bcast_plan_reserve_reduce(plan, count, 0)
+        assert B.bcast_reduce_info(plan, count)["stages"] == B.bcast_tune_reduce_get(P, count * 4)["stages"]
+        reduce_and_check(P, 3, count, 0, seed=77, plan=plan, cap=count)
+        plan.destroy()
+    finally:
+        B.bcast_tune_clear()
 
 
 @pytest.mark.parametrize("seed", [11, 12])
