@@ -8,7 +8,8 @@ largest configurations the oracle runs its schedule at full scale (step count)
 and its payload simulation at full P on a prefix of the message, and the GPU
 buffers are compared with the message itself: three ranks completely, every
 other rank on seeded 1 MiB windows copied back to the host, plus a device-side
-whole-buffer comparison."""
+whole-buffer comparison.  Every rank buffer sits between two 256-byte guard
+bands of 0xFF that are compared after every run."""
 import numpy as np
 import pytest
 import torch
@@ -30,25 +31,38 @@ def shipped_table():
     B.bcast_tune_clear()
 
 
-def device_buffers(P, M, root, msg, slack=0):
-    bufs = [torch.full((M + slack,), FILL, dtype=torch.uint8, device="cuda") for _ in range(P)]
-    bufs[root][:M].copy_(torch.from_numpy(msg))
-    return bufs
+GUARD = 256  # bytes of 0xFF kept before and after every rank buffer, compared after every run
 
 
-def check_against_message(bufs, msg, M, root, full_ranks, windows=64, seed=0):
+def device_buffers(P, M, root, msg):
+    """P allocations of GUARD + M + GUARD bytes of 0xFF; rank r's buffer is the
+    middle M bytes.  Returns (rank buffers, whole allocations)."""
+    raws = [torch.full((GUARD + M + GUARD,), FILL, dtype=torch.uint8, device="cuda") for _ in range(P)]
+    bufs = [t[GUARD: GUARD + M] for t in raws]
+    bufs[root].copy_(torch.from_numpy(msg))
+    return bufs, raws
+
+
+def check_against_message(bufs, raws, msg, M, root, full_ranks, windows=64, seed=0):
     d_msg = torch.from_numpy(msg).cuda()
     rng = np.random.default_rng(seed)
     for r, t in enumerate(bufs):
-        assert torch.equal(t[:M], d_msg), "rank %d differs from the message (device compare)" % r
-        assert bool((t[M:] == FILL).all()), "rank %d: bytes beyond the message were written" % r
+        assert torch.equal(t, d_msg), "rank %d differs from the message (device compare)" % r
+        assert bool((raws[r][:GUARD] == FILL).all()), "rank %d: bytes before the buffer were written" % r
+        assert bool((raws[r][GUARD + M:] == FILL).all()), "rank %d: bytes beyond the message were written" % r
         if r in full_ranks:
-            assert np.array_equal(t[:M].cpu().numpy(), msg), "rank %d differs from the message" % r
+            assert np.array_equal(t.cpu().numpy(), msg), "rank %d differs from the message" % r
         else:
             starts = [0, max(0, M - MiB)] + [int(x) for x in rng.integers(0, max(1, M - MiB), size=windows)]
             for s in starts:
                 e = min(M, s + MiB)
                 assert np.array_equal(t[s:e].cpu().numpy(), msg[s:e]), "rank %d differs in [%d, %d)" % (r, s, e)
+
+
+def refill(bufs, root):
+    for r, b in enumerate(bufs):
+        if r != root:
+            b.fill_(FILL)
 
 
 def oracle_prefix_check(P, root, msg, C, prefix):
@@ -63,8 +77,9 @@ def oracle_prefix_check(P, root, msg, C, prefix):
 
 
 def test_config2_message_size_sweep_p8():
-    """4 B .. 64 MiB in powers of two, P=8, root 0: chain (tuned chunk and one
-    swept chunk), direct and binomial against the oracle's full simulation."""
+    """4 B .. 64 MiB in powers of two, P=8, root 0: chain (tuned, and one swept
+    chunk with a wavefront per stage and per rank), direct, binomial and AUTO
+    against the oracle's full simulation."""
     P, root = 8, 0
     draw = inputs.random_bytes(1, 64 * MiB)
     sizes = inputs.sweep_message_sizes(4, 64 * MiB)
@@ -79,19 +94,22 @@ def test_config2_message_size_sweep_p8():
         swept = chunks[i % len(chunks)]
         steps = oracle.chain_bcast(want, P, root, M, swept).steps
         assert steps == -(-M // swept) + P - 2
-        for algo, C in [(B.BCAST_ALGO_CHAIN, 0), (B.BCAST_ALGO_CHAIN, swept), (B.BCAST_ALGO_DIRECT, 0),
-                        (B.BCAST_ALGO_BINOMIAL, 0), (B.BCAST_ALGO_AUTO, 0)]:
-            bufs = device_buffers(P, M, root, msg, slack=64)
+        for algo, C, waves in [(B.BCAST_ALGO_CHAIN, 0, 0), (B.BCAST_ALGO_CHAIN, swept, B.BCAST_CHAIN_WAVE_PER_STAGE),
+                               (B.BCAST_ALGO_CHAIN, swept, B.BCAST_CHAIN_WAVE_PER_RANK), (B.BCAST_ALGO_DIRECT, 0, 0),
+                               (B.BCAST_ALGO_BINOMIAL, 0, 0), (B.BCAST_ALGO_AUTO, 0, 0)]:
+            bufs, raws = device_buffers(P, M, root, msg)
             plan = B.bcast_plan_create(P, M, C, algo)
+            if waves:
+                B.bcast_plan_set_chain_waves(plan, waves)
             B.bcast_run(plan, bufs, root, M, stream)
             torch.cuda.synchronize()
             assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
             plan.destroy()
             for r in range(P):
-                got = bufs[r].cpu().numpy()
-                assert np.array_equal(got[:M], want[r]), (M, algo, C, r)
-                assert (got[M:] == FILL).all(), (M, algo, C, r)
-            del bufs
+                got = raws[r].cpu().numpy()
+                assert np.array_equal(got[GUARD: GUARD + M], want[r]), (M, algo, C, waves, r)
+                assert (got[:GUARD] == FILL).all() and (got[GUARD + M:] == FILL).all(), (M, algo, C, waves, r)
+            del bufs, raws
 
 
 def test_config3_vgg16_per_tensor_and_packed_p16():
@@ -104,7 +122,7 @@ def test_config3_vgg16_per_tensor_and_packed_p16():
     stream = torch.cuda.current_stream()
 
     # tensor by tensor, each tensor in its own set of P buffers carved out of one allocation per rank
-    bufs = device_buffers(P, M, root, msg)
+    bufs, raws = device_buffers(P, M, root, msg)
     plan = B.bcast_plan_create(P, max(n for _, n in spans), 0, B.BCAST_ALGO_AUTO)
     algos = set()
     for off, n in spans:
@@ -115,53 +133,90 @@ def test_config3_vgg16_per_tensor_and_packed_p16():
     assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
     plan.destroy()
     assert len(algos) >= 2, "the message mix should exercise more than one algorithm"
-    check_against_message(bufs, msg, M, root, full_ranks={1, 8, 15}, seed=3)
+    check_against_message(bufs, raws, msg, M, root, full_ranks={1, 8, 15}, seed=3)
 
-    # packed into one buffer, chain
-    for b in bufs[1:]:
-        b.fill_(FILL)
-    plan = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_CHAIN)
-    info = B.bcast_plan_info(plan, M, bufs)
-    B.bcast_run(plan, bufs, root, M, stream)
-    torch.cuda.synchronize()
-    assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
-    plan.destroy()
-    check_against_message(bufs, msg, M, root, full_ranks={1, 8, 15}, seed=4)
+    # packed into one buffer: the tuned chain, and the chain with a wavefront per stage and per rank
+    for waves in (B.BCAST_CHAIN_AUTO, B.BCAST_CHAIN_WAVE_PER_STAGE, B.BCAST_CHAIN_WAVE_PER_RANK):
+        refill(bufs, root)
+        plan = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_CHAIN)
+        B.bcast_plan_set_chain_waves(plan, waves)
+        info = B.bcast_plan_info(plan, M, bufs)
+        B.bcast_run(plan, bufs, root, M, stream)
+        torch.cuda.synchronize()
+        assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+        plan.destroy()
+        check_against_message(bufs, raws, msg, M, root, full_ranks={1, 8, 15} if waves == B.BCAST_CHAIN_AUTO else {15}, seed=4 + waves)
     oracle_prefix_check(P, root, msg, int(info["chunk_bytes"]), 32 * MiB)
 
 
 def test_config4_512mib_p32():
     P, root, M = 32, 0, 512 * MiB
     msg = inputs.random_bytes(3, M)
-    bufs = device_buffers(P, M, root, msg)
-    plan = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_CHAIN)
-    info = B.bcast_plan_info(plan, M, bufs)
-    B.bcast_run(plan, bufs, root, M, torch.cuda.current_stream())
-    torch.cuda.synchronize()
-    assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
-    plan.destroy()
-    check_against_message(bufs, msg, M, root, full_ranks={1, 16, 31}, seed=5)
-    oracle_prefix_check(P, root, msg, int(info["chunk_bytes"]), 8 * MiB)
+    bufs, raws = device_buffers(P, M, root, msg)
+    for waves in (B.BCAST_CHAIN_AUTO, B.BCAST_CHAIN_WAVE_PER_STAGE, B.BCAST_CHAIN_WAVE_PER_RANK):
+        refill(bufs, root)
+        plan = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_CHAIN)
+        B.bcast_plan_set_chain_waves(plan, waves)
+        info = B.bcast_plan_info(plan, M, bufs)
+        B.bcast_run(plan, bufs, root, M, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+        plan.destroy()
+        check_against_message(bufs, raws, msg, M, root, full_ranks={1, 16, 31} if waves == B.BCAST_CHAIN_AUTO else {31}, seed=5 + waves)
+        oracle_prefix_check(P, root, msg, int(info["chunk_bytes"]), 8 * MiB)
 
 
 def test_config5_1gib_p64_root17():
     P, root, M = 64, 17, 1 * GiB
     msg = inputs.random_bytes(4, M)
-    bufs = device_buffers(P, M, root, msg, slack=4096)
-    for algo in (B.BCAST_ALGO_CHAIN, B.BCAST_ALGO_AUTO):
-        for r in range(P):
-            if r != root:
-                bufs[r].fill_(FILL)
+    bufs, raws = device_buffers(P, M, root, msg)
+    for algo, waves in ((B.BCAST_ALGO_CHAIN, B.BCAST_CHAIN_AUTO), (B.BCAST_ALGO_CHAIN, B.BCAST_CHAIN_WAVE_PER_RANK), (B.BCAST_ALGO_AUTO, B.BCAST_CHAIN_AUTO)):
+        refill(bufs, root)
         plan = B.bcast_plan_create(P, M, 0, algo)
+        B.bcast_plan_set_chain_waves(plan, waves)
         info = B.bcast_plan_info(plan, M, bufs)
         B.bcast_run(plan, bufs, root, M, torch.cuda.current_stream())
         torch.cuda.synchronize()
         assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
         plan.destroy()
         # chain positions 1, 32 and 63 (the last: rank root - 1) completely
-        full = {(root + 1) % P, (root + 32) % P, (root + P - 1) % P}
-        check_against_message(bufs, msg, M, root, full_ranks=full, seed=6)
+        full = {(root + 1) % P, (root + 32) % P, (root + P - 1) % P} if waves == B.BCAST_CHAIN_AUTO and algo == B.BCAST_ALGO_CHAIN else {(root + P - 1) % P}
+        check_against_message(bufs, raws, msg, M, root, full_ranks=full, seed=6 + waves + algo)
     oracle_prefix_check(P, root, msg, int(info["chunk_bytes"]) if info["algo"] == B.BCAST_ALGO_CHAIN else 4 * MiB, 4 * MiB)
+
+
+@pytest.mark.parametrize("algo", [B.BCAST_ALGO_AUTO, B.BCAST_ALGO_CHAIN])
+def test_config5_burst_of_1000_small_broadcasts(algo):
+    """1000 back-to-back 4 KiB broadcasts at P=64, root 17, with the shipped
+    table (AUTO: the pipelined tree; CHAIN: the tuned chain), a distinct message
+    in every run and no flag reset in between: chain positions 1, 32 and 63 are
+    captured after every run, so a stale flag that let a wave forward an earlier
+    run's bytes would show."""
+    P, root, M, N = 64, 17, 4 * KiB, 1000
+    msgs = inputs.random_bytes(4, N * M).reshape(N, M)
+    d_msgs = torch.from_numpy(msgs).cuda()
+    bufs, raws = device_buffers(P, M, root, msgs[0])
+    watch = [(root + k) % P for k in (1, 32, 63)]
+    outs = [torch.empty((N, M), dtype=torch.uint8, device="cuda") for _ in watch]
+    plan = B.bcast_plan_create(P, M, 0, algo)
+    info = B.bcast_plan_info(plan, M, bufs)
+    assert info["algo"] == (B.bcast_tune_lookup(P, M)[0] if algo == B.BCAST_ALGO_AUTO else B.BCAST_ALGO_CHAIN)
+    ptrs = B.RankPointers(bufs)
+    stream = torch.cuda.current_stream()
+    for i in range(N):
+        bufs[root].copy_(d_msgs[i])
+        B.bcast_run(plan, ptrs, root, M, stream)
+        for o, r in zip(outs, watch):
+            o[i].copy_(bufs[r])
+    torch.cuda.synchronize()
+    assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+    plan.destroy()
+    for o, r in zip(outs, watch):
+        assert np.array_equal(o.cpu().numpy(), msgs), "rank %d saw a stale or wrong message in some run" % r
+    for r in range(P):
+        got = raws[r].cpu().numpy()
+        assert np.array_equal(got[GUARD: GUARD + M], msgs[N - 1]), r
+        assert (got[:GUARD] == FILL).all() and (got[GUARD + M:] == FILL).all(), r
 
 
 @pytest.mark.parametrize("P", [3, 6, 12, 24, 48, 63])

@@ -179,7 +179,8 @@ def test_wait_limit_in_the_reduction():
 
 def test_vgg16_gradient_sized_reduction_p16():
     """The VGG-16 parameter count (138M fp32, N(0, 0.01)) summed over 16 ranks:
-    the full result is compared with the oracle's."""
+    the full result is compared with the oracle's; then the same as an allreduce,
+    every rank's full result compared."""
     P, root = 16, 0
     count = sum(inputs.vgg16_tensor_bytes()) // 4
     base = inputs.vgg16_packed_message(2)[0].view(np.float32)   # one N(0, 0.01) draw of the right size
@@ -200,6 +201,15 @@ def test_vgg16_gradient_sized_reduction_p16():
     want, res = oracle.chain_reduce_f32(host, P, root, count, info["chunk_bytes"] // 4)
     assert res.steps == info["nchunks"] + P - 2
     assert np.array_equal(recv.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    del recv
+    # the same size as an allreduce, in place: every rank must end with exactly these bits
+    plan = B.bcast_plan_create(P, count * 4, 0, B.BCAST_ALGO_CHAIN)
+    B.bcast_allreduce_sum_f32(plan, dev, dev, root, count, torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+    plan.destroy()
+    for r in range(P):
+        assert np.array_equal(dev[r].cpu().numpy().view(np.uint32), want.view(np.uint32)), "rank %d" % r
 
 
 @pytest.mark.parametrize("P,root,count,in_place", [(2, 1, 5, False), (4, 0, 70001, True), (8, 5, 1 << 20, False), (16, 3, 300000, True), (64, 17, 65536, False)])
