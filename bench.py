@@ -113,8 +113,13 @@ def profile_traffic(prof):
             raise ValueError("%s: %d rows match %r" % (prof["path"], len(hits), name))
         return hits[0]
 
-    f_cal = msg_kib / pick(rows["FETCH_SIZE"], "__amd_rocclr_copyBuffer")["avg_kib"]
-    w_cal = msg_kib / pick(rows["WRITE_SIZE"], "__amd_rocclr_copyBuffer")["avg_kib"]
+    if leg["calibration_copy_bytes"] >= MiB:
+        f_cal = msg_kib / pick(rows["FETCH_SIZE"], "__amd_rocclr_copyBuffer")["avg_kib"]
+        w_cal = msg_kib / pick(rows["WRITE_SIZE"], "__amd_rocclr_copyBuffer")["avg_kib"]
+    else:
+        # a copy of a few KiB is lost in the counters' fixed overheads: use what every large copy shows
+        # (FETCH_SIZE reads half the bytes, WRITE_SIZE all of them)
+        f_cal, w_cal = 2.0, 1.0
     fetch = pick(rows["FETCH_SIZE"], kernel)["avg_kib"] * f_cal
     write = pick(rows["WRITE_SIZE"], kernel)["avg_kib"] * w_cal
     launches = leg.get("launches_per_step", 1)
@@ -407,7 +412,7 @@ def vgg_tensor_by_tensor(B, torch, bufs, P, root, stream, quick):
     return st
 
 
-def burst(B, torch, inputs, np, P, root, M, stream, variant, n_runs, no_verify):
+def burst(B, torch, inputs, np, P, root, M, stream, variant, n_runs, no_verify, profiles):
     """n_runs back-to-back broadcasts of M bytes between two HIP events: what a
     small broadcast costs when launches queue up behind each other."""
     msg = inputs.random_bytes(4, M)
@@ -434,8 +439,15 @@ def burst(B, torch, inputs, np, P, root, M, stream, variant, n_runs, no_verify):
         if err:
             raise RuntimeError("cfg5b %s: %s" % (variant, err))
     row = stats_us(samples)
-    row.update({"runs_per_sample": n_runs, "algo": B.ALGO_NAMES[info["algo"]], "geometry": geometry_of(B, info),
+    geometry = geometry_of(B, info)
+    row.update({"runs_per_sample": n_runs, "algo": B.ALGO_NAMES[info["algo"]], "kernel": kernel_name(info, B), "geometry": geometry,
                 "algorithmic_GBps": round(2 * (P - 1) * M / row["median_us"] / 1e3, 2), "verified_bit_exact": None if no_verify else True})
+    traffic, why = traffic_for(profiles, "cfg5b", variant, geometry)
+    if traffic:
+        row.update({"traffic_bytes": traffic["bytes"], "traffic_GBps": round(traffic["bytes"] / row["median_us"] / 1e3, 2), "profile": traffic["file"],
+                    "profile_kernel_us": round(traffic["avg_kernel_ns"] * 1e-3, 3)})
+    else:
+        row.update({"traffic_bytes": None, "traffic_note": why})
     return row
 
 
@@ -625,7 +637,7 @@ def main() -> int:
         if name == "cfg5b":
             n = 200 if args.quick else 1000
             for variant in VARIANTS[name]:
-                row["variants"][variant] = burst(B, torch, inputs, np, P, root, M, stream, variant, n, args.no_verify)
+                row["variants"][variant] = burst(B, torch, inputs, np, P, root, M, stream, variant, n, args.no_verify, profiles)
             configs.append(row)
             continue
         msg = make_message(name, seed, M)

@@ -87,10 +87,11 @@ long oracle_knomial_bcast(unsigned char **bufs, int P, int root, size_t M, int k
                           oracle_trace_t *tr);
 
 /* Pipelined k-nomial tree: the k-nomial levels of Eq. 3 with the message cut
- * into chunks of C bytes as in Sec. IV-B.  The paper's source carries, after
- * Eq. 5, a remark (not typeset) that the tree can be pipelined too: a sender
- * needs M/C steps to push the message to the children of one level and there
- * are ceil(log_k n) levels, (M/C * ceil(log_k n)) steps of (t_s + C/B) each.
+ * into chunks of C bytes as in Sec. IV-B.  The paper pipelines the chain only;
+ * this is the build's own extension of the same chunking to the tree, taken
+ * level by level: a sender needs ceil(M/C) steps to push the message to its
+ * children of one level and there are ceil(log_k n) levels, so
+ * (ceil(M/C) * ceil(log_k n)) steps of (t_s + C/B) each.
  * This function walks exactly that: level after level, and inside a level one
  * step per chunk in which every holder sends that chunk to each of its k - 1
  * children of the level.  C >= M is oracle_knomial_bcast.  Returns the number
@@ -135,7 +136,7 @@ double oracle_model_direct(int n, double M, double ts, double B);
 double oracle_model_chain(int n, double M, double ts, double B);
 double oracle_model_knomial(int n, int k, double M, double ts, double B);
 double oracle_model_scatter_allgather(int n, double M, double ts, double B);
-/* the pipelined k-nomial remark after Eq. 5: (M/C * ceil(log_k n)) (t_s + C/B) */
+/* the level-by-level pipelined k-nomial tree (the build's extension, see above): (M/C * ceil(log_k n)) (t_s + C/B) */
 double oracle_model_knomial_pipeline(int n, int k, double M, double C, double ts, double B);
 double oracle_model_chain_pipeline(int n, double M, double C, double ts, double B);
 

@@ -24,6 +24,7 @@ struct bcast_plan {
     int max_waves[3] = {0, 0, 0};
     int max_flags = 0;                    // flags allocated: the largest of the above
     int max_waves_reduce = 0;             // the same limit for the reduction kernel (256-thread workgroups)
+    int max_waves_tree = 0;               // ... and for the pipelined tree kernel
     char *d_scratch = nullptr;            // reduction: running sums handed from stage to stage
     size_t scratch_bytes = 0;             // (bcast_plan_reserve_reduce; the run path never allocates)
     char *static_scratch = nullptr;       // this device's copy of the library's static scratch array
@@ -231,6 +232,13 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
         e = reduce_max_blocks_per_cu(&per_cu);
         per_cu = std::max(1, std::min(per_cu, 8));
         p->max_waves_reduce = std::min(p->max_flags, std::max(nranks, p->cu_count * per_cu * kWavesPerBlock));
+    }
+    if (e == hipSuccess) {
+        // the tree kernel's own residency limit (its waves wait for their parents' waves)
+        int per_cu = 0;
+        e = tree_max_blocks_per_cu(&per_cu);
+        per_cu = std::max(1, std::min(per_cu, 8));
+        p->max_waves_tree = std::min(p->max_flags, std::max(nranks, p->cu_count * per_cu * kWavesPerBlock));
     }
     if (e == hipSuccess) {
         size_t flag_bytes = ((size_t)p->max_flags + 2) * kFlagStrideWords * sizeof(u64);
@@ -458,7 +466,7 @@ static int waves_for(const bcast_plan *p, size_t)
 // its own, all resident at once; a power of two like the chain's lanes.
 static u64 tree_lanes_max(const bcast_plan *p)
 {
-    const u64 per_pos = (u64)p->max_waves[block_index(kBlockThreads)] / (u64)std::max(1, p->nranks - 1);
+    const u64 per_pos = (u64)p->max_waves_tree / (u64)std::max(1, p->nranks - 1);
     u64 l = 1;
     while (l * 2 <= per_pos) l *= 2;
     return l;
@@ -710,7 +718,7 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
         const u64 nchunks = ceil_div(bytes, C);
         if (nchunks >= (1ull << 27)) return BCAST_ERR_ARG;  // the flag word keeps the count in 28 bits
         u64 lanes = std::max<u64>(1, std::min(tree_lanes_max(p), ceil_div(C, trip)));
-        if (p->lanes_request > 0) lanes = std::min<u64>((u64)p->lanes_request, (u64)p->max_waves[block_index(kBlockThreads)] / (u64)(P - 1));
+        if (p->lanes_request > 0) lanes = std::min<u64>((u64)p->lanes_request, (u64)p->max_waves_tree / (u64)(P - 1));
         else {
             u64 l = 1;
             while (l * 2 <= lanes) l *= 2;
@@ -925,7 +933,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         if (rc != BCAST_OK) return rc;
         const int k = info.stages;
         if (k < 2) return BCAST_ERR_ARG;
-        if ((u64)(P - 1) * a.lanes > (u64)p->max_waves[block_index(kBlockThreads)]) return BCAST_ERR_ARG;
+        if ((u64)(P - 1) * a.lanes > (u64)p->max_waves_tree) return BCAST_ERR_ARG;
         // the k-nomial tree of Eq. 3: position q = holder + i k^j (holder < k^j,
         // 1 <= i < k) receives from holder, i.e. from q without its leading
         // base-k digit

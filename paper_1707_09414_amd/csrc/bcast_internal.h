@@ -184,6 +184,7 @@ hipError_t rank_chain_max_blocks_per_cu(int block_threads, int *blocks);
 hipError_t launch_tree(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
 hipError_t launch_reduce(const ChainArgs &a, int grid_blocks, hipStream_t stream);
 hipError_t reduce_max_blocks_per_cu(int *blocks);
+hipError_t tree_max_blocks_per_cu(int *blocks);
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);

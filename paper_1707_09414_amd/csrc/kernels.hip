@@ -355,6 +355,9 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
         if (in_flag) {
             const u64 want = a.base + ((u64)(c + 1) << 4);
             if (seen < want && !wait_ready(in_flag, want, a, first_hop, c, lane, &seen)) return;
+            // whichever read of the flag showed the chunk (this wait, or the look-ahead after the chunk
+            // before): no payload load of this chunk may be moved above it
+            asm volatile("" ::: "memory");
             const bool same_xcd = (unsigned)(seen & 15u) == xcd;
             near += same_xcd;
             far += !same_xcd;
@@ -490,6 +493,7 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
         if (in_flag) {
             const u64 want = a.base + ((u64)(c + 1) << 4);
             if (seen < want && !wait_ready(in_flag, want, a, hop, c, lane, &seen)) return;
+            asm volatile("" ::: "memory");  // also behind the look-ahead read of the flag
         }
         for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
             const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
@@ -520,8 +524,8 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
 
 // ---------------------------------------------------------------------------
 // Pipelined k-nomial tree in one launch: the tree of Eq. 3 with the chunking and
-// the ready flags of the pipelined chain (the paper's source notes after Eq. 5
-// that the tree can be pipelined in the same way).  Every receiving position
+// the ready flags of the pipelined chain (this build's own combination of the
+// two: Sec. IV-B pipelines the chain only).  Every receiving position
 // has `lanes` wavefronts of its own; wavefront (position, lane) waits until its
 // PARENT position has published lane's share of chunk c, copies it out of the
 // parent's buffer into its own, and publishes it for its children.  A chunk
@@ -557,6 +561,7 @@ __global__ void __launch_bounds__(kBlockThreads) tree_kernel(const ChainArgs a)
         if (in_flag) {
             const u64 want = a.base + ((u64)(c + 1) << 4);
             if (seen < want && !wait_ready(in_flag, want, a, pos, c, lane, &seen)) return;
+            asm volatile("" ::: "memory");  // also behind the look-ahead read of the flag
         }
         for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
             const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
@@ -681,6 +686,7 @@ __global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a
         if (in_flag) {
             const u64 want = a.base + ((u64)(c + 1) << 4);
             if (seen < want && !wait_ready(in_flag, want, a, first_hop, c, lane, &seen)) return;
+            asm volatile("" ::: "memory");  // also behind the look-ahead read of the flag
         }
         for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
             const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
@@ -863,6 +869,11 @@ hipError_t launch_reduce(const ChainArgs &a, int grid_blocks, hipStream_t stream
     else if (a.unroll == (unsigned)kRedUnroll) reduce_kernel<kRedUnroll, 4><<<dim3(grid_blocks), dim3(kBlockThreads), 0, stream>>>(a);
     else return hipErrorInvalidValue;
     return hipGetLastError();
+}
+
+hipError_t tree_max_blocks_per_cu(int *blocks)
+{
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks, tree_kernel<16>, kBlockThreads, 0);
 }
 
 hipError_t reduce_max_blocks_per_cu(int *blocks)

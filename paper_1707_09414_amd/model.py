@@ -64,8 +64,10 @@ def t_chain_pipeline(n, M, C, ts, B):
 
 
 def t_knomial_pipeline(n, k, M, C, ts, B):
-    """The pipelined k-nomial remark after Eq. 5 in the paper's source:
-    (M/C ceil(log_k n))(t_s + C/B)."""
+    """This build's extension of Eq. 5's chunking to the tree of Eq. 3, level by
+    level: a level is done when its senders have pushed all M/C chunks to their
+    children, one chunk per step of (t_s + C/B), and there are ceil(log_k n)
+    levels: (M/C ceil(log_k n))(t_s + C/B).  Not a formula of the paper."""
     return (M / C * ceil_log(n, k)) * (ts + C / B)
 
 
