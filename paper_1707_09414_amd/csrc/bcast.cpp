@@ -1210,4 +1210,4 @@ extern "C" const char *bcast_strerror(int status)
 
 extern "C" int bcast_last_hip_error(void) { return g_last_hip_error; }
 
-extern "C" const char *bcast_version(void) { return "bcast-gfx950 0.1"; }
+extern "C" const char *bcast_version(void) { return "bcast-gfx950 0.2"; }
