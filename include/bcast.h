@@ -75,7 +75,7 @@ typedef struct {
                               where nranks-1 is no multiple of stages this is the larger of the two counts */
     int lanes;             /* chain: wavefronts per stage, each streaming its own share of every chunk */
     int rotating_spans;    /* chain: 1 if the stages that play one hop more change from chunk to chunk */
-    int trip_bytes;        /* chain: bytes a wavefront moves per trip at 16-byte accesses (3072 or 4096) */
+    int trip_bytes;        /* chain: bytes a wavefront moves per trip at 16-byte accesses (a multiple of 1024) */
     uint64_t slice_bytes;  /* chain: bytes of every chunk owned by one lane, in trips dealt round-robin over the lanes */
     int grid_blocks;       /* workgroups of the (first) launch */
     int block_threads;     /* threads per workgroup */
@@ -197,7 +197,7 @@ int bcast_plan_set_radix(bcast_plan_t *plan, int radix);
 typedef struct {
     int lanes;         /* wavefronts per stage */
     int stages;        /* groups of consecutive chain positions served by one set of wavefronts */
-    int trip_bytes;    /* 3072 or 4096 */
+    int trip_bytes;    /* 2048, 3072, 4096 or 6144 */
     int block_threads; /* 64, 128 or 256 */
 } bcast_chain_request_t;
 

@@ -40,7 +40,7 @@ struct bcast_plan {
     int lanes_request = 0;
     int stages_request = 0;
     int radix_request = 0;
-    int trip_request = 0;  // bytes at 16-byte vectors: 0 = choose, else 3072 or 4096
+    int trip_request = 0;  // bytes at 16-byte vectors: 0 = choose, else a size the run's chain kernel is built for
     int block_request = 0; // chain workgroup size: 0 = choose, else 64, 128 or 256
     u64 spin_ticks = kDefaultSpinTicks;
     int mute_hop = 0;

@@ -41,7 +41,9 @@ constexpr u64 kTileBytes = (u64)kWaveSize * 16 * kUnroll;
 // per wave at 16 bytes per lane.  The trips of a CU's resident waves must fit
 // its 32 KiB vector L1 to be read back from it (see chain_kernel); measured on
 // MI355X, 8 waves per CU with 3 KiB trips (24 KiB) is best for many ranks and
-// 4 KiB trips for few, so both are built and the tuner chooses.
+// 4 KiB trips for few; the kernel is built for 2, 3, 4 and 6 KiB (the chain with
+// a wavefront per rank also for 1 and 8), the tuner sweeps 3 and 4, and these two
+// are the rules without a table.
 constexpr int kTripUnrollDefault = 4;
 constexpr int kTripUnrollSmall = 3;
 
@@ -81,7 +83,7 @@ struct ChainArgs {
     unsigned lanes;    // wavefronts per stage
     unsigned stages;   // groups of consecutive chain positions, each served by its own waves
     unsigned hops_per_stage; // the most hops a stage plays for one chunk (informational)
-    unsigned unroll;   // vector instructions per lane and trip: kTripUnrollDefault or kTripUnrollSmall
+    unsigned unroll;   // vector instructions per lane and trip (KiB per wave at 16-byte vectors): one the kernel is built for
     unsigned nranks;
     unsigned mute_hop; // debug: this position never publishes (0 = off)
     unsigned mode;     // kMode* bits
