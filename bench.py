@@ -485,7 +485,17 @@ def reduce_row(B, torch, np, P, root, M, seed, stream, profiles, name, quick, no
         verified = bool(np.array_equal(recv[:sample].cpu().numpy().view(np.uint32), want.view(np.uint32)))
         if not verified:
             raise RuntimeError("reduce %s: differs from the oracle" % name)
+    n = count * 4 // 4096 * 4096
+    scratch = torch.empty(count, dtype=torch.float32, device="cuda")
+    load_ms = stats_us(time_runs(torch, lambda: B.bcast_debug_load_pattern(send, n, scratch, False, stream), stream, 2, 5 if quick else 10))
+    both_ms = stats_us(time_runs(torch, lambda: B.bcast_debug_load_pattern(send, n, scratch, True, stream), stream, 2, 5 if quick else 10))
+    del scratch
     row = stats_us(ms)
+    # the same P buffers only read, and read with the fold written out, by the library's dependency-free
+    # measurement kernel: what this memory system gives the reduction's access pattern
+    row["ceilings"] = {"load_only_median_us": load_ms["median_us"], "load_only_GBps": round(P * n / load_ms["median_us"] / 1e3, 1),
+                       "load_and_store_result_median_us": both_ms["median_us"],
+                       "load_and_store_result_GBps": round((P + 1) * n / both_ms["median_us"] / 1e3, 1)}
     med_s = row["median_us"] * 1e-6
     algorithmic = (P + 1) * count * 4
     fl = algorithmic + 2 * (info["stages"] - 1) * count * 4  # + the running sum through memory at every stage boundary
@@ -502,6 +512,22 @@ def reduce_row(B, torch, np, P, root, M, seed, stream, profiles, name, quick, no
     else:
         row.update({"traffic_bytes": None, "traffic_note": why})
     return row
+
+
+def ceilings(B, torch, bufs, root, M, stream, quick):
+    """What the device's memory gives the broadcast's write set with no
+    dependencies at all: the P-1 receiving buffers overwritten tile by tile by
+    the library's measurement kernel (bcast_debug_store_pattern).  No broadcast
+    to P-1 ranks on one die can finish sooner."""
+    targets = [b for r, b in enumerate(bufs) if r != root]
+    n = M // 4096 * 4096
+    if n == 0:
+        return None
+    ms = time_runs(torch, lambda: B.bcast_debug_store_pattern(targets, n, stream), stream, 2, 5 if quick else 10)
+    st = stats_us(ms)
+    return {"store_only_median_us": st["median_us"], "store_only_min_us": st["min_us"], "store_only_bytes": len(targets) * n,
+            "store_only_GBps": round(len(targets) * n / st["median_us"] / 1e3, 1),
+            "store_only_frac_of_peak": round(len(targets) * n / st["median_us"] / 1e3 / HBM_PEAK_GBS, 4)}
 
 
 def cpu_baseline(P, root, M, C, msg, budget_s=5.0):
@@ -678,6 +704,10 @@ def main() -> int:
             row["cold"] = cold_rows(B, torch, ranks.bufs, P, root, [8 * MiB, 16 * MiB, 32 * MiB, 64 * MiB], stream, args.quick)
         if name == "cfg3":
             row["per_tensor"] = vgg_tensor_by_tensor(B, torch, ranks.bufs, P, root, stream, args.quick)
+        if M >= MiB:
+            row["ceilings"] = ceilings(B, torch, ranks.bufs, root, M, stream, args.quick)
+            for v in row["variants"].values():
+                v["of_store_only_rate"] = round(row["ceilings"]["store_only_median_us"] / v["median_us"], 4)
         if name == HEADLINE and not args.no_cpu_baseline:
             C = row["variants"]["chain"]["geometry"]["chunk_bytes"] or M
             cpu = cpu_baseline(P, root, M, C, msg)
@@ -693,7 +723,9 @@ def main() -> int:
         configs.append(row)
 
     P, root, M, seed, what = WORKLOADS[HEADLINE]
-    head = next(c for c in configs if c["workload"] == HEADLINE)["variants"]["chain"]
+    head_cfg = next(c for c in configs if c["workload"] == HEADLINE)
+    head = head_cfg["variants"]["chain"]
+    head_ceiling = head_cfg.get("ceilings")
     g = head["geometry"]
     algorithmic = head["algorithmic_bytes"]
     wall_ms, avg_launch_ms = headline["wall_ms"], headline["avg_launch_ms"]
@@ -739,6 +771,11 @@ def main() -> int:
             "algorithmic_GBps": round(algorithmic / launch_s / 1e9, 2),
             "kernel": head["kernel"],
             "avg_launch_ms": round(avg_launch_ms, 5),
+            # the same P-1 buffers only written, with no dependencies (bcast_debug_store_pattern), in this run:
+            # the rate this device's memory gives the broadcast's write set, and the chain's time relative to it
+            "store_only_GBps": head_ceiling["store_only_GBps"] if head_ceiling else None,
+            "store_only_ms": round(head_ceiling["store_only_median_us"] * 1e-3, 5) if head_ceiling else None,
+            "of_store_only_rate": head.get("of_store_only_rate"),
         },
         "cpu_baseline": cpu,
         "configs": configs,

@@ -73,6 +73,20 @@ int bcast_plan_set_cache_policy(bcast_plan_t *plan, int ld_root, int ld_edge, in
  * 4 positions at a time) or 1024 (16 at a time), 0 = the library's choice. */
 int bcast_plan_set_reduce_trip(bcast_plan_t *plan, int trip_bytes);
 
+/* Measurement kernels: what the device's memory gives the two access patterns
+ * every algorithm here is made of, with no dependencies between accesses.
+ * bufs: HOST array of nbufs (1..BCAST_MAX_RANKS) DEVICE pointers, 16-byte
+ * aligned; bytes: a multiple of 4096.
+ * bcast_debug_store_pattern overwrites bytes [0, bytes) of every buffer, tile
+ * by tile over all buffers (the fan-out without its read): the floor of any
+ * broadcast to nbufs ranks on one die.
+ * bcast_debug_load_pattern reads every buffer once (streaming loads, xor-folded
+ * in registers) and, if write_result != 0, writes the fold to out (DEVICE,
+ * bytes bytes, 16-byte aligned; required either way): the floor of a reduction
+ * of nbufs contributions.  Errors: ERR_ARG, ERR_HIP. */
+int bcast_debug_store_pattern(void *const *bufs, int nbufs, size_t bytes, bcast_stream_t stream);
+int bcast_debug_load_pattern(void *const *bufs, int nbufs, size_t bytes, void *out, int write_result, bcast_stream_t stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -44,7 +44,7 @@ EXPORTS = [
     "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_reduce_sum_f32_static", "bcast_plan_reserve_reduce", "bcast_allreduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
     "bcast_plan_handoff_counts", "bcast_plan_set_cache_policy", "bcast_plan_set_chain_waves", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
-    "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_tune_reduce", "bcast_tune_reduce_put", "bcast_tune_reduce_get", "bcast_plan_set_reduce_trip", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
+    "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_tune_reduce", "bcast_tune_reduce_put", "bcast_tune_reduce_get", "bcast_plan_set_reduce_trip", "bcast_debug_store_pattern", "bcast_debug_load_pattern", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
 ]
 
 
@@ -164,6 +164,8 @@ def _load():
         "bcast_tune_reduce_put": ([i, sz, ctypes.POINTER(ReduceEntry)], i),
         "bcast_tune_reduce_get": ([i, sz, ctypes.POINTER(ReduceEntry)], i),
         "bcast_plan_set_reduce_trip": ([vp, i], i),
+        "bcast_debug_store_pattern": ([pvp, i, sz, vp], i),
+        "bcast_debug_load_pattern": ([pvp, i, sz, vp, i, vp], i),
         "bcast_strerror": ([i], ctypes.c_char_p),
         "bcast_last_hip_error": ([], i),
         "bcast_version": ([], ctypes.c_char_p),
@@ -475,6 +477,17 @@ def bcast_tune_reduce_get(nranks: int, bytes: int) -> dict:
 
 def bcast_plan_set_reduce_trip(plan: Plan, trip_bytes: int) -> None:
     _check(_lib.bcast_plan_set_reduce_trip(plan.handle, trip_bytes), "bcast_plan_set_reduce_trip")
+
+
+def bcast_debug_store_pattern(bufs, bytes: int, stream=None) -> None:
+    """Overwrite [0, bytes) of every buffer with the dependency-free store pattern (measurement)."""
+    _check(_lib.bcast_debug_store_pattern(_ptr_array(bufs), len(bufs), bytes, _stream(stream)), "bcast_debug_store_pattern")
+
+
+def bcast_debug_load_pattern(bufs, bytes: int, out, write_result: bool, stream=None) -> None:
+    """Read every buffer once with the dependency-free load pattern; optionally write the xor fold to out."""
+    _check(_lib.bcast_debug_load_pattern(_ptr_array(bufs), len(bufs), bytes, _ptr(out), int(write_result), _stream(stream)),
+           "bcast_debug_load_pattern")
 
 
 def bcast_tune_count() -> int:

@@ -1194,6 +1194,48 @@ extern "C" int bcast_allreduce_sum_f32(bcast_plan_t *p, const void *const *send_
     return bcast_run(p, recv_bufs, root, bytes, stream);
 }
 
+// Measurement calls (bcast_debug.h): the two dependency-free access patterns.
+static int pattern_args(void *const *bufs, int nbufs, size_t bytes, CopyArgs *c)
+{
+    if (!bufs || nbufs < 1 || nbufs > BCAST_MAX_RANKS || bytes == 0 || bytes % kTileBytes != 0) return BCAST_ERR_ARG;
+    memset(c, 0, sizeof *c);
+    for (int i = 0; i < nbufs; ++i) {
+        if (!bufs[i] || ((uintptr_t)bufs[i] & 15u)) return BCAST_ERR_ARG;
+        c->buf[i] = (char *)bufs[i];
+    }
+    c->nranks = (unsigned)nbufs;
+    c->hi = bytes;
+    return BCAST_OK;
+}
+
+static int pattern_grid(size_t bytes)
+{
+    hipDeviceProp_t prop;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 2048;
+    const u64 need = std::max<u64>(1, ceil_div(bytes, kTileBytes * kWavesPerBlock));
+    return (int)std::min<u64>(need, (u64)prop.multiProcessorCount * 8);
+}
+
+extern "C" int bcast_debug_store_pattern(void *const *bufs, int nbufs, size_t bytes, bcast_stream_t stream)
+{
+    CopyArgs c;
+    int rc = pattern_args(bufs, nbufs, bytes, &c);
+    if (rc != BCAST_OK) return rc;
+    HIP_TRY(launch_store_pattern(c, pattern_grid(bytes), stream));
+    return BCAST_OK;
+}
+
+extern "C" int bcast_debug_load_pattern(void *const *bufs, int nbufs, size_t bytes, void *out, int write_result, bcast_stream_t stream)
+{
+    CopyArgs c;
+    int rc = pattern_args(bufs, nbufs, bytes, &c);
+    if (rc != BCAST_OK) return rc;
+    if (!out || ((uintptr_t)out & 15u)) return BCAST_ERR_ARG;
+    HIP_TRY(launch_load_pattern(c, (char *)out, write_result != 0, pattern_grid(bytes), stream));
+    return BCAST_OK;
+}
+
 extern "C" const char *bcast_strerror(int status)
 {
     switch (status) {

@@ -189,6 +189,8 @@ hipError_t reduce_max_blocks_per_cu(int *blocks);
 hipError_t tree_max_blocks_per_cu(int *blocks);
 hipError_t launch_pair_copy(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t launch_fanout(const CopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
+hipError_t launch_store_pattern(const CopyArgs &a, int grid_x, hipStream_t stream);
+hipError_t launch_load_pattern(const CopyArgs &a, char *out, bool write_result, int grid_x, hipStream_t stream);
 hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x, hipStream_t stream);
 hipError_t chain_max_blocks_per_cu(int block_threads, int *blocks);
 
