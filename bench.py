@@ -384,6 +384,14 @@ def cold_rows(B, torch, bufs, P, root, sizes, stream, quick):
     return rows
 
 
+def record_graph(torch, enqueue):
+    """What enqueue(stream) launches, recorded during stream capture."""
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue(torch.cuda.current_stream())
+    return graph
+
+
 def vgg_tensor_by_tensor(B, torch, bufs, P, root, stream, quick):
     """The same VGG-16 parameters broadcast as 32 messages, one per tensor, each
     with the tuned choice (AUTO), back to back: the alternative to packing them
@@ -401,14 +409,24 @@ def vgg_tensor_by_tensor(B, torch, bufs, P, root, stream, quick):
         name = B.ALGO_NAMES[B.bcast_plan_info(plan, n, ptrs)["algo"]]
         algos[name] = algos.get(name, 0) + 1
 
-    def one_pass():
+    def one_pass(on_stream=stream):
         for ptrs, n in views:
-            B.bcast_run(plan, ptrs, root, n, stream)
+            B.bcast_run(plan, ptrs, root, n, on_stream)
 
-    st = stats_us(time_runs(torch, one_pass, stream, 2, 5 if quick else 20))
+    reps = 5 if quick else 20
+    st = stats_us(time_runs(torch, one_pass, stream, 2, reps))
+    # the same pass recorded once during stream capture and replayed as a graph (what a training loop
+    # that repeats it every iteration would do): the plan keeps its run counter on the device for that
+    B.bcast_plan_set_replayable(plan, True)
+    one_pass()
+    torch.cuda.synchronize()
+    graph = record_graph(torch, one_pass)
+    replayed = stats_us(time_runs(torch, graph.replay, stream, 2, reps))
+    del graph
     plan.destroy()
     total = sum(n for _, n in spans)
-    st.update({"tensors": len(spans), "algorithms": algos, "algorithmic_GBps": round(2 * (P - 1) * total / st["median_us"] / 1e3, 1)})
+    st.update({"tensors": len(spans), "algorithms": algos, "algorithmic_GBps": round(2 * (P - 1) * total / st["median_us"] / 1e3, 1),
+               "graph_replay_median_us": replayed["median_us"], "graph_replay_min_us": replayed["min_us"]})
     return st
 
 
@@ -430,6 +448,19 @@ def burst(B, torch, inputs, np, P, root, M, stream, variant, n_runs, no_verify, 
         torch.cuda.synchronize()
         if it:
             samples.append(e0.elapsed_time(e1) / n_runs)
+    # the same burst recorded once and replayed as a graph, on a replayable plan
+    B.bcast_plan_set_replayable(plan, True)
+    B.bcast_run(plan, ptrs, root, M, stream)
+    torch.cuda.synchronize()
+    ranks.clear()
+
+    def many(on_stream):
+        for _ in range(n_runs):
+            B.bcast_run(plan, ptrs, root, M, on_stream)
+
+    graph = record_graph(torch, many)
+    replayed = stats_us([t / n_runs for t in time_runs(torch, graph.replay, stream, 1, 5)])
+    del graph
     status, _ = B.bcast_plan_status(plan)
     plan.destroy()
     if status != B.BCAST_OK:
@@ -439,6 +470,7 @@ def burst(B, torch, inputs, np, P, root, M, stream, variant, n_runs, no_verify, 
         if err:
             raise RuntimeError("cfg5b %s: %s" % (variant, err))
     row = stats_us(samples)
+    row.update({"graph_replay_median_us": replayed["median_us"], "graph_replay_min_us": replayed["min_us"]})
     geometry = geometry_of(B, info)
     row.update({"runs_per_sample": n_runs, "algo": B.ALGO_NAMES[info["algo"]], "kernel": kernel_name(info, B), "geometry": geometry,
                 "algorithmic_GBps": round(2 * (P - 1) * M / row["median_us"] / 1e3, 2), "verified_bit_exact": None if no_verify else True})

@@ -126,9 +126,10 @@ int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, size_t chunk
  * rank root+1, which forwards to root+2, ... and rank root-1 only receives.
  * Returns after enqueueing; completion follows stream order.  Every run gets a
  * fresh epoch from the host as a kernel argument, so a bcast_run recorded into
- * a HIP graph must not be replayed: call it directly.  The epoch is a 32-bit
- * count: once in 2^32 - 2 runs of a plan, bcast_run waits for the device and
- * clears the plan's flags before it goes on.
+ * a HIP graph must not be replayed unless the plan is replayable (see
+ * bcast_plan_set_replayable).  The epoch is a 32-bit count: once in 2^32 - 2
+ * runs of a plan, bcast_run waits for the device and clears the plan's flags
+ * before it goes on (a replayable plan does that on the device, without waiting).
  * bytes == 0 or nranks == 1 succeed without launching.
  * Errors: ERR_ARG (NULL/duplicate/overlapping pointers, root or bytes out of
  * range), ERR_UNTUNED, ERR_HIP.  A wave that waits longer than the plan's
@@ -145,6 +146,23 @@ int bcast_run(bcast_plan_t *plan, void *const *rank_bufs, int root, size_t bytes
  */
 int bcast_plan_status(bcast_plan_t *plan, uint64_t *detail);
 int bcast_plan_clear_status(bcast_plan_t *plan);
+
+/*
+ * bcast_plan_set_replayable -- on = 1: from now on the plan's runs (bcast_run,
+ * bcast_reduce_sum_f32, bcast_allreduce_sum_f32) read their epoch from a word in
+ * the plan's device memory, which a one-workgroup kernel enqueued ahead of each
+ * run that uses flags advances.  Such a run enqueues kernels only -- no
+ * allocation, no wait, no memset, nothing that differs from one execution to
+ * the next -- so it may be recorded during stream capture and the graph
+ * replayed any number of times (deep-learning steps repeat the same broadcasts
+ * every iteration, Sec. I); captured and directly issued runs of the plan may
+ * alternate.  What is recorded is what the call saw: buffers, root, size, the
+ * launch shape and the tuning table's choice.  Costs one small launch per run.
+ * on = 0 returns to the host's count.  Either change waits for the device.
+ * As for any run: one plan must not run on two streams, or in two graph
+ * branches, at once.  Errors: ERR_ARG, ERR_HIP.
+ */
+int bcast_plan_set_replayable(bcast_plan_t *plan, int on);
 
 /* bcast_plan_info -- HOST-side description of what a run of `bytes` bytes over
  * these pointers (nullable: then 16-byte alignment is assumed) would launch. */
@@ -264,9 +282,12 @@ int bcast_plan_reserve_reduce(bcast_plan_t *plan, size_t count, int stages);
  * Every call on a GPU shares that GPU's array: calls that overlap in time on
  * one GPU (two streams, two threads, two plans) race and give undefined
  * results; calls that follow one another in stream order are fine -- runs are
- * told apart by a per-device run count in the flag words, nothing needs to be
- * cleared between them (once in 2^32 - 2 runs a fill kernel on `stream` clears
- * the flags).  Timeouts surface through the plan's status word as usual.
+ * told apart by a run count in the flag words, nothing needs to be cleared
+ * between them.  That count lives in the array itself and is advanced by a
+ * one-workgroup kernel enqueued ahead of every run that uses flags (once in
+ * 2^32 - 2 runs it clears the flags first), so a call recorded during stream
+ * capture replays correctly.  Timeouts surface through the plan's status word
+ * as usual.
  */
 int bcast_reduce_sum_f32_static(bcast_plan_t *plan, const void *const *send_bufs, void *recv_buf, int root, size_t count,
                                 bcast_stream_t stream);

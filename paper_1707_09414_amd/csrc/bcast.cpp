@@ -4,7 +4,6 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
-#include <mutex>
 #include <new>
 
 #include "bcast_internal.h"
@@ -31,6 +30,8 @@ struct bcast_plan {
     u64 *d_flags = nullptr;  // max_waves flags, kFlagStrideWords apart, plus the abort word
     u64 *d_abort = nullptr;
     u64 *d_counters = nullptr; // two words after the abort word
+    u64 *d_epoch = nullptr;    // the run counter in device memory, one line after the counters (replayable plans)
+    bool replayable = false;   // runs take their epoch from d_epoch (bcast_plan_set_replayable)
     u64 *d_trace = nullptr;    // optional (bcast_plan_enable_trace)
     size_t trace_entries = 0;
     unsigned mode = 0;
@@ -241,12 +242,13 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
         p->max_waves_tree = std::min(p->max_flags, std::max(nranks, p->cu_count * per_cu * kWavesPerBlock));
     }
     if (e == hipSuccess) {
-        size_t flag_bytes = ((size_t)p->max_flags + 2) * kFlagStrideWords * sizeof(u64);
+        size_t flag_bytes = ((size_t)p->max_flags + 3) * kFlagStrideWords * sizeof(u64);
         e = hipMalloc((void **)&p->d_flags, flag_bytes);
         if (e == hipSuccess) e = hipMemset(p->d_flags, 0, flag_bytes);
         if (e == hipSuccess) {
             p->d_abort = p->d_flags + (size_t)p->max_flags * kFlagStrideWords;
             p->d_counters = p->d_abort + kFlagStrideWords;
+            p->d_epoch = p->d_counters + kFlagStrideWords;
         }
     }
     // set-up for bcast_reduce_sum_f32_static: the address of this device's copy of
@@ -357,11 +359,41 @@ extern "C" int bcast_plan_set_chain_waves(bcast_plan_t *p, int mode)
     return BCAST_OK;
 }
 
+// The plan's run count: the host's, or (replayable plans) the word in device
+// memory, which only the device advances; reading it waits for the device.
+static int current_epoch(bcast_plan *p, u64 *epoch)
+{
+    *epoch = p->epoch;
+    if (!p->replayable) return BCAST_OK;
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(epoch, p->d_epoch, sizeof(u64), hipMemcpyDeviceToHost));
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_set_replayable(bcast_plan_t *p, int on)
+{
+    if (!p || (on != 0 && on != 1)) return BCAST_ERR_ARG;
+    if ((on != 0) == p->replayable) return BCAST_OK;
+    // the count moves to where the next runs will look for it; runs in flight finish first
+    u64 epoch = 0;
+    int rc = current_epoch(p, &epoch);
+    if (rc != BCAST_OK) return rc;
+    HIP_TRY(hipDeviceSynchronize());
+    if (on) HIP_TRY(hipMemcpy(p->d_epoch, &epoch, sizeof(u64), hipMemcpyHostToDevice));
+    p->epoch = epoch;
+    p->replayable = on != 0;
+    return BCAST_OK;
+}
+
 extern "C" int bcast_plan_debug_set_epoch(bcast_plan_t *p, uint64_t epoch)
 {
     if (!p || epoch > kEpochLimit) return BCAST_ERR_ARG;
     // flags left by earlier runs must stay below every later run's base
-    if (epoch < p->epoch) return BCAST_ERR_ARG;
+    u64 now = 0;
+    int rc = current_epoch(p, &now);
+    if (rc != BCAST_OK) return rc;
+    if (epoch < now) return BCAST_ERR_ARG;
+    if (p->replayable) HIP_TRY(hipMemcpy(p->d_epoch, &epoch, sizeof(u64), hipMemcpyHostToDevice));
     p->epoch = epoch;
     return BCAST_OK;
 }
@@ -769,23 +801,24 @@ extern "C" int bcast_plan_info(bcast_plan_t *p, void *const *rank_bufs, size_t b
 }
 
 // Where a run's ready flags live and which run counter tells its runs apart:
-// the plan's own, or (bcast_reduce_sum_f32_static) the static scratch array's,
-// whose counter is per device because every plan on the device shares the array.
+// the plan's own flags with the host's count or (replayable plans) the plan's
+// word in device memory, or the static scratch array's flags with that array's
+// word -- always in device memory there, because every plan on the device shares
+// the array and its callers may replay captured launches.
 struct FlagHome {
     u64 *flags;
     u64 *abort_word;
-    u64 *epoch;      // host counter of runs that used these flags
-    u64 clear_words; // 64-bit words from `flags` on to clear before the counter wraps
-    bool own_memory; // plan-owned: may wait for the device and memset; else a fill kernel on the run's stream
+    u64 *epoch;       // host counter of runs that used these flags, or null
+    u64 *epoch_word;  // ... or the counter in device memory, advanced by a kernel ahead of every run
+    u64 clear_words;  // 64-bit words from `flags` on to clear before the counter wraps
 };
 
-static std::mutex g_static_mu;
-static u64 g_static_epoch[kStaticMaxDevices];
-
 // What the chain, the pipelined tree and the reduction share: buffers by
-// position, ready flags, status words and wait limit, the chunking, and a fresh epoch.
+// position, ready flags, status words and wait limit, the chunking, and a fresh
+// epoch.  uses_flags: whether any wave of the launch waits for or raises a flag
+// (a single stage does neither and needs no epoch).
 static int begin_flag_run(bcast_plan *p, ChainArgs *a, char *const *by_pos, size_t bytes, const bcast_plan_info_t &info,
-                          const FlagHome &home, hipStream_t stream)
+                          const FlagHome &home, bool uses_flags, hipStream_t stream)
 {
     memset(a, 0, sizeof *a);
     memcpy(a->buf, by_pos, sizeof(char *) * p->nranks);
@@ -801,20 +834,21 @@ static int begin_flag_run(bcast_plan *p, ChainArgs *a, char *const *by_pos, size
     a->mute_hop = (unsigned)p->mute_hop;
     if (a->nchunks == 0 || a->lanes == 0 || a->chunk_bytes == 0) return BCAST_ERR_ARG;
     if ((u64)a->nchunks * a->chunk_bytes < a->bytes) return BCAST_ERR_ARG;
-    // the flag word keeps the epoch in its upper 32 bits: before that would
-    // wrap (after 2^32 - 2 runs on these flags), clear the flags and the abort
-    // word and count from one again.  Plan-owned flags: let the device drain
-    // first.  The static array: a fill kernel on this run's stream, which is in
-    // order with every earlier run on it (runs that overlap are the caller's
-    // responsibility there), allocates nothing and may be captured.
+    // The flag word keeps the epoch in its upper 32 bits: before that would
+    // wrap (after 2^32 - 2 runs on these flags), the flags and the abort word
+    // are cleared and the count starts from one again.
+    if (home.epoch_word) {
+        // counted on the device: one small kernel ahead of the run adds one (and
+        // clears at the wrap); nothing here waits, allocates or differs from
+        // replay to replay
+        a->epoch_word = home.epoch_word;
+        if (uses_flags) HIP_TRY(launch_advance_epoch(home.epoch_word, home.flags, home.clear_words, kEpochLimit, stream));
+        return BCAST_OK;
+    }
     if (*home.epoch >= kEpochLimit) {
-        if (home.own_memory) {
-            HIP_TRY(hipDeviceSynchronize());
-            HIP_TRY(hipMemset(home.flags, 0, home.clear_words * sizeof(u64)));
-            HIP_TRY(hipDeviceSynchronize());
-        } else {
-            HIP_TRY(launch_zero_words(home.flags, home.clear_words, stream));
-        }
+        HIP_TRY(hipDeviceSynchronize());
+        HIP_TRY(hipMemset(home.flags, 0, home.clear_words * sizeof(u64)));
+        HIP_TRY(hipDeviceSynchronize());
         *home.epoch = 0;
     }
     a->base = (++*home.epoch) << 32;
@@ -823,7 +857,9 @@ static int begin_flag_run(bcast_plan *p, ChainArgs *a, char *const *by_pos, size
 
 static FlagHome plan_flags(bcast_plan *p)
 {
-    return FlagHome{p->d_flags, p->d_abort, &p->epoch, ((u64)p->max_flags + 2) * kFlagStrideWords, true};
+    const u64 clear_words = ((u64)p->max_flags + 2) * kFlagStrideWords;  // flags, abort word, counters
+    if (p->replayable) return FlagHome{p->d_flags, p->d_abort, nullptr, p->d_epoch, clear_words};
+    return FlagHome{p->d_flags, p->d_abort, &p->epoch, nullptr, clear_words};
 }
 
 extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size_t bytes, bcast_stream_t stream)
@@ -854,7 +890,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
 
     if (info.algo == BCAST_ALGO_CHAIN) {
         ChainArgs a;
-        rc = begin_flag_run(p, &a, by_pos, bytes, info, plan_flags(p), stream);
+        rc = begin_flag_run(p, &a, by_pos, bytes, info, plan_flags(p), info.stages > 1, stream);
         if (rc != BCAST_OK) return rc;
         a.counters = p->d_counters;
         a.trace = p->d_trace;
@@ -929,7 +965,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
     }
     if (info.algo == BCAST_ALGO_KNOMIAL_PIPELINED) {
         ChainArgs a;
-        rc = begin_flag_run(p, &a, by_pos, bytes, info, plan_flags(p), stream);
+        rc = begin_flag_run(p, &a, by_pos, bytes, info, plan_flags(p), true, stream);
         if (rc != BCAST_OK) return rc;
         const int k = info.stages;
         if (k < 2) return BCAST_ERR_ARG;
@@ -1094,8 +1130,8 @@ static int reduce_check(const bcast_plan *p, const void *const *send_bufs, const
 }
 
 // Enqueue the reduction kernel with the given flags and staging memory.  Calls
-// nothing that allocates or waits for the device (the flags' once-in-2^32-runs
-// clearing aside, see begin_flag_run).
+// nothing that allocates or waits for the device (a host-counted plan's
+// once-in-2^32-runs clearing aside, see begin_flag_run).
 static int reduce_enqueue(bcast_plan *p, const void *const *send_bufs, void *recv_buf, int root, size_t bytes,
                           const bcast_plan_info_t &info, const FlagHome &home, char *staging, size_t staging_bytes, int max_waves,
                           hipStream_t stream)
@@ -1106,7 +1142,7 @@ static int reduce_enqueue(bcast_plan *p, const void *const *send_bufs, void *rec
     char *by_pos[BCAST_MAX_RANKS];
     for (int k = 0; k < P; ++k) by_pos[k] = (char *)const_cast<void *>(send_bufs[(root + k) % P]);
     ChainArgs a;
-    int rc = begin_flag_run(p, &a, by_pos, bytes, info, home, stream);
+    int rc = begin_flag_run(p, &a, by_pos, bytes, info, home, info.stages > 1, stream);
     if (rc != BCAST_OK) return rc;
     a.stages = (unsigned)info.stages;
     a.hops_per_stage = (unsigned)info.hops_per_stage;
@@ -1158,10 +1194,10 @@ extern "C" int bcast_reduce_sum_f32_static(bcast_plan_t *p, const void *const *s
     bcast_plan_info_t info;
     rc = reduce_shape(p, bytes, (size_t)kStaticStagingBytes, max_waves, &info);
     if (rc != BCAST_OK) return rc;
+    // flags, then the abort word, then the array's run counter
     u64 *flags = reinterpret_cast<u64 *>(p->static_scratch);
-    std::lock_guard<std::mutex> g(g_static_mu);
-    const FlagHome home{flags, flags + (u64)kStaticFlagWaves * kFlagStrideWords, &g_static_epoch[device],
-                        kStaticFlagBytes / sizeof(u64), false};
+    u64 *abort_word = flags + (u64)kStaticFlagWaves * kFlagStrideWords;
+    const FlagHome home{flags, abort_word, nullptr, abort_word + kFlagStrideWords, ((u64)kStaticFlagWaves + 1) * kFlagStrideWords};
     return reduce_enqueue(p, send_bufs, recv_buf, root, bytes, info, home, p->static_scratch + kStaticFlagBytes,
                           (size_t)kStaticStagingBytes, max_waves, stream);
 }

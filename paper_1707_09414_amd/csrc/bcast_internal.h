@@ -76,6 +76,7 @@ struct ChainArgs {
     u64 trace_entries; // (stage, chunk) pairs the trace buffer holds
     u64 *counters;     // device: [0] hand-offs within an XCD, [1] across XCDs (kModeCount)
     u64 base;          // epoch << 32; chunk c of this run is ready when flag >= base + ((c + 1) << 4)
+    u64 *epoch_word;   // device, or null: if set, the epoch is read from here instead (see advance_epoch_kernel) and base is unused
     u64 bytes;         // M
     u64 chunk_bytes;   // C (multiple of 16)
     u64 spin_ticks;    // wait limit in 100 MHz ticks
@@ -166,7 +167,7 @@ struct RangedCopyArgs {
 
 // The statically allocated scratch array (kernels.hip): flag lines, then staging.
 constexpr int kStaticFlagWaves = 8192;                                  // ready flags it holds
-constexpr u64 kStaticFlagLines = (u64)kStaticFlagWaves + 2;             // + abort word + one spare line
+constexpr u64 kStaticFlagLines = (u64)kStaticFlagWaves + 2;             // + abort word + run counter
 constexpr u64 kStaticFlagBytes = kStaticFlagLines * kFlagStrideWords * sizeof(u64);
 constexpr u64 kStaticStagingBytes = 32ull << 20;                        // running sums between stages
 constexpr u64 kStaticScratchBytes = kStaticFlagBytes + kStaticStagingBytes;
@@ -174,7 +175,7 @@ constexpr int kStaticMaxDevices = 64;
 // Device address of the current device's copy of the array (looked up once per
 // device; `device` must be the current device on that first call).
 hipError_t static_scratch_address(int device, char **ptr);
-hipError_t launch_zero_words(u64 *dst, u64 words, hipStream_t stream);
+hipError_t launch_advance_epoch(u64 *epoch_word, u64 *flags, u64 clear_words, u64 limit, hipStream_t stream);
 
 // Launchers implemented in kernels.hip.  vec_bytes is 16, 8, 4 or 1: every
 // buffer address in the call is congruent modulo vec_bytes.

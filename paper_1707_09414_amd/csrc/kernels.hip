@@ -234,9 +234,9 @@ __device__ __forceinline__ void fanout_span(const CopyArgs &a, u64 lo, u64 hi, u
 // limit: a wave that gives up records (first hop of its stage, chunk), raises
 // the abort word so that the others stop waiting too, and returns.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void report_timeout(const ChainArgs &a, unsigned hop, unsigned chunk)
+__device__ __forceinline__ void report_timeout(const ChainArgs &a, u64 base, unsigned hop, unsigned chunk)
 {
-    const u64 epoch = a.base >> 32;
+    const u64 epoch = base >> 32;
     const u64 old = __hip_atomic_fetch_max(a.abort_word, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old < epoch && a.status[0] == 0) {  // first wave of this run to give up
         __hip_atomic_store(&a.status[1], ((u64)hop << 32) | chunk, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -257,13 +257,23 @@ __device__ __forceinline__ u64 read_flag(const u64 *flag, unsigned lane)
     return ((u64)hi << 32) | lo;
 }
 
-__device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const ChainArgs &a, unsigned hop,
+// The run's flag base, epoch << 32.  The host either passes it as an argument
+// (it counts the runs itself) or names a word in device memory that a small
+// kernel enqueued ahead of this one has advanced: then the launch can be
+// recorded into a graph and replayed, every replay finding a new epoch.
+__device__ __forceinline__ u64 run_base(const ChainArgs &a, unsigned lane)
+{
+    if (a.epoch_word == nullptr) return a.base;
+    return read_flag(a.epoch_word, lane) << 32;
+}
+
+__device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const ChainArgs &a, u64 base, unsigned hop,
                                            unsigned chunk, unsigned lane, u64 *seen)
 {
     u64 v = read_flag(flag, lane);
     if (v < want) {
         const u64 t0 = wall_clock64();
-        const u64 epoch = a.base >> 32;
+        const u64 epoch = base >> 32;
         unsigned spins = 0;
         for (;;) {
             __builtin_amdgcn_s_sleep(2);
@@ -272,7 +282,7 @@ __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const Chai
             if ((++spins & 31u) == 0) {
                 if (read_flag(a.abort_word, lane) >= epoch) return false;
                 if (wall_clock64() - t0 > a.spin_ticks) {
-                    if (lane == 0) report_timeout(a, hop, chunk);
+                    if (lane == 0) report_timeout(a, base, hop, chunk);
                     return false;
                 }
             }
@@ -311,6 +321,7 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
     // the workgroup is only the unit the dispatcher places on a CU
     const unsigned gw = __builtin_amdgcn_readfirstlane(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
     if (gw >= a.stages * a.lanes) return;
+    const u64 base = run_base(a, lane);
     // Stage g serves consecutive chain positions first_hop .. last_hop: its waves
     // play those ranks one after the other (one hop per stage is one stage per
     // rank).  Hand-offs between stages go through flags; inside a stage the
@@ -353,8 +364,8 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 
         // flag value: base + (chunks stored << 4) + producer's XCD
         if (in_flag) {
-            const u64 want = a.base + ((u64)(c + 1) << 4);
-            if (seen < want && !wait_ready(in_flag, want, a, first_hop, c, lane, &seen)) return;
+            const u64 want = base + ((u64)(c + 1) << 4);
+            if (seen < want && !wait_ready(in_flag, want, a, base, first_hop, c, lane, &seen)) return;
             // whichever read of the flag showed the chunk (this wait, or the look-ahead after the chunk
             // before): no payload load of this chunk may be moved above it
             asm volatile("" ::: "memory");
@@ -395,7 +406,7 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
         }
         if (out_flag) {
             if (lane == 0)
-                __hip_atomic_store(out_flag, a.base + ((u64)(c + 1) << 4) + xcd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(out_flag, base + ((u64)(c + 1) << 4) + xcd, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     if ((a.mode & kModeCount) && lane == 0) {
@@ -430,13 +441,13 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 // workgroup (resident with it) or for a workgroup with a lower index; waits are
 // bounded by the clock limit like everywhere else.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ bool wait_trip(const unsigned *count, unsigned want, const ChainArgs &a, unsigned hop, unsigned chunk,
-                                          unsigned lane)
+__device__ __forceinline__ bool wait_trip(const unsigned *count, unsigned want, const ChainArgs &a, u64 base, unsigned hop,
+                                          unsigned chunk, unsigned lane)
 {
     unsigned v = __builtin_amdgcn_readfirstlane(__hip_atomic_load(count, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP));
     if (v < want) {
         const u64 t0 = wall_clock64();
-        const u64 epoch = a.base >> 32;
+        const u64 epoch = base >> 32;
         unsigned spins = 0;
         for (;;) {
             __builtin_amdgcn_s_sleep(1);
@@ -445,7 +456,7 @@ __device__ __forceinline__ bool wait_trip(const unsigned *count, unsigned want, 
             if ((++spins & 63u) == 0) {
                 if (read_flag(a.abort_word, lane) >= epoch) return false;
                 if (wall_clock64() - t0 > a.spin_ticks) {
-                    if (lane == 0) report_timeout(a, hop, chunk);
+                    if (lane == 0) report_timeout(a, base, hop, chunk);
                     return false;
                 }
             }
@@ -473,6 +484,7 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
     const unsigned last_hop = stage_begin(g + 1, 0, a.stages, hops_min, hops_extra);
     const unsigned hop = first_hop + j;  // the one chain position this wave plays
     if (hop > last_hop) return;
+    const u64 base = run_base(a, lane);
     const bool first = j == 0, last = hop == last_hop;
     const bool muted = a.mute_hop == hop;
     const u64 *in_flag = (first && g > 0) ? a.flags + ((u64)(g - 1) * a.lanes + s) * kFlagStrideWords : nullptr;
@@ -491,17 +503,17 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
         u64 chunk_hi = chunk_lo + a.chunk_bytes;
         if (chunk_hi > a.bytes) chunk_hi = a.bytes;
         if (in_flag) {
-            const u64 want = a.base + ((u64)(c + 1) << 4);
-            if (seen < want && !wait_ready(in_flag, want, a, hop, c, lane, &seen)) return;
+            const u64 want = base + ((u64)(c + 1) << 4);
+            if (seen < want && !wait_ready(in_flag, want, a, base, hop, c, lane, &seen)) return;
             asm volatile("" ::: "memory");  // also behind the look-ahead read of the flag
         }
         for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
             const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
-            if (!first && !wait_trip(&trips_done[j - 1], seq + 1, a, hop, c, lane)) return;
+            if (!first && !wait_trip(&trips_done[j - 1], seq + 1, a, base, hop, c, lane)) return;
             // Back-pressure: a rank stays at most kRankLead trips ahead of its
             // right neighbour's reading, so that what it stores is read out of
             // the CU's cache before later trips push it out.
-            if (!last && seq >= kRankLead && !wait_trip(&trips_read[j + 1], seq + 1 - kRankLead, a, hop + 1, c, lane)) return;
+            if (!last && seq >= kRankLead && !wait_trip(&trips_read[j + 1], seq + 1 - kRankLead, a, base, hop + 1, c, lane)) return;
             copy_span_policy<V, U>(dst, src, lo, hi, lane, ld, st);
             ++seq;
             // the stores above were issued with the loaded data, so the loads of this trip have returned
@@ -517,7 +529,7 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
         if (out_flag) {
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             if (lane == 0)
-                __hip_atomic_store(out_flag, a.base + ((u64)(c + 1) << 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(out_flag, base + ((u64)(c + 1) << 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -542,6 +554,7 @@ __global__ void __launch_bounds__(kBlockThreads) tree_kernel(const ChainArgs a)
     const unsigned lane = threadIdx.x & (kWaveSize - 1);
     const unsigned gw = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     if (gw >= (a.nranks - 1) * a.lanes) return;
+    const u64 base = run_base(a, lane);
     const unsigned pos = gw / a.lanes + 1;  // the position this wave receives for
     const unsigned s = gw - (pos - 1) * a.lanes;
     const unsigned par = a.parent[pos];
@@ -559,8 +572,8 @@ __global__ void __launch_bounds__(kBlockThreads) tree_kernel(const ChainArgs a)
         u64 chunk_hi = chunk_lo + a.chunk_bytes;
         if (chunk_hi > a.bytes) chunk_hi = a.bytes;
         if (in_flag) {
-            const u64 want = a.base + ((u64)(c + 1) << 4);
-            if (seen < want && !wait_ready(in_flag, want, a, pos, c, lane, &seen)) return;
+            const u64 want = base + ((u64)(c + 1) << 4);
+            if (seen < want && !wait_ready(in_flag, want, a, base, pos, c, lane, &seen)) return;
             asm volatile("" ::: "memory");  // also behind the look-ahead read of the flag
         }
         for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
@@ -572,7 +585,7 @@ __global__ void __launch_bounds__(kBlockThreads) tree_kernel(const ChainArgs a)
             // all payload stores of this wave are complete and, being
             // write-through, visible device-wide before the flag is raised
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            if (lane == 0) __hip_atomic_store(out_flag, a.base + ((u64)(c + 1) << 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0) __hip_atomic_store(out_flag, base + ((u64)(c + 1) << 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -658,6 +671,7 @@ __global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a
     const unsigned lane = threadIdx.x & (kWaveSize - 1);
     const unsigned gw = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6));
     if (gw >= a.stages * a.lanes) return;
+    const u64 base = run_base(a, lane);
     const unsigned g = gw / a.lanes;
     const unsigned s = gw - g * a.lanes;
     const unsigned hops = a.nranks - 1;
@@ -684,8 +698,8 @@ __global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a
         u64 chunk_hi = chunk_lo + a.chunk_bytes;
         if (chunk_hi > a.bytes) chunk_hi = a.bytes;
         if (in_flag) {
-            const u64 want = a.base + ((u64)(c + 1) << 4);
-            if (seen < want && !wait_ready(in_flag, want, a, first_hop, c, lane, &seen)) return;
+            const u64 want = base + ((u64)(c + 1) << 4);
+            if (seen < want && !wait_ready(in_flag, want, a, base, first_hop, c, lane, &seen)) return;
             asm volatile("" ::: "memory");  // also behind the look-ahead read of the flag
         }
         for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
@@ -718,7 +732,7 @@ __global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a
         if (out_flag) {
             // the running sums of this chunk are written through and complete before the flag is raised
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            if (lane == 0) __hip_atomic_store(out_flag, a.base + ((u64)(c + 1) << 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0) __hip_atomic_store(out_flag, base + ((u64)(c + 1) << 4), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }
@@ -989,8 +1003,8 @@ hipError_t launch_ranged_copy(const RangedCopyArgs &a, int vec_bytes, int grid_x
 // ---------------------------------------------------------------------------
 // Scratch memory that exists without any allocation call: one array in the
 // code object's data segment, for the entry point that callers use who cannot
-// allocate (bcast_reduce_sum_f32_static).  Layout: the ready flags and the
-// abort word first (kStaticFlagLines lines of 128 bytes), then the staging area
+// allocate (bcast_reduce_sum_f32_static).  Layout: the ready flags, the abort
+// word and the run counter first (kStaticFlagLines lines of 128 bytes), then the staging area
 // for the running sums that cross a stage boundary (kStaticStagingBytes).  Every
 // GPU the library runs on holds its own copy, zero-filled when the code object
 // is loaded, until the process ends.  In host code the array's name is only a
@@ -1030,18 +1044,31 @@ hipError_t static_scratch_address(int device, char **ptr)
     return hipSuccess;
 }
 
-// Clears `words` 64-bit words at `dst` on `stream` with a kernel (a fill that a
-// captured graph replays correctly, and no allocation).
-__global__ void __launch_bounds__(kBlockThreads) zero_words_kernel(u64 *dst, u64 words)
+// The run counter in device memory, for launches that must be replayable from a
+// captured graph (and for the static array, which no host counter could follow
+// through replays).  One workgroup, enqueued ahead of every flag kernel that
+// reads the counter: it adds one, and when the 32-bit count in the flag words
+// would wrap it first clears `clear_words` words at `flags` (ready flags and
+// abort word) and starts again at one -- a fill by a kernel, which a graph
+// replays correctly, with no allocation.  Stream order puts it after the run
+// before and ahead of the run that reads it.
+__global__ void __launch_bounds__(kBlockThreads) advance_epoch_kernel(u64 *epoch_word, u64 *flags, u64 clear_words, u64 limit)
 {
-    for (u64 i = (u64)blockIdx.x * kBlockThreads + threadIdx.x; i < words; i += (u64)gridDim.x * kBlockThreads) dst[i] = 0;
+    u64 epoch = *epoch_word;  // every thread reads it before thread 0 writes it (barrier below)
+    if (epoch >= limit) {
+        for (u64 i = threadIdx.x; i < clear_words; i += kBlockThreads) flags[i] = 0;
+        epoch = 0;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) *epoch_word = epoch + 1;
 }
 
-hipError_t launch_zero_words(u64 *dst, u64 words, hipStream_t stream)
+hipError_t launch_advance_epoch(u64 *epoch_word, u64 *flags, u64 clear_words, u64 limit, hipStream_t stream)
 {
-    if (!dst || words == 0) return hipErrorInvalidValue;
-    const unsigned blocks = (unsigned)std::min<u64>(1024, (words + kBlockThreads - 1) / kBlockThreads);
-    zero_words_kernel<<<dim3(blocks), dim3(kBlockThreads), 0, stream>>>(dst, words);
+    if (!epoch_word || !flags || clear_words == 0) return hipErrorInvalidValue;
+    // the counter must lie outside what a wrap clears
+    if (epoch_word >= flags && epoch_word < flags + clear_words) return hipErrorInvalidValue;
+    advance_epoch_kernel<<<dim3(1), dim3(kBlockThreads), 0, stream>>>(epoch_word, flags, clear_words, limit);
     return hipGetLastError();
 }
 
