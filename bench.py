@@ -257,14 +257,58 @@ def reps_for(M, quick):
     return 200 if M < MiB else 20
 
 
-class Ranks:
-    """P rank buffers of M bytes in HBM: the root's holds the message, the others 0xFF."""
+PLACED_NAMES = {0: "not placed", 1: "placed by allocation order", 2: "placed, confirmed by measurement"}
+PLACE_MIN_BYTES = 8 * MiB  # smaller rank buffers are allocated plainly: their broadcasts are bound by latency, not by memory
 
-    def __init__(self, torch, inputs, P, root, M, msg):
+
+class _DeviceSpan:
+    """Device memory the library allocated, described the way torch reads foreign device arrays."""
+
+    def __init__(self, ptr, nbytes):
+        self.__cuda_array_interface__ = {"shape": (int(nbytes),), "typestr": "|u1", "data": (int(ptr), False), "version": 2}
+
+
+def tensor_at(torch, ptr, nbytes):
+    return torch.as_tensor(_DeviceSpan(ptr, nbytes), device="cuda")
+
+
+class Placed:
+    """Device buffers from bcast_buffers_alloc (library=True) or from torch."""
+
+    def __init__(self, B, torch, sizes, regions, library):
+        self.B, self.ptrs = B, None
+        if library:
+            self.ptrs, verdict = B.bcast_buffers_alloc(sizes, regions)
+            self.bufs = [tensor_at(torch, p, n) for p, n in zip(self.ptrs, sizes)]
+            self.how = {"by": "bcast_buffers_alloc", "verdict": PLACED_NAMES[verdict]}
+        else:
+            self.bufs = [torch.empty(n, dtype=torch.uint8, device="cuda") for n in sizes]
+            self.how = {"by": "torch.empty (plain allocations)", "verdict": None}
+
+    def free(self):
+        self.bufs = None
+        if self.ptrs is not None:
+            self.B.bcast_buffers_free(self.ptrs)
+            self.ptrs = None
+
+
+class Ranks:
+    """P rank buffers of M bytes in HBM: the root's holds the message, the others 0xFF.
+    With library=True they come from bcast_buffers_alloc, the first half of the
+    chain (positions 0 .. P/2-1, the root among them) in one region of the device's
+    memory and the second half in the next."""
+
+    def __init__(self, B, torch, inputs, P, root, M, msg, library):
         self.P, self.root, self.M = P, root, M
         self.msg = msg
         d_msg = torch.from_numpy(msg).cuda()
-        self.bufs = [torch.empty(M, dtype=torch.uint8, device="cuda") for _ in range(P)]
+        library = library and M >= PLACE_MIN_BYTES
+        regions = [0 if (r - root) % P < P // 2 else 1 for r in range(P)]
+        self.mem = Placed(B, torch, [M] * P, regions, library)
+        self.allocation = dict(self.mem.how)
+        if library:
+            self.allocation["layout"] = "chain positions 0..%d in one memory region, %d..%d in the next" % (P // 2 - 1, P // 2, P - 1)
+        self.bufs = self.mem.bufs
         for r in range(P):
             if r == root:
                 # the runtime's device-to-device copy of the whole message (M bytes read, M written): in a
@@ -273,6 +317,10 @@ class Ranks:
             else:
                 self.bufs[r].fill_(inputs.FILL_BYTE)
         self.fill = inputs.FILL_BYTE
+
+    def free(self):
+        self.bufs = None
+        self.mem.free()
 
     def clear(self):
         for r in range(self.P):
@@ -434,7 +482,7 @@ def burst(B, torch, inputs, np, P, root, M, stream, variant, n_runs, no_verify, 
     """n_runs back-to-back broadcasts of M bytes between two HIP events: what a
     small broadcast costs when launches queue up behind each other."""
     msg = inputs.random_bytes(4, M)
-    ranks = Ranks(torch, inputs, P, root, M, msg)
+    ranks = Ranks(B, torch, inputs, P, root, M, msg, False)
     plan = make_plan(B, "cfg5b", variant, P, M)
     info = B.bcast_plan_info(plan, M, ranks.bufs)
     ptrs = B.RankPointers(ranks.bufs)
@@ -483,11 +531,13 @@ def burst(B, torch, inputs, np, P, root, M, stream, variant, n_runs, no_verify, 
     return row
 
 
-def reduce_row(B, torch, np, P, root, M, seed, stream, profiles, name, quick, no_verify):
+def reduce_row(B, torch, np, P, root, M, seed, stream, profiles, name, quick, no_verify, library=True):
     """The pipelined chain reduction (fp32 sum to the root) at the workload's rank
     count and message size: every rank contributes M bytes of N(0, 0.01) values
     (one seeded draw, shifted and rescaled per rank).  Algorithmic bytes: every
-    input read once, the result written once, (P + 1) M."""
+    input read once, the result written once, (P + 1) M.  With library=True the
+    buffers come from bcast_buffers_alloc: the contributions in one region of the
+    device's memory, the result in the next."""
     import oracle
 
     count = M // 4
@@ -497,8 +547,11 @@ def reduce_row(B, torch, np, P, root, M, seed, stream, profiles, name, quick, no
     calib = torch.empty_like(d_base)
     calib.copy_(d_base)  # a plain device-to-device copy of count * 4 bytes: calibrates the counters in a profiled run
     del calib
-    send = [torch.roll(d_base, 4099 * r) * (1.0 + r / 64.0) for r in range(P)]
-    recv = torch.empty(count, dtype=torch.float32, device="cuda")
+    mem = Placed(B, torch, [count * 4] * (P + 1), [0] * P + [1], library)
+    send = [b.view(torch.float32) for b in mem.bufs[:P]]
+    recv = mem.bufs[P].view(torch.float32)
+    for r in range(P):
+        send[r].copy_(torch.roll(d_base, 4099 * r) * (1.0 + r / 64.0))
     plan = B.bcast_plan_create(P, count * 4, 0, B.BCAST_ALGO_CHAIN)
     B.bcast_plan_reserve_reduce(plan, count, 2)
     info = B.bcast_reduce_info(plan, count)
@@ -518,11 +571,13 @@ def reduce_row(B, torch, np, P, root, M, seed, stream, profiles, name, quick, no
         if not verified:
             raise RuntimeError("reduce %s: differs from the oracle" % name)
     n = count * 4 // 4096 * 4096
-    scratch = torch.empty(count, dtype=torch.float32, device="cuda")
-    load_ms = stats_us(time_runs(torch, lambda: B.bcast_debug_load_pattern(send, n, scratch, False, stream), stream, 2, 5 if quick else 10))
-    both_ms = stats_us(time_runs(torch, lambda: B.bcast_debug_load_pattern(send, n, scratch, True, stream), stream, 2, 5 if quick else 10))
-    del scratch
+    # (the measurement kernel overwrites the result buffer, which has been checked by now)
+    load_ms = stats_us(time_runs(torch, lambda: B.bcast_debug_load_pattern(send, n, recv, False, stream), stream, 2, 5 if quick else 10))
+    both_ms = stats_us(time_runs(torch, lambda: B.bcast_debug_load_pattern(send, n, recv, True, stream), stream, 2, 5 if quick else 10))
+    del send, recv
+    mem.free()
     row = stats_us(ms)
+    row["allocation"] = dict(mem.how, layout="the contributions in one memory region, the result in the next") if library else dict(mem.how)
     # the same P buffers only read, and read with the fold written out, by the library's dependency-free
     # measurement kernel: what this memory system gives the reduction's access pattern
     row["ceilings"] = {"load_only_median_us": load_ms["median_us"], "load_only_GBps": round(P * n / load_ms["median_us"] / 1e3, 1),
@@ -626,13 +681,13 @@ def run_leg(args, B, torch, np, inputs):
     P, root, M, seed, what = WORKLOADS[name]
     stream = torch.cuda.current_stream()
     if variant == "reduce":
-        row = reduce_row(B, torch, np, P, root, M, seed, stream, {}, name, True, True)
+        row = reduce_row(B, torch, np, P, root, M, seed, stream, {}, name, True, True, args.allocation == "library")
         leg = {"workload": name, "variant": variant, "kernel": row["kernel"].split("<")[0], "geometry": row["geometry"], "launches_per_step": 1,
                "calibration_copy_bytes": (M // 4) * 4, "median_us": row["median_us"]}
         print(json.dumps(leg))
         return 0
     msg = make_message(name, seed, M)
-    ranks = Ranks(torch, inputs, P, root, M, msg)
+    ranks = Ranks(B, torch, inputs, P, root, M, msg, args.allocation == "library")
     plan = make_plan(B, name, variant, P, M)
     info = B.bcast_plan_info(plan, M, ranks.bufs)
     ptrs = B.RankPointers(ranks.bufs)
@@ -640,7 +695,9 @@ def run_leg(args, B, torch, np, inputs):
     st, _ = B.bcast_plan_status(plan)
     plan.destroy()
     leg = {"workload": name, "variant": variant, "kernel": kernel_name(info, B).split("<")[0], "geometry": geometry_of(B, info),
-           "launches_per_step": info["launches"], "calibration_copy_bytes": M, "median_us": stats_us(ms)["median_us"], "status": st}
+           "launches_per_step": info["launches"], "calibration_copy_bytes": M, "median_us": stats_us(ms)["median_us"], "status": st,
+           "allocation": ranks.allocation}
+    ranks.free()
     print(json.dumps(leg))
     return 0 if st == B.BCAST_OK else 1
 
@@ -655,6 +712,8 @@ def main() -> int:
     ap.add_argument("--quick", action="store_true", help="5 timed runs per variant instead of 20 / 200")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true")
+    ap.add_argument("--allocation", choices=("library", "plain"), default="library",
+                    help="rank buffers from bcast_buffers_alloc (placed by region of the device's memory) or from torch.empty")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -689,7 +748,9 @@ def main() -> int:
     configs, headline, cpu = [], None, None
     t_start = time.perf_counter()
 
-    for name in [w for w in WORKLOADS if w in wanted]:
+    library = args.allocation == "library"
+    # the headline first: placing buffers by region works best while the device's memory is unused
+    for name in [HEADLINE] + [w for w in WORKLOADS if w in wanted and w != HEADLINE]:
         P, root, M, seed, what = WORKLOADS[name]
         row = {"workload": name, "what": what, "P": P, "root": root, "message_bytes": M, "variants": {}}
         if name == "cfg5b":
@@ -700,7 +761,8 @@ def main() -> int:
             continue
         msg = make_message(name, seed, M)
         assert msg.nbytes == M
-        ranks = Ranks(torch, inputs, P, root, M, msg)
+        ranks = Ranks(B, torch, inputs, P, root, M, msg, library)
+        row["allocation"] = ranks.allocation
         for variant in VARIANTS[name]:
             reps = 5 if args.quick else max(20, reps_for(M, False))
             if name == HEADLINE and variant == "chain":
@@ -743,16 +805,18 @@ def main() -> int:
         if name == HEADLINE and not args.no_cpu_baseline:
             C = row["variants"]["chain"]["geometry"]["chunk_bytes"] or M
             cpu = cpu_baseline(P, root, M, C, msg)
+        ranks.free()
         del ranks, msg
         torch.cuda.empty_cache()
         if name in ("cfg2", "cfg4"):
             try:
-                row["reduce"] = reduce_row(B, torch, np, P, root, M, seed, stream, profiles, name, args.quick, args.no_verify)
+                row["reduce"] = reduce_row(B, torch, np, P, root, M, seed, stream, profiles, name, args.quick, args.no_verify, library)
             except RuntimeError as e:
                 print("bench.py: %s" % e, file=sys.stderr)
                 return 1
             torch.cuda.empty_cache()
         configs.append(row)
+    configs.sort(key=lambda c: list(WORKLOADS).index(c["workload"]))
 
     P, root, M, seed, what = WORKLOADS[HEADLINE]
     head_cfg = next(c for c in configs if c["workload"] == HEADLINE)
@@ -779,7 +843,7 @@ def main() -> int:
         "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (HEADLINE, what), "P": P, "root": root, "message_bytes": M, "variant": "tuned pipelined chain",
-                   "tuning_table": table, **g},
+                   "tuning_table": table, "allocation": head_cfg.get("allocation"), **g},
         "delivered_GBps": round((P - 1) * M / (wall_ms * 1e-3) / 1e9, 2),
         "median_us": head["median_us"], "min_us": head["min_us"],
         "verified_bit_exact": head["verified_bit_exact"],

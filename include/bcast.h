@@ -84,6 +84,7 @@ typedef struct {
     uint64_t algorithmic_bytes; /* HBM bytes the schedule must move: reads + writes */
     int rank_waves;        /* chain: 1 if every rank has wavefronts of its own (a stage is a workgroup of
                               hops_per_stage wavefronts), 0 if one wavefront plays its stage's ranks in turn */
+    int stage_store;       /* chain: how stores inside a stage are issued, BCAST_STORE_THROUGH or BCAST_STORE_BACK */
 } bcast_plan_info_t;
 
 /*
@@ -198,6 +199,17 @@ int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
 #define BCAST_CHAIN_WAVE_PER_STAGE 1
 #define BCAST_CHAIN_WAVE_PER_RANK 2
 int bcast_plan_set_chain_waves(bcast_plan_t *plan, int mode);
+/* How the chain issues the stores that stay inside a stage (those the storing
+ * wavefront, or its workgroup, reads back itself, and the last position's;
+ * what another stage reads is always written through).  BCAST_STORE_THROUGH:
+ * written through to memory; BCAST_STORE_BACK: ordinary write-back stores,
+ * which the cache acknowledges sooner and the end of the kernel writes back.
+ * BCAST_STORE_AUTO (default): the tuning table's choice, else write-back up to
+ * 2 MiB and write-through above.  Same bytes either way. */
+#define BCAST_STORE_AUTO 0
+#define BCAST_STORE_THROUGH 1
+#define BCAST_STORE_BACK 2
+int bcast_plan_set_stage_store(bcast_plan_t *plan, int mode);
 int bcast_plan_set_stages(bcast_plan_t *plan, int stages);
 /* Bytes a chain wavefront moves per trip (16-byte accesses): a multiple of
  * 1024 the run's kernel is built for (2048, 3072, 4096 or 6144 with a wavefront
@@ -227,6 +239,49 @@ typedef struct {
  */
 int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_waves,
                          const bcast_chain_request_t *request, bcast_plan_info_t *info);
+
+/*
+ * Placement of buffers in the device's memory.  Measured on MI355X, the memory
+ * answers as three regions, each a third of the physical address range: writes
+ * spread over two regions run 1.2 times faster than writes into one, and reads
+ * mixed with writes to the same region cost far more than their bytes.  The
+ * broadcast's receiving buffers are therefore best spread over two regions, a
+ * reduction's contributions kept in one region and its result in another.
+ * Every call here takes plain device pointers allocated by anyone; these calls
+ * are for callers who want the library to allocate them well placed.
+ *
+ * bcast_memory_regions -- how many regions the current device's memory has
+ * (3) and the size of each (a third of the device's memory).
+ *
+ * bcast_buffers_alloc -- allocate n device buffers, buffer i of bytes[i] > 0
+ * bytes in region region[i] (0, 1 or 2), counted from the region the device's
+ * allocator is handing out at the time of the call: 0 = that one, 1 = the next.
+ * bytes, region: HOST arrays of n; ptrs: HOST array of n, receives the DEVICE
+ * pointers (hipMalloc'ed, 256-byte aligned or better; free them with
+ * bcast_buffers_free or hipFree).  The contents are undefined (the library may
+ * have written to them).  *placed (HOST, nullable) receives
+ *   BCAST_PLACED_NO        the buffers are allocated, but not where asked: the
+ *                          regions cannot be reached from where the allocator
+ *                          stands, a group does not fit its region, there is no
+ *                          room for the temporary fillers, or a measurement
+ *                          showed the placement did not take;
+ *   BCAST_PLACED_BY_ORDER  placed by allocation order (fillers push the
+ *                          allocator across region boundaries), too small a set
+ *                          to confirm by measurement;
+ *   BCAST_PLACED_MEASURED  placed, and writing to neighbouring regions' buffers
+ *                          together was measured clearly faster than to one
+ *                          region's alone.
+ * The call waits for the device while it measures, and temporarily allocates up
+ * to a region's worth of memory.  It works best early in a process, before the
+ * device's memory is fragmented.  On failure nothing stays allocated.
+ * Errors: ERR_ARG, ERR_NOMEM, ERR_HIP.
+ */
+#define BCAST_PLACED_NO 0
+#define BCAST_PLACED_BY_ORDER 1
+#define BCAST_PLACED_MEASURED 2
+int bcast_memory_regions(int *count, size_t *region_bytes);
+int bcast_buffers_alloc(int n, const size_t *bytes, const int *region, void **ptrs, int *placed);
+int bcast_buffers_free(int n, void *const *ptrs);
 
 /*
  * bcast_reduce_sum_f32 -- enqueue one rooted reduction (MPI_Reduce with MPI_SUM
@@ -355,10 +410,12 @@ typedef struct {
     double chain_usec;          /* chain: time at that setting */
     int rank_waves;             /* winner is the chain with a wavefront per rank (1) or per stage (0) */
     int chain_rank_waves;       /* the same for the chain's own best setting */
+    int stage_store;            /* winner (chain only): BCAST_STORE_THROUGH / _BACK, 0 = the library's rule */
+    int chain_stage_store;      /* the same for the chain's own best setting */
 } bcast_tune_entry_t;
 
 /* While a log path (HOST, NULL = off) is set, bcast_tune appends one line per
- * candidate it times: "nranks bytes algo chunk_bytes stages usec trip_bytes rank_waves"
+ * candidate it times: "nranks bytes algo chunk_bytes stages usec trip_bytes rank_waves stage_store"
  * (stages holds the radix for the k-nomial trees) -- the raw
  * material for fitting the cost models of Sec. III-A / IV-B. */
 int bcast_tune_set_log(const char *log_path);

@@ -42,7 +42,7 @@ BCAST_ERR_CAPACITY = -6
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
     "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_reduce_sum_f32_static", "bcast_plan_reserve_reduce", "bcast_allreduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
-    "bcast_plan_handoff_counts", "bcast_plan_set_cache_policy", "bcast_plan_set_chain_waves", "bcast_plan_set_replayable", "bcast_chain_geometry",
+    "bcast_plan_handoff_counts", "bcast_plan_set_cache_policy", "bcast_plan_set_chain_waves", "bcast_plan_set_stage_store", "bcast_plan_set_replayable", "bcast_memory_regions", "bcast_buffers_alloc", "bcast_buffers_free", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_tune_reduce", "bcast_tune_reduce_put", "bcast_tune_reduce_get", "bcast_plan_set_reduce_trip", "bcast_debug_store_pattern", "bcast_debug_load_pattern", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
 ]
@@ -78,6 +78,7 @@ class PlanInfo(ctypes.Structure):
         ("launches", ctypes.c_int),
         ("algorithmic_bytes", ctypes.c_uint64),
         ("rank_waves", ctypes.c_int),
+        ("stage_store", ctypes.c_int),
     ]
 
     def as_dict(self):
@@ -97,6 +98,8 @@ class TuneEntry(ctypes.Structure):
         ("chain_usec", ctypes.c_double),
         ("rank_waves", ctypes.c_int),
         ("chain_rank_waves", ctypes.c_int),
+        ("stage_store", ctypes.c_int),
+        ("chain_stage_store", ctypes.c_int),
     ]
 
     def as_dict(self):
@@ -147,6 +150,11 @@ def _load():
         "bcast_plan_set_cache_policy": ([vp, i, i, i, i], i),
         "bcast_plan_set_chain_waves": ([vp, i], i),
         "bcast_plan_set_replayable": ([vp, i], i),
+        "bcast_plan_set_stage_store": ([vp, i], i),
+        "bcast_memory_regions": ([ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_size_t)], i),
+        "bcast_buffers_alloc": ([i, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_void_p),
+                                ctypes.POINTER(ctypes.c_int)], i),
+        "bcast_buffers_free": ([i, ctypes.POINTER(ctypes.c_void_p)], i),
         "bcast_plan_enable_trace": ([vp, sz], i),
         "bcast_plan_read_trace": ([vp, ctypes.POINTER(u64), sz], i),
         "bcast_plan_handoff_counts": ([vp, ctypes.POINTER(u64), ctypes.POINTER(u64)], i),
@@ -385,6 +393,40 @@ BCAST_CHAIN_WAVE_PER_RANK = 2
 
 def bcast_plan_set_chain_waves(plan: Plan, mode: int) -> None:
     _check(_lib.bcast_plan_set_chain_waves(plan.handle, mode), "bcast_plan_set_chain_waves")
+
+
+BCAST_STORE_AUTO, BCAST_STORE_THROUGH, BCAST_STORE_BACK = 0, 1, 2
+
+
+def bcast_plan_set_stage_store(plan: Plan, mode: int) -> None:
+    _check(_lib.bcast_plan_set_stage_store(plan.handle, mode), "bcast_plan_set_stage_store")
+
+
+BCAST_PLACED_NO, BCAST_PLACED_BY_ORDER, BCAST_PLACED_MEASURED = 0, 1, 2
+
+
+def bcast_memory_regions() -> Tuple[int, int]:
+    """(number of regions of the current device's memory, bytes of each)."""
+    n, each = ctypes.c_int(0), ctypes.c_size_t(0)
+    _check(_lib.bcast_memory_regions(ctypes.byref(n), ctypes.byref(each)), "bcast_memory_regions")
+    return n.value, each.value
+
+
+def bcast_buffers_alloc(bytes_each: Sequence[int], regions: Sequence[int]) -> Tuple[list, int]:
+    """Device buffers placed by region; returns (device addresses, BCAST_PLACED_*)."""
+    n = len(bytes_each)
+    if len(regions) != n:
+        raise BcastError(BCAST_ERR_ARG, "bcast_buffers_alloc: %d sizes, %d regions" % (n, len(regions)))
+    ptrs = (ctypes.c_void_p * n)()
+    placed = ctypes.c_int(0)
+    _check(_lib.bcast_buffers_alloc(n, (ctypes.c_size_t * n)(*bytes_each), (ctypes.c_int * n)(*regions), ptrs, ctypes.byref(placed)),
+           "bcast_buffers_alloc")
+    return [int(p or 0) for p in ptrs], placed.value
+
+
+def bcast_buffers_free(ptrs: Sequence[int]) -> None:
+    n = len(ptrs)
+    _check(_lib.bcast_buffers_free(n, (ctypes.c_void_p * n)(*ptrs)), "bcast_buffers_free")
 
 
 def bcast_plan_set_replayable(plan: Plan, on: bool) -> None:

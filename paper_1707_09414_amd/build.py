@@ -17,7 +17,7 @@ PKG = Path(__file__).resolve().parent
 REPO = PKG.parent
 CSRC = PKG / "csrc"
 LIB = PKG / "lib" / "libbcast.so"
-SOURCES = ["kernels.hip", "bcast.cpp", "tune.cpp"]
+SOURCES = ["kernels.hip", "bcast.cpp", "tune.cpp", "memory.cpp"]
 
 
 def hipcc_path() -> str:

@@ -47,6 +47,7 @@ struct bcast_plan {
     int mute_hop = 0;
     int policy_request[4] = {-1, -1, -1, -1};  // ld_root, ld_edge, ld_back, st_mid; -1 = choose
     int reduce_trip_request = 0;               // reduction: 0 = choose, 4096 or 1024
+    int stage_store = BCAST_STORE_AUTO;        // chain: in-stage stores written through or write-back
     int chain_waves = BCAST_CHAIN_AUTO;        // chain: a wavefront per stage (chain_kernel) or per rank (rank_chain_kernel)
     int rank_blocks_per_cu[kRankWavesMax + 1] = {0};  // workgroups of w waves a CU holds (0 = not asked yet)
 };
@@ -352,6 +353,13 @@ extern "C" int bcast_plan_set_reduce_trip(bcast_plan_t *p, int trip_bytes)
     return BCAST_OK;
 }
 
+extern "C" int bcast_plan_set_stage_store(bcast_plan_t *p, int mode)
+{
+    if (!p || mode < BCAST_STORE_AUTO || mode > BCAST_STORE_BACK) return BCAST_ERR_ARG;
+    p->stage_store = mode;
+    return BCAST_OK;
+}
+
 extern "C" int bcast_plan_set_chain_waves(bcast_plan_t *p, int mode)
 {
     if (!p || mode < BCAST_CHAIN_AUTO || mode > BCAST_CHAIN_WAVE_PER_RANK) return BCAST_ERR_ARG;
@@ -480,6 +488,7 @@ struct Resolved {
     int radix;   // k-nomial only
     int trip;    // chain: bytes per trip
     bool rank_waves;  // chain: a wavefront per rank
+    int stage_store;  // chain: BCAST_STORE_THROUGH or _BACK
 };
 
 // Without a measurement: two stages (hops 1..h | h+1..P-1).  On one die the
@@ -511,6 +520,7 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
     r->stages = p->stages_request;
     r->trip = p->trip_request;
     r->rank_waves = p->chain_waves == BCAST_CHAIN_WAVE_PER_RANK;
+    r->stage_store = p->stage_store;
     bcast_tune_entry_t e;
     const bool tuned = bcast_tune_get(p->nranks, bytes, &e) == BCAST_OK;
     // a table entry's chunk, stages and trip belong to the wave mode it was
@@ -527,6 +537,7 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
             if (e.algo == BCAST_ALGO_CHAIN) {
                 if (r->trip == 0) r->trip = e.trip_bytes;
                 r->rank_waves = e.rank_waves != 0;
+                if (r->stage_store == BCAST_STORE_AUTO) r->stage_store = e.stage_store;
             }
         }
     } else if (p->algo == BCAST_ALGO_CHAIN && r->chunk == 0 && tuned && e.chain_chunk_bytes != 0 && mode_fits(e.chain_rank_waves)) {
@@ -534,7 +545,11 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
         if (r->stages == 0) r->stages = e.chain_stages;
         if (r->trip == 0) r->trip = e.chain_trip_bytes;
         r->rank_waves = e.chain_rank_waves != 0;
+        if (r->stage_store == BCAST_STORE_AUTO) r->stage_store = e.chain_stage_store;
     }
+    // no request and no table entry: write-back for small messages, whose time is
+    // the sum of their hops' round trips, write-through for those that stream
+    if (r->stage_store == BCAST_STORE_AUTO) r->stage_store = bytes <= kStageWriteBackMaxBytes ? BCAST_STORE_BACK : BCAST_STORE_THROUGH;
     r->radix = p->radix_request;
     if (r->algo == BCAST_ALGO_KNOMIAL || r->algo == BCAST_ALGO_KNOMIAL_PIPELINED) {
         // an AUTO plan takes the radix the table recorded (in the stages column)
@@ -704,6 +719,7 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
         rc = rank_chain_geometry(p, bytes, r.chunk, r.stages, r.trip, info);
         if (rc != BCAST_OK) return rc;
         info->vec_bytes = vec;
+        info->stage_store = r.stage_store;
         return BCAST_OK;
     }
     if (r.algo == BCAST_ALGO_CHAIN) {
@@ -712,6 +728,7 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
         if (rc != BCAST_OK) return rc;
         info->vec_bytes = vec;
         info->rotating_spans = info->stages > 0 && rotate_spans(p->mode, P - 1, info->stages) ? 1 : 0;
+        info->stage_store = r.stage_store;
         return BCAST_OK;
     }
     memset(info, 0, sizeof *info);
@@ -900,7 +917,7 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         // cache policies: everything another wave reads or wrote at agent scope;
         // the wave's own read-back cached; its in-stage stores write-through, or
         // write-back for small messages
-        const int chosen[4] = {kAuxAgent, kAuxAgent, kAuxCached, bytes <= kStageWriteBackMaxBytes ? kAuxCached : kAuxAgent};
+        const int chosen[4] = {kAuxAgent, kAuxAgent, kAuxCached, info.stage_store == BCAST_STORE_BACK ? kAuxCached : kAuxAgent};
         unsigned char pol[4];
         for (int i = 0; i < 4; ++i) pol[i] = (unsigned char)(p->policy_request[i] >= 0 ? p->policy_request[i] : chosen[i]);
         a.ld_root = pol[0];

@@ -52,6 +52,9 @@ static bool valid_entry(int nranks, const bcast_tune_entry_t &e)
     };
     if (!trip_ok(e.trip_bytes, e.rank_waves) || !trip_ok(e.chain_trip_bytes, e.chain_rank_waves)) return false;
     if (e.rank_waves && e.algo != BCAST_ALGO_CHAIN) return false;
+    if (e.stage_store < BCAST_STORE_AUTO || e.stage_store > BCAST_STORE_BACK) return false;
+    if (e.chain_stage_store < BCAST_STORE_AUTO || e.chain_stage_store > BCAST_STORE_BACK) return false;
+    if (e.stage_store != BCAST_STORE_AUTO && e.algo != BCAST_ALGO_CHAIN) return false;
     return true;
 }
 
@@ -86,6 +89,7 @@ extern "C" int bcast_tune_put(int nranks, size_t bytes, const bcast_tune_entry_t
         e.chain_trip_bytes = e.trip_bytes;
         e.chain_usec = e.usec;
         e.chain_rank_waves = e.rank_waves;
+        e.chain_stage_store = e.stage_store;
     }
     std::lock_guard<std::mutex> g(g_mu);
     g_table[{nranks, log2_bucket(bytes)}] = e;
@@ -199,18 +203,19 @@ extern "C" int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *ch
 
 static const char kHeaderLine[] =
     "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout 5=scatter-allgather 6=knomial 7=pipelined-knomial) chunk_bytes usec "
-    "chain_chunk_bytes chain_usec stages chain_stages trip_bytes chain_trip_bytes rank_waves chain_rank_waves\n";
+    "chain_chunk_bytes chain_usec stages chain_stages trip_bytes chain_trip_bytes rank_waves chain_rank_waves "
+    "stage_store(0=rule 1=through 2=back) chain_stage_store\n";
 
 // Text format, one entry per line (columns after usec are optional; for a
 // k-nomial winner the stages column holds the radix):
 //   nranks log2_bytes algo chunk_bytes usec [chain_chunk_bytes chain_usec [stages chain_stages
-//   [trip_bytes chain_trip_bytes [rank_waves chain_rank_waves]]]]
+//   [trip_bytes chain_trip_bytes [rank_waves chain_rank_waves [stage_store chain_stage_store]]]]]
 // Lines starting with '#' are comments.
 static void print_entry(FILE *f, int nranks, int bucket, const bcast_tune_entry_t &e)
 {
-    fprintf(f, "%d %d %d %llu %.3f %llu %.3f %d %d %d %d %d %d\n", nranks, bucket, e.algo, (unsigned long long)e.chunk_bytes,
+    fprintf(f, "%d %d %d %llu %.3f %llu %.3f %d %d %d %d %d %d %d %d\n", nranks, bucket, e.algo, (unsigned long long)e.chunk_bytes,
             e.usec, (unsigned long long)e.chain_chunk_bytes, e.chain_usec, e.stages, e.chain_stages, e.trip_bytes,
-            e.chain_trip_bytes, e.rank_waves, e.chain_rank_waves);
+            e.chain_trip_bytes, e.rank_waves, e.chain_rank_waves, e.stage_store, e.chain_stage_store);
 }
 
 static const char kReduceHeaderLine[] = "# reduce nranks log2_bytes chunk_bytes stages trip_bytes usec   (the chain reduction's own entries)\n";
@@ -239,7 +244,7 @@ extern "C" int bcast_tune_load(const char *path)
     if (!path) return BCAST_ERR_ARG;
     FILE *f = fopen(path, "r");
     if (!f) return BCAST_ERR_ARG;
-    char line[256];
+    char line[1024];  // longer than the header line that bcast_tune_save writes
     int rc = BCAST_OK;
     std::vector<std::pair<std::pair<int, int>, bcast_tune_entry_t>> rows;
     std::vector<std::pair<std::pair<int, int>, bcast_reduce_entry_t>> reduce_rows;
@@ -265,9 +270,9 @@ extern "C" int bcast_tune_load(const char *path)
         unsigned long long chunk = 0, cchunk = 0;
         bcast_tune_entry_t e;
         memset(&e, 0, sizeof e);
-        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf %d %d %d %d %d %d", &nranks, &bucket, &e.algo, &chunk, &e.usec, &cchunk,
+        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf %d %d %d %d %d %d %d %d", &nranks, &bucket, &e.algo, &chunk, &e.usec, &cchunk,
                          &e.chain_usec, &e.stages, &e.chain_stages, &e.trip_bytes, &e.chain_trip_bytes, &e.rank_waves,
-                         &e.chain_rank_waves);
+                         &e.chain_rank_waves, &e.stage_store, &e.chain_stage_store);
         e.chunk_bytes = chunk;
         e.chain_chunk_bytes = cchunk;
         if (got < 4 || bucket < 0 || bucket > 62 || !valid_entry(nranks, e)) {
@@ -280,6 +285,7 @@ extern "C" int bcast_tune_load(const char *path)
             e.chain_trip_bytes = e.trip_bytes;
             e.chain_usec = e.usec;
             e.chain_rank_waves = e.rank_waves;
+            e.chain_stage_store = e.stage_store;
         }
         rows.push_back({{nranks, bucket}, e});
     }
@@ -307,8 +313,8 @@ struct Scratch {
 
 // Microseconds per run of one candidate.  One timed run warms up and sizes
 // the batches (about 20 ms each, 2..40 runs); the best of three batches counts.
-int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages, int trip, int rank_waves, Scratch &sc,
-                   hipStream_t stream, double *usec)
+int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages, int trip, int rank_waves, int stage_store,
+                   Scratch &sc, hipStream_t stream, double *usec)
 {
     bcast_plan_t *plan = nullptr;
     int rc = bcast_plan_create(&plan, nranks, bytes, chunk, algo);
@@ -317,6 +323,7 @@ int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages,
     if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN) rc = bcast_plan_set_trip(plan, trip);
     if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN)
         rc = bcast_plan_set_chain_waves(plan, rank_waves ? BCAST_CHAIN_WAVE_PER_RANK : BCAST_CHAIN_WAVE_PER_STAGE);
+    if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN) rc = bcast_plan_set_stage_store(plan, stage_store);
     int reps = 1;
     double best = 1e30;
     for (int batch = 0; batch < 4 && rc == BCAST_OK; ++batch) {
@@ -348,12 +355,20 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
     if ((algo_mask & ~(BCAST_TUNE_FOLDED | BCAST_TUNE_NO_RANK_WAVES)) == 0)
         algo_mask |= (1u << BCAST_ALGO_CHAIN) | (1u << BCAST_ALGO_DIRECT) | (1u << BCAST_ALGO_BINOMIAL);
 
+    // rank buffers placed as the library recommends for a broadcast: the two halves
+    // of the chain in two regions of the device's memory (see memory.cpp)
     Scratch sc;
     sc.bufs.assign(nranks, nullptr);
+    {
+        std::vector<size_t> sizes(nranks, max_bytes);
+        std::vector<int> region(nranks, 0);
+        for (int r = nranks / 2; r < nranks; ++r) region[r] = 1;
+        int rc_alloc = bcast_buffers_alloc(nranks, sizes.data(), region.data(), sc.bufs.data(), nullptr);
+        if (rc_alloc != BCAST_OK) return rc_alloc;
+    }
     for (int r = 0; r < nranks; ++r) {
-        hipError_t e = hipMalloc(&sc.bufs[r], max_bytes);
-        if (e == hipSuccess) e = hipMemset(sc.bufs[r], r == 0 ? 0x5a : 0xff, max_bytes);
-        if (e != hipSuccess) return e == hipErrorOutOfMemory ? BCAST_ERR_NOMEM : BCAST_ERR_HIP;
+        hipError_t e = hipMemset(sc.bufs[r], r == 0 ? 0x5a : 0xff, max_bytes);
+        if (e != hipSuccess) return BCAST_ERR_HIP;
     }
     if (hipEventCreate(&sc.e0) != hipSuccess || hipEventCreate(&sc.e1) != hipSuccess) return BCAST_ERR_HIP;
 
@@ -362,7 +377,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         std::lock_guard<std::mutex> g(g_mu);
         if (!g_log_path.empty()) log = fopen(g_log_path.c_str(), "a");
     }
-    if (log) fprintf(log, "# nranks bytes algo chunk_bytes stages usec trip_bytes rank_waves\n");
+    if (log) fprintf(log, "# nranks bytes algo chunk_bytes stages usec trip_bytes rank_waves stage_store\n");
     struct LogCloser {
         FILE *f;
         ~LogCloser() { if (f) fclose(f); }
@@ -392,17 +407,18 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         bcast_tune_entry_t best;
         memset(&best, 0, sizeof best);
         best.usec = best.chain_usec = 1e30;
-        auto consider = [&](int algo, size_t chunk, int stages, int trip = 0, int rank_waves = 0) {
+        auto consider = [&](int algo, size_t chunk, int stages, int trip = 0, int rank_waves = 0, int stage_store = BCAST_STORE_AUTO) {
             if (rc != BCAST_OK || !(algo_mask & (1u << algo))) return;
             double us = 0.0;
-            rc = time_candidate(nranks, M, algo, chunk, stages, trip, rank_waves, sc, stream, &us);
+            rc = time_candidate(nranks, M, algo, chunk, stages, trip, rank_waves, stage_store, sc, stream, &us);
             if (rc != BCAST_OK) return;
-            if (log) fprintf(log, "%d %zu %d %zu %d %.3f %d %d\n", nranks, M, algo, chunk, stages, us, trip, rank_waves);
+            if (log) fprintf(log, "%d %zu %d %zu %d %.3f %d %d %d\n", nranks, M, algo, chunk, stages, us, trip, rank_waves, stage_store);
             if (algo == BCAST_ALGO_CHAIN && us < best.chain_usec) {
                 best.chain_chunk_bytes = chunk;
                 best.chain_stages = stages;
                 best.chain_trip_bytes = trip;
                 best.chain_rank_waves = rank_waves;
+                best.chain_stage_store = stage_store;
                 best.chain_usec = us;
             }
             if (us < best.usec) {
@@ -411,6 +427,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
                 best.stages = (algo == BCAST_ALGO_CHAIN || has_radix(algo)) ? stages : 0;
                 best.trip_bytes = algo == BCAST_ALGO_CHAIN ? trip : 0;
                 best.rank_waves = algo == BCAST_ALGO_CHAIN ? rank_waves : 0;
+                best.stage_store = algo == BCAST_ALGO_CHAIN ? stage_store : BCAST_STORE_AUTO;
                 best.usec = us;
             }
         };
@@ -432,6 +449,11 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
                     if (C >= M || M / C > 4096 || C > (64u << 20)) continue;
                     if (trip == 3072 && lanes * (size_t)stages < 512) continue;
                     consider(BCAST_ALGO_CHAIN, C, stages, trip);
+                    // the same with write-back stores inside the stages where the message streams (below
+                    // that the library's rule already stores write-back): the cache acknowledges them
+                    // sooner, so fewer waves fill the memory system
+                    if (M >= ((size_t)4 << 20) && stages <= 4 && lanes * (size_t)stages >= 256 && lanes * (size_t)stages <= 2048)
+                        consider(BCAST_ALGO_CHAIN, C, stages, trip, 0, BCAST_STORE_BACK);
                 }
             }
         }
@@ -489,12 +511,20 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
 extern "C" int bcast_tune_reduce(int nranks, size_t min_bytes, size_t max_bytes, bcast_stream_t stream, const char *table_path)
 {
     if (nranks < 2 || nranks > BCAST_MAX_RANKS || min_bytes < 4 || max_bytes < min_bytes) return BCAST_ERR_ARG;
+    // placed as the library recommends for a reduction: the contributions in one
+    // region of the device's memory, the result in another (see memory.cpp)
     Scratch sc;
     sc.bufs.assign(nranks + 1, nullptr);
+    {
+        std::vector<size_t> sizes(nranks + 1, max_bytes);
+        std::vector<int> region(nranks + 1, 0);
+        region[nranks] = 1;
+        int rc_alloc = bcast_buffers_alloc(nranks + 1, sizes.data(), region.data(), sc.bufs.data(), nullptr);
+        if (rc_alloc != BCAST_OK) return rc_alloc;
+    }
     for (int r = 0; r <= nranks; ++r) {
-        hipError_t e = hipMalloc(&sc.bufs[r], max_bytes);
-        if (e == hipSuccess) e = hipMemset(sc.bufs[r], 0, max_bytes);  // fp32 zeros: sums stay finite
-        if (e != hipSuccess) return e == hipErrorOutOfMemory ? BCAST_ERR_NOMEM : BCAST_ERR_HIP;
+        hipError_t e = hipMemset(sc.bufs[r], 0, max_bytes);  // fp32 zeros: sums stay finite
+        if (e != hipSuccess) return BCAST_ERR_HIP;
     }
     if (hipEventCreate(&sc.e0) != hipSuccess || hipEventCreate(&sc.e1) != hipSuccess) return BCAST_ERR_HIP;
     FILE *log = nullptr;

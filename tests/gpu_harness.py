@@ -124,3 +124,15 @@ def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0,
         assert info["launches"] == res.steps, "one launch per k-nomial round"
     assert_same(got, exp, "P=%d root=%d M=%d C=%d algo=%d offsets=%s" % (P, root, M, C, algo, offsets))
     return info
+
+
+class _DeviceSpan:
+    """`nbytes` bytes of device memory at `ptr`, described the way torch reads foreign device arrays."""
+
+    def __init__(self, ptr, nbytes):
+        self.__cuda_array_interface__ = {"shape": (int(nbytes),), "typestr": "|u1", "data": (int(ptr), False), "version": 2}
+
+
+def tensor_at(ptr, nbytes):
+    """A uint8 tensor over device memory the library allocated (no copy, no ownership)."""
+    return torch.as_tensor(_DeviceSpan(ptr, nbytes), device="cuda")

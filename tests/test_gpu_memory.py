@@ -1,0 +1,145 @@
+"""bcast_buffers_alloc: rank buffers placed by region of the device's memory.
+
+The method's result does not depend on where its buffers lie, its speed on this
+device does: the tests check that the placed buffers are sound (distinct,
+aligned, usable by every entry point, results bit-exact against the oracle),
+that the verdict the call reports agrees with a measurement taken here, and the
+error paths.  The placement itself relies on the order in which the device's
+allocator hands memory out, which earlier allocations and frees (of this or an
+earlier process) change: no verdict is required, only an honest one.
+"""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1707_09414_amd import binding as B
+from paper_1707_09414_amd import inputs
+from gpu_harness import tensor_at
+
+pytestmark = pytest.mark.gpu
+KiB, MiB, GiB = inputs.KiB, inputs.MiB, 1 << 30
+SLACK = 64 * MiB  # what the runtime itself may allocate meanwhile (code objects, events)
+
+
+def used_bytes():
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    free, total = torch.cuda.mem_get_info()
+    return total - free
+
+
+def store_rate(ptrs, nbytes):
+    """GB/s of the dependency-free store pattern over nbytes of each buffer."""
+    s = torch.cuda.current_stream()
+    best = 0.0
+    B.bcast_debug_store_pattern(ptrs, nbytes, s)
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(s)
+        B.bcast_debug_store_pattern(ptrs, nbytes, s)
+        e1.record(s)
+        torch.cuda.synchronize()
+        best = max(best, len(ptrs) * nbytes / e0.elapsed_time(e1) / 1e6)
+    return best
+
+
+def test_regions_of_the_device():
+    n, each = B.bcast_memory_regions()
+    _, total = torch.cuda.mem_get_info()
+    assert n == 3 and each == total // 3
+
+
+def test_broadcast_buffers_spread_over_two_regions():
+    P, M, root = 16, 256 * MiB, 3
+    before = used_bytes()
+    ptrs, placed = B.bcast_buffers_alloc([M] * P, [0] * (P // 2) + [1] * (P // 2))
+    try:
+        assert len(set(ptrs)) == P and all(p and p % 256 == 0 for p in ptrs)
+        order = sorted(ptrs)
+        assert all(b - a >= M for a, b in zip(order, order[1:])), "buffers overlap"
+        assert placed in (B.BCAST_PLACED_NO, B.BCAST_PLACED_BY_ORDER, B.BCAST_PLACED_MEASURED)
+        # the verdict against a measurement taken here: both halves together vs the slower half alone
+        together = store_rate(ptrs, M)
+        halves = store_rate(ptrs[: P // 2], M), store_rate(ptrs[P // 2:], M)
+        gain = together / min(halves)
+        print("verdict %d, %.2f GiB in use before; store-only GB/s: halves %.0f and %.0f, together %.0f" % (
+            placed, before / GiB, halves[0], halves[1], together))
+        if placed == B.BCAST_PLACED_MEASURED:
+            assert gain > 1.05 or together > 6300.0, \
+                "reported as measured-spread, but writes to both halves run at %.0f GB/s, %.2fx the slower half alone" % (together, gain)
+        # the buffers serve as rank buffers: a broadcast of the whole size, every rank against the root on the
+        # device, and a prefix of every rank against the oracle's end state
+        message = inputs.random_bytes(81, M)
+        views = [tensor_at(p, M) for p in ptrs]
+        for r in range(P):
+            views[r].fill_(inputs.FILL_BYTE)
+        views[root].copy_(torch.from_numpy(message))
+        plan = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_CHAIN)
+        B.bcast_run(plan, ptrs, root, M, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+        plan.destroy()
+        for r in range(P):
+            assert torch.equal(views[r], views[root]), "rank %d" % r
+        n = 1 * MiB + 5
+        state = np.full((P, n), inputs.FILL_BYTE, np.uint8)
+        state[root] = message[:n]
+        oracle.chain_bcast(state, P, root, n, 64 * KiB)
+        for r in range(P):
+            assert np.array_equal(views[r][:n].cpu().numpy(), state[r]), "rank %d differs from the oracle" % r
+        del views
+    finally:
+        B.bcast_buffers_free(ptrs)
+
+
+def test_reduction_buffers_result_in_another_region():
+    P, root, count = 8, 5, 8 * MiB + 3
+    nbytes = (count * 4 + 255) // 256 * 256
+    ptrs, placed = B.bcast_buffers_alloc([nbytes] * (P + 1), [0] * P + [1])
+    try:
+        assert placed in (B.BCAST_PLACED_NO, B.BCAST_PLACED_BY_ORDER, B.BCAST_PLACED_MEASURED)
+        rng = np.random.default_rng(82)
+        x = rng.normal(0.0, 0.01, size=(P, count)).astype(np.float32)
+        views = [tensor_at(p, nbytes) for p in ptrs]
+        for r in range(P):
+            views[r][: count * 4].copy_(torch.from_numpy(x[r].view(np.uint8)))
+        views[P].fill_(0xEE)
+        plan = B.bcast_plan_create(P, count * 4, 0, B.BCAST_ALGO_CHAIN)
+        B.bcast_reduce_sum_f32(plan, ptrs[:P], ptrs[P], root, count, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        assert B.bcast_plan_status(plan)[0] == B.BCAST_OK
+        plan.destroy()
+        got = views[P].cpu().numpy()
+        want, _ = oracle.chain_reduce_f32(np.ascontiguousarray(x), P, root, count, 16 * KiB)
+        assert np.array_equal(got[: count * 4].view(np.uint32), want.view(np.uint32))
+        assert (got[count * 4:] == 0xEE).all(), "wrote beyond the result"
+        del views
+    finally:
+        B.bcast_buffers_free(ptrs)
+
+
+def test_requests_that_cannot_be_placed_and_errors():
+    before = used_bytes()
+    E = B.BCAST_ERR_ARG
+    for sizes, regions in ([[], []], [[0], [0]], [[4096], [3]], [[4096], [-1]]):
+        with pytest.raises(B.BcastError) as err:
+            B.bcast_buffers_alloc(sizes, regions)
+        assert err.value.status == E
+    with pytest.raises(B.BcastError):
+        B.bcast_buffers_alloc([4096, 4096], [0])
+    assert abs(used_bytes() - before) <= SLACK, "a refused request left memory allocated"
+    # a group larger than a region cannot be placed: it is allocated where it falls, and says so
+    _, each = B.bcast_memory_regions()
+    ptrs, placed = B.bcast_buffers_alloc([4096, each], [0, 1])
+    assert placed == B.BCAST_PLACED_NO and all(ptrs)
+    B.bcast_buffers_free(ptrs)
+    assert abs(used_bytes() - before) <= SLACK
+    # more memory than the device has: nothing stays allocated
+    with pytest.raises(B.BcastError) as err:
+        B.bcast_buffers_alloc([each, each, each, each], [0, 0, 1, 1])
+    assert err.value.status == B.BCAST_ERR_NOMEM
+    assert abs(used_bytes() - before) <= SLACK

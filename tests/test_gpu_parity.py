@@ -129,6 +129,25 @@ def test_chain_workgroup_sizes(noise, block, P, stages, lanes, M, C):
     assert info["grid_blocks"] == -(-info["stages"] * info["lanes"] // (block // 64))
 
 
+@pytest.mark.parametrize("store", [B.BCAST_STORE_THROUGH, B.BCAST_STORE_BACK])
+@pytest.mark.parametrize("waves", [B.BCAST_CHAIN_WAVE_PER_STAGE, B.BCAST_CHAIN_WAVE_PER_RANK])
+@pytest.mark.parametrize("P,stages,M,C", [(5, 4, 300 * KiB + 3, 16 * KiB), (8, 2, 6 * MiB + 77, 256 * KiB), (16, 3, 9 * MiB, MiB),
+                                          (64, 4, 5 * MiB + 16, 0), (33, 4, 3000, 1024)])
+def test_stage_store_modes(noise, store, waves, P, stages, M, C):
+    """The stores that stay inside a stage written through or written back: the
+    same bytes either way, at sizes on both sides of the size rule, for both
+    chain kernels; the plan reports what it will use."""
+    plan = B.bcast_plan_create(P, M, C, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_stage_store(plan, store)
+    info = run_and_check(P, 1, M, C, B.BCAST_ALGO_CHAIN, noise, stages=stages, waves=waves, plan=plan)
+    assert info["stage_store"] == store
+    B.bcast_plan_set_stage_store(plan, B.BCAST_STORE_AUTO)
+    assert B.bcast_plan_info(plan, M)["stage_store"] == (B.BCAST_STORE_BACK if M <= 2 * MiB else B.BCAST_STORE_THROUGH)
+    with pytest.raises(B.BcastError):
+        B.bcast_plan_set_stage_store(plan, 3)
+    plan.destroy()
+
+
 @pytest.mark.parametrize("P,radix", [(2, 2), (5, 3), (9, 3), (10, 3), (16, 4), (17, 4), (64, 4), (64, 8), (64, 64), (33, 2), (7, 9)])
 @pytest.mark.parametrize("M", [9, 4096, MiB + 3])
 def test_knomial_radices(noise, P, radix, M):

@@ -167,7 +167,13 @@ def test_tuning_table_lookup_rules(tmp_path):
         B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_DIRECT, chain_stages=65)
     with pytest.raises(B.BcastError):
         B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=4096, trip_bytes=5120)
-    B.bcast_tune_put(16, 1 << 24, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=3 << 20, stages=2, trip_bytes=3072, usec=80.0)
+    B.bcast_tune_put(16, 1 << 24, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=3 << 20, stages=2, trip_bytes=3072, usec=80.0,
+                     stage_store=B.BCAST_STORE_BACK)
+    # how the chain stores inside a stage is part of a chain entry, and of nothing else
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=4096, stage_store=3)
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_DIRECT, stage_store=B.BCAST_STORE_BACK)
 
     path = tmp_path / "table.txt"
     B.bcast_tune_save(str(path))
@@ -176,6 +182,8 @@ def test_tuning_table_lookup_rules(tmp_path):
     assert B.bcast_tune_count() == 5
     e = B.bcast_tune_get(16, 1 << 24)
     assert (e["trip_bytes"], e["chain_trip_bytes"], e["chain_chunk_bytes"], e["stages"]) == (3072, 3072, 3 << 20, 2)
+    assert (e["stage_store"], e["chain_stage_store"]) == (B.BCAST_STORE_BACK, B.BCAST_STORE_BACK)
+    assert B.bcast_tune_get(8, 1 << 20)["stage_store"] == B.BCAST_STORE_AUTO
     assert B.bcast_tune_lookup(8, 1 << 20) == (B.BCAST_ALGO_CHAIN, 64 << 10, 50.0)
     e = B.bcast_tune_get(16, 1 << 20)
     assert (e["chain_chunk_bytes"], e["chain_stages"], e["chain_usec"]) == (128 << 10, 4, 90.0)
