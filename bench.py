@@ -368,6 +368,8 @@ def measure_variant(B, torch, ranks, name, variant, stream, warmup, reps, profil
         "floor_bytes": fl, "floor_GBps": round(fl / med_s / 1e9, 1), "floor_frac": round(fl / med_s / 1e9 / HBM_PEAK_GBS, 4),
         "kernel": kernel_name(info, B), "geometry": geometry, "verified_bit_exact": verified,
     })
+    if info["algo"] == B.BCAST_ALGO_CHAIN:
+        row["stage_store"] = "write-back" if info["stage_store"] == B.BCAST_STORE_BACK else "write-through"
     traffic, why = traffic_for(profiles, name, variant, geometry)
     if traffic:
         row.update({"traffic_bytes": traffic["bytes"], "traffic_fetch_bytes": traffic["fetch_bytes"], "traffic_write_bytes": traffic["write_bytes"],
@@ -843,7 +845,7 @@ def main() -> int:
         "dtype": "u8",
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (HEADLINE, what), "P": P, "root": root, "message_bytes": M, "variant": "tuned pipelined chain",
-                   "tuning_table": table, "allocation": head_cfg.get("allocation"), **g},
+                   "tuning_table": table, "allocation": head_cfg.get("allocation"), "stage_store": head.get("stage_store"), **g},
         "delivered_GBps": round((P - 1) * M / (wall_ms * 1e-3) / 1e9, 2),
         "median_us": head["median_us"], "min_us": head["min_us"],
         "verified_bit_exact": head["verified_bit_exact"],
