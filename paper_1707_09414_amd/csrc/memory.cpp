@@ -44,8 +44,8 @@ constexpr size_t kProbePieces = 8;                 // filler pieces on either si
 constexpr size_t kProbeMinBytes = 2 * kGiB;        // a probe must write more than the memory-side cache holds (256 MiB), by a wide margin
 constexpr size_t kProbeWindowMax = (size_t)256 << 20;
 static_assert(kProbeWindowMax <= kFillerPiece, "a probe writes at most one filler piece's size into a piece");
-constexpr double kProbeGain = 1.08;
-constexpr double kSpreadRateGBps = 6500.0;         // store-only rate: 5800-6000 into one region, 6900-7200 over two (measured)                // two regions together vs one alone: measured 1.18-1.20
+constexpr double kProbeGain = 1.08;                // both sides of a boundary together vs the slower side alone: measured 1.18-1.20
+constexpr double kSpreadRateGBps = 6500.0;         // store-only rate: 5800-6000 GB/s into one region, 6900-7200 over two (measured)
 
 size_t round_up_unit(size_t n) { return (n + kAllocUnit - 1) / kAllocUnit * kAllocUnit; }
 
