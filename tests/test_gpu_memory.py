@@ -122,6 +122,61 @@ def test_reduction_buffers_result_in_another_region():
         B.bcast_buffers_free(ptrs)
 
 
+def check_sound(ptrs, sizes):
+    assert len(set(ptrs)) == len(ptrs) and all(p and p % 256 == 0 for p in ptrs)
+    spans = sorted(zip(ptrs, sizes))
+    assert all(a + n <= b for (a, n), (b, _) in zip(spans, spans[1:])), "buffers overlap"
+    # every byte of every buffer is usable: write a pattern through the whole length, read it back
+    for p, n in zip(ptrs, sizes):
+        t = tensor_at(p, n)
+        t.fill_(p >> 21 & 0xFF)
+    torch.cuda.synchronize()
+    for p, n in zip(ptrs, sizes):
+        t = tensor_at(p, n)
+        assert int(t[0]) == int(t[n - 1]) == int(t[n // 2]) == (p >> 21 & 0xFF)
+
+
+def test_three_regions_and_a_start_close_to_a_boundary():
+    """Groups in all three regions; then the same with memory in use up to a few GiB
+    before a region boundary, so that the first group is moved to the next region."""
+    sizes = [256 * MiB] * 12
+    used_bytes()
+    ptrs, placed = B.bcast_buffers_alloc(sizes, [0] * 4 + [1] * 4 + [2] * 4)
+    try:
+        assert placed in (B.BCAST_PLACED_NO, B.BCAST_PLACED_BY_ORDER, B.BCAST_PLACED_MEASURED)
+        check_sound(ptrs, sizes)
+    finally:
+        B.bcast_buffers_free(ptrs)
+    _, each = B.bcast_memory_regions()
+    in_use = used_bytes()
+    if in_use > 16 * GiB:
+        pytest.skip("the device's memory is in use by something else")
+    # pieces of 1 GiB up to 5 GiB short of the first boundary: the next 8 GiB group does not fit before it
+    ballast = [torch.empty(GiB, dtype=torch.uint8, device="cuda") for _ in range((each - in_use - 5 * GiB) // GiB)]
+    sizes = [GiB] * 16
+    ptrs, placed = B.bcast_buffers_alloc(sizes, [0] * 8 + [1] * 8)
+    try:
+        assert placed in (B.BCAST_PLACED_NO, B.BCAST_PLACED_BY_ORDER, B.BCAST_PLACED_MEASURED)
+        check_sound(ptrs, sizes)
+        together = store_rate(ptrs, GiB)
+        slower = min(store_rate(ptrs[:8], GiB), store_rate(ptrs[8:], GiB))
+        print("verdict %d with %.1f GiB in use; store-only GB/s: together %.0f, slower half %.0f" % (placed, (in_use + len(ballast) * GiB) / GiB, together, slower))
+        if placed == B.BCAST_PLACED_MEASURED:
+            assert together / slower > 1.05 or together > 6300.0
+    finally:
+        B.bcast_buffers_free(ptrs)
+        del ballast
+    # a request whose last region lies beyond the device's memory is allocated where it falls
+    ballast = [torch.empty(GiB, dtype=torch.uint8, device="cuda") for _ in range((2 * each + 2 * GiB - used_bytes()) // GiB)]
+    ptrs, placed = B.bcast_buffers_alloc([64 * MiB] * 4, [0, 0, 1, 1])
+    try:
+        assert placed == B.BCAST_PLACED_NO
+        check_sound(ptrs, [64 * MiB] * 4)
+    finally:
+        B.bcast_buffers_free(ptrs)
+        del ballast
+
+
 def test_requests_that_cannot_be_placed_and_errors():
     before = used_bytes()
     E = B.BCAST_ERR_ARG
