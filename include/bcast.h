@@ -412,10 +412,20 @@ typedef struct {
     int chain_rank_waves;       /* the same for the chain's own best setting */
     int stage_store;            /* winner (chain only): BCAST_STORE_THROUGH / _BACK, 0 = the library's rule */
     int chain_stage_store;      /* the same for the chain's own best setting */
+    int lanes;                  /* winner (chain with a wavefront per stage only): wavefronts per stage, 0 = one per
+                                   trip of a chunk (so chunk_bytes / lanes / trip_bytes trips per lane and chunk) */
+    int chain_lanes;            /* the same for the chain's own best setting */
+    int spans;                  /* winner (chain with a wavefront per stage only), where nranks-1 is no multiple of
+                                   stages: BCAST_SPANS_FIXED (the first stages keep the extra hop) or BCAST_SPANS_ROTATE
+                                   (it is passed round from chunk to chunk, see bcast_chain_stage_span); 0 = the library's rule */
+    int chain_spans;            /* the same for the chain's own best setting */
 } bcast_tune_entry_t;
+#define BCAST_SPANS_AUTO 0
+#define BCAST_SPANS_FIXED 1
+#define BCAST_SPANS_ROTATE 2
 
 /* While a log path (HOST, NULL = off) is set, bcast_tune appends one line per
- * candidate it times: "nranks bytes algo chunk_bytes stages usec trip_bytes rank_waves stage_store"
+ * candidate it times: "nranks bytes algo chunk_bytes stages usec trip_bytes rank_waves stage_store lanes spans"
  * (stages holds the radix for the k-nomial trees) -- the raw
  * material for fitting the cost models of Sec. III-A / IV-B. */
 int bcast_tune_set_log(const char *log_path);

@@ -100,6 +100,10 @@ class TuneEntry(ctypes.Structure):
         ("chain_rank_waves", ctypes.c_int),
         ("stage_store", ctypes.c_int),
         ("chain_stage_store", ctypes.c_int),
+        ("lanes", ctypes.c_int),
+        ("chain_lanes", ctypes.c_int),
+        ("spans", ctypes.c_int),
+        ("chain_spans", ctypes.c_int),
     ]
 
     def as_dict(self):
@@ -396,6 +400,7 @@ def bcast_plan_set_chain_waves(plan: Plan, mode: int) -> None:
 
 
 BCAST_STORE_AUTO, BCAST_STORE_THROUGH, BCAST_STORE_BACK = 0, 1, 2
+BCAST_SPANS_AUTO, BCAST_SPANS_FIXED, BCAST_SPANS_ROTATE = 0, 1, 2
 
 
 def bcast_plan_set_stage_store(plan: Plan, mode: int) -> None:

@@ -176,11 +176,14 @@ extern "C" int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes
 // 6.5 vs 5.4), where the idle time of the shorter stages is large; with long
 // stages (P >= 16 in two stages) it loses 5 % at 3 KiB trips -- there the short
 // idle time of one stage relieves the CUs' L1, which those trips fill to the brim.
-static bool rotate_spans(unsigned mode, int hops, int stages)
+static bool rotate_spans(unsigned mode, int table_choice, int hops, int stages)
 {
     if (mode & kModeRotateSpans) return true;
     if (mode & kModeFixedSpans) return false;
-    return hops % stages != 0 && hops / stages < 4;
+    if (hops % stages == 0) return false;
+    if (table_choice == BCAST_SPANS_ROTATE) return true;
+    if (table_choice == BCAST_SPANS_FIXED) return false;
+    return hops / stages < 4;
 }
 
 extern "C" int bcast_chain_stage_span(int nranks, int stages, int stage, uint64_t chunk, int *first_hop, int *last_hop)
@@ -489,6 +492,8 @@ struct Resolved {
     int trip;    // chain: bytes per trip
     bool rank_waves;  // chain: a wavefront per rank
     int stage_store;  // chain: BCAST_STORE_THROUGH or _BACK
+    int lanes;        // chain with a wavefront per stage: wavefronts per stage, 0 = derive from the chunk
+    int spans;        // chain with a wavefront per stage: BCAST_SPANS_*
 };
 
 // Without a measurement: two stages (hops 1..h | h+1..P-1).  On one die the
@@ -521,6 +526,8 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
     r->trip = p->trip_request;
     r->rank_waves = p->chain_waves == BCAST_CHAIN_WAVE_PER_RANK;
     r->stage_store = p->stage_store;
+    r->lanes = p->lanes_request;
+    r->spans = BCAST_SPANS_AUTO;
     bcast_tune_entry_t e;
     const bool tuned = bcast_tune_get(p->nranks, bytes, &e) == BCAST_OK;
     // a table entry's chunk, stages and trip belong to the wave mode it was
@@ -538,6 +545,8 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
                 if (r->trip == 0) r->trip = e.trip_bytes;
                 r->rank_waves = e.rank_waves != 0;
                 if (r->stage_store == BCAST_STORE_AUTO) r->stage_store = e.stage_store;
+                if (r->lanes == 0) r->lanes = e.lanes;
+                r->spans = e.spans;
             }
         }
     } else if (p->algo == BCAST_ALGO_CHAIN && r->chunk == 0 && tuned && e.chain_chunk_bytes != 0 && mode_fits(e.chain_rank_waves)) {
@@ -546,6 +555,8 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
         if (r->trip == 0) r->trip = e.chain_trip_bytes;
         r->rank_waves = e.chain_rank_waves != 0;
         if (r->stage_store == BCAST_STORE_AUTO) r->stage_store = e.chain_stage_store;
+        if (r->lanes == 0) r->lanes = e.chain_lanes;
+        r->spans = e.chain_spans;
     }
     // no request and no table entry: write-back for small messages, whose time is
     // the sum of their hops' round trips, write-through for those that stream
@@ -723,11 +734,11 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
         return BCAST_OK;
     }
     if (r.algo == BCAST_ALGO_CHAIN) {
-        const bcast_chain_request_t req = {p->lanes_request, r.stages, r.trip, p->block_request};
+        const bcast_chain_request_t req = {r.lanes, r.stages, r.trip, p->block_request};
         rc = bcast_chain_geometry(P, bytes, (size_t)r.chunk, waves_for(p, bytes), &req, info);
         if (rc != BCAST_OK) return rc;
         info->vec_bytes = vec;
-        info->rotating_spans = info->stages > 0 && rotate_spans(p->mode, P - 1, info->stages) ? 1 : 0;
+        info->rotating_spans = info->stages > 0 && rotate_spans(p->mode, r.spans, P - 1, info->stages) ? 1 : 0;
         info->stage_store = r.stage_store;
         return BCAST_OK;
     }

@@ -55,6 +55,12 @@ static bool valid_entry(int nranks, const bcast_tune_entry_t &e)
     if (e.stage_store < BCAST_STORE_AUTO || e.stage_store > BCAST_STORE_BACK) return false;
     if (e.chain_stage_store < BCAST_STORE_AUTO || e.chain_stage_store > BCAST_STORE_BACK) return false;
     if (e.stage_store != BCAST_STORE_AUTO && e.algo != BCAST_ALGO_CHAIN) return false;
+    // lanes and spans belong to the chain with a wavefront per stage
+    if (e.lanes < 0 || e.lanes > 8192 || e.chain_lanes < 0 || e.chain_lanes > 8192) return false;
+    if (e.spans < BCAST_SPANS_AUTO || e.spans > BCAST_SPANS_ROTATE || e.chain_spans < BCAST_SPANS_AUTO || e.chain_spans > BCAST_SPANS_ROTATE)
+        return false;
+    if ((e.lanes != 0 || e.spans != BCAST_SPANS_AUTO) && (e.algo != BCAST_ALGO_CHAIN || e.rank_waves)) return false;
+    if ((e.chain_lanes != 0 || e.chain_spans != BCAST_SPANS_AUTO) && e.chain_rank_waves) return false;
     return true;
 }
 
@@ -90,6 +96,8 @@ extern "C" int bcast_tune_put(int nranks, size_t bytes, const bcast_tune_entry_t
         e.chain_usec = e.usec;
         e.chain_rank_waves = e.rank_waves;
         e.chain_stage_store = e.stage_store;
+        e.chain_lanes = e.lanes;
+        e.chain_spans = e.spans;
     }
     std::lock_guard<std::mutex> g(g_mu);
     g_table[{nranks, log2_bucket(bytes)}] = e;
@@ -204,18 +212,20 @@ extern "C" int bcast_tune_lookup(int nranks, size_t bytes, int *algo, size_t *ch
 static const char kHeaderLine[] =
     "# nranks log2_bytes algo(1=chain 2=direct 3=binomial 4=fanout 5=scatter-allgather 6=knomial 7=pipelined-knomial) chunk_bytes usec "
     "chain_chunk_bytes chain_usec stages chain_stages trip_bytes chain_trip_bytes rank_waves chain_rank_waves "
-    "stage_store(0=rule 1=through 2=back) chain_stage_store\n";
+    "stage_store(0=rule 1=through 2=back) chain_stage_store lanes(0=from the chunk) chain_lanes spans(0=rule 1=fixed 2=rotate) chain_spans\n";
 
 // Text format, one entry per line (columns after usec are optional; for a
 // k-nomial winner the stages column holds the radix):
 //   nranks log2_bytes algo chunk_bytes usec [chain_chunk_bytes chain_usec [stages chain_stages
-//   [trip_bytes chain_trip_bytes [rank_waves chain_rank_waves [stage_store chain_stage_store]]]]]
+//   [trip_bytes chain_trip_bytes [rank_waves chain_rank_waves [stage_store chain_stage_store
+//   [lanes chain_lanes spans chain_spans]]]]]]
 // Lines starting with '#' are comments.
 static void print_entry(FILE *f, int nranks, int bucket, const bcast_tune_entry_t &e)
 {
-    fprintf(f, "%d %d %d %llu %.3f %llu %.3f %d %d %d %d %d %d %d %d\n", nranks, bucket, e.algo, (unsigned long long)e.chunk_bytes,
-            e.usec, (unsigned long long)e.chain_chunk_bytes, e.chain_usec, e.stages, e.chain_stages, e.trip_bytes,
-            e.chain_trip_bytes, e.rank_waves, e.chain_rank_waves, e.stage_store, e.chain_stage_store);
+    fprintf(f, "%d %d %d %llu %.3f %llu %.3f %d %d %d %d %d %d %d %d %d %d %d %d\n", nranks, bucket, e.algo,
+            (unsigned long long)e.chunk_bytes, e.usec, (unsigned long long)e.chain_chunk_bytes, e.chain_usec, e.stages, e.chain_stages,
+            e.trip_bytes, e.chain_trip_bytes, e.rank_waves, e.chain_rank_waves, e.stage_store, e.chain_stage_store, e.lanes,
+            e.chain_lanes, e.spans, e.chain_spans);
 }
 
 static const char kReduceHeaderLine[] = "# reduce nranks log2_bytes chunk_bytes stages trip_bytes usec   (the chain reduction's own entries)\n";
@@ -270,9 +280,9 @@ extern "C" int bcast_tune_load(const char *path)
         unsigned long long chunk = 0, cchunk = 0;
         bcast_tune_entry_t e;
         memset(&e, 0, sizeof e);
-        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf %d %d %d %d %d %d %d %d", &nranks, &bucket, &e.algo, &chunk, &e.usec, &cchunk,
-                         &e.chain_usec, &e.stages, &e.chain_stages, &e.trip_bytes, &e.chain_trip_bytes, &e.rank_waves,
-                         &e.chain_rank_waves, &e.stage_store, &e.chain_stage_store);
+        int got = sscanf(s, "%d %d %d %llu %lf %llu %lf %d %d %d %d %d %d %d %d %d %d %d %d", &nranks, &bucket, &e.algo, &chunk, &e.usec,
+                         &cchunk, &e.chain_usec, &e.stages, &e.chain_stages, &e.trip_bytes, &e.chain_trip_bytes, &e.rank_waves,
+                         &e.chain_rank_waves, &e.stage_store, &e.chain_stage_store, &e.lanes, &e.chain_lanes, &e.spans, &e.chain_spans);
         e.chunk_bytes = chunk;
         e.chain_chunk_bytes = cchunk;
         if (got < 4 || bucket < 0 || bucket > 62 || !valid_entry(nranks, e)) {
@@ -286,6 +296,8 @@ extern "C" int bcast_tune_load(const char *path)
             e.chain_usec = e.usec;
             e.chain_rank_waves = e.rank_waves;
             e.chain_stage_store = e.stage_store;
+            e.chain_lanes = e.lanes;
+            e.chain_spans = e.spans;
         }
         rows.push_back({{nranks, bucket}, e});
     }
@@ -314,7 +326,7 @@ struct Scratch {
 // Microseconds per run of one candidate.  One timed run warms up and sizes
 // the batches (about 20 ms each, 2..40 runs); the best of three batches counts.
 int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages, int trip, int rank_waves, int stage_store,
-                   Scratch &sc, hipStream_t stream, double *usec)
+                   int lanes, int spans, Scratch &sc, hipStream_t stream, double *usec)
 {
     bcast_plan_t *plan = nullptr;
     int rc = bcast_plan_create(&plan, nranks, bytes, chunk, algo);
@@ -324,6 +336,9 @@ int time_candidate(int nranks, size_t bytes, int algo, size_t chunk, int stages,
     if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN)
         rc = bcast_plan_set_chain_waves(plan, rank_waves ? BCAST_CHAIN_WAVE_PER_RANK : BCAST_CHAIN_WAVE_PER_STAGE);
     if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN) rc = bcast_plan_set_stage_store(plan, stage_store);
+    if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN && lanes > 0) rc = bcast_plan_set_lanes(plan, lanes);
+    if (rc == BCAST_OK && algo == BCAST_ALGO_CHAIN && spans != BCAST_SPANS_AUTO)
+        rc = bcast_plan_set_mode(plan, spans == BCAST_SPANS_ROTATE ? BCAST_MODE_ROTATE_SPANS : BCAST_MODE_FIXED_SPANS);
     int reps = 1;
     double best = 1e30;
     for (int batch = 0; batch < 4 && rc == BCAST_OK; ++batch) {
@@ -377,7 +392,7 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         std::lock_guard<std::mutex> g(g_mu);
         if (!g_log_path.empty()) log = fopen(g_log_path.c_str(), "a");
     }
-    if (log) fprintf(log, "# nranks bytes algo chunk_bytes stages usec trip_bytes rank_waves stage_store\n");
+    if (log) fprintf(log, "# nranks bytes algo chunk_bytes stages usec trip_bytes rank_waves stage_store lanes spans\n");
     struct LogCloser {
         FILE *f;
         ~LogCloser() { if (f) fclose(f); }
@@ -407,18 +422,23 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         bcast_tune_entry_t best;
         memset(&best, 0, sizeof best);
         best.usec = best.chain_usec = 1e30;
-        auto consider = [&](int algo, size_t chunk, int stages, int trip = 0, int rank_waves = 0, int stage_store = BCAST_STORE_AUTO) {
+        auto consider = [&](int algo, size_t chunk, int stages, int trip = 0, int rank_waves = 0, int stage_store = BCAST_STORE_AUTO,
+                            int lanes = 0, int spans = BCAST_SPANS_AUTO) {
             if (rc != BCAST_OK || !(algo_mask & (1u << algo))) return;
             double us = 0.0;
-            rc = time_candidate(nranks, M, algo, chunk, stages, trip, rank_waves, stage_store, sc, stream, &us);
+            rc = time_candidate(nranks, M, algo, chunk, stages, trip, rank_waves, stage_store, lanes, spans, sc, stream, &us);
             if (rc != BCAST_OK) return;
-            if (log) fprintf(log, "%d %zu %d %zu %d %.3f %d %d %d\n", nranks, M, algo, chunk, stages, us, trip, rank_waves, stage_store);
+            if (log)
+                fprintf(log, "%d %zu %d %zu %d %.3f %d %d %d %d %d\n", nranks, M, algo, chunk, stages, us, trip, rank_waves, stage_store, lanes,
+                        spans);
             if (algo == BCAST_ALGO_CHAIN && us < best.chain_usec) {
                 best.chain_chunk_bytes = chunk;
                 best.chain_stages = stages;
                 best.chain_trip_bytes = trip;
                 best.chain_rank_waves = rank_waves;
                 best.chain_stage_store = stage_store;
+                best.chain_lanes = lanes;
+                best.chain_spans = spans;
                 best.chain_usec = us;
             }
             if (us < best.usec) {
@@ -428,6 +448,8 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
                 best.trip_bytes = algo == BCAST_ALGO_CHAIN ? trip : 0;
                 best.rank_waves = algo == BCAST_ALGO_CHAIN ? rank_waves : 0;
                 best.stage_store = algo == BCAST_ALGO_CHAIN ? stage_store : BCAST_STORE_AUTO;
+                best.lanes = algo == BCAST_ALGO_CHAIN ? lanes : 0;
+                best.spans = algo == BCAST_ALGO_CHAIN ? spans : BCAST_SPANS_AUTO;
                 best.usec = us;
             }
         };
@@ -477,6 +499,29 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
                         const size_t C = lanes * (size_t)trip;
                         if (lanes < 1 || C >= M || M / C > 4096) continue;
                         consider(BCAST_ALGO_CHAIN, C, stages, trip, 1);
+                    }
+                }
+            }
+        }
+        // Refinement around the best staged chain of a message that streams: the same
+        // lanes with several trips per lane and chunk (fewer flag hand-offs), and,
+        // where the stages are unequal, the extra hop kept in place or passed round.
+        if (M >= ((size_t)16 << 20) && best.chain_chunk_bytes != 0 && !best.chain_rank_waves && best.chain_trip_bytes != 0 &&
+            best.chain_chunk_bytes < M) {
+            const bcast_tune_entry_t base = best;
+            // the lanes that setting ran with: one per trip of its chunk, up to the power of two its stage count allows
+            u64 lanes_max = 1;
+            while (lanes_max * 2 * (u64)base.chain_stages <= 8192) lanes_max *= 2;
+            const int lanes = (int)std::min<u64>(lanes_max, base.chain_chunk_bytes / (u64)base.chain_trip_bytes);
+            if (lanes >= 1 && base.chain_chunk_bytes % ((u64)lanes * (u64)base.chain_trip_bytes) == 0) {
+                const bool unequal = hops % base.chain_stages != 0;
+                for (int spans : {BCAST_SPANS_AUTO, BCAST_SPANS_FIXED, BCAST_SPANS_ROTATE}) {
+                    if (spans != BCAST_SPANS_AUTO && !unequal) continue;
+                    for (int mult : {1, 2, 4, 8}) {
+                        if (mult == 1 && spans == BCAST_SPANS_AUTO) continue;  // that is `base` itself
+                        const size_t C = (size_t)base.chain_chunk_bytes * mult;
+                        if (C >= M) continue;
+                        consider(BCAST_ALGO_CHAIN, C, base.chain_stages, base.chain_trip_bytes, 0, base.chain_stage_store, lanes, spans);
                     }
                 }
             }

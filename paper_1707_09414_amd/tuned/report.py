@@ -31,9 +31,11 @@ def read(path):
             trip = int(cols[6]) if len(cols) > 6 else 0
             rank_waves = int(cols[7]) if len(cols) > 7 else 0
             store = int(cols[8]) if len(cols) > 8 else 0
+            lanes = int(cols[9]) if len(cols) > 9 else 0
+            spans = int(cols[10]) if len(cols) > 10 else 0
             cur = best[(n, M)].get(algo)
             if cur is None or us < cur[0]:
-                best[(n, M)][algo] = (us, C, stages, trip, rank_waves, store)
+                best[(n, M)][algo] = (us, C, stages, trip, rank_waves, store, lanes, spans)
     return best
 
 
@@ -51,7 +53,7 @@ def report(path, ranks=None):
     for n in sorted({k[0] for k in best}):
         if ranks and n not in ranks:
             continue
-        out.append("P = %d   (best time per algorithm in us; chain setting = chunk / stages / trip bytes / a wavefront per stage or per rank / stage stores written back)" % n)
+        out.append("P = %d   (best time per algorithm in us; chain setting = chunk / stages / trip bytes / a wavefront per stage or per rank [/ stage stores written back] [/ lanes] [/ unequal stages fixed or rotating])" % n)
         out.append("%9s " % "bytes" + " ".join("%17s" % NAMES[a] for a in algos) + "  %9s  %-17s %s" % ("chain GB/s", "winner", "chain setting"))
         for M in sorted(k[1] for k in best if k[0] == n):
             row = best[(n, M)]
@@ -59,7 +61,8 @@ def report(path, ranks=None):
             cells = " ".join("%17s" % ("%.2f" % row[a][0] if a in row else "-") for a in algos)
             c = row.get(1)
             gbs = "%9.1f" % (2.0 * (n - 1) * M / c[0] / 1e3) if c else "%9s" % "-"
-            setting = "%d / %d / %d / %s%s" % (c[1], c[2], c[3], "rank" if c[4] else "stage", " / back" if c[5] == 2 else "") if c else ""
+            setting = "%d / %d / %d / %s%s%s%s" % (c[1], c[2], c[3], "rank" if c[4] else "stage", " / back" if c[5] == 2 else "",
+                                                 " / %d lanes" % c[6] if c[6] else "", ("", " / fixed", " / rotating")[c[7]]) if c else ""
             out.append("%9s %s  %s  %-17s %s" % (size_name(M), cells, gbs, NAMES[win], setting))
         out.append("")
     return "\n".join(out)

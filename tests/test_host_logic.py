@@ -174,12 +174,22 @@ def test_tuning_table_lookup_rules(tmp_path):
         B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=4096, stage_store=3)
     with pytest.raises(B.BcastError):
         B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_DIRECT, stage_store=B.BCAST_STORE_BACK)
+    # ... and so are an explicit lane count and the handling of unequal stages, of the chain with a wavefront per stage
+    B.bcast_tune_put(16, 1 << 25, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=6 << 20, stages=2, trip_bytes=3072, usec=90.0,
+                     lanes=512, spans=B.BCAST_SPANS_ROTATE)
+    for bad in (dict(lanes=-1), dict(lanes=8193), dict(spans=3), dict(lanes=64, rank_waves=1), dict(spans=B.BCAST_SPANS_FIXED, rank_waves=1)):
+        with pytest.raises(B.BcastError):
+            B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=4096, **bad)
+    with pytest.raises(B.BcastError):
+        B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_BINOMIAL, lanes=64)
 
     path = tmp_path / "table.txt"
     B.bcast_tune_save(str(path))
     B.bcast_tune_clear()
     B.bcast_tune_load(str(path))
-    assert B.bcast_tune_count() == 5
+    assert B.bcast_tune_count() == 6
+    e = B.bcast_tune_get(16, 1 << 25)
+    assert (e["lanes"], e["chain_lanes"], e["spans"], e["chain_spans"]) == (512, 512, B.BCAST_SPANS_ROTATE, B.BCAST_SPANS_ROTATE)
     e = B.bcast_tune_get(16, 1 << 24)
     assert (e["trip_bytes"], e["chain_trip_bytes"], e["chain_chunk_bytes"], e["stages"]) == (3072, 3072, 3 << 20, 2)
     assert (e["stage_store"], e["chain_stage_store"]) == (B.BCAST_STORE_BACK, B.BCAST_STORE_BACK)
