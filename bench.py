@@ -295,8 +295,9 @@ class Placed:
 class Ranks:
     """P rank buffers of M bytes in HBM: the root's holds the message, the others 0xFF.
     With library=True they come from bcast_buffers_alloc, the first half of the
-    chain (positions 0 .. P/2-1, the root among them) in one region of the device's
-    memory and the second half in the next."""
+    chain (positions 0 .. P/2-1, the root among them) under one region label and the
+    second half under another: the library places the two in different regions of
+    the device's memory."""
 
     def __init__(self, B, torch, inputs, P, root, M, msg, library):
         self.P, self.root, self.M = P, root, M
@@ -307,7 +308,7 @@ class Ranks:
         self.mem = Placed(B, torch, [M] * P, regions, library)
         self.allocation = dict(self.mem.how)
         if library:
-            self.allocation["layout"] = "chain positions 0..%d in one memory region, %d..%d in the next" % (P // 2 - 1, P // 2, P - 1)
+            self.allocation["layout"] = "chain positions 0..%d under one region label, %d..%d under another" % (P // 2 - 1, P // 2, P - 1)
         self.bufs = self.mem.bufs
         for r in range(P):
             if r == root:
@@ -579,7 +580,7 @@ def reduce_row(B, torch, np, P, root, M, seed, stream, profiles, name, quick, no
     del send, recv
     mem.free()
     row = stats_us(ms)
-    row["allocation"] = dict(mem.how, layout="the contributions in one memory region, the result in the next") if library else dict(mem.how)
+    row["allocation"] = dict(mem.how, layout="the contributions under one region label, the result under another") if library else dict(mem.how)
     # the same P buffers only read, and read with the fold written out, by the library's dependency-free
     # measurement kernel: what this memory system gives the reduction's access pattern
     row["ceilings"] = {"load_only_median_us": load_ms["median_us"], "load_only_GBps": round(P * n / load_ms["median_us"] / 1e3, 1),

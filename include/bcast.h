@@ -254,27 +254,35 @@ int bcast_chain_geometry(int nranks, size_t bytes, size_t chunk_bytes, int max_w
  * (3) and the size of each (a third of the device's memory).
  *
  * bcast_buffers_alloc -- allocate n device buffers, buffer i of bytes[i] > 0
- * bytes in region region[i] (0, 1 or 2), counted from the region the device's
- * allocator is handing out at the time of the call: 0 = that one, 1 = the next.
+ * bytes with region label region[i] (0, 1 or 2): buffers with the same label
+ * are packed together (in slabs of a power-of-two size, 16 GiB at most, each
+ * from one region of the device's memory), buffers with different labels are
+ * placed in different regions.  Labels only tell groups apart; which physical
+ * region a label gets is the library's business.
  * bytes, region: HOST arrays of n; ptrs: HOST array of n, receives the DEVICE
- * pointers (hipMalloc'ed, 256-byte aligned or better; free them with
- * bcast_buffers_free or hipFree).  The contents are undefined (the library may
- * have written to them).  *placed (HOST, nullable) receives
- *   BCAST_PLACED_NO        the buffers are allocated, but not where asked: the
- *                          regions cannot be reached from where the allocator
- *                          stands, a group does not fit its region, there is no
- *                          room for the temporary fillers, or a measurement
- *                          showed the placement did not take;
- *   BCAST_PLACED_BY_ORDER  placed by allocation order (fillers push the
- *                          allocator across region boundaries), too small a set
- *                          to confirm by measurement;
- *   BCAST_PLACED_MEASURED  placed, and writing to neighbouring regions' buffers
- *                          together was measured clearly faster than to one
- *                          region's alone.
- * The call waits for the device while it measures, and temporarily allocates up
- * to a region's worth of memory.  It works best early in a process, before the
- * device's memory is fragmented.  On failure nothing stays allocated.
+ * pointers (2 MiB aligned).  They point INTO the slabs: give them back with
+ * bcast_buffers_free, never with hipFree; a slab is freed when the last of its
+ * buffers is.  The contents are undefined (the library has written to them).
+ * Memory: a group occupies the next power of two of its size (2 GiB at least).
+ * *placed (HOST, nullable) receives
+ *   BCAST_PLACED_NO        the buffers are allocated, but a slab could not be
+ *                          got apart from those of other labels (ten allocations
+ *                          tried, or memory ran out): it was taken where it fell;
+ *   BCAST_PLACED_BY_ORDER  nothing to tell apart (one label only);
+ *   BCAST_PLACED_MEASURED  every slab was measured to lie apart from the slabs
+ *                          of other labels: writing to both at once ran at the
+ *                          rate of a write set spread over regions.
+ * How: the order in which the driver hands memory out depends on all that was
+ * allocated and freed before, so nothing is assumed about addresses.  A
+ * candidate slab is written together with the slabs already placed under other
+ * labels (a few ms each); one that lies in the same region as any of them is
+ * kept aside, so that the next candidate is other memory, and freed at the end.
+ * The call therefore waits for the device and temporarily allocates up to a
+ * few times 16 GiB more.  On failure nothing stays allocated.
  * Errors: ERR_ARG, ERR_NOMEM, ERR_HIP.
+ * bcast_buffers_free -- give back buffers from bcast_buffers_alloc (any subset,
+ * any order; NULL entries are skipped).  ERR_ARG for a pointer that is not one
+ * of them (the others are still freed).
  */
 #define BCAST_PLACED_NO 0
 #define BCAST_PLACED_BY_ORDER 1

@@ -14,19 +14,22 @@
 // regions, a reduction its contributions in one region and its result in
 // another -- a choice only the allocating side can make.
 //
-// HIP has no call that allocates at a physical address.  What it does have is
-// an allocator that, while the device's memory is not fragmented, hands memory
-// out in address order from one end; hipMemGetInfo tells how far it has come.
-// bcast_buffers_alloc uses that: it allocates the buffers region by region and,
-// between two regions, a temporary filler that pushes the allocator past the
-// boundary (plus a margin for what the accounting does not show); the fillers
-// are freed before it returns.  The placement is then confirmed by measurement:
-// writing to memory on both sides of a boundary together must be clearly faster
-// than writing to one side alone -- measured on the fillers next to the groups
-// and, where they are large enough (their writes must exceed the memory-side
-// cache by far), on the groups themselves.
+// HIP has no call that allocates at a physical address, and the order in which
+// the driver hands memory out depends on everything allocated and freed before,
+// by this process and by earlier ones.  Two things hold regardless (measured in
+// first and in later processes on a device): an allocation of a power-of-two
+// size up to 16 GiB comes out of one region, and whether two allocations lie in
+// the same region shows plainly when both are written at once (5.7-6.3 TB/s
+// against 6.9-7.2).  bcast_buffers_alloc builds on just these: buffers that
+// share a region label are packed into slabs of a power-of-two size; a slab
+// whose label differs from that of slabs placed before is accepted only if
+// writing to it together with each of them runs at the spread rate; a candidate
+// that fails is kept aside, so that the next one is other memory, and freed at
+// the end.  Nothing is assumed about addresses, and the verdict is a measurement.
 #include <algorithm>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <vector>
 
 #include "bcast_internal.h"
@@ -36,18 +39,31 @@ using namespace bcast;
 namespace {
 
 constexpr int kRegionCount = 3;
+constexpr size_t kMiB = (size_t)1 << 20;
 constexpr size_t kGiB = (size_t)1 << 30;
-constexpr size_t kAllocUnit = (size_t)2 << 20;     // allocations are accounted in 2 MiB units
-constexpr size_t kBoundaryMargin = 10 * kGiB;      // how far past a boundary the next group starts
-constexpr size_t kFillerPiece = kGiB;              // fillers are allocated in pieces of this size
-constexpr size_t kProbePieces = 8;                 // filler pieces on either side of a boundary that a probe writes to
-constexpr size_t kProbeMinBytes = 2 * kGiB;        // a probe must write more than the memory-side cache holds (256 MiB), by a wide margin
-constexpr size_t kProbeWindowMax = (size_t)256 << 20;
-static_assert(kProbeWindowMax <= kFillerPiece, "a probe writes at most one filler piece's size into a piece");
-constexpr double kProbeGain = 1.08;                // both sides of a boundary together vs the slower side alone: measured 1.18-1.20
-constexpr double kSpreadRateGBps = 6500.0;         // store-only rate: 5800-6000 GB/s into one region, 6900-7200 over two (measured)
+constexpr size_t kBufferAlign = 2 * kMiB;          // buffers start on 2 MiB boundaries inside a slab
+constexpr size_t kSlabMax = 16 * kGiB;             // the largest power-of-two allocation seen to lie in one region every time
+constexpr size_t kSlabMin = 2 * kGiB;              // the smallest slab a probe can judge: the 256 MiB memory-side cache takes that much of
+                                                   // every pass off the memory, which must stay a few percent of what a probe writes
+constexpr size_t kProbeWindows = 8;                // windows of a slab that a probe writes to, spread evenly over it
+constexpr size_t kProbeWindowMax = 256 * kMiB;
+constexpr size_t kProbeMinBytes = 4 * kGiB;        // least bytes a probe of two slabs writes
+constexpr size_t kAttempts = 10;                   // allocations tried for one slab, at least, before it is taken as it comes
+constexpr size_t kWalkBytes = 112 * kGiB;          // ... and as many as walk past a region (96 GiB) and a margin
+constexpr size_t kWalkAllocsMax = 64;              // ... but never more than this
+constexpr size_t kProbeEvery = 8 * kGiB;           // small candidates are probed once per this many bytes walked
+constexpr int kProbedAgainst = 4;                  // slabs of other labels a candidate is probed against, at most
+constexpr double kProbeGain = 1.08;                // two slabs together vs the slower one alone: measured 1.15-1.20 across regions
+constexpr double kSpreadRateGBps = 6500.0;         // store-only rate: 5700-6300 GB/s into one region, 6900-7200 over two (measured)
 
-size_t round_up_unit(size_t n) { return (n + kAllocUnit - 1) / kAllocUnit * kAllocUnit; }
+size_t round_up(size_t n, size_t to) { return (n + to - 1) / to * to; }
+
+size_t pow2_ceil(size_t n)
+{
+    size_t p = 1;
+    while (p < n) p <<= 1;
+    return p;
+}
 
 int hip_status(hipError_t e)
 {
@@ -55,11 +71,41 @@ int hip_status(hipError_t e)
     return e == hipErrorOutOfMemory ? BCAST_ERR_NOMEM : BCAST_ERR_HIP;
 }
 
-// A device allocation as the probes see it: they never write beyond `bytes`.
+// One allocation that carries the buffers of one region label.
+struct Slab {
+    char *base = nullptr;
+    size_t bytes = 0;           // allocated size
+    int label = 0;
+    std::vector<int> members;   // indices of the caller's buffers
+    std::vector<size_t> offset; // of each member inside the slab
+};
+
+// Slabs handed out, so that bcast_buffers_free can return them: buffer address
+// -> slab base, slab base -> buffers still alive.
+std::mutex g_mu;
+std::map<void *, void *> g_slab_of;
+std::map<void *, int> g_live;
+
+// A part of a device allocation as the probes see it: they never write beyond `bytes`.
 struct Span {
     void *ptr;
     size_t bytes;
 };
+
+// kProbeWindows windows spread evenly over a slab; every window lies inside it.
+std::vector<Span> windows_of(const Slab &s)
+{
+    std::vector<Span> out;
+    const size_t step = s.bytes / kProbeWindows / (size_t)kTileBytes * (size_t)kTileBytes;
+    const size_t window = std::min(kProbeWindowMax, step);
+    if (window == 0 || !s.base) return out;
+    for (size_t k = 0; k < kProbeWindows; ++k) {
+        const size_t at = k * step;
+        if (at + window > s.bytes) break;  // cannot happen (kProbeWindows * step <= bytes): the bound is checked all the same
+        out.push_back(Span{s.base + at, window});
+    }
+    return out;
+}
 
 // Milliseconds for one pass of the store-only pattern over the first `window`
 // bytes of each span.  Refuses a window that any span does not hold.
@@ -87,21 +133,22 @@ int time_store_pattern(const std::vector<Span> &spans, size_t window, hipEvent_t
     return BCAST_OK;
 }
 
-// Whether writing to spans of a and b together runs at the rate of a write set
+// Whether writing to slabs a and b together runs at the rate of a write set
 // spread over regions: clearly faster, byte for byte, than writing to the slower
-// of the two alone, or at the spread rate outright.  *told is false if the sets are
-// too small to tell (the writes must exceed the memory-side cache by far).
-int probe_spread(const std::vector<Span> &in_a, const std::vector<Span> &in_b, bool *told, bool *spread)
+// of the two alone, or at the spread rate outright.  *told is false if they are
+// too small to tell.
+int probe_spread(const Slab &sa, const Slab &sb, bool *told, bool *spread)
 {
     *told = *spread = false;
-    const size_t each = std::min<size_t>({in_a.size(), in_b.size(), (size_t)BCAST_MAX_RANKS / 2});
-    if (each == 0) return BCAST_OK;
-    std::vector<Span> a(in_a.begin(), in_a.begin() + each), b(in_b.begin(), in_b.begin() + each), both(a);
-    both.insert(both.end(), b.begin(), b.end());
+    std::vector<Span> a = windows_of(sa), b = windows_of(sb), both;
+    if (a.size() != kProbeWindows || b.size() != kProbeWindows) return BCAST_OK;
     size_t window = kProbeWindowMax;
-    for (const Span &s : both) window = std::min(window, s.bytes);  // no span is written beyond its size
+    for (const Span &s : a) window = std::min(window, s.bytes);
+    for (const Span &s : b) window = std::min(window, s.bytes);  // no span is written beyond its size
     window = window / (size_t)kTileBytes * (size_t)kTileBytes;
-    if (window == 0 || 2 * each * window < kProbeMinBytes) return BCAST_OK;
+    if (window == 0 || 2 * kProbeWindows * window < kProbeMinBytes) return BCAST_OK;
+    both = a;
+    both.insert(both.end(), b.begin(), b.end());
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
         if (e0) (void)hipEventDestroy(e0);
@@ -115,12 +162,9 @@ int probe_spread(const std::vector<Span> &in_a, const std::vector<Span> &in_b, b
     (void)hipEventDestroy(e1);
     if (rc != BCAST_OK) return rc;
     *told = true;
-    // `both` writes twice the bytes of either alone.  Spread: clearly faster than
-    // the slower of the two alone -- or as fast as only writes over more than one
-    // region are (where earlier allocations and frees have scattered a group over
-    // the regions already, it is no slower alone than together with the other)
+    // `both` writes twice the bytes of either alone
     const double gain = 2.0 * std::max(t_a, t_b) / t_both;
-    const double rate_gbps = 2.0 * (double)each * (double)window / (t_both * 1e-3) / 1e9;
+    const double rate_gbps = 2.0 * (double)kProbeWindows * (double)window / (t_both * 1e-3) / 1e9;
     *spread = gain >= kProbeGain || rate_gbps >= kSpreadRateGBps;
     return BCAST_OK;
 }
@@ -142,136 +186,149 @@ extern "C" int bcast_buffers_free(int n, void *const *ptrs)
 {
     if (n < 0 || (n > 0 && !ptrs)) return BCAST_ERR_ARG;
     int rc = BCAST_OK;
-    for (int i = 0; i < n; ++i)
-        if (ptrs[i]) {
-            hipError_t e = hipFree(ptrs[i]);
+    std::lock_guard<std::mutex> g(g_mu);
+    for (int i = 0; i < n; ++i) {
+        if (!ptrs[i]) continue;
+        auto it = g_slab_of.find(ptrs[i]);
+        if (it == g_slab_of.end()) {
+            rc = BCAST_ERR_ARG;  // not a buffer this library handed out (or freed already)
+            continue;
+        }
+        void *base = it->second;
+        g_slab_of.erase(it);
+        auto live = g_live.find(base);
+        if (live != g_live.end() && --live->second == 0) {
+            g_live.erase(live);
+            hipError_t e = hipFree(base);
             if (e != hipSuccess) rc = hip_status(e);
         }
+    }
     return rc;
 }
 
 extern "C" int bcast_buffers_alloc(int n, const size_t *bytes, const int *region, void **ptrs, int *placed)
 {
     if (n < 1 || n > (1 << 16) || !bytes || !region || !ptrs) return BCAST_ERR_ARG;
-    int top = 0;
     for (int i = 0; i < n; ++i) {
         if (bytes[i] == 0 || region[i] < 0 || region[i] >= kRegionCount) return BCAST_ERR_ARG;
-        top = std::max(top, region[i]);
         ptrs[i] = nullptr;
     }
     if (placed) *placed = BCAST_PLACED_NO;
 
-    size_t free_bytes = 0, total = 0;
-    hipError_t e = hipMemGetInfo(&free_bytes, &total);
-    if (e != hipSuccess) return hip_status(e);
-    const size_t third = total / kRegionCount;
-    const size_t used_now = total - free_bytes;
-    const size_t here = used_now / third;  // the third the allocator is handing out now
-
-    // Region 0 of the request is that third if its group still fits there (clear
-    // of the next boundary), else the next one.  Can every region asked for be
-    // reached from there, fillers and margins included?
-    size_t group_bytes[kRegionCount] = {0, 0, 0};
-    for (int i = 0; i < n; ++i) group_bytes[region[i]] += round_up_unit(bytes[i]);
-    const bool fits_here = used_now - here * third + group_bytes[0] + kBoundaryMargin / 2 <= third;
-    const size_t first = fits_here ? here : here + 1;
-    bool arrange = first + (size_t)top < (size_t)kRegionCount;
-    for (int r = 0; r <= top && arrange; ++r)
-        if (group_bytes[r] + 2 * kBoundaryMargin > third) arrange = false;  // a group must fit inside its third
-    if (arrange && (first != here || top > 0)) {
-        const size_t end = (first + (size_t)top) * third + kBoundaryMargin + group_bytes[top];
-        if (end + kGiB > total) arrange = false;
+    // Pack the buffers of each label, in the caller's order, into slabs of at most
+    // kSlabMax bytes (a buffer larger than that gets a slab of its own); a slab is
+    // allocated at the next power of two, kSlabMin at least.
+    std::vector<Slab> slabs;
+    int labels_used = 0;
+    for (int label = 0; label < kRegionCount; ++label) {
+        Slab cur;
+        size_t fill = 0;
+        const size_t before = slabs.size();
+        auto close = [&]() {
+            if (cur.members.empty()) return;
+            cur.label = label;
+            cur.bytes = std::max(kSlabMin, fill <= kSlabMax ? pow2_ceil(fill) : fill);
+            slabs.push_back(cur);
+            cur = Slab();
+            fill = 0;
+        };
+        for (int i = 0; i < n; ++i) {
+            if (region[i] != label) continue;
+            const size_t need = round_up(bytes[i], kBufferAlign);
+            if (!cur.members.empty() && fill + need > kSlabMax) close();
+            cur.members.push_back(i);
+            cur.offset.push_back(fill);
+            fill += need;
+        }
+        close();
+        if (slabs.size() > before) ++labels_used;
     }
 
-    std::vector<void *> fillers;
-    auto release = [&](bool buffers_too) {
-        for (void *f : fillers) (void)hipFree(f);
-        fillers.clear();
-        if (buffers_too)
-            for (int i = 0; i < n; ++i)
-                if (ptrs[i]) {
-                    (void)hipFree(ptrs[i]);
-                    ptrs[i] = nullptr;
+    std::vector<char *> aside;  // candidates that lay in the wrong region, and jumps past them
+    auto release = [&](bool slabs_too) {
+        for (char *p : aside) (void)hipFree(p);
+        aside.clear();
+        if (slabs_too)
+            for (Slab &s : slabs)
+                if (s.base) {
+                    (void)hipFree(s.base);
+                    s.base = nullptr;
                 }
     };
 
-    bool arranged = arrange;
-    bool any_told = false, any_flat = false;
-    for (int r = 0; r <= top; ++r) {
-        if (arranged && (r > 0 || first != here)) {
-            // push the allocator to kBoundaryMargin past the start of third first + r,
-            // in pieces of 1 GiB: equal, moderate allocations are what the allocator
-            // hands out in order (one huge block it may take from anywhere)
-            e = hipMemGetInfo(&free_bytes, &total);
+    bool any_told = false, any_failed = false;
+    for (size_t k = 0; k < slabs.size(); ++k) {
+        Slab &s = slabs[k];
+        // the slabs placed so far whose label differs: this one must lie apart from each (the first few are checked)
+        std::vector<const Slab *> others;
+        for (size_t j = 0; j < k && (int)others.size() < kProbedAgainst; ++j)
+            if (slabs[j].label != s.label) others.push_back(&slabs[j]);
+        // Candidates are allocations of the slab's own size, taken one after the other
+        // and kept aside while they fail: equal allocations are what the driver hands
+        // out in order where it has an order, so the walk crosses into another region
+        // after at most a region's worth of them; where it has none, the first or
+        // second candidate already lies apart.  Small candidates are probed only every
+        // kProbeEvery bytes of the walk.
+        const size_t stride = std::max<size_t>(1, kProbeEvery / s.bytes);
+        const size_t max_allocs = std::min<size_t>(kWalkAllocsMax, std::max<size_t>(kAttempts, kWalkBytes / s.bytes));
+        for (size_t alloc = 0;; ++alloc) {
+            void *p = nullptr;
+            hipError_t e = hipMalloc(&p, s.bytes);
             if (e != hipSuccess) {
-                release(true);
-                return hip_status(e);
-            }
-            size_t used = total - free_bytes;
-            const size_t target = (first + (size_t)r) * third + kBoundaryMargin;
-            const size_t run_begin = fillers.size();
-            while (arranged && used < target) {
-                // every piece has the full size (the last one overshoots the target by less
-                // than a piece): the probe below writes kProbeWindowMax bytes into pieces
-                void *filler = nullptr;
-                e = hipMalloc(&filler, kFillerPiece);
-                if (e == hipSuccess) {
-                    fillers.push_back(filler);
-                    used += kFillerPiece;
-                } else {
+                // out of memory with candidates kept aside: give those back and take the next allocation as it comes
+                const bool had_aside = !aside.empty();
+                (void)hipGetLastError();
+                release(false);
+                if (!had_aside || hipMalloc(&p, s.bytes) != hipSuccess) {
                     (void)hipGetLastError();
-                    arranged = false;  // no room for the fillers: the rest is allocated where it falls
-                }
-            }
-            // The pieces right after the group before and the pieces just allocated lie
-            // on either side of the boundary if the allocator works as assumed: measure it
-            // (whole pieces of 1 GiB each, so any set, however small, gets its placement checked).
-            const size_t run = fillers.size() - run_begin;
-            if (arranged && run >= 2 * kProbePieces + kBoundaryMargin / kFillerPiece) {
-                std::vector<Span> before, after;
-                for (size_t k = 0; k < kProbePieces; ++k) {
-                    before.push_back(Span{fillers[run_begin + k], kFillerPiece});
-                    after.push_back(Span{fillers[fillers.size() - kProbePieces + k], kFillerPiece});
-                }
-                bool told = false, spread = false;
-                int rc = probe_spread(before, after, &told, &spread);
-                if (rc != BCAST_OK) {
                     release(true);
-                    return rc;
+                    return e == hipErrorOutOfMemory ? BCAST_ERR_NOMEM : BCAST_ERR_HIP;
                 }
-                any_told = any_told || told;
-                any_flat = any_flat || (told && !spread);
+                s.base = (char *)p;
+                if (!others.empty()) any_failed = true;
+                break;
             }
-        }
-        for (int i = 0; i < n; ++i) {
-            if (region[i] != r) continue;
-            e = hipMalloc(&ptrs[i], bytes[i]);
-            if (e != hipSuccess) {
-                release(true);
-                return hip_status(e);
+            s.base = (char *)p;
+            if (others.empty()) break;
+            const bool last = alloc + 1 >= max_allocs;
+            bool apart = false;
+            if (alloc % stride == 0 || last) {
+                apart = true;
+                for (const Slab *o : others) {
+                    bool told = false, spread = false;
+                    int rc = probe_spread(s, *o, &told, &spread);
+                    if (rc != BCAST_OK) {
+                        release(true);
+                        return rc;
+                    }
+                    any_told = any_told || told;
+                    if (told && !spread) {
+                        apart = false;
+                        break;
+                    }
+                }
             }
+            if (apart) break;
+            if (last) {
+                any_failed = true;  // taken where it fell
+                break;
+            }
+            aside.push_back(s.base);  // the wrong region (or not looked at): kept, so that the next allocation is other memory
+            s.base = nullptr;
         }
     }
     release(false);
-    if (!arranged) return BCAST_OK;
 
-    // and the groups themselves, wherever two neighbouring ones are large enough to tell
-    for (int r = 0; r + 1 <= top && !any_flat; ++r) {
-        std::vector<Span> a, b;
-        for (int i = 0; i < n; ++i) {
-            if (region[i] != r && region[i] != r + 1) continue;
-            (region[i] == r ? a : b).push_back(Span{ptrs[i], bytes[i]});
+    {
+        std::lock_guard<std::mutex> g(g_mu);
+        for (const Slab &s : slabs) {
+            g_live[s.base] = (int)s.members.size();
+            for (size_t m = 0; m < s.members.size(); ++m) {
+                ptrs[s.members[m]] = s.base + s.offset[m];
+                g_slab_of[ptrs[s.members[m]]] = s.base;
+            }
         }
-        if (a.empty() || b.empty()) continue;
-        bool told = false, spread = false;
-        int rc = probe_spread(a, b, &told, &spread);
-        if (rc != BCAST_OK) {
-            release(true);
-            return rc;
-        }
-        any_told = any_told || told;
-        any_flat = any_flat || (told && !spread);
     }
-    if (placed) *placed = any_flat ? BCAST_PLACED_NO : any_told ? BCAST_PLACED_MEASURED : BCAST_PLACED_BY_ORDER;
+    if (placed) *placed = any_failed ? BCAST_PLACED_NO : (labels_used > 1 && any_told) ? BCAST_PLACED_MEASURED : BCAST_PLACED_BY_ORDER;
     return BCAST_OK;
 }

@@ -316,8 +316,7 @@ struct Scratch {
     hipEvent_t e0 = nullptr, e1 = nullptr;
     ~Scratch()
     {
-        for (void *b : bufs)
-            if (b) (void)hipFree(b);
+        if (!bufs.empty()) (void)bcast_buffers_free((int)bufs.size(), bufs.data());  // they come from bcast_buffers_alloc
         if (e0) (void)hipEventDestroy(e0);
         if (e1) (void)hipEventDestroy(e1);
     }
