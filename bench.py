@@ -257,7 +257,7 @@ def reps_for(M, quick):
     return 200 if M < MiB else 20
 
 
-PLACED_NAMES = {0: "not placed", 1: "placed by allocation order", 2: "placed, confirmed by measurement"}
+PLACED_NAMES = {0: "a slab was taken where it fell", 1: "one label only: nothing to tell apart", 2: "placed, confirmed by measurement"}
 PLACE_MIN_BYTES = 8 * MiB  # smaller rank buffers are allocated plainly: their broadcasts are bound by latency, not by memory
 
 
