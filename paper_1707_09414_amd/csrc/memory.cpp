@@ -54,6 +54,7 @@ constexpr size_t kWalkAllocsMax = 64;              // ... but never more than th
 constexpr size_t kProbeEvery = 8 * kGiB;           // small candidates are probed once per this many bytes walked
 constexpr int kProbedAgainst = 4;                  // slabs of other labels a candidate is probed against, at most
 constexpr double kProbeGain = 1.08;                // two slabs together vs the slower one alone: measured 1.15-1.20 across regions
+constexpr size_t kMemorySideCache = 256 * kMiB;
 constexpr double kSpreadRateGBps = 6500.0;         // store-only rate: 5700-6300 GB/s into one region, 6900-7200 over two (measured)
 
 size_t round_up(size_t n, size_t to) { return (n + to - 1) / to * to; }
@@ -92,16 +93,17 @@ struct Span {
     size_t bytes;
 };
 
-// kProbeWindows windows spread evenly over a slab; every window lies inside it.
-std::vector<Span> windows_of(const Slab &s)
+// `count` windows spread evenly over a slab; every window lies inside it.
+std::vector<Span> windows_of(const Slab &s, size_t count = kProbeWindows)
 {
     std::vector<Span> out;
-    const size_t step = s.bytes / kProbeWindows / (size_t)kTileBytes * (size_t)kTileBytes;
+    if (count == 0 || !s.base) return out;
+    const size_t step = s.bytes / count / (size_t)kTileBytes * (size_t)kTileBytes;
     const size_t window = std::min(kProbeWindowMax, step);
-    if (window == 0 || !s.base) return out;
-    for (size_t k = 0; k < kProbeWindows; ++k) {
+    if (window == 0) return out;
+    for (size_t k = 0; k < count; ++k) {
         const size_t at = k * step;
-        if (at + window > s.bytes) break;  // cannot happen (kProbeWindows * step <= bytes): the bound is checked all the same
+        if (at + window > s.bytes) break;  // cannot happen (count * step <= bytes): the bound is checked all the same
         out.push_back(Span{s.base + at, window});
     }
     return out;
@@ -131,6 +133,17 @@ int time_store_pattern(const std::vector<Span> &spans, size_t window, hipEvent_t
     }
     *ms = best;
     return BCAST_OK;
+}
+
+// The rate from which a pass that writes `written` bytes counts as spread over
+// regions: the memory-side cache keeps the last 256 MiB of every pass off the
+// memory, which makes a short pass look faster than the memory is.
+double spread_rate_for(size_t written)
+{
+    // kSpreadRateGBps is what separates the two cases in passes of kProbeMinBytes (4 GiB)
+    const double kept_there = (double)kMemorySideCache / (double)kProbeMinBytes;
+    const double kept = std::min(0.5, (double)kMemorySideCache / (double)written);
+    return kSpreadRateGBps * (1.0 - kept_there) / (1.0 - kept);
 }
 
 // Whether writing to slabs a and b together runs at the rate of a write set
@@ -164,8 +177,38 @@ int probe_spread(const Slab &sa, const Slab &sb, bool *told, bool *spread)
     *told = true;
     // `both` writes twice the bytes of either alone
     const double gain = 2.0 * std::max(t_a, t_b) / t_both;
-    const double rate_gbps = 2.0 * (double)kProbeWindows * (double)window / (t_both * 1e-3) / 1e9;
-    *spread = gain >= kProbeGain || rate_gbps >= kSpreadRateGBps;
+    const size_t written = 2 * kProbeWindows * window;
+    const double rate_gbps = (double)written / (t_both * 1e-3) / 1e9;
+    *spread = gain >= kProbeGain || rate_gbps >= spread_rate_for(written);
+    return BCAST_OK;
+}
+
+// Whether a slab lies in one region: written alone, it stays below the rate of a
+// write set spread over regions.  (A power-of-two allocation mostly does; where
+// much has been allocated and freed before, the driver may piece one together
+// from several regions.)
+int probe_one_region(const Slab &s, bool *told, bool *one_region)
+{
+    *told = *one_region = false;
+    // as many bytes as a probe of two slabs writes, where the slab has them
+    const size_t count = s.bytes >= 2 * kProbeWindows * kProbeWindowMax ? 2 * kProbeWindows : kProbeWindows;
+    std::vector<Span> w = windows_of(s, count);
+    if (w.size() != count) return BCAST_OK;
+    const size_t window = w[0].bytes / (size_t)kTileBytes * (size_t)kTileBytes;
+    const size_t written = count * window;
+    if (window == 0 || written < kProbeMinBytes / 2) return BCAST_OK;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        return BCAST_ERR_HIP;
+    }
+    float t = 0.f;
+    int rc = time_store_pattern(w, window, e0, e1, &t);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != BCAST_OK) return rc;
+    *told = true;
+    *one_region = (double)written / (t * 1e-3) / 1e9 < spread_rate_for(written);
     return BCAST_OK;
 }
 
@@ -289,12 +332,21 @@ extern "C" int bcast_buffers_alloc(int n, const size_t *bytes, const int *region
                 break;
             }
             s.base = (char *)p;
-            if (others.empty()) break;
+            if (labels_used < 2) break;  // one label only: nothing to place
             const bool last = alloc + 1 >= max_allocs;
             bool apart = false;
             if (alloc % stride == 0 || last) {
-                apart = true;
+                // in one region itself, and apart from the slabs of other labels
+                bool told = false, one_region = false;
+                int rc1 = probe_one_region(s, &told, &one_region);
+                if (rc1 != BCAST_OK) {
+                    release(true);
+                    return rc1;
+                }
+                any_told = any_told || told;
+                apart = !told || one_region;
                 for (const Slab *o : others) {
+                    if (!apart) break;
                     bool told = false, spread = false;
                     int rc = probe_spread(s, *o, &told, &spread);
                     if (rc != BCAST_OK) {
