@@ -208,7 +208,10 @@ def geometry_of(B, info):
 
 def kernel_name(info, B):
     if info["algo"] == B.BCAST_ALGO_CHAIN:
-        return ("bcast::rank_chain_kernel<%d, %d>" if info["rank_waves"] else "bcast::chain_kernel<%d, %d>") % (info["vec_bytes"], info["trip_bytes"] // 1024)
+        if info["rank_waves"]:
+            return "bcast::rank_chain_kernel<%d, %d>" % (info["vec_bytes"], info["trip_bytes"] // 1024)
+        # third parameter: in-stage stores written through (0) or back (1); bench.py sets no cache policies of its own
+        return "bcast::chain_kernel<%d, %d, %d>" % (info["vec_bytes"], info["trip_bytes"] // 1024, int(info["stage_store"] == B.BCAST_STORE_BACK))
     return {B.BCAST_ALGO_DIRECT: "bcast::pair_copy_kernel<%d>", B.BCAST_ALGO_BINOMIAL: "bcast::pair_copy_kernel<%d>",
             B.BCAST_ALGO_FANOUT: "bcast::fanout_kernel<%d>", B.BCAST_ALGO_KNOMIAL_PIPELINED: "bcast::tree_kernel<%d>",
             B.BCAST_ALGO_KNOMIAL: "bcast::ranged_copy_kernel<%d>", B.BCAST_ALGO_SCATTER_ALLGATHER: "bcast::ranged_copy_kernel<%d>"}[info["algo"]] % info["vec_bytes"]

@@ -295,6 +295,70 @@ __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const Chai
     return true;
 }
 
+// The chain kernel's sets of cache policies (see chain_kernel).
+constexpr int kPolicyThrough = 0;
+constexpr int kPolicyBack = 1;
+constexpr int kPolicyArgs = 2;
+
+// One trip of whole vectors, U loads then U stores per lane, through two buffer
+// descriptors that end with the trip: a lane beyond the end is range-checked by
+// the hardware (its load returns zero, its store is dropped).
+template <int V, int U, int LD, int ST>
+__device__ __forceinline__ void move_trip(__amdgpu_buffer_rsrc_t rs, __amdgpu_buffer_rsrc_t rd, unsigned off)
+{
+    typedef AgentIO<V, LD, ST> IO;
+    typename IO::T r[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) r[u] = IO::ld(rs, off + u * kWaveSize * V);
+#pragma unroll
+    for (int u = 0; u < U; ++u) IO::st(r[u], rd, off + u * kWaveSize * V);
+}
+
+// Wait for every store of the wave to complete.  `next` (the next position's
+// descriptor) is named as an input only so that the compiler has it in registers BEFORE the
+// wait: what the wave needs for its next hop is then computed while its stores
+// drain, and the loads go out the moment the wait returns.
+__device__ __forceinline__ void stores_done_then(__amdgpu_buffer_rsrc_t next)
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::"s"(next) : "memory");
+}
+
+// A trip of n bytes at offset lo (whole vectors from a vector-aligned address,
+// n <= one trip) carried through positions first_hop .. last_hop of a stage with
+// the policies the host chooses by itself.  What the loop over the hops does
+// between the completion of a hop's stores and the issue of the next hop's loads
+// is time in which the wave has nothing in flight, and the hops of a stage follow
+// each other every 0.5-0.8 us: so the hops are told apart outside the loop (first:
+// agent-scope load; last: agent-scope store unless the chain ends here), the
+// next position's address is fetched ahead of the wait, and the loop body is the
+// wait, one descriptor, U loads and U stores.
+template <int V, int U, int POLICY>
+__device__ __forceinline__ void carry_trip(const ChainArgs &a, u64 lo, unsigned n, unsigned first_hop, unsigned last_hop,
+                                           bool chain_ends, unsigned lane)
+{
+    constexpr int ST_MID = POLICY == kPolicyBack ? kAuxCached : kAuxAgent;
+    const unsigned off = lane * V;
+    __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(a.buf[first_hop - 1] + lo, 0, n, kRsrcWord3);
+    __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(a.buf[first_hop] + lo, 0, n, kRsrcWord3);
+    if (first_hop == last_hop) {
+        if (chain_ends) move_trip<V, U, kAuxAgent, ST_MID>(rs, rd, off);
+        else move_trip<V, U, kAuxAgent, kAuxAgent>(rs, rd, off);
+        return;
+    }
+    move_trip<V, U, kAuxAgent, ST_MID>(rs, rd, off);
+    for (unsigned hop = first_hop + 1; hop < last_hop; ++hop) {
+        rs = rd;
+        rd = __builtin_amdgcn_make_buffer_rsrc(a.buf[hop] + lo, 0, n, kRsrcWord3);
+        stores_done_then(rd);
+        move_trip<V, U, kAuxCached, ST_MID>(rs, rd, off);
+    }
+    rs = rd;
+    rd = __builtin_amdgcn_make_buffer_rsrc(a.buf[last_hop] + lo, 0, n, kRsrcWord3);
+    stores_done_then(rd);
+    if (chain_ends) move_trip<V, U, kAuxCached, ST_MID>(rs, rd, off);
+    else move_trip<V, U, kAuxCached, kAuxAgent>(rs, rd, off);
+}
+
 // Cache policy inside a stage.  A buffer that a wave stores as position h and
 // reads back for position h+1 is touched by no other wave during the kernel, and
 // a wave always sees its own earlier stores once s_waitcnt has passed, whatever
@@ -313,7 +377,14 @@ __device__ __forceinline__ bool wait_ready(const u64 *flag, u64 want, const Chai
 //            the L2 round trip is about half the memory one, which is what a
 //            small broadcast over many hops consists of).
 // Buffers handed from stage to stage are always stored at agent scope.
-template <int V, int U>
+// POLICY: the two sets of policies the host chooses by itself are built in
+// (kPolicyThrough, kPolicyBack: root and edge loads at agent scope, read-back
+// cached, in-stage stores write-through / write-back), any other set is read from
+// the arguments at every hop (kPolicyArgs).  The selection sits in the hop loop,
+// whose length is what a short broadcast consists of: measured at 8 ranks x 64
+// MiB, 114 us with the policies built in against 122 us when read from the
+// arguments.
+template <int V, int U, int POLICY>
 __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 {
     const unsigned lane = threadIdx.x & (kWaveSize - 1);
@@ -381,6 +452,13 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
         // few enough waves per CU it is still in that CU's vector L1.
         for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
             const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
+            if constexpr (POLICY != kPolicyArgs) {
+                // whole vectors from an aligned address (all buffers are congruent modulo V): the short way
+                if ((((uintptr_t)(a.buf[0] + lo) | (uintptr_t)(hi - lo)) & (V - 1)) == 0) {
+                    carry_trip<V, U, POLICY>(a, lo, (unsigned)(hi - lo), first_hop, last_hop, g + 1 == a.stages, lane);
+                    continue;
+                }
+            }
             for (unsigned hop = first_hop; hop <= last_hop; ++hop) {
                 const char *src = a.buf[hop - 1];
                 char *dst = a.buf[hop];
@@ -390,9 +468,18 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
                 // measured it is 10-25 % slower with 3 KiB trips: loads issued
                 // behind stores still in flight miss the L1.)
                 if (hop != first_hop) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                const unsigned ld = hop != first_hop ? a.ld_back : (g == 0 ? a.ld_root : a.ld_edge);
-                const unsigned st = (hop != last_hop || g + 1 == a.stages) ? a.st_mid : (unsigned)kAuxAgent;
-                copy_span_policy<V, U>(dst, src, lo, hi, lane, ld, st);
+                if constexpr (POLICY == kPolicyArgs) {
+                    const unsigned ld = hop != first_hop ? a.ld_back : (g == 0 ? a.ld_root : a.ld_edge);
+                    const unsigned st = (hop != last_hop || g + 1 == a.stages) ? a.st_mid : (unsigned)kAuxAgent;
+                    copy_span_policy<V, U>(dst, src, lo, hi, lane, ld, st);
+                } else {
+                    const bool ld_cached = hop != first_hop;
+                    const bool st_cached = POLICY == kPolicyBack && (hop != last_hop || g + 1 == a.stages);
+                    if (ld_cached && st_cached) copy_span_agent<V, U, kAuxCached, kAuxCached>(dst, src, lo, hi, lane);
+                    else if (ld_cached) copy_span_agent<V, U, kAuxCached, kAuxAgent>(dst, src, lo, hi, lane);
+                    else if (st_cached) copy_span_agent<V, U, kAuxAgent, kAuxCached>(dst, src, lo, hi, lane);
+                    else copy_span_agent<V, U>(dst, src, lo, hi, lane);
+                }
             }
         }
         // Look at the next chunk's flag while this chunk's stores drain: in
@@ -493,6 +580,7 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
     char *dst = a.buf[hop];
     const unsigned ld = first ? (g == 0 ? a.ld_root : a.ld_edge) : a.ld_back;
     const unsigned st = (last && g + 1 < a.stages) ? (unsigned)kAuxAgent : a.st_mid;
+    const bool plain_policies = (ld == kAuxAgent || ld == kAuxCached) && (st == kAuxAgent || st == kAuxCached);
 
     const u64 trip = (u64)U * kWaveSize * V;
     const u64 stride = trip * a.lanes;
@@ -509,12 +597,29 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
         }
         for (u64 lo = chunk_lo + (u64)s * trip; lo < chunk_hi; lo += stride) {
             const u64 hi = lo + trip < chunk_hi ? lo + trip : chunk_hi;
+            // whole vectors from an aligned address, policies without the streaming bit: the trip's two
+            // descriptors are made before the waits, and the loads go out the moment the last wait returns
+            const bool lean = plain_policies && (((uintptr_t)(src + lo) | (uintptr_t)(hi - lo)) & (V - 1)) == 0;
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(src) + lo, 0, (unsigned)(hi - lo), kRsrcWord3);
+            const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(dst + lo, 0, (unsigned)(hi - lo), kRsrcWord3);
+            asm volatile("" ::"s"(rs), "s"(rd));
             if (!first && !wait_trip(&trips_done[j - 1], seq + 1, a, base, hop, c, lane)) return;
             // Back-pressure: a rank stays at most kRankLead trips ahead of its
             // right neighbour's reading, so that what it stores is read out of
             // the CU's cache before later trips push it out.
             if (!last && seq >= kRankLead && !wait_trip(&trips_read[j + 1], seq + 1 - kRankLead, a, base, hop + 1, c, lane)) return;
-            copy_span_policy<V, U>(dst, src, lo, hi, lane, ld, st);
+            if (lean) {
+                const unsigned off = lane * V;
+                if (ld == kAuxAgent) {
+                    if (st == kAuxAgent) move_trip<V, U, kAuxAgent, kAuxAgent>(rs, rd, off);
+                    else move_trip<V, U, kAuxAgent, kAuxCached>(rs, rd, off);
+                } else {
+                    if (st == kAuxAgent) move_trip<V, U, kAuxCached, kAuxAgent>(rs, rd, off);
+                    else move_trip<V, U, kAuxCached, kAuxCached>(rs, rd, off);
+                }
+            } else {
+                copy_span_policy<V, U>(dst, src, lo, hi, lane, ld, st);
+            }
             ++seq;
             // the stores above were issued with the loaded data, so the loads of this trip have returned
             if (!first && lane == 0)
@@ -898,13 +1003,22 @@ hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int 
     if (!(a.ld_edge & kAuxAgent)) return hipErrorInvalidValue;
     if (!(a.st_mid & kAuxAgent) && (a.ld_back & kAuxAgent)) return hipErrorInvalidValue;
     const dim3 grid(grid_blocks), block(block_threads);
+    const bool usual = a.ld_root == kAuxAgent && a.ld_edge == kAuxAgent && a.ld_back == kAuxCached;
+    const int policy = usual && a.st_mid == kAuxAgent ? kPolicyThrough : usual && a.st_mid == kAuxCached ? kPolicyBack : kPolicyArgs;
+#define BCAST_LAUNCH_CHAIN(U)                                                                      \
+    switch (policy) {                                                                              \
+    case kPolicyThrough: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, U, kPolicyThrough); break; \
+    case kPolicyBack: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, U, kPolicyBack); break;       \
+    default: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, U, kPolicyArgs); break;                \
+    }
     switch (a.unroll) {
-    case 2: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, 2); break;
-    case 3: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, 3); break;
-    case 4: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, 4); break;
-    case 6: BCAST_LAUNCH_VB(chain_kernel, vec_bytes, grid, block, stream, a, 6); break;
+    case 2: BCAST_LAUNCH_CHAIN(2) break;
+    case 3: BCAST_LAUNCH_CHAIN(3) break;
+    case 4: BCAST_LAUNCH_CHAIN(4) break;
+    case 6: BCAST_LAUNCH_CHAIN(6) break;
     default: return hipErrorInvalidValue;
     }
+#undef BCAST_LAUNCH_CHAIN
     return hipGetLastError();
 }
 
@@ -1076,12 +1190,21 @@ bool valid_chain_unroll(int unroll) { return unroll == 2 || unroll == 3 || unrol
 
 hipError_t chain_max_blocks_per_cu(int block_threads, int *blocks)
 {
-    // the smallest over the trip sizes the kernel is built for
-    int n[4] = {0, 0, 0, 0};
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[0], chain_kernel<16, 2>, block_threads, 0);
-    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[1], chain_kernel<16, 3>, block_threads, 0);
-    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[2], chain_kernel<16, 4>, block_threads, 0);
-    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[3], chain_kernel<16, 6>, block_threads, 0);
+    // the smallest over the trip sizes and policy sets the kernel is built for
+    int n[12] = {0};
+    hipError_t e = hipSuccess;
+    int k = 0;
+#define BCAST_CHAIN_OCCUPANCY(U, POLICY) \
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n[k++], chain_kernel<16, U, POLICY>, block_threads, 0);
+#define BCAST_CHAIN_OCCUPANCY_U(U) \
+    BCAST_CHAIN_OCCUPANCY(U, kPolicyThrough) BCAST_CHAIN_OCCUPANCY(U, kPolicyBack) BCAST_CHAIN_OCCUPANCY(U, kPolicyArgs)
+    BCAST_CHAIN_OCCUPANCY_U(2)
+    BCAST_CHAIN_OCCUPANCY_U(3)
+    BCAST_CHAIN_OCCUPANCY_U(4)
+    BCAST_CHAIN_OCCUPANCY_U(6)
+#undef BCAST_CHAIN_OCCUPANCY_U
+#undef BCAST_CHAIN_OCCUPANCY
+    if (e != hipSuccess) return e;
     *blocks = n[0];
     for (int x : n)
         if (x < *blocks) *blocks = x;
