@@ -64,7 +64,10 @@ int bcast_plan_read_trace(bcast_plan_t *plan, uint64_t *out, size_t entries);
  *   ld_back  a wavefront's read-back of its own stores inside a stage;
  *   st_mid   stores the wavefront itself reads back, and the last position's.
  * Write-back stores (st_mid without AGENT) must not be read back at agent scope.
- * Every admitted combination gives the same bytes; only the speed differs. */
+ * Every admitted combination gives the same bytes; only the speed differs.
+ * The two sets the library chooses by itself are built into the kernel; any
+ * other set is read from the arguments at every hop, which alone costs a few
+ * per cent (measured 6 % at 8 ranks x 64 MiB). */
 #define BCAST_CACHE_STREAM 2
 #define BCAST_CACHE_AGENT 16
 int bcast_plan_set_cache_policy(bcast_plan_t *plan, int ld_root, int ld_edge, int ld_back, int st_mid);
