@@ -118,6 +118,28 @@ def test_chain_three_kib_trips(noise, stages, M, C, offsets):
     assert info["trip_bytes"] == 3072 and info["slice_bytes"] % 3072 == 0
 
 
+@pytest.mark.parametrize("policy", [None, (16, 16, 0, 16), (16, 16, 0, 0), (0, 16, 0, 16), (16, 16, 16, 16), (18, 16, 2, 16), (16, 18, 0, 18)])
+@pytest.mark.parametrize("trip", [2048, 3072, 4096, 6144])
+@pytest.mark.parametrize("P,stages", [(5, 4), (9, 2), (12, 3)])
+@pytest.mark.parametrize("tail", [0, 5])
+def test_chain_trip_paths_and_cache_policies(noise, policy, trip, P, stages, tail):
+    """The chain kernel's two ways through a trip and its three policy builds.
+    Chunks of two trips and three vectors: a chunk's last trip is short but made
+    of whole vectors (the short way: the descriptors end with the trip); with
+    `tail` the message's last trip has a ragged end (the general way).  The
+    policy sets the library chooses by itself (None, and the two written out) are
+    built into the kernel, every other one is read from the arguments at each
+    hop; one hop per stage (first = last) and several."""
+    C = 2 * trip + 48
+    M = 5 * C + 16 * 7 + tail
+    plan = B.bcast_plan_create(P, M, C, B.BCAST_ALGO_CHAIN)
+    if policy is not None:
+        B.bcast_plan_set_cache_policy(plan, *policy)
+    info = run_and_check(P, 1, M, C, B.BCAST_ALGO_CHAIN, noise, stages=stages, trip=trip, lanes=2, plan=plan)
+    assert info["trip_bytes"] == trip and info["stages"] == stages and info["rank_waves"] == 0
+    plan.destroy()
+
+
 @pytest.mark.parametrize("block", [64, 128, 256])
 @pytest.mark.parametrize("P,stages,lanes,M,C", [(2, 1, 1, 5, 16), (5, 4, 3, 70001, 8192), (9, 3, 7, MiB + 3, 64 * KiB),
                                                 (64, 2, 0, 3 * MiB + 5, 384 * KiB), (64, 63, 5, 100000, 4096)])
