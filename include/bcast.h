@@ -389,7 +389,7 @@ int bcast_chain_stage_span(int nranks, int stages, int stage, uint64_t chunk, in
  * wavefront per stage and with a wavefront per rank, direct, binomial, and
  * -- only if `algo_mask` has their bits -- the fan-out, scatter + allgather,
  * the k-nomial tree at radix 4 and 8 and the one-launch pipelined k-nomial
- * tree at radix 2, 4 and 8) for message sizes that are
+ * tree at radix 2, 4, 8, 16 and nranks (the flat tree)) for message sizes that are
  * powers of two in [min_bytes, max_bytes], keeps the fastest per size, installs
  * the entries, and, if table_path (HOST, nullable) is given, appends them there
  * as text.  It allocates nranks scratch buffers of max_bytes itself.

@@ -28,7 +28,7 @@ def main() -> int:
     ap.add_argument("--with-fanout", action="store_true")
     ap.add_argument("--with-knomial", action="store_true", help="also try the k-nomial tree at radix 4 and 8")
     ap.add_argument("--with-knomial-pipelined", action="store_true",
-                    help="also try the one-launch pipelined k-nomial tree at radix 2, 4 and 8")
+                    help="also try the one-launch pipelined k-nomial tree at radix 2, 4, 8, 16 and the rank count")
     ap.add_argument("--with-scatter-allgather", action="store_true")
     ap.add_argument("--log", default=None, help="also append every timed candidate to this file")
     ap.add_argument("--folded", action="store_true", help="also try the chain with a single stage (no flag hand-off)")
