@@ -13,8 +13,9 @@ default run measures every benchmark configuration and prints ONE JSON line:
     cfg5a -- 1 GiB to P = 64 ranks, root 17 -- with the tuned pipelined chain;
     exactly --steps broadcasts back to back between two synchronisations.
   * `configs`: one row per configuration (cfg1, cfg2, cfg3, cfg4, cfg5a, cfg5b),
-    each with its variants -- the tuned chain, the chain with one wavefront per
-    rank (the literal Sec. IV-B picture), the chain with one stage per hop and
+    each with its variants -- the tuned chain (whichever chain kernel the table
+    holds), the chain with one wavefront per rank (the literal Sec. IV-B picture),
+    the chain with one wavefront per stage, the chain with one stage per hop and
     every hand-off through a flag in memory, direct (Eq. 1), the one-die fan-out
     -- timed run by run with HIP events: median, min and mean latency,
     algorithmic GB/s (2(P-1)M/t), the fraction of the 8 TB/s HBM peak that the
@@ -55,10 +56,10 @@ WORKLOADS = {
 HEADLINE = "cfg5a"
 VARIANTS = {
     "cfg1": ["chain", "auto"],
-    "cfg2": ["chain", "chain_wave_per_rank", "chain_stage_per_hop", "direct", "fanout"],
-    "cfg3": ["chain", "chain_wave_per_rank", "direct"],
-    "cfg4": ["chain", "chain_wave_per_rank", "chain_stage_per_hop", "direct", "fanout"],
-    "cfg5a": ["chain", "chain_wave_per_rank", "chain_stage_per_hop", "direct", "fanout"],
+    "cfg2": ["chain", "chain_wave_per_rank", "chain_wave_per_stage", "chain_stage_per_hop", "direct", "fanout"],
+    "cfg3": ["chain", "chain_wave_per_rank", "chain_wave_per_stage", "direct"],
+    "cfg4": ["chain", "chain_wave_per_rank", "chain_wave_per_stage", "chain_stage_per_hop", "direct", "fanout"],
+    "cfg5a": ["chain", "chain_wave_per_rank", "chain_wave_per_stage", "chain_stage_per_hop", "direct", "fanout"],
     "cfg5b": ["auto", "chain", "chain_wave_per_rank"],
 }
 PROFILE_DIR = os.path.join(ROOT, "profiles")
@@ -374,6 +375,8 @@ def measure_variant(B, torch, ranks, name, variant, stream, warmup, reps, profil
     })
     if info["algo"] == B.BCAST_ALGO_CHAIN:
         row["stage_store"] = "write-back" if info["stage_store"] == B.BCAST_STORE_BACK else "write-through"
+        if info["rank_waves"]:
+            row["rank_handoff"] = "LDS" if info["rank_handoff"] == B.BCAST_HANDOFF_LDS else "cache"
     traffic, why = traffic_for(profiles, name, variant, geometry)
     if traffic:
         row.update({"traffic_bytes": traffic["bytes"], "traffic_fetch_bytes": traffic["fetch_bytes"], "traffic_write_bytes": traffic["write_bytes"],

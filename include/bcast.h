@@ -85,6 +85,8 @@ typedef struct {
     int rank_waves;        /* chain: 1 if every rank has wavefronts of its own (a stage is a workgroup of
                               hops_per_stage wavefronts), 0 if one wavefront plays its stage's ranks in turn */
     int stage_store;       /* chain: how stores inside a stage are issued, BCAST_STORE_THROUGH or BCAST_STORE_BACK */
+    int rank_handoff;      /* chain with a wavefront per rank: how a trip travels between the ranks of a workgroup,
+                              BCAST_HANDOFF_CACHE or BCAST_HANDOFF_LDS (0 otherwise) */
 } bcast_plan_info_t;
 
 /*
@@ -188,7 +190,7 @@ int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
  * wavefronts, one per consecutive rank, on one compute unit; neighbours inside
  * it hand a trip (the pipelining unit there, bcast_plan_set_trip) over with a
  * workgroup-scope release/acquire on a counter in LDS and the payload moves
- * through the compute unit's cache; between stages whole chunks are handed over
+ * through LDS or the compute unit's cache (bcast_plan_set_rank_handoff); between stages whole chunks are handed over
  * through the ready flags in memory.  stages = 0 then means: as few stages as
  * 8 ranks per workgroup allow (at least ceil((nranks-1)/16) are needed).
  * BCAST_CHAIN_WAVE_PER_STAGE: one wavefront plays all ranks of its stage in
@@ -199,6 +201,23 @@ int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
 #define BCAST_CHAIN_WAVE_PER_STAGE 1
 #define BCAST_CHAIN_WAVE_PER_RANK 2
 int bcast_plan_set_chain_waves(bcast_plan_t *plan, int mode);
+/* Chain with a wavefront per rank: how a trip's payload gets from a rank to its
+ * right neighbour inside a workgroup (the counters in LDS tell when in both).
+ * BCAST_HANDOFF_CACHE: the neighbour reads it out of the rank's buffer, which the
+ * compute unit's cache serves while the trips in flight fit it.
+ * BCAST_HANDOFF_LDS: the rank stores the trip into its buffer and also into one
+ * of its two trip slots in LDS, and the neighbour takes it from there: the LDS is
+ * the link between the two ranks, the buffers in memory are written and not
+ * read again, and a rank need not wait for its stores to memory before it tells
+ * its neighbour.  Needs 2 x trip bytes of LDS per wavefront of the workgroup;
+ * BCAST_ERR_ARG from bcast_run / bcast_plan_info if the device has less.
+ * BCAST_HANDOFF_AUTO (default): LDS where it fits, else the cache.  Trips with a
+ * ragged end or a misaligned start always go through the cache.  Same bytes
+ * either way; bcast_plan_info reports the one in use. */
+#define BCAST_HANDOFF_AUTO 0
+#define BCAST_HANDOFF_CACHE 1
+#define BCAST_HANDOFF_LDS 2
+int bcast_plan_set_rank_handoff(bcast_plan_t *plan, int mode);
 /* How the chain issues the stores that stay inside a stage (those the storing
  * wavefront, or its workgroup, reads back itself, and the last position's;
  * what another stage reads is always written through).  BCAST_STORE_THROUGH:

@@ -42,7 +42,7 @@ BCAST_ERR_CAPACITY = -6
 EXPORTS = [
     "bcast_plan_create", "bcast_run", "bcast_plan_status", "bcast_plan_clear_status", "bcast_plan_info",
     "bcast_plan_destroy", "bcast_plan_set_lanes", "bcast_plan_set_stages", "bcast_plan_set_trip", "bcast_plan_set_block_threads", "bcast_plan_set_radix", "bcast_plan_set_debug", "bcast_plan_debug_set_epoch", "bcast_chain_stage_span", "bcast_reduce_sum_f32", "bcast_reduce_sum_f32_static", "bcast_plan_reserve_reduce", "bcast_allreduce_sum_f32", "bcast_reduce_info", "bcast_plan_set_mode", "bcast_plan_enable_trace", "bcast_plan_read_trace",
-    "bcast_plan_handoff_counts", "bcast_plan_set_cache_policy", "bcast_plan_set_chain_waves", "bcast_plan_set_stage_store", "bcast_plan_set_replayable", "bcast_memory_regions", "bcast_buffers_alloc", "bcast_buffers_free", "bcast_chain_geometry",
+    "bcast_plan_handoff_counts", "bcast_plan_set_cache_policy", "bcast_plan_set_chain_waves", "bcast_plan_set_rank_handoff", "bcast_plan_set_stage_store", "bcast_plan_set_replayable", "bcast_memory_regions", "bcast_buffers_alloc", "bcast_buffers_free", "bcast_chain_geometry",
     "bcast_tune", "bcast_tune_load", "bcast_tune_save", "bcast_tune_clear", "bcast_tune_set",
     "bcast_tune_lookup", "bcast_tune_set_log", "bcast_tune_put", "bcast_tune_get", "bcast_tune_count", "bcast_tune_reduce", "bcast_tune_reduce_put", "bcast_tune_reduce_get", "bcast_plan_set_reduce_trip", "bcast_debug_store_pattern", "bcast_debug_load_pattern", "bcast_strerror", "bcast_last_hip_error", "bcast_version",
 ]
@@ -79,6 +79,7 @@ class PlanInfo(ctypes.Structure):
         ("algorithmic_bytes", ctypes.c_uint64),
         ("rank_waves", ctypes.c_int),
         ("stage_store", ctypes.c_int),
+        ("rank_handoff", ctypes.c_int),
     ]
 
     def as_dict(self):
@@ -153,6 +154,7 @@ def _load():
         "bcast_plan_set_mode": ([vp, ctypes.c_uint], i),
         "bcast_plan_set_cache_policy": ([vp, i, i, i, i], i),
         "bcast_plan_set_chain_waves": ([vp, i], i),
+        "bcast_plan_set_rank_handoff": ([vp, i], i),
         "bcast_plan_set_replayable": ([vp, i], i),
         "bcast_plan_set_stage_store": ([vp, i], i),
         "bcast_memory_regions": ([ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_size_t)], i),
@@ -397,6 +399,13 @@ BCAST_CHAIN_WAVE_PER_RANK = 2
 
 def bcast_plan_set_chain_waves(plan: Plan, mode: int) -> None:
     _check(_lib.bcast_plan_set_chain_waves(plan.handle, mode), "bcast_plan_set_chain_waves")
+
+
+BCAST_HANDOFF_AUTO, BCAST_HANDOFF_CACHE, BCAST_HANDOFF_LDS = 0, 1, 2
+
+
+def bcast_plan_set_rank_handoff(plan: Plan, mode: int) -> None:
+    _check(_lib.bcast_plan_set_rank_handoff(plan.handle, mode), "bcast_plan_set_rank_handoff")
 
 
 BCAST_STORE_AUTO, BCAST_STORE_THROUGH, BCAST_STORE_BACK = 0, 1, 2

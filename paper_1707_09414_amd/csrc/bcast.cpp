@@ -50,6 +50,9 @@ struct bcast_plan {
     int stage_store = BCAST_STORE_AUTO;        // chain: in-stage stores written through or write-back
     int chain_waves = BCAST_CHAIN_AUTO;        // chain: a wavefront per stage (chain_kernel) or per rank (rank_chain_kernel)
     int rank_blocks_per_cu[kRankWavesMax + 1] = {0};  // workgroups of w waves a CU holds (0 = not asked yet)
+    int rank_handoff = BCAST_HANDOFF_AUTO;     // wave-per-rank chain: trips between ranks through LDS or the CU's cache
+    int lds_per_block = 0;                     // LDS a workgroup may use / a compute unit has, bytes
+    int lds_per_cu = 0;
 };
 
 static thread_local int g_last_hip_error = 0;
@@ -217,6 +220,15 @@ extern "C" int bcast_plan_create(bcast_plan_t **out, int nranks, size_t bytes, s
     hipDeviceProp_t prop;
     hipError_t e = hipGetDevice(&p->device);
     if (e == hipSuccess) e = hipGetDeviceProperties(&prop, p->device);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&p->lds_per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, p->device);
+    if (e == hipSuccess) {
+        // what a compute unit has for all its resident workgroups; never less than one workgroup's share
+        if (hipDeviceGetAttribute(&p->lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, p->device) != hipSuccess) {
+            (void)hipGetLastError();
+            p->lds_per_cu = 0;
+        }
+        p->lds_per_cu = std::max(p->lds_per_cu, p->lds_per_block);
+    }
     if (e == hipSuccess) {
         p->cu_count = prop.multiProcessorCount;
         // the chain grid never exceeds what the device holds at once, so every
@@ -360,6 +372,13 @@ extern "C" int bcast_plan_set_stage_store(bcast_plan_t *p, int mode)
 {
     if (!p || mode < BCAST_STORE_AUTO || mode > BCAST_STORE_BACK) return BCAST_ERR_ARG;
     p->stage_store = mode;
+    return BCAST_OK;
+}
+
+extern "C" int bcast_plan_set_rank_handoff(bcast_plan_t *p, int mode)
+{
+    if (!p || mode < BCAST_HANDOFF_AUTO || mode > BCAST_HANDOFF_LDS) return BCAST_ERR_ARG;
+    p->rank_handoff = mode;
     return BCAST_OK;
 }
 
@@ -681,11 +700,20 @@ static int rank_chain_geometry(bcast_plan *p, size_t bytes, u64 chunk, int stage
         HIP_TRY(rank_chain_max_blocks_per_cu(waves * kWaveSize, &n));
         p->rank_blocks_per_cu[waves] = std::max(1, std::min(n, 32 / waves));
     }
-    // every workgroup resident at once, and a flag for every (stage, lane)
-    const u64 lanes_most = std::min<u64>((u64)p->rank_blocks_per_cu[waves] * p->cu_count, (u64)p->max_flags) / stages;
-    if (lanes_most < 1) return BCAST_ERR_ARG;
     const u64 trip = trip_request ? (u64)trip_request : kRankTripDefault;
     if (!valid_rank_trip(trip)) return BCAST_ERR_ARG;
+    // trips between the ranks of a workgroup through LDS (two slots per wave, beside the kernel's own
+    // counters) where that fits, else through the compute unit's cache
+    const u64 lds = rank_chain_lds_bytes(waves, (int)(trip / (kWaveSize * 16)), 16) + kRankStaticLdsBytes;
+    const bool lds_fits = lds <= (u64)p->lds_per_block;
+    if (p->rank_handoff == BCAST_HANDOFF_LDS && !lds_fits) return BCAST_ERR_ARG;
+    const bool via_lds = waves > 1 && lds_fits && p->rank_handoff != BCAST_HANDOFF_CACHE;
+    info->rank_handoff = via_lds ? BCAST_HANDOFF_LDS : BCAST_HANDOFF_CACHE;
+    u64 blocks_per_cu = (u64)p->rank_blocks_per_cu[waves];
+    if (via_lds) blocks_per_cu = std::max<u64>(1, std::min<u64>(blocks_per_cu, (u64)p->lds_per_cu / lds));
+    // every workgroup resident at once, and a flag for every (stage, lane)
+    const u64 lanes_most = std::min<u64>(blocks_per_cu * p->cu_count, (u64)p->max_flags) / stages;
+    if (lanes_most < 1) return BCAST_ERR_ARG;
     auto pow2_floor = [](u64 x) {
         u64 l = 1;
         while (l * 2 <= x) l *= 2;
@@ -941,8 +969,9 @@ extern "C" int bcast_run(bcast_plan_t *p, void *const *rank_bufs, int root, size
         a.unroll = (unsigned)(info.trip_bytes / (kWaveSize * 16));
         if (info.rank_waves) {
             a.mode |= kModeFixedSpans;
+            if (info.rank_handoff == BCAST_HANDOFF_LDS) a.mode |= kModeLdsHandoff;
             if ((u64)a.stages * a.lanes > (u64)p->max_flags) return BCAST_ERR_ARG;
-            HIP_TRY(launch_rank_chain(a, info.vec_bytes, info.grid_blocks, info.block_threads, stream));
+            HIP_TRY(launch_rank_chain(a, info.vec_bytes, info.grid_blocks, info.block_threads, p->device, p->lds_per_block, stream));
             return BCAST_OK;
         }
         // the launch must match what the kernel indexes: stages*lanes waves, each with its own flag,

@@ -135,6 +135,10 @@ constexpr unsigned kModeTrace = 8;
 // caller's request to rotate regardless and never reaches the kernel.
 constexpr unsigned kModeFixedSpans = 16;
 constexpr unsigned kModeRotateSpans = 32;
+// Wave-per-rank chain: inside a workgroup a trip travels from rank to rank
+// through LDS (two slots per rank) instead of being read back out of the left
+// neighbour's buffer through the compute unit's cache.
+constexpr unsigned kModeLdsHandoff = 64;
 // Largest message whose in-stage stores are write-back by default (measured
 // crossover on MI355X: 2-4 MiB).
 constexpr u64 kStageWriteBackMaxBytes = 2u << 20;
@@ -182,8 +186,12 @@ hipError_t launch_advance_epoch(u64 *epoch_word, u64 *flags, u64 clear_words, u6
 hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream);
 bool valid_chain_block(int block_threads);  // 64, 128 or 256
 bool valid_chain_unroll(int unroll);        // vector instructions per lane and trip the chain kernel is built for
-hipError_t launch_rank_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream);
+// device: the current device; lds_limit: the LDS a workgroup may use there (both only looked at under kModeLdsHandoff)
+hipError_t launch_rank_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, int device, int lds_limit,
+                             hipStream_t stream);
 hipError_t rank_chain_max_blocks_per_cu(int block_threads, int *blocks);
+size_t rank_chain_lds_bytes(int waves, int unroll, int vec_bytes);  // dynamic LDS of a workgroup under kModeLdsHandoff
+constexpr size_t kRankStaticLdsBytes = 2 * kRankWavesMax * sizeof(unsigned);  // the kernel's own trip counters
 hipError_t launch_tree(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
 hipError_t launch_reduce(const ChainArgs &a, int grid_blocks, hipStream_t stream);
 hipError_t reduce_max_blocks_per_cu(int *blocks);

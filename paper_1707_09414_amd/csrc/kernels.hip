@@ -6,6 +6,7 @@
 // and byte accesses for a head/tail that is not 16-byte aligned.  There are no
 // workgroup barriers and no LDS: the path is bound by HBM, not by arithmetic.
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 
 #include "bcast_internal.h"
@@ -558,6 +559,8 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
 {
     __shared__ unsigned trips_done[kRankWavesMax];  // per wave of this workgroup: trips stored so far
     __shared__ unsigned trips_read[kRankWavesMax];  // per wave: trips whose loads have returned
+    extern __shared__ __align__(16) unsigned char trip_slots[];  // kModeLdsHandoff: [wave][2] trips
+    typedef typename AgentIO<V, 0, 0>::T T;
     const unsigned lane = threadIdx.x & (kWaveSize - 1);
     const unsigned j = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const unsigned g = blockIdx.x / a.lanes;
@@ -608,7 +611,33 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
             // right neighbour's reading, so that what it stores is read out of
             // the CU's cache before later trips push it out.
             if (!last && seq >= kRankLead && !wait_trip(&trips_read[j + 1], seq + 1 - kRankLead, a, base, hop + 1, c, lane)) return;
-            if (lean) {
+            const bool via_lds = lean && (a.mode & kModeLdsHandoff);
+            if (via_lds) {
+                // the trip comes out of the left neighbour's slot (the first rank of the workgroup: out of
+                // memory), goes into this rank's buffer and, for the right neighbour, into this rank's slot
+                const unsigned off = lane * V;
+                T r[U];
+                if (first) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) r[u] = AgentIO<V, kAuxAgent, 0>::ld(rs, off + u * kWaveSize * V);
+                } else {
+                    const T *in = reinterpret_cast<const T *>(trip_slots) + ((j - 1) * 2 + (seq & 1)) * (U * kWaveSize);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) r[u] = in[u * kWaveSize + lane];
+                }
+                if (st == kAuxAgent) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) AgentIO<V, 0, kAuxAgent>::st(r[u], rd, off + u * kWaveSize * V);
+                } else {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) AgentIO<V, 0, kAuxCached>::st(r[u], rd, off + u * kWaveSize * V);
+                }
+                if (!last) {
+                    T *out = reinterpret_cast<T *>(trip_slots) + (j * 2 + (seq & 1)) * (U * kWaveSize);
+#pragma unroll
+                    for (int u = 0; u < U; ++u) out[u * kWaveSize + lane] = r[u];
+                }
+            } else if (lean) {
                 const unsigned off = lane * V;
                 if (ld == kAuxAgent) {
                     if (st == kAuxAgent) move_trip<V, U, kAuxAgent, kAuxAgent>(rs, rd, off);
@@ -625,8 +654,9 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
             if (!first && lane == 0)
                 __hip_atomic_store(&trips_read[j], seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
             if (!last && !muted) {
-                // forward: the trip is stored (complete and written through) before the right neighbour is told
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                // forward: the trip is stored (complete and written through) before the right neighbour is told;
+                // a trip handed over in LDS is complete there once the release below has waited for the LDS writes
+                if (!via_lds) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 if (lane == 0) __hip_atomic_store(&trips_done[j], seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
             }
         }
@@ -1022,7 +1052,29 @@ hipError_t launch_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int 
     return hipGetLastError();
 }
 
-hipError_t launch_rank_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, hipStream_t stream)
+size_t rank_chain_lds_bytes(int waves, int unroll, int vec_bytes)
+{
+    return (size_t)waves * 2 * unroll * kWaveSize * vec_bytes;
+}
+
+// A launch with more dynamic LDS than the default allowance has to be announced
+// to the runtime once per kernel and device; the largest size announced so far
+// is remembered so that a run enqueues nothing but its kernel.
+template <int V, int U>
+static hipError_t allow_rank_chain_lds(int device, size_t lds)
+{
+    static std::atomic<size_t> allowed[kStaticMaxDevices];
+    constexpr size_t kDefaultAllowance = 48u << 10;
+    if (lds <= kDefaultAllowance || lds <= allowed[device].load(std::memory_order_acquire)) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(rank_chain_kernel<V, U>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    size_t seen = allowed[device].load(std::memory_order_relaxed);
+    while (seen < lds && !allowed[device].compare_exchange_weak(seen, lds, std::memory_order_release)) {}
+    return hipSuccess;
+}
+
+hipError_t launch_rank_chain(const ChainArgs &a, int vec_bytes, int grid_blocks, int block_threads, int device, int lds_limit,
+                             hipStream_t stream)
 {
     if (a.nranks < 2 || a.stages < 1 || a.stages > a.nranks - 1 || a.lanes < 1) return hipErrorInvalidValue;
     // one wave per hop of the longest stage, one workgroup per (stage, lane)
@@ -1033,15 +1085,37 @@ hipError_t launch_rank_chain(const ChainArgs &a, int vec_bytes, int grid_blocks,
     if (!valid_policy(a.ld_root) || !valid_policy(a.ld_edge) || !valid_policy(a.ld_back) || !valid_policy(a.st_mid)) return hipErrorInvalidValue;
     if (!(a.ld_edge & kAuxAgent)) return hipErrorInvalidValue;
     const dim3 grid(grid_blocks), block(block_threads);
+    // LDS hand-off: two trip slots per wave of the workgroup, beside the kernel's own counters
+    size_t lds = 0;
+    if (a.mode & kModeLdsHandoff) {
+        lds = rank_chain_lds_bytes((int)longest, (int)a.unroll, vec_bytes);
+        if (device < 0 || device >= kStaticMaxDevices || lds_limit < 0 || lds + kRankStaticLdsBytes > (size_t)lds_limit) return hipErrorInvalidValue;
+    }
+#define BCAST_LAUNCH_RANK_V(V, U)                                                                                        \
+    {                                                                                                                    \
+        hipError_t e = allow_rank_chain_lds<V, U>(device, lds);                                                          \
+        if (e != hipSuccess) return e;                                                                                   \
+        rank_chain_kernel<V, U><<<grid, block, lds, stream>>>(a);                                                        \
+    }
+#define BCAST_LAUNCH_RANK(U)                        \
+    switch (vec_bytes) {                            \
+    case 16: BCAST_LAUNCH_RANK_V(16, U) break;      \
+    case 8: BCAST_LAUNCH_RANK_V(8, U) break;        \
+    case 4: BCAST_LAUNCH_RANK_V(4, U) break;        \
+    case 1: BCAST_LAUNCH_RANK_V(1, U) break;        \
+    default: return hipErrorInvalidValue;           \
+    }
     switch (a.unroll) {
-    case 1: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 1); break;
-    case 2: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 2); break;
-    case 3: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 3); break;
-    case 4: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 4); break;
-    case 6: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 6); break;
-    case 8: BCAST_LAUNCH_VB(rank_chain_kernel, vec_bytes, grid, block, stream, a, 8); break;
+    case 1: BCAST_LAUNCH_RANK(1) break;
+    case 2: BCAST_LAUNCH_RANK(2) break;
+    case 3: BCAST_LAUNCH_RANK(3) break;
+    case 4: BCAST_LAUNCH_RANK(4) break;
+    case 6: BCAST_LAUNCH_RANK(6) break;
+    case 8: BCAST_LAUNCH_RANK(8) break;
     default: return hipErrorInvalidValue;
     }
+#undef BCAST_LAUNCH_RANK
+#undef BCAST_LAUNCH_RANK_V
     return hipGetLastError();
 }
 

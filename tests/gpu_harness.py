@@ -10,6 +10,9 @@ from paper_1707_09414_amd import inputs
 
 GUARD = 256  # bytes of 0xFF kept before and after every rank buffer
 FILL = inputs.FILL_BYTE
+# How run_and_check asks the wave-per-rank chain to hand trips over inside a workgroup
+# (a test module sets it for all its cases): BCAST_HANDOFF_AUTO = LDS where it fits.
+RANK_HANDOFF = B.BCAST_HANDOFF_AUTO
 
 
 class RankBuffers:
@@ -104,6 +107,8 @@ def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0,
             B.bcast_plan_set_block_threads(plan, block)
         if waves:
             B.bcast_plan_set_chain_waves(plan, waves)
+        if waves == B.BCAST_CHAIN_WAVE_PER_RANK:
+            B.bcast_plan_set_rank_handoff(plan, RANK_HANDOFF)
         info = B.bcast_plan_info(plan, M, rb.ptrs())
         B.bcast_run(plan, rb.ptrs(), root, M, stream)
         got = rb.to_host()

@@ -3,7 +3,8 @@ every rank receives from its left neighbour, stores, and tells its right
 neighbour) against the CPU oracle, byte for byte, guard bands included.
 
 A stage is a workgroup of up to 16 wavefronts, one per consecutive rank, whose
-hand-offs go through LDS counters and the compute unit's cache; between stages
+hand-offs go through LDS counters and the payload through LDS trip slots or the
+compute unit's cache (every test runs both ways); between stages
 chunks are handed over through the ready flags in memory.  Covered: every rank
 count up to 64, stage counts from the fewest possible to one rank per workgroup,
 every trip size, ragged sizes, misaligned pointers, empty and short messages,
@@ -17,6 +18,7 @@ import torch
 import oracle
 from paper_1707_09414_amd import binding as B
 from paper_1707_09414_amd import inputs
+import gpu_harness
 from gpu_harness import RankBuffers, run_and_check, FILL
 
 pytestmark = pytest.mark.gpu
@@ -28,6 +30,15 @@ STAGE = B.BCAST_CHAIN_WAVE_PER_STAGE
 @pytest.fixture(scope="module")
 def noise():
     return inputs.random_bytes(7, 8 * MiB + 64)
+
+
+@pytest.fixture(autouse=True, params=[B.BCAST_HANDOFF_CACHE, B.BCAST_HANDOFF_AUTO], ids=["cache", "lds"])
+def handoff(request):
+    """Every test of this module twice: trips between the ranks of a workgroup
+    through the compute unit's cache, and through LDS wherever the slots fit."""
+    gpu_harness.RANK_HANDOFF = request.param
+    yield request.param
+    gpu_harness.RANK_HANDOFF = B.BCAST_HANDOFF_AUTO
 
 
 def fewest_stages(P):
@@ -102,6 +113,7 @@ def test_wait_limit_inside_and_between_workgroups(noise, mute, stages):
     rb.reset(0, noise[:M])
     plan = B.bcast_plan_create(P, M, 16 * KiB, B.BCAST_ALGO_CHAIN)
     B.bcast_plan_set_chain_waves(plan, RANK)
+    B.bcast_plan_set_rank_handoff(plan, gpu_harness.RANK_HANDOFF)
     B.bcast_plan_set_stages(plan, stages)
     B.bcast_plan_set_debug(plan, 200000, mute)  # 2 ms of the 100 MHz clock
     B.bcast_run(plan, rb.ptrs(), 0, M)
@@ -145,6 +157,7 @@ def test_burst_of_small_broadcasts_reuses_flags_and_counters():
     watch = [(root + k) % P for k in (1, 8, 9, 31, 63)]
     outs = [torch.empty((N, M), dtype=torch.uint8, device="cuda") for _ in watch]
     plan = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_rank_handoff(plan, gpu_harness.RANK_HANDOFF)
     ptrs = rb.ptrs()
     s0 = rb.start(root)
     stream = torch.cuda.current_stream()
@@ -184,6 +197,7 @@ def test_pipeline_really_overlaps_ranks():
         bufs[0].random_(0, 256)
         plan = B.bcast_plan_create(P, M, M, B.BCAST_ALGO_CHAIN)
         B.bcast_plan_set_chain_waves(plan, RANK)
+        B.bcast_plan_set_rank_handoff(plan, gpu_harness.RANK_HANDOFF)
         B.bcast_plan_set_stages(plan, 1)
         B.bcast_plan_set_lanes(plan, 1)
         B.bcast_plan_set_trip(plan, trip)
@@ -221,3 +235,53 @@ def test_random_configurations(noise, seed):
         except Exception as e:
             raise AssertionError("case %d: P=%d root=%d M=%d C=%d stages=%d lanes=%d trip=%d offsets=%s: %s"
                                  % (case, P, root, M, C, stages, lanes, trip, offsets, e))
+
+
+def test_handoff_knob(noise, handoff):
+    """What the plan reports and refuses: LDS needs two trip slots per wavefront
+    of the workgroup (9 ranks in one workgroup at 4 KiB trips: 64 KiB; 17 ranks at
+    8 KiB trips: 256 KiB, more than a workgroup can have); AUTO takes LDS where it
+    fits; a workgroup of one rank has nothing to hand over; ragged trips go
+    through the cache in either mode (covered by every ragged size above)."""
+    P, M = 10, 2 * MiB + 16
+    plan = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_chain_waves(plan, RANK)
+    B.bcast_plan_set_stages(plan, 1)
+    B.bcast_plan_set_trip(plan, 4096)
+    for mode, want in ((B.BCAST_HANDOFF_AUTO, B.BCAST_HANDOFF_LDS), (B.BCAST_HANDOFF_LDS, B.BCAST_HANDOFF_LDS),
+                       (B.BCAST_HANDOFF_CACHE, B.BCAST_HANDOFF_CACHE)):
+        B.bcast_plan_set_rank_handoff(plan, mode)
+        gpu_harness.RANK_HANDOFF = mode
+        info = run_and_check(P, 3, M, 0, B.BCAST_ALGO_CHAIN, noise, plan=plan, waves=RANK)
+        assert info["rank_handoff"] == want and info["hops_per_stage"] == 9
+    with pytest.raises(B.BcastError):
+        B.bcast_plan_set_rank_handoff(plan, 3)
+    plan.destroy()
+    gpu_harness.RANK_HANDOFF = handoff
+    # 16 ranks per workgroup at 8 KiB trips: 256 KiB of slots
+    plan = B.bcast_plan_create(17, M, 0, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_chain_waves(plan, RANK)
+    B.bcast_plan_set_stages(plan, 1)
+    B.bcast_plan_set_trip(plan, 8192)
+    B.bcast_plan_set_rank_handoff(plan, B.BCAST_HANDOFF_AUTO)
+    assert B.bcast_plan_info(plan, M)["rank_handoff"] == B.BCAST_HANDOFF_CACHE
+    B.bcast_plan_set_rank_handoff(plan, B.BCAST_HANDOFF_LDS)
+    with pytest.raises(B.BcastError):
+        B.bcast_plan_info(plan, M)
+    rb = RankBuffers(17, M)
+    rb.reset(0, noise[:M])
+    with pytest.raises(B.BcastError):
+        B.bcast_run(plan, rb.ptrs(), 0, M)
+    assert all((t == FILL).all() for t in rb.to_host()[1:])  # nothing was launched
+    plan.destroy()
+    # one rank per workgroup: nothing to hand over inside it
+    plan = B.bcast_plan_create(5, M, 0, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_chain_waves(plan, RANK)
+    B.bcast_plan_set_stages(plan, 4)
+    assert B.bcast_plan_info(plan, M)["rank_handoff"] == B.BCAST_HANDOFF_CACHE
+    plan.destroy()
+    # the wave-per-stage chain has no such hand-off
+    plan = B.bcast_plan_create(5, M, 0, B.BCAST_ALGO_CHAIN)
+    B.bcast_plan_set_chain_waves(plan, STAGE)
+    assert B.bcast_plan_info(plan, M)["rank_handoff"] == 0
+    plan.destroy()
