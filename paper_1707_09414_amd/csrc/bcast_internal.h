@@ -28,7 +28,7 @@ constexpr int kRankBlockThreadsMax = kRankWavesMax * kWaveSize;
 // should be read out of the compute unit's cache before later trips push it out
 // (measured on MI355X: without a limit 19-21 ms at 64 ranks x 1 GiB, with 1, 2
 // or 4 trips 15.0 ms).
-constexpr unsigned kRankLead = 2;
+constexpr unsigned kRankLead = 2;  // also the number of trip slots a wave has in LDS (kModeLdsHandoff)
 
 // One ready flag per (hop, lane), each alone in a 128-byte line so that a
 // producer's store and other lanes' polls never share a line.

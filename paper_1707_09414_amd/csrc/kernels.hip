@@ -518,11 +518,27 @@ __global__ void __launch_bounds__(kBlockThreads) chain_kernel(const ChainArgs a)
 //                        moment ago) or its XCD's L2 serves.
 // At workgroup scope (and without threadgroup-split mode) the CU's L1 is the
 // point of coherence for the workgroup's waves, so this is the plain
-// release/acquire protocol with nothing to write back or invalidate.  The
-// pipelining unit inside a workgroup is the trip (U KiB); between workgroups
+// release/acquire protocol with nothing to write back or invalidate.
+// With kModeLdsHandoff the payload takes the other on-chip way, LDS as the link
+// between two ranks: every wave has two trip slots there;
+//   producer (rank h):   stores the trip into its buffer in memory AND into its
+//                        slot (trip t into slot t mod 2), then the same release
+//                        store of its trip count, which waits for the LDS writes
+//                        only -- the stores to memory drain behind it and are
+//                        waited for where a chunk is published to another
+//                        workgroup or the kernel ends;
+//   consumer (rank h+1): the same acquire load, then the trip out of rank h's
+//                        slot.
+// A slot is written again once the right neighbour has read the trip before the
+// last one out of it (the back-pressure count below, kRankLead = 2 = the number
+// of slots).  The L1 then has nothing to keep, the buffers in memory are written
+// once and read only across workgroups, and the round trip of a store to memory
+// is no longer part of a hop.  Trips with a ragged end or a misaligned start go
+// through the cache as above, decided per trip by producer and consumer alike.
+// The pipelining unit inside a workgroup is the trip (U KiB); between workgroups
 // (stage g's last rank to stage g+1's first) it is the chunk, handed over
-// through the flags in memory exactly as in chain_kernel.  Every rank's bytes
-// come out of its left neighbour's buffer, every hop is a flag hand-off, and
+// through the flags in memory exactly as in chain_kernel.  Every rank stores
+// what its left neighbour stored, every hop is a flag hand-off, and
 // every rank has wavefronts of its own: lanes workgroups per stage, each
 // sweeping its share (every lanes-th trip) of every chunk.
 // Forward progress: a wave waits either for the wave before it in its own
@@ -611,6 +627,7 @@ __global__ void __launch_bounds__(kRankBlockThreadsMax) rank_chain_kernel(const 
             // right neighbour's reading, so that what it stores is read out of
             // the CU's cache before later trips push it out.
             if (!last && seq >= kRankLead && !wait_trip(&trips_read[j + 1], seq + 1 - kRankLead, a, base, hop + 1, c, lane)) return;
+            static_assert(kRankLead == 2, "a wave has two trip slots: its right neighbour may be that many trips behind");
             const bool via_lds = lean && (a.mode & kModeLdsHandoff);
             if (via_lds) {
                 // the trip comes out of the left neighbour's slot (the first rank of the workgroup: out of
