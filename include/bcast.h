@@ -439,8 +439,9 @@ typedef struct {
     int chain_rank_waves;       /* the same for the chain's own best setting */
     int stage_store;            /* winner (chain only): BCAST_STORE_THROUGH / _BACK, 0 = the library's rule */
     int chain_stage_store;      /* the same for the chain's own best setting */
-    int lanes;                  /* winner (chain with a wavefront per stage only): wavefronts per stage, 0 = one per
-                                   trip of a chunk (so chunk_bytes / lanes / trip_bytes trips per lane and chunk) */
+    int lanes;                  /* winner (chain only): wavefronts (with a wavefront per rank: workgroups) per stage,
+                                   0 = one per trip of a chunk, up to what the kernel's rule allows (so chunk_bytes /
+                                   lanes / trip_bytes trips per lane and chunk) */
     int chain_lanes;            /* the same for the chain's own best setting */
     int spans;                  /* winner (chain with a wavefront per stage only), where nranks-1 is no multiple of
                                    stages: BCAST_SPANS_FIXED (the first stages keep the extra hop) or BCAST_SPANS_ROTATE

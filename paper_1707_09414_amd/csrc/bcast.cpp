@@ -681,7 +681,8 @@ constexpr int kRankWavesPreferred = 8;
 constexpr u64 kRankTripDefault = 8192;
 constexpr u64 kRankBytesPerCu = 64u << 10;
 
-static int rank_chain_geometry(bcast_plan *p, size_t bytes, u64 chunk, int stages_request, int trip_request, bcast_plan_info_t *info)
+static int rank_chain_geometry(bcast_plan *p, size_t bytes, u64 chunk, int stages_request, int trip_request, int lanes_request,
+                               bcast_plan_info_t *info)
 {
     const int P = p->nranks;
     memset(info, 0, sizeof *info);
@@ -721,8 +722,8 @@ static int rank_chain_geometry(bcast_plan *p, size_t bytes, u64 chunk, int stage
     };
     const u64 lanes_rule = pow2_floor(std::max<u64>(1, kRankBytesPerCu * p->cu_count / (trip * waves * stages)));
     u64 lanes;
-    if (p->lanes_request > 0) {
-        lanes = std::min<u64>((u64)p->lanes_request, lanes_most);
+    if (lanes_request > 0) {  // the plan's, else the table's
+        lanes = std::min<u64>((u64)lanes_request, lanes_most);
     } else if (chunk == 0) {
         lanes = std::min(lanes_rule, pow2_floor(std::min<u64>(lanes_most, std::max<u64>(1, ceil_div(bytes, trip)))));
     } else {
@@ -755,7 +756,7 @@ static int describe(bcast_plan *p, void *const *rank_bufs, size_t bytes, bcast_p
     const int P = p->nranks;
     const int vec = common_vec_bytes(rank_bufs, P);
     if (r.algo == BCAST_ALGO_CHAIN && r.rank_waves) {
-        rc = rank_chain_geometry(p, bytes, r.chunk, r.stages, r.trip, info);
+        rc = rank_chain_geometry(p, bytes, r.chunk, r.stages, r.trip, r.lanes, info);
         if (rc != BCAST_OK) return rc;
         info->vec_bytes = vec;
         info->stage_store = r.stage_store;

@@ -55,12 +55,12 @@ static bool valid_entry(int nranks, const bcast_tune_entry_t &e)
     if (e.stage_store < BCAST_STORE_AUTO || e.stage_store > BCAST_STORE_BACK) return false;
     if (e.chain_stage_store < BCAST_STORE_AUTO || e.chain_stage_store > BCAST_STORE_BACK) return false;
     if (e.stage_store != BCAST_STORE_AUTO && e.algo != BCAST_ALGO_CHAIN) return false;
-    // lanes and spans belong to the chain with a wavefront per stage
+    // lanes belong to the chain (either kernel), spans to the chain with a wavefront per stage
     if (e.lanes < 0 || e.lanes > 8192 || e.chain_lanes < 0 || e.chain_lanes > 8192) return false;
     if (e.spans < BCAST_SPANS_AUTO || e.spans > BCAST_SPANS_ROTATE || e.chain_spans < BCAST_SPANS_AUTO || e.chain_spans > BCAST_SPANS_ROTATE)
         return false;
-    if ((e.lanes != 0 || e.spans != BCAST_SPANS_AUTO) && (e.algo != BCAST_ALGO_CHAIN || e.rank_waves)) return false;
-    if ((e.chain_lanes != 0 || e.chain_spans != BCAST_SPANS_AUTO) && e.chain_rank_waves) return false;
+    if ((e.lanes != 0 || e.spans != BCAST_SPANS_AUTO) && e.algo != BCAST_ALGO_CHAIN) return false;
+    if ((e.spans != BCAST_SPANS_AUTO && e.rank_waves) || (e.chain_spans != BCAST_SPANS_AUTO && e.chain_rank_waves)) return false;
     return true;
 }
 
@@ -421,6 +421,12 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         bcast_tune_entry_t best;
         memset(&best, 0, sizeof best);
         best.usec = best.chain_usec = 1e30;
+        // the best setting of the chain with a wavefront per stage alone, and the best candidate of all but
+        // the wave-per-rank chains of several stages (see the end of the sweep)
+        bcast_tune_entry_t relay, runner;
+        memset(&relay, 0, sizeof relay);
+        memset(&runner, 0, sizeof runner);
+        relay.usec = runner.usec = 1e30;
         auto consider = [&](int algo, size_t chunk, int stages, int trip = 0, int rank_waves = 0, int stage_store = BCAST_STORE_AUTO,
                             int lanes = 0, int spans = BCAST_SPANS_AUTO) {
             if (rc != BCAST_OK || !(algo_mask & (1u << algo))) return;
@@ -430,6 +436,26 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
             if (log)
                 fprintf(log, "%d %zu %d %zu %d %.3f %d %d %d %d %d\n", nranks, M, algo, chunk, stages, us, trip, rank_waves, stage_store, lanes,
                         spans);
+            if (algo == BCAST_ALGO_CHAIN && !rank_waves && us < relay.usec) {
+                relay.chunk_bytes = chunk;
+                relay.stages = stages;
+                relay.trip_bytes = trip;
+                relay.stage_store = stage_store;
+                relay.lanes = lanes;
+                relay.spans = spans;
+                relay.usec = us;
+            }
+            if (!(algo == BCAST_ALGO_CHAIN && rank_waves && stages >= 2) && us < runner.usec) {
+                runner.algo = algo;
+                runner.chunk_bytes = chunk;
+                runner.stages = (algo == BCAST_ALGO_CHAIN || has_radix(algo)) ? stages : 0;
+                runner.trip_bytes = algo == BCAST_ALGO_CHAIN ? trip : 0;
+                runner.rank_waves = algo == BCAST_ALGO_CHAIN ? rank_waves : 0;
+                runner.stage_store = algo == BCAST_ALGO_CHAIN ? stage_store : BCAST_STORE_AUTO;
+                runner.lanes = algo == BCAST_ALGO_CHAIN ? lanes : 0;
+                runner.spans = algo == BCAST_ALGO_CHAIN ? spans : BCAST_SPANS_AUTO;
+                runner.usec = us;
+            }
             if (algo == BCAST_ALGO_CHAIN && us < best.chain_usec) {
                 best.chain_chunk_bytes = chunk;
                 best.chain_stages = stages;
@@ -481,7 +507,8 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
         // The chain with a wavefront per rank: as few stages as 8 and as 16 ranks
         // per workgroup allow; 4 and 8 KiB trips; chunks of one trip per lane for
         // lane counts around 64 KiB of trips in flight per compute unit (the
-        // library's rule), half and twice that; and the whole message as one chunk.
+        // library's rule), half and twice that, from 16 MiB also with several trips per
+        // lane and chunk; and the whole message as one chunk.
         if (!(algo_mask & BCAST_TUNE_NO_RANK_WAVES)) {
             std::vector<int> rank_stages;
             for (int per : {8, 16}) {
@@ -498,6 +525,11 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
                         const size_t C = lanes * (size_t)trip;
                         if (lanes < 1 || C >= M || M / C > 4096) continue;
                         consider(BCAST_ALGO_CHAIN, C, stages, trip, 1);
+                        // messages that stream: the same lanes with 4 and 8 trips per lane and chunk (a chunk
+                        // is what crosses a workgroup boundary, one flag hand-off each)
+                        if (M < ((size_t)16 << 20) || stages < 2) continue;
+                        for (size_t mult : {(size_t)4, (size_t)8})
+                            if (C * mult < M) consider(BCAST_ALGO_CHAIN, C * mult, stages, trip, 1, BCAST_STORE_AUTO, (int)lanes);
                     }
                 }
             }
@@ -549,6 +581,32 @@ extern "C" int bcast_tune(int nranks, size_t min_bytes, size_t max_bytes, unsign
                 if (C < M && M / C <= 4096) consider(BCAST_ALGO_KNOMIAL_PIPELINED, C, k);
         }
         if (rc != BCAST_OK) break;
+        // A wave-per-rank chain of several stages must win clearly.  Its time moves more with where the rank
+        // buffers happen to lie than the wave-per-stage chain's does (the same shape at 64 ranks x 1 GiB: 10.1 to
+        // 10.9 ms from one set of placed buffers to the next, the wave-per-stage chain 10.2 to 10.5), and the
+        // tuner sees one set only.  Within kRankWavesMargin the steadier kernel keeps the entry.
+        constexpr double kRankWavesMargin = 1.05;
+        if (best.algo == BCAST_ALGO_CHAIN && best.rank_waves && best.stages >= 2 && runner.usec <= best.usec * kRankWavesMargin) {
+            best.algo = runner.algo;
+            best.chunk_bytes = runner.chunk_bytes;
+            best.stages = runner.stages;
+            best.trip_bytes = runner.trip_bytes;
+            best.rank_waves = runner.rank_waves;
+            best.stage_store = runner.stage_store;
+            best.lanes = runner.lanes;
+            best.spans = runner.spans;
+            best.usec = runner.usec;
+        }
+        if (best.chain_rank_waves && best.chain_stages >= 2 && relay.usec <= best.chain_usec * kRankWavesMargin) {
+            best.chain_chunk_bytes = relay.chunk_bytes;
+            best.chain_stages = relay.stages;
+            best.chain_trip_bytes = relay.trip_bytes;
+            best.chain_rank_waves = 0;
+            best.chain_stage_store = relay.stage_store;
+            best.chain_lanes = relay.lanes;
+            best.chain_spans = relay.spans;
+            best.chain_usec = relay.usec;
+        }
         if (best.chain_chunk_bytes == 0) best.chain_usec = 0.0;
         rc = bcast_tune_put(nranks, M, &best);
         if (f) print_entry(f, nranks, log2_bucket(M), best);

@@ -174,10 +174,13 @@ def test_tuning_table_lookup_rules(tmp_path):
         B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=4096, stage_store=3)
     with pytest.raises(B.BcastError):
         B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_DIRECT, stage_store=B.BCAST_STORE_BACK)
-    # ... and so are an explicit lane count and the handling of unequal stages, of the chain with a wavefront per stage
+    # ... and so are an explicit lane count (either chain kernel) and the handling of unequal stages (the chain
+    # with a wavefront per stage)
     B.bcast_tune_put(16, 1 << 25, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=6 << 20, stages=2, trip_bytes=3072, usec=90.0,
                      lanes=512, spans=B.BCAST_SPANS_ROTATE)
-    for bad in (dict(lanes=-1), dict(lanes=8193), dict(spans=3), dict(lanes=64, rank_waves=1), dict(spans=B.BCAST_SPANS_FIXED, rank_waves=1)):
+    B.bcast_tune_put(16, 1 << 21, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=1 << 20, stages=2, trip_bytes=4096, usec=9.0, lanes=64, rank_waves=1)
+    assert (B.bcast_tune_get(16, 1 << 21)["lanes"], B.bcast_tune_get(16, 1 << 21)["rank_waves"]) == (64, 1)
+    for bad in (dict(lanes=-1), dict(lanes=8193), dict(spans=3), dict(spans=B.BCAST_SPANS_FIXED, rank_waves=1)):
         with pytest.raises(B.BcastError):
             B.bcast_tune_put(16, 1 << 20, algo=B.BCAST_ALGO_CHAIN, chunk_bytes=4096, **bad)
     with pytest.raises(B.BcastError):
@@ -187,7 +190,7 @@ def test_tuning_table_lookup_rules(tmp_path):
     B.bcast_tune_save(str(path))
     B.bcast_tune_clear()
     B.bcast_tune_load(str(path))
-    assert B.bcast_tune_count() == 6
+    assert B.bcast_tune_count() == 7
     e = B.bcast_tune_get(16, 1 << 25)
     assert (e["lanes"], e["chain_lanes"], e["spans"], e["chain_spans"]) == (512, 512, B.BCAST_SPANS_ROTATE, B.BCAST_SPANS_ROTATE)
     e = B.bcast_tune_get(16, 1 << 24)
