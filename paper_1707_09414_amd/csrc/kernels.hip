@@ -777,9 +777,20 @@ __device__ __forceinline__ void add_f32x4(VecOf<16>::type &acc, const VecOf<16>:
 
 // One span [lo, hi) (at most one trip; a multiple of sizeof(T) bytes) through the
 // hops first_hop .. last_hop: T is a 16-byte vector of four floats or one float.
+// The buffer address that lane `pos` of the wave holds in (ptr_lo, ptr_hi): a
+// register read instead of a dependent scalar load from the argument segment
+// per position (measured: a reduction of up to 64 KiB over 64 ranks 6.9 ->
+// 5.3-5.5 us).
+__device__ __forceinline__ const char *position_buffer(unsigned ptr_lo, unsigned ptr_hi, unsigned pos)
+{
+    const u64 lo = (u64)(unsigned)__builtin_amdgcn_readlane((int)ptr_lo, (int)pos);
+    const u64 hi = (u64)(unsigned)__builtin_amdgcn_readlane((int)ptr_hi, (int)pos);
+    return reinterpret_cast<const char *>((hi << 32) | lo);
+}
+
 template <int V, int U, int B, int LD_IN, int ST_OUT>
-__device__ __forceinline__ void reduce_span(const ChainArgs &a, const char *in, char *out, unsigned first_hop, unsigned last_hop,
-                                            u64 lo, unsigned n, unsigned lane)
+__device__ __forceinline__ void reduce_span(const ChainArgs &a, unsigned ptr_lo, unsigned ptr_hi, const char *in, char *out,
+                                            unsigned first_hop, unsigned last_hop, u64 lo, unsigned n, unsigned lane)
 {
     typedef AgentIO<V, LD_IN, ST_OUT> EDGE;            // the running sum coming in and going out
     typedef AgentIO<V, kAuxStream, kAuxCached> OWN;    // contributions: read once, never written
@@ -796,7 +807,7 @@ __device__ __forceinline__ void reduce_span(const ChainArgs &a, const char *in, 
         for (int b = 0; b < B; ++b) {
             if (hop + b <= last_hop) {  // wave-uniform
                 const __amdgpu_buffer_rsrc_t rx =
-                    __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(a.buf[top - (hop + b)] + lo), 0, n, kRsrcWord3);
+                    __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(position_buffer(ptr_lo, ptr_hi, top - (hop + b)) + lo), 0, n, kRsrcWord3);
 #pragma unroll
                 for (int u = 0; u < U; ++u) x[b][u] = OWN::ld(rx, off + u * kWaveSize * V);
             }
@@ -842,6 +853,12 @@ __global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a
     const char *in = g > 0 ? a.scratch + (u64)(g - 1) * a.scratch_stride : a.buf[hops];
     char *out = last_stage ? a.recv : a.scratch + (u64)g * a.scratch_stride;
 
+    // lane l keeps the address of position l's contribution (the table has a
+    // slot per lane; slots beyond the rank count are never read out)
+    static_assert(BCAST_MAX_RANKS == kWaveSize, "one lane per chain position");
+    const u64 mine = reinterpret_cast<u64>(a.buf[lane]);
+    const unsigned ptr_lo = (unsigned)mine, ptr_hi = (unsigned)(mine >> 32);
+
     const u64 trip = (u64)U * kWaveSize * 16;
     const u64 stride = trip * a.lanes;
     u64 seen = 0;
@@ -859,25 +876,25 @@ __global__ void __launch_bounds__(kBlockThreads) reduce_kernel(const ChainArgs a
             const unsigned n = (unsigned)(hi - lo);
             const unsigned body = n & ~15u;  // whole vectors of four floats; the rest (at the message's end) float by float
             if (g > 0 && !last_stage) {
-                if (body) reduce_span<16, U, B, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
-                if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                if (body) reduce_span<16, U, B, kAuxAgent, kAuxAgent>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxAgent>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo + body, n - body, lane);
             } else if (g > 0) {
                 if (result_through) {
-                    if (body) reduce_span<16, U, B, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
-                    if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                    if (body) reduce_span<16, U, B, kAuxAgent, kAuxAgent>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo, body, lane);
+                    if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxAgent>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo + body, n - body, lane);
                 } else {
-                    if (body) reduce_span<16, U, B, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo, body, lane);
-                    if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxCached>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                    if (body) reduce_span<16, U, B, kAuxAgent, kAuxCached>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo, body, lane);
+                    if (n != body) reduce_span<4, 1, B, kAuxAgent, kAuxCached>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo + body, n - body, lane);
                 }
             } else if (!last_stage) {
-                if (body) reduce_span<16, U, B, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
-                if (n != body) reduce_span<4, 1, B, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                if (body) reduce_span<16, U, B, kAuxStream, kAuxAgent>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, B, kAuxStream, kAuxAgent>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo + body, n - body, lane);
             } else if (result_through) {
-                if (body) reduce_span<16, U, B, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo, body, lane);
-                if (n != body) reduce_span<4, 1, B, kAuxStream, kAuxAgent>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                if (body) reduce_span<16, U, B, kAuxStream, kAuxAgent>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, B, kAuxStream, kAuxAgent>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo + body, n - body, lane);
             } else {
-                if (body) reduce_span<16, U, B, kAuxStream, kAuxCached>(a, in, out, first_hop, last_hop, lo, body, lane);
-                if (n != body) reduce_span<4, 1, B, kAuxStream, kAuxCached>(a, in, out, first_hop, last_hop, lo + body, n - body, lane);
+                if (body) reduce_span<16, U, B, kAuxStream, kAuxCached>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo, body, lane);
+                if (n != body) reduce_span<4, 1, B, kAuxStream, kAuxCached>(a, ptr_lo, ptr_hi, in, out, first_hop, last_hop, lo + body, n - body, lane);
             }
         }
         if (in_flag && c + 1 < a.nchunks) seen = read_flag(in_flag, lane);
