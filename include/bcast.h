@@ -211,7 +211,8 @@ int bcast_plan_set_chain_waves(bcast_plan_t *plan, int mode);
  * read again, and a rank need not wait for its stores to memory before it tells
  * its neighbour.  Needs 2 x trip bytes of LDS per wavefront of the workgroup;
  * BCAST_ERR_ARG from bcast_run / bcast_plan_info if the device has less.
- * BCAST_HANDOFF_AUTO (default): LDS where it fits, else the cache.  Trips with a
+ * BCAST_HANDOFF_AUTO (default): LDS where it fits and the message is longer than
+ * 2 MiB (below that the cache is the faster way), else the cache.  Trips with a
  * ragged end or a misaligned start always go through the cache.  Same bytes
  * either way; bcast_plan_info reports the one in use. */
 #define BCAST_HANDOFF_AUTO 0

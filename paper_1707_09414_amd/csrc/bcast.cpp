@@ -708,7 +708,10 @@ static int rank_chain_geometry(bcast_plan *p, size_t bytes, u64 chunk, int stage
     const u64 lds = rank_chain_lds_bytes(waves, (int)(trip / (kWaveSize * 16)), 16) + kRankStaticLdsBytes;
     const bool lds_fits = lds <= (u64)p->lds_per_block;
     if (p->rank_handoff == BCAST_HANDOFF_LDS && !lds_fits) return BCAST_ERR_ARG;
-    const bool via_lds = waves > 1 && lds_fits && p->rank_handoff != BCAST_HANDOFF_CACHE;
+    // left to the library: LDS for messages that stream (measured crossover 1-4 MiB: below it a hop is an LDS
+    // round trip more with nothing to overlap it with, 42 vs 38 us for 4 KiB over 64 ranks)
+    const bool via_lds = waves > 1 && lds_fits &&
+                         (p->rank_handoff == BCAST_HANDOFF_LDS || (p->rank_handoff == BCAST_HANDOFF_AUTO && bytes > kRankLdsMinBytes));
     info->rank_handoff = via_lds ? BCAST_HANDOFF_LDS : BCAST_HANDOFF_CACHE;
     u64 blocks_per_cu = (u64)p->rank_blocks_per_cu[waves];
     if (via_lds) blocks_per_cu = std::max<u64>(1, std::min<u64>(blocks_per_cu, (u64)p->lds_per_cu / lds));

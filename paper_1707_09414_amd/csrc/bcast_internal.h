@@ -191,6 +191,7 @@ hipError_t launch_rank_chain(const ChainArgs &a, int vec_bytes, int grid_blocks,
                              hipStream_t stream);
 hipError_t rank_chain_max_blocks_per_cu(int block_threads, int *blocks);
 size_t rank_chain_lds_bytes(int waves, int unroll, int vec_bytes);  // dynamic LDS of a workgroup under kModeLdsHandoff
+constexpr u64 kRankLdsMinBytes = 2u << 20;  // without a request: trips through LDS for messages above this size
 constexpr size_t kRankStaticLdsBytes = 2 * kRankWavesMax * sizeof(unsigned);  // the kernel's own trip counters
 hipError_t launch_tree(const ChainArgs &a, int vec_bytes, int grid_blocks, hipStream_t stream);
 hipError_t launch_reduce(const ChainArgs &a, int grid_blocks, hipStream_t stream);

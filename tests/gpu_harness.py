@@ -11,8 +11,22 @@ from paper_1707_09414_amd import inputs
 GUARD = 256  # bytes of 0xFF kept before and after every rank buffer
 FILL = inputs.FILL_BYTE
 # How run_and_check asks the wave-per-rank chain to hand trips over inside a workgroup
-# (a test module sets it for all its cases): BCAST_HANDOFF_AUTO = LDS where it fits.
+# (a test module sets it for all its cases): one of the library's modes, or PREFER_LDS =
+# LDS wherever the slots fit the device (whatever the message size), else the library's choice.
+PREFER_LDS = -1
 RANK_HANDOFF = B.BCAST_HANDOFF_AUTO
+
+
+def set_rank_handoff(plan, M, ptrs=None):
+    """Apply RANK_HANDOFF to a plan that runs the wave-per-rank chain on M bytes."""
+    if RANK_HANDOFF != PREFER_LDS:
+        B.bcast_plan_set_rank_handoff(plan, RANK_HANDOFF)
+        return
+    B.bcast_plan_set_rank_handoff(plan, B.BCAST_HANDOFF_LDS)
+    try:
+        B.bcast_plan_info(plan, M, ptrs)
+    except B.BcastError:
+        B.bcast_plan_set_rank_handoff(plan, B.BCAST_HANDOFF_AUTO)  # the slots do not fit this shape
 
 
 class RankBuffers:
@@ -108,7 +122,7 @@ def run_and_check(P, root, M, C, algo, message, offsets=None, cap=None, lanes=0,
         if waves:
             B.bcast_plan_set_chain_waves(plan, waves)
         if waves == B.BCAST_CHAIN_WAVE_PER_RANK:
-            B.bcast_plan_set_rank_handoff(plan, RANK_HANDOFF)
+            set_rank_handoff(plan, M, rb.ptrs())
         info = B.bcast_plan_info(plan, M, rb.ptrs())
         B.bcast_run(plan, rb.ptrs(), root, M, stream)
         got = rb.to_host()

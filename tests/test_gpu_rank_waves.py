@@ -32,7 +32,7 @@ def noise():
     return inputs.random_bytes(7, 8 * MiB + 64)
 
 
-@pytest.fixture(autouse=True, params=[B.BCAST_HANDOFF_CACHE, B.BCAST_HANDOFF_AUTO], ids=["cache", "lds"])
+@pytest.fixture(autouse=True, params=[B.BCAST_HANDOFF_CACHE, gpu_harness.PREFER_LDS], ids=["cache", "lds"])
 def handoff(request):
     """Every test of this module twice: trips between the ranks of a workgroup
     through the compute unit's cache, and through LDS wherever the slots fit."""
@@ -113,8 +113,8 @@ def test_wait_limit_inside_and_between_workgroups(noise, mute, stages):
     rb.reset(0, noise[:M])
     plan = B.bcast_plan_create(P, M, 16 * KiB, B.BCAST_ALGO_CHAIN)
     B.bcast_plan_set_chain_waves(plan, RANK)
-    B.bcast_plan_set_rank_handoff(plan, gpu_harness.RANK_HANDOFF)
     B.bcast_plan_set_stages(plan, stages)
+    gpu_harness.set_rank_handoff(plan, M)
     B.bcast_plan_set_debug(plan, 200000, mute)  # 2 ms of the 100 MHz clock
     B.bcast_run(plan, rb.ptrs(), 0, M)
     torch.cuda.synchronize()
@@ -157,7 +157,8 @@ def test_burst_of_small_broadcasts_reuses_flags_and_counters():
     watch = [(root + k) % P for k in (1, 8, 9, 31, 63)]
     outs = [torch.empty((N, M), dtype=torch.uint8, device="cuda") for _ in watch]
     plan = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_CHAIN)
-    B.bcast_plan_set_rank_handoff(plan, gpu_harness.RANK_HANDOFF)
+    B.bcast_plan_set_chain_waves(plan, RANK)
+    gpu_harness.set_rank_handoff(plan, M)
     ptrs = rb.ptrs()
     s0 = rb.start(root)
     stream = torch.cuda.current_stream()
@@ -197,10 +198,10 @@ def test_pipeline_really_overlaps_ranks():
         bufs[0].random_(0, 256)
         plan = B.bcast_plan_create(P, M, M, B.BCAST_ALGO_CHAIN)
         B.bcast_plan_set_chain_waves(plan, RANK)
-        B.bcast_plan_set_rank_handoff(plan, gpu_harness.RANK_HANDOFF)
         B.bcast_plan_set_stages(plan, 1)
         B.bcast_plan_set_lanes(plan, 1)
         B.bcast_plan_set_trip(plan, trip)
+        gpu_harness.set_rank_handoff(plan, M)
         ptrs = B.RankPointers(bufs)
         stream = torch.cuda.current_stream()
         best = 1e9
@@ -241,7 +242,7 @@ def test_handoff_knob(noise, handoff):
     """What the plan reports and refuses: LDS needs two trip slots per wavefront
     of the workgroup (9 ranks in one workgroup at 4 KiB trips: 64 KiB; 17 ranks at
     8 KiB trips: 256 KiB, more than a workgroup can have); AUTO takes LDS where it
-    fits; a workgroup of one rank has nothing to hand over; ragged trips go
+    fits and the message is longer than 2 MiB; a workgroup of one rank has nothing to hand over; ragged trips go
     through the cache in either mode (covered by every ragged size above)."""
     P, M = 10, 2 * MiB + 16
     plan = B.bcast_plan_create(P, M, 0, B.BCAST_ALGO_CHAIN)
@@ -256,6 +257,12 @@ def test_handoff_knob(noise, handoff):
         assert info["rank_handoff"] == want and info["hops_per_stage"] == 9
     with pytest.raises(B.BcastError):
         B.bcast_plan_set_rank_handoff(plan, 3)
+    # left to the library, messages up to 2 MiB go through the cache (the faster way there), longer ones through LDS
+    B.bcast_plan_set_rank_handoff(plan, B.BCAST_HANDOFF_AUTO)
+    assert B.bcast_plan_info(plan, 2 * MiB)["rank_handoff"] == B.BCAST_HANDOFF_CACHE
+    assert B.bcast_plan_info(plan, 2 * MiB + 16)["rank_handoff"] == B.BCAST_HANDOFF_LDS
+    B.bcast_plan_set_rank_handoff(plan, B.BCAST_HANDOFF_LDS)
+    assert B.bcast_plan_info(plan, 4096)["rank_handoff"] == B.BCAST_HANDOFF_LDS
     plan.destroy()
     gpu_harness.RANK_HANDOFF = handoff
     # 16 ranks per workgroup at 8 KiB trips: 256 KiB of slots
