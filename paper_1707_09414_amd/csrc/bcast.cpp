@@ -676,10 +676,15 @@ static void walk_scatter_allgather(int P, u64 M, F &&emit)
 // once.  Rules without a measurement (from the sweeps on MI355X): stages so that
 // a workgroup holds at most 8 ranks; 8 KiB trips; lanes so that the waves of a
 // compute unit have about 64 KiB of trips in flight (a power of two, like the
-// staged chain's lanes); one trip per lane and chunk.
+// staged chain's lanes); one trip per lane and chunk.  From 16 MiB and 10 ranks up,
+// where the hand-offs go through LDS: 16 ranks per workgroup, 4 KiB trips, 8 trips
+// per lane and chunk (see `deep` below).
 constexpr int kRankWavesPreferred = 8;
 constexpr u64 kRankTripDefault = 8192;
 constexpr u64 kRankBytesPerCu = 64u << 10;
+constexpr u64 kRankDeepMinBytes = 16u << 20;
+constexpr u64 kRankDeepTripBytes = 4096;
+constexpr u64 kRankDeepTripsPerChunk = 8;
 
 static int rank_chain_geometry(bcast_plan *p, size_t bytes, u64 chunk, int stages_request, int trip_request, int lanes_request,
                                bcast_plan_info_t *info)
@@ -692,8 +697,17 @@ static int rank_chain_geometry(bcast_plan *p, size_t bytes, u64 chunk, int stage
     info->chunk_bytes = chunk;
     if (P < 2 || bytes == 0) return BCAST_OK;
     const int hops = P - 1;
+    // Long chains of a message that streams, with stages and trips left open and LDS at hand for the hand-offs:
+    // 16 ranks per workgroup at 4 KiB trips (half the stages, so half the reads of the message from memory) and
+    // several trips per lane and chunk -- measured at 64 ranks x 1 GiB 10.3-10.4 ms against 10.7-10.9 with 8 ranks
+    // per workgroup and 8 KiB trips, at 32 ranks x 512 MiB 2.60 against 2.69 ms.
+    const bool deep = stages_request == 0 && trip_request == 0 && hops > kRankWavesPreferred && bytes >= kRankDeepMinBytes &&
+                      p->rank_handoff != BCAST_HANDOFF_CACHE &&
+                      rank_chain_lds_bytes(kRankWavesMax, (int)(kRankDeepTripBytes / (kWaveSize * 16)), 16) + kRankStaticLdsBytes <=
+                          (u64)p->lds_per_block;
     // as many stages as asked for, but no stage longer than a workgroup can hold waves
-    int stages = stages_request > 0 ? std::min(stages_request, hops) : (hops + kRankWavesPreferred - 1) / kRankWavesPreferred;
+    const int per_workgroup = deep ? kRankWavesMax : kRankWavesPreferred;
+    int stages = stages_request > 0 ? std::min(stages_request, hops) : (hops + per_workgroup - 1) / per_workgroup;
     stages = std::max(stages, (hops + kRankWavesMax - 1) / kRankWavesMax);
     const int waves = (hops + stages - 1) / stages;  // of the longest stage = of every workgroup
     if (p->rank_blocks_per_cu[waves] == 0) {
@@ -701,7 +715,7 @@ static int rank_chain_geometry(bcast_plan *p, size_t bytes, u64 chunk, int stage
         HIP_TRY(rank_chain_max_blocks_per_cu(waves * kWaveSize, &n));
         p->rank_blocks_per_cu[waves] = std::max(1, std::min(n, 32 / waves));
     }
-    const u64 trip = trip_request ? (u64)trip_request : kRankTripDefault;
+    const u64 trip = trip_request ? (u64)trip_request : (deep ? kRankDeepTripBytes : kRankTripDefault);
     if (!valid_rank_trip(trip)) return BCAST_ERR_ARG;
     // trips between the ranks of a workgroup through LDS (two slots per wave, beside the kernel's own
     // counters) where that fits, else through the compute unit's cache
@@ -733,7 +747,7 @@ static int rank_chain_geometry(bcast_plan *p, size_t bytes, u64 chunk, int stage
         // a given chunk: a lane should own at least one trip of it
         lanes = pow2_floor(std::min<u64>(std::min(lanes_rule, lanes_most), std::max<u64>(1, ceil_div(std::min<u64>(chunk, bytes), trip))));
     }
-    if (chunk == 0) chunk = lanes * trip;
+    if (chunk == 0) chunk = lanes * trip * (deep && stages >= 2 ? kRankDeepTripsPerChunk : 1);
     const u64 C = std::min<u64>(chunk, round_up(bytes, 16));
     const u64 nchunks = ceil_div(bytes, C);
     if (C == 0 || C % 16 != 0 || nchunks >= (1ull << 27)) return BCAST_ERR_ARG;
