@@ -207,9 +207,8 @@ int bcast_plan_set_chain_waves(bcast_plan_t *plan, int mode);
  * compute unit's cache serves while the trips in flight fit it.
  * BCAST_HANDOFF_LDS: the rank stores the trip into its buffer and also into one
  * of its two trip slots in LDS, and the neighbour takes it from there: the LDS is
- * the link between the two ranks, the buffers in memory are written and not
- * read again, and a rank need not wait for its stores to memory before it tells
- * its neighbour.  Needs 2 x trip bytes of LDS per wavefront of the workgroup;
+ * the link between the two ranks, and the buffers in memory are written and not
+ * read again inside the workgroup.  Needs 2 x trip bytes of LDS per wavefront of the workgroup;
  * BCAST_ERR_ARG from bcast_run / bcast_plan_info if the device has less.
  * BCAST_HANDOFF_AUTO (default): LDS where it fits and the message is longer than
  * 2 MiB (below that the cache is the faster way), else the cache.  Trips with a
