@@ -599,10 +599,10 @@ static int resolve(const bcast_plan *p, size_t bytes, Resolved *r)
     }
     if (r->algo == BCAST_ALGO_CHAIN) {
         if (r->stages == 0) r->stages = default_stages(p->nranks);
-        // without a table: 3 KiB trips where they were measured to win (16 ranks
+        // without a table: 3 KiB trips where they were measured to win (8 ranks
         // and more, messages of 8 MiB and more), provided the chunk follows suit
         if (!valid_trip((u64)r->trip))
-            r->trip = (int)trip_bytes_of(r->chunk == 0 && p->nranks >= 16 && bytes >= ((size_t)8 << 20) ? kTripUnrollSmall
+            r->trip = (int)trip_bytes_of(r->chunk == 0 && p->nranks >= 8 && bytes >= ((size_t)8 << 20) ? kTripUnrollSmall
                                                                                                       : kTripUnrollDefault);
         if (r->chunk == 0) r->chunk = default_chunk(p->nranks, waves_for(p, bytes), r->stages, (u64)r->trip);
         r->chunk = round_up(r->chunk, 16);

@@ -191,11 +191,13 @@ def test_pipelined_knomial_tree(noise, P, radix, M, C, lanes):
 
 def test_defaults_without_a_table(noise):
     """No tuning table: two stages, one trip per lane and chunk, 3 KiB trips for
-    many ranks and large messages, 4 KiB otherwise."""
+    8 ranks and more and large messages, 4 KiB otherwise."""
     B.bcast_tune_clear()
     info = run_and_check(32, 3, 9 * MiB + 40, 0, B.BCAST_ALGO_CHAIN, noise)
     assert (info["stages"], info["trip_bytes"], info["lanes"], info["chunk_bytes"]) == (2, 3072, 1024, 3 * MiB)
     info = run_and_check(8, 3, 9 * MiB + 40, 0, B.BCAST_ALGO_CHAIN, noise)
+    assert (info["stages"], info["trip_bytes"], info["lanes"], info["chunk_bytes"]) == (2, 3072, 1024, 3 * MiB)
+    info = run_and_check(4, 3, 9 * MiB + 40, 0, B.BCAST_ALGO_CHAIN, noise)
     assert (info["stages"], info["trip_bytes"], info["lanes"], info["chunk_bytes"]) == (2, 4096, 1024, 4 * MiB)
     info = run_and_check(32, 3, 1 * MiB, 0, B.BCAST_ALGO_CHAIN, noise)
     assert info["trip_bytes"] == 4096
