@@ -46,6 +46,19 @@ def store_rate(ptrs, nbytes):
     return best
 
 
+def spread_measured(pa, pb, nbytes):
+    """Whether writes to both groups together run clearly faster than to the slower
+    group alone, or at the rate of a write set spread over regions.  A pass over a
+    few GiB takes a fraction of a millisecond, so one disturbed pass is not a verdict:
+    up to three attempts.  Returns (yes, together, slower) of the last attempt."""
+    for attempt in range(3):
+        together = store_rate(pa + pb, nbytes)
+        slower = min(store_rate(pa, nbytes), store_rate(pb, nbytes))
+        if together / slower > 1.05 or together > 6300.0:
+            return True, together, slower
+    return False, together, slower
+
+
 def test_regions_of_the_device():
     n, each = B.bcast_memory_regions()
     _, total = torch.cuda.mem_get_info()
@@ -62,14 +75,11 @@ def test_broadcast_buffers_spread_over_two_regions():
         assert all(b - a >= M for a, b in zip(order, order[1:])), "buffers overlap"
         assert placed in (B.BCAST_PLACED_NO, B.BCAST_PLACED_MEASURED)
         # the verdict against a measurement taken here: both halves together vs the slower half alone
-        together = store_rate(ptrs, M)
-        halves = store_rate(ptrs[: P // 2], M), store_rate(ptrs[P // 2:], M)
-        gain = together / min(halves)
-        print("verdict %d, %.2f GiB in use before; store-only GB/s: halves %.0f and %.0f, together %.0f" % (
-            placed, before / GiB, halves[0], halves[1], together))
+        yes, together, slower = spread_measured(ptrs[: P // 2], ptrs[P // 2:], M)
+        print("verdict %d, %.2f GiB in use before; store-only GB/s: slower half %.0f, together %.0f" % (placed, before / GiB, slower, together))
         if placed == B.BCAST_PLACED_MEASURED:
-            assert gain > 1.05 or together > 6300.0, \
-                "reported as measured-spread, but writes to both halves run at %.0f GB/s, %.2fx the slower half alone" % (together, gain)
+            assert yes, "reported as measured-spread, but writes to both halves run at %.0f GB/s, %.2fx the slower half alone" % (
+                together, together / slower)
         # the buffers serve as rank buffers: a broadcast of the whole size, every rank against the root on the
         # device, and a prefix of every rank against the oracle's end state
         message = inputs.random_bytes(81, M)
@@ -148,12 +158,8 @@ def test_three_labels_large_groups_and_memory_mostly_in_use():
             # any two groups together are faster than the slower of them alone, or at the spread rate
             for a, b in ((0, 1), (0, 2), (1, 2)):
                 pa, pb = ptrs[4 * a: 4 * a + 4], ptrs[4 * b: 4 * b + 4]
-                for attempt in range(3):  # a measurement of 2 GiB takes 0.3 ms: one disturbed pass is not a verdict
-                    together = store_rate(pa + pb, 256 * MiB)
-                    slower = min(store_rate(pa, 256 * MiB), store_rate(pb, 256 * MiB))
-                    if together / slower > 1.05 or together > 6300.0:
-                        break
-                assert together / slower > 1.05 or together > 6300.0, (a, b, together, slower)
+                yes, together, slower = spread_measured(pa, pb, 256 * MiB)
+                assert yes, (a, b, together, slower)
     finally:
         B.bcast_buffers_free(ptrs)
     # 40 GiB under one label (three slabs) and 3 GiB under another
@@ -176,11 +182,10 @@ def test_three_labels_large_groups_and_memory_mostly_in_use():
     try:
         assert placed in (B.BCAST_PLACED_NO, B.BCAST_PLACED_MEASURED)
         check_sound(ptrs, sizes)
-        together = store_rate(ptrs, GiB)
-        slower = min(store_rate(ptrs[:8], GiB), store_rate(ptrs[8:], GiB))
+        yes, together, slower = spread_measured(ptrs[:8], ptrs[8:], GiB)
         print("verdict %d with %.0f GiB in use; store-only GB/s: together %.0f, slower half %.0f" % (placed, (in_use + len(ballast) * GiB) / GiB, together, slower))
         if placed == B.BCAST_PLACED_MEASURED:
-            assert together / slower > 1.05 or together > 6300.0
+            assert yes, (together, slower)
     finally:
         B.bcast_buffers_free(ptrs)
         del ballast
