@@ -192,7 +192,9 @@ int bcast_plan_set_lanes(bcast_plan_t *plan, int lanes);
  * workgroup-scope release/acquire on a counter in LDS and the payload moves
  * through LDS or the compute unit's cache (bcast_plan_set_rank_handoff); between stages whole chunks are handed over
  * through the ready flags in memory.  stages = 0 then means: as few stages as
- * 8 ranks per workgroup allow (at least ceil((nranks-1)/16) are needed).
+ * 8 ranks per workgroup allow (at least ceil((nranks-1)/16) are needed); for
+ * messages from 16 MiB whose trips go through LDS, with the trip size left open
+ * too: 16 ranks per workgroup at 4 KiB trips.
  * BCAST_CHAIN_WAVE_PER_STAGE: one wavefront plays all ranks of its stage in
  * turn, reading back from each rank's buffer what it stored there.
  * BCAST_CHAIN_AUTO (default): the tuning table's choice, else WAVE_PER_STAGE.
